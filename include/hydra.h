@@ -1,0 +1,255 @@
+/*
+ * hydra.h - C ABI of the MI355X (gfx950) library for spilled, shard-alternated
+ * training of several GPT-2-style decoders on one GPU.
+ *
+ * The method (paper, Section 2.3 "Spilling" and Section 2.4 "Shard Alternator
+ * Parallelism"): a model is cut into shards - contiguous runs of layers - whose
+ * parameters live in host DRAM.  A shard is promoted to GPU memory, executed,
+ * and demoted again; each shard is visited twice per minibatch (forward, then
+ * backward).  Only the activation at a shard boundary is kept between visits;
+ * the backward visit recomputes the shard's forward from it.  While one shard
+ * executes, the next one - possibly of another model - is prefetched into a
+ * second buffer (double buffering).  After every shard task the Sharded-LRTF
+ * scheduler picks the model with the longest remaining time.
+ *
+ * Conventions
+ *  - All functions return hydra_status (0 = ok, <0 = error).  Nothing aborts
+ *    and no exception crosses the boundary; hydra_last_error() gives text.
+ *  - The CALLER owns all memory: one device arena (sub-allocated by the
+ *    library, never freed by it) and the pinned host arrays of every model.
+ *    The library allocates no device memory.
+ *  - Every hydra_shard_* call only enqueues work on the three streams given to
+ *    hydra_init; ordering between streams is by events on the device.
+ *  - Shards of a model: 0 = EMBED (wte, wpe); 1..S = runs of layers_per_shard
+ *    blocks; S+1 = HEAD (final LayerNorm, LM head, loss).
+ *  - Canonical flat parameter layout (fp32, row-major, matrices are [in,out]
+ *    with y = x*W + b):
+ *      EMBED  wte[V,d] wpe[T,d]
+ *      block  ln1_g[d] ln1_b[d] w_qkv[d,3d] b_qkv[3d] w_o[d,d] b_o[d]
+ *             ln2_g[d] ln2_b[d] w_fc[d,F] b_fc[F] w_proj[F,d] b_proj[d]
+ *      HEAD   lnf_g[d] lnf_b[d] w_lm[d,V]
+ *    One shard is one contiguous range, so a promote/demote is one large copy
+ *    per state array.
+ *  - Decoder mathematics (the paper only names "GPT-2", Section 3): pre-LN
+ *    blocks, LayerNorm eps 1e-5 with biased variance, scores scaled by
+ *    1/sqrt(d/H), causal mask with masked probabilities exactly 0, tanh-form
+ *    GELU, no bias on the LM head, untied LM head, no dropout, loss = mean
+ *    cross-entropy over positions with target >= 0, Adam without weight decay.
+ *  - Shape limits: d, F, T multiples of 8; d/H a multiple of 8; V arbitrary.
+ */
+#ifndef HYDRA_H
+#define HYDRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hydra_ctx hydra_ctx;
+typedef struct hydra_sched hydra_sched;
+typedef int32_t hydra_status;
+
+enum {
+  HYDRA_OK = 0,
+  HYDRA_E_INVAL = -1,  /* bad argument (null pointer, unsupported shape, bad index) */
+  HYDRA_E_NOSLOT = -2, /* no free shard buffer: spill something first              */
+  HYDRA_E_STATE = -3,  /* call not valid in the shard's / model's current state    */
+  HYDRA_E_HIP = -4,    /* a HIP call failed; text in hydra_last_error              */
+  HYDRA_E_NOMEM = -5   /* device arena too small                                   */
+};
+
+/* hydra_init_desc.flags */
+enum {
+  HYDRA_FLAG_DRY_RUN = 1,    /* no HIP call is made: state machine, slot table and traces only (host tests) */
+  HYDRA_FLAG_CKPT_SPILL = 2, /* boundary activations travel through host DRAM between visits                */
+  HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
+  HYDRA_FLAG_TIMING = 8      /* record device-side start/stop events per task for hydra_get_stats            */
+};
+
+/* 'what' of hydra_shard_load_async */
+enum {
+  HYDRA_LOAD_PARAMS = 1, /* master weights only (forward visit)            */
+  HYDRA_LOAD_OPT = 2     /* Adam m and v as well (backward visit: 1|2 = 3) */
+};
+/* 'what' of hydra_shard_spill */
+enum {
+  HYDRA_SPILL_WRITEBACK = 1, /* copy weights/m/v back to the host arrays if Adam changed them */
+  HYDRA_SPILL_EVICT = 2      /* release the shard buffer                                       */
+};
+/* 'which' of hydra_read_device */
+enum {
+  HYDRA_RD_LOGITS = 0, /* fp32 [B*T, V] of the model's last HEAD forward            */
+  HYDRA_RD_GRADS = 1,  /* fp32 gradients of a resident shard after its backward     */
+  HYDRA_RD_PARAMS = 2, /* fp32 master weights of a resident shard                   */
+  HYDRA_RD_ADAM_M = 3,
+  HYDRA_RD_ADAM_V = 4,
+  HYDRA_RD_CKPT = 5,   /* fp32 [B*T, d]: output activation of shard 'shard' (0..S)  */
+  HYDRA_RD_DBOUND = 6  /* fp32 [B*T, d]: gradient w.r.t. the input of the last backward visit */
+};
+
+typedef struct {
+  void *dev_arena;                 /* device pointer; one buffer the library carves up        */
+  uint64_t dev_arena_bytes;
+  uint64_t shard_buffer_cap_bytes; /* upper bound on memory used for shard buffers; 0 = none  */
+  int32_t max_slots;               /* upper bound on the number of shard buffers; 0 = none    */
+  int32_t flags;
+  void *compute_stream;            /* hipStream_t handles; NULL = the null stream             */
+  void *h2d_stream;
+  void *d2h_stream;
+} hydra_init_desc;
+
+typedef struct {
+  int32_t n_layer, d_model, n_head, d_ff, vocab, seq, batch;
+  int32_t layers_per_shard; /* must divide n_layer                                        */
+  int32_t dtype;            /* 0 = fp32 compute; 1 = bf16 MFMA compute, fp32 master/Adam  */
+  float lr, beta1, beta2, eps;
+} hydra_model_desc;
+
+typedef struct {
+  /* caller-owned, page-locked host memory; must outlive the model */
+  float *master;  /* [n_params] fp32, canonical flat layout */
+  float *adam_m;  /* [n_params]                               */
+  float *adam_v;  /* [n_params]                               */
+  float *ckpt;    /* [(S+1) * B*T * d] fp32; only read/written with HYDRA_FLAG_CKPT_SPILL, else may be NULL */
+} hydra_host_state;
+
+typedef struct {
+  int64_t n_params;
+  int64_t params_per_block; /* 12 d^2 + 13 d when F = 4d */
+  int32_t n_block_shards;   /* S                          */
+  int32_t n_shards;         /* S + 2                      */
+  int32_t n_tensors;
+  int32_t reserved;
+} hydra_layout;
+
+typedef struct {
+  int32_t model, shard;
+  int32_t phase; /* 0 = forward visit, 1 = backward visit (includes the shard's Adam step) */
+  int32_t minibatch;
+} hydra_task;
+
+typedef struct {
+  uint64_t bytes_h2d, bytes_d2h;   /* parameter / optimizer / checkpoint traffic enqueued  */
+  uint64_t n_loads, n_load_hits;   /* promote requests, and those already resident        */
+  uint64_t n_evictions, n_writebacks;
+  uint64_t n_tasks;
+  int32_t n_slots;
+  int32_t reserved;
+  uint64_t slot_bytes, workspace_bytes, model_state_bytes;
+  double compute_ms, h2d_ms, d2h_ms; /* device time per stream, only with HYDRA_FLAG_TIMING  */
+} hydra_stats;
+
+/* ---- context ------------------------------------------------------------ */
+/* Creates a context over the caller's arena and streams.  With
+ * HYDRA_FLAG_DRY_RUN the arena pointer may be any non-null value. */
+hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out);
+hydra_status hydra_destroy(hydra_ctx *ctx);
+/* Blocks until all three streams are idle. */
+hydra_status hydra_sync(hydra_ctx *ctx);
+/* Text of the last error seen on this context (ctx may be NULL for errors of
+ * functions that take no context). Never NULL. */
+const char *hydra_last_error(const hydra_ctx *ctx);
+hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out);
+
+/* ---- layout (pure functions of the model description) ------------------- */
+hydra_status hydra_model_layout(const hydra_model_desc *desc, hydra_layout *out);
+/* Tensor 'index' (0..n_tensors-1) in canonical order: name ("wte", "h3.w_qkv",
+ * "lnf_g", ...; at most 31 chars + NUL), element offset into the flat arrays,
+ * rows and cols (cols = 1 for vectors), and the shard that owns it. */
+hydra_status hydra_model_tensor(const hydra_model_desc *desc, int32_t index, char name[32],
+                                int64_t *offset, int64_t *rows, int64_t *cols, int32_t *shard);
+/* Element range [offset, offset+count) of a shard in the flat arrays. */
+hydra_status hydra_shard_range(const hydra_model_desc *desc, int32_t shard, int64_t *offset, int64_t *count);
+
+/* ---- models -------------------------------------------------------------- */
+/* Registers a model (the paper's interface takes a list of models with their
+ * training specifications, Section 2.1).  All models must be registered before
+ * the first load / forward / scheduler call. */
+hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc,
+                                  const hydra_host_state *host, int32_t *model_id);
+/* Hands the next minibatch of a model to the library: host int32 [B,T] token
+ * ids in [0,V) and targets (id or -1 = ignore).  Copied before returning
+ * control of the arrays; advances the model's Adam step counter t. */
+hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *tokens, const int32_t *targets);
+
+/* ---- shard tasks (paper Section 2.3) ------------------------------------- */
+/* Promote: start copying the shard's state from the host arrays into a free
+ * shard buffer on the h2d stream; returns at once.  Already resident: only
+ * missing parts are fetched.  No free buffer: HYDRA_E_NOSLOT. */
+hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what);
+/* Forward visit: reads the boundary activation at the shard's input, writes
+ * the one at its output (EMBED reads the tokens; HEAD writes logits and loss). */
+hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard);
+/* Backward visit: recompute the shard's forward from its input checkpoint,
+ * back-propagate the incoming boundary gradient, leave parameter gradients in
+ * the shard buffer and the outgoing boundary gradient for the next visit. */
+hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard);
+/* Adam on the shard's parameters with the gradients left by the backward
+ * visit; needs m and v resident (HYDRA_LOAD_OPT). */
+hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard);
+/* Demote: write back changed state on the d2h stream and/or release the buffer. */
+hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what);
+
+/* Loss of the model's last HEAD forward (synchronises the compute stream). */
+hydra_status hydra_get_loss(hydra_ctx *ctx, int32_t model, float *loss);
+/* Copies device data to host memory for inspection (synchronous). */
+hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t which,
+                               void *host_dst, uint64_t bytes);
+
+/* ---- Sharded-LRTF scheduler (paper Section 2.4) --------------------------- */
+/* task_cost[m] points to 2*(S_m+2) integers: forward-visit cost of shards
+ * 0..S+1, then backward-visit cost of shards 0..S+1.  The remaining time of a
+ * model is the summed cost of its tasks not yet started; the next task comes
+ * from the model with the largest remaining time, ties to the lowest index.
+ * ctx may be NULL when only hydra_sched_next is used (decision only). With a
+ * ctx, shapes are taken from the registered models model_ids[m]; without,
+ * n_block_shards[m] gives S per model. */
+hydra_status hydra_sched_create(hydra_ctx *ctx, int32_t n_models, const int32_t *model_ids,
+                                const int32_t *n_block_shards, const int32_t *n_minibatches,
+                                const int64_t *const *task_cost, hydra_sched **out);
+hydra_status hydra_sched_destroy(hydra_sched *s);
+/* Next decision; returns 1 (not an error) when all tasks have been handed out. */
+hydra_status hydra_sched_next(hydra_sched *s, hydra_task *out);
+/* Runs every remaining task: prefetch of task n+1 is issued before task n is
+ * enqueued, dirty shards are written back when their buffer is needed.
+ * tokens[m] / targets[m]: host int32 [n_minibatches[m], B, T].  trace (may be
+ * NULL) receives the executed order. Returns after everything is enqueued
+ * (call hydra_sync to wait). */
+hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const int32_t *const *targets,
+                             hydra_task *trace, int64_t trace_cap, int64_t *n_executed);
+
+/* ---- single kernels, exposed for parity tests and roofline measurement ----
+ * All pointers are DEVICE pointers, 'stream' a hipStream_t (NULL = null
+ * stream).  dtype: 0 = fp32 operands, 1 = bf16 operands (fp32 accumulate). */
+
+/* C[M,N] = alpha * op(A) * op(B) (+ bias[N]) (+ resid[M,N]); ta = 0: A is [M,K]
+ * row-major, 1: A is [K,M]; tb = 0: B is [N,K] row-major, 1: B is [K,N].
+ * out_f32 / out_act (operand dtype) may each be NULL. Leading dimensions in
+ * elements. */
+hydra_status hydra_op_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K,
+                           float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
+                           const float *bias, const float *resid, float *out_f32, void *out_act,
+                           int64_t ldc, void *stream);
+/* Fused Adam on n elements (Kingma & Ba update without weight decay, bias
+ * corrections passed in as 1-beta1^t and 1-beta2^t); shadow_bf16 may be NULL. */
+hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *shadow_bf16, int64_t n,
+                           float lr, float beta1, float beta2, float eps, float corr1, float corr2,
+                           void *stream);
+/* Row LayerNorm: y (dtype) [M,d], mean/rstd fp32 [M]. */
+hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *gamma, const float *beta,
+                                    void *y, float *mean, float *rstd, int32_t M, int32_t d, void *stream);
+/* Causal softmax over rows of S fp32 [n_mat, T, T] -> P (dtype); entries j>i are 0. */
+hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T,
+                                     void *stream);
+/* Cross-entropy: logits fp32 [M, ld] (first V columns valid), targets int32 [M];
+ * writes row_loss fp32 [M] and dlogits (dtype) [M, ld] = (softmax - onehot)*inv_n. */
+hydra_status hydra_op_cross_entropy(int32_t dtype, const float *logits, const int32_t *targets,
+                                    float *row_loss, void *dlogits, int32_t M, int32_t V, int64_t ld,
+                                    float inv_n, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYDRA_H */

@@ -1,0 +1,553 @@
+// Context, shard buffers (slots) and the swap engine: promote / demote of
+// shard state between pinned host arrays and device buffers on dedicated copy
+// streams, ordered against the compute stream by events only (paper Section
+// 2.3: spilling with double buffering).
+#include <cstdio>
+#include <cstring>
+
+#include "hydra_internal.h"
+
+namespace hydra {
+
+const char *global_error();
+
+hydra_status fail(hydra_ctx *ctx, hydra_status code, const std::string &msg) {
+  if (ctx) ctx->err = msg;
+  else set_global_error(msg);
+  return code;
+}
+
+hydra_status hipfail(hydra_ctx *ctx, hipError_t e, const char *what) {
+  std::string m = std::string("HIP error '") + hipGetErrorString(e) + "' at " + what;
+  return fail(ctx, HYDRA_E_HIP, m);
+}
+
+static inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+static char *arena_take(hydra_ctx *ctx, uint64_t bytes) {
+  const uint64_t off = align_up(ctx->arena_used, 256);
+  if (off + bytes > ctx->arena_bytes) return nullptr;
+  ctx->arena_used = off + bytes;
+  return ctx->arena + off;
+}
+
+Slot *slot_for(hydra_ctx *ctx, int model, int shard) {
+  const int i = ctx->models[model]->slot_of[shard];
+  return i < 0 ? nullptr : &ctx->slots[i];
+}
+
+static hydra_status make_event(hydra_ctx *ctx, hipEvent_t *ev) {
+  if (ctx->dry) return HYDRA_OK;
+  HYDRA_HIP(ctx, hipEventCreateWithFlags(ev, hipEventDisableTiming));
+  return HYDRA_OK;
+}
+
+// Carve the rest of the arena into the shared workspace and the shard buffers.
+hydra_status ensure_planned(hydra_ctx *ctx) {
+  if (ctx->planned) return HYDRA_OK;
+  if (ctx->models.empty()) return fail(ctx, HYDRA_E_STATE, "no model registered");
+  uint64_t ws = 0, max_shard = 0, total_shards = 0;
+  for (Model *m : ctx->models) {
+    const uint64_t need = workspace_need(m->sh, m->dtype);
+    if (need > ws) ws = need;
+    if ((uint64_t)m->sh.max_shard > max_shard) max_shard = m->sh.max_shard;
+    total_shards += m->sh.S + 2;
+  }
+  ctx->stats.model_state_bytes = ctx->arena_used;
+  ctx->ws_bytes = align_up(ws, 256);
+  ctx->ws = arena_take(ctx, ctx->ws_bytes);
+  if (!ctx->ws) return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the workspace");
+  // a slot: fp32 master, m, v, grad and a bf16 working copy of the largest shard
+  ctx->slot_elems = align_up(max_shard, 64);
+  ctx->slot_bytes = align_up(ctx->slot_elems * 18, 256);
+  const uint64_t base = align_up(ctx->arena_used, 256);
+  uint64_t room = ctx->arena_bytes > base ? ctx->arena_bytes - base : 0;
+  if (ctx->init.shard_buffer_cap_bytes && ctx->init.shard_buffer_cap_bytes < room)
+    room = ctx->init.shard_buffer_cap_bytes;
+  uint64_t n = room / ctx->slot_bytes;
+  if (ctx->init.max_slots > 0 && n > (uint64_t)ctx->init.max_slots) n = ctx->init.max_slots;
+  if (n > total_shards) n = total_shards;
+  if (n < 1) return fail(ctx, HYDRA_E_NOMEM, "no room for a single shard buffer (arena or cap too small)");
+  ctx->slots.resize(n);
+  for (uint64_t i = 0; i < n; ++i) {
+    Slot &s = ctx->slots[i];
+    s.base = arena_take(ctx, ctx->slot_bytes);
+    if (!s.base) return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the shard buffers");
+    s.w = (float *)s.base;
+    s.m = s.w + ctx->slot_elems;
+    s.v = s.m + ctx->slot_elems;
+    s.g = s.v + ctx->slot_elems;
+    s.wb = (bf16_t *)(s.g + ctx->slot_elems);
+    hydra_status st;
+    if ((st = make_event(ctx, &s.ev_loaded)) || (st = make_event(ctx, &s.ev_compute)) ||
+        (st = make_event(ctx, &s.ev_spilled)))
+      return st;
+  }
+  ctx->stats.n_slots = (int32_t)n;
+  ctx->stats.slot_bytes = ctx->slot_bytes;
+  ctx->stats.workspace_bytes = ctx->ws_bytes;
+  ctx->planned = true;
+  return HYDRA_OK;
+}
+
+static hydra_status check_model(hydra_ctx *ctx, int model, int shard) {
+  if (!ctx) return fail(nullptr, HYDRA_E_INVAL, "null context");
+  if (model < 0 || model >= (int)ctx->models.size()) return fail(ctx, HYDRA_E_INVAL, "model index out of range");
+  if (shard < 0 || shard >= ctx->models[model]->sh.S + 2) return fail(ctx, HYDRA_E_INVAL, "shard index out of range");
+  return HYDRA_OK;
+}
+
+}  // namespace hydra
+
+using namespace hydra;
+
+extern "C" {
+
+hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
+  if (!desc || !out) return fail(nullptr, HYDRA_E_INVAL, "null argument");
+  if (!desc->dev_arena || desc->dev_arena_bytes == 0) return fail(nullptr, HYDRA_E_INVAL, "empty device arena");
+  if (((uintptr_t)desc->dev_arena) & 255) return fail(nullptr, HYDRA_E_INVAL, "device arena must be 256-byte aligned");
+  hydra_ctx *ctx = new hydra_ctx();
+  ctx->init = *desc;
+  ctx->dry = (desc->flags & HYDRA_FLAG_DRY_RUN) != 0;
+  ctx->s_compute = (hipStream_t)desc->compute_stream;
+  ctx->s_h2d = (hipStream_t)desc->h2d_stream;
+  ctx->s_d2h = (hipStream_t)desc->d2h_stream;
+  ctx->arena = (char *)desc->dev_arena;
+  ctx->arena_bytes = desc->dev_arena_bytes;
+  memset(&ctx->stats, 0, sizeof ctx->stats);
+  if (!ctx->dry) {
+    int n = 0;
+    hipError_t e = hipGetDeviceCount(&n);
+    if (e != hipSuccess || n < 1) {
+      delete ctx;
+      return fail(nullptr, HYDRA_E_HIP, "no HIP device available");
+    }
+  }
+  *out = ctx;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_destroy(hydra_ctx *ctx) {
+  if (!ctx) return HYDRA_OK;
+  if (!ctx->dry) {
+    (void)hipStreamSynchronize(ctx->s_compute);
+    (void)hipStreamSynchronize(ctx->s_h2d);
+    (void)hipStreamSynchronize(ctx->s_d2h);
+    for (Slot &s : ctx->slots) {
+      if (s.ev_loaded) (void)hipEventDestroy(s.ev_loaded);
+      if (s.ev_compute) (void)hipEventDestroy(s.ev_compute);
+      if (s.ev_spilled) (void)hipEventDestroy(s.ev_spilled);
+    }
+  }
+  for (Model *m : ctx->models) {
+    if (!ctx->dry) {
+      for (int i = 0; i < 2; ++i) {
+        if (m->ev_stage[i]) (void)hipEventDestroy(m->ev_stage[i]);
+        if (m->ev_ckpt_d2h[i]) (void)hipEventDestroy(m->ev_ckpt_d2h[i]);
+        if (m->ev_ckpt_h2d[i]) (void)hipEventDestroy(m->ev_ckpt_h2d[i]);
+      }
+      if (m->ev_last_compute) (void)hipEventDestroy(m->ev_last_compute);
+      if (m->stage) (void)hipHostFree(m->stage);
+    } else {
+      delete[] m->stage;
+    }
+    delete m;
+  }
+  delete ctx;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_sync(hydra_ctx *ctx) {
+  if (!ctx) return fail(nullptr, HYDRA_E_INVAL, "null context");
+  if (ctx->dry) return HYDRA_OK;
+  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
+  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
+  return HYDRA_OK;
+}
+
+const char *hydra_last_error(const hydra_ctx *ctx) { return ctx ? ctx->err.c_str() : global_error(); }
+
+hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out) {
+  if (!ctx || !out) return fail(ctx, HYDRA_E_INVAL, "null argument");
+  *out = ctx->stats;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, const hydra_host_state *host,
+                                  int32_t *model_id) {
+  if (!ctx || !desc || !host || !model_id) return fail(ctx, HYDRA_E_INVAL, "null argument");
+  if (ctx->planned) return fail(ctx, HYDRA_E_STATE, "models must be registered before the first shard call");
+  if (!host->master || !host->adam_m || !host->adam_v) return fail(ctx, HYDRA_E_INVAL, "null host state array");
+  if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && !host->ckpt)
+    return fail(ctx, HYDRA_E_INVAL, "checkpoint spilling needs a host checkpoint array");
+  Model *m = new Model();
+  std::string err;
+  hydra_status st = build_shape(desc, &m->sh, &err);
+  if (st != HYDRA_OK) {
+    delete m;
+    return fail(ctx, st, err);
+  }
+  m->desc = *desc;
+  m->host = *host;
+  m->dtype = desc->dtype;
+  const ModelShape &s = m->sh;
+  const uint64_t act = (uint64_t)s.M * s.d * 4;
+  const bool spill = (ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) != 0;
+  auto take = [&](uint64_t bytes) -> char * { return arena_take(ctx, bytes); };
+  bool ok = true;
+  ok &= (m->tok = (int32_t *)take(s.M * 4)) != nullptr;
+  ok &= (m->tgt = (int32_t *)take(s.M * 4)) != nullptr;
+  m->ckpt.assign(s.S + 1, nullptr);
+  if (spill) {
+    float *pp[2];
+    ok &= (pp[0] = (float *)take(act)) != nullptr;
+    ok &= (pp[1] = (float *)take(act)) != nullptr;
+    for (int b = 0; b <= s.S; ++b) m->ckpt[b] = pp[b & 1];
+  } else {
+    for (int b = 0; b <= s.S; ++b) ok &= (m->ckpt[b] = (float *)take(act)) != nullptr;
+  }
+  ok &= (m->dbound[0] = (float *)take(act)) != nullptr;
+  ok &= (m->dbound[1] = (float *)take(act)) != nullptr;
+  ok &= (m->dlogits = take((uint64_t)s.M * s.Vpad * dt_size(m->dtype))) != nullptr;
+  ok &= (m->row_loss = (float *)take(s.M * 4)) != nullptr;
+  ok &= (m->loss = (float *)take(256)) != nullptr;
+  if (!ok) {
+    delete m;
+    return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the model's activations");
+  }
+  m->slot_of.assign(s.S + 2, -1);
+  if (!ctx->dry) {
+    hipError_t e = hipHostMalloc((void **)&m->stage, (size_t)s.M * 4 * 4, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      delete m;
+      return hipfail(ctx, e, "hipHostMalloc(token staging)");
+    }
+    for (int i = 0; i < 2; ++i) {
+      if ((st = make_event(ctx, &m->ev_stage[i])) || (st = make_event(ctx, &m->ev_ckpt_d2h[i])) ||
+          (st = make_event(ctx, &m->ev_ckpt_h2d[i])))
+        return st;
+    }
+    if ((st = make_event(ctx, &m->ev_last_compute))) return st;
+  } else {
+    m->stage = new int32_t[(size_t)s.M * 4];
+  }
+  *model_id = (int32_t)ctx->models.size();
+  ctx->models.push_back(m);
+  return HYDRA_OK;
+}
+
+hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *tokens, const int32_t *targets) {
+  hydra_status st = check_model(ctx, model, 0);
+  if (st) return st;
+  if (!tokens || !targets) return fail(ctx, HYDRA_E_INVAL, "null token / target array");
+  Model *m = ctx->models[model];
+  const int64_t M = m->sh.M;
+  int64_t nv = 0;
+  for (int64_t i = 0; i < M; ++i) {
+    if (tokens[i] < 0 || tokens[i] >= m->sh.V) return fail(ctx, HYDRA_E_INVAL, "token id out of range");
+    if (targets[i] >= m->sh.V) return fail(ctx, HYDRA_E_INVAL, "target id out of range");
+    nv += targets[i] >= 0;
+  }
+  if (nv == 0) return fail(ctx, HYDRA_E_INVAL, "minibatch has no valid target");
+  const int si = m->stage_idx;
+  int32_t *st_tok = m->stage + (size_t)si * 2 * M, *st_tgt = st_tok + M;
+  if (!ctx->dry && m->stage_used[si]) HYDRA_HIP(ctx, hipEventSynchronize(m->ev_stage[si]));
+  memcpy(st_tok, tokens, M * 4);
+  memcpy(st_tgt, targets, M * 4);
+  if (!ctx->dry) {
+    HYDRA_HIP(ctx, hipMemcpyAsync(m->tok, st_tok, M * 4, hipMemcpyHostToDevice, ctx->s_compute));
+    HYDRA_HIP(ctx, hipMemcpyAsync(m->tgt, st_tgt, M * 4, hipMemcpyHostToDevice, ctx->s_compute));
+    HYDRA_HIP(ctx, hipEventRecord(m->ev_stage[si], ctx->s_compute));
+    m->stage_used[si] = true;
+  }
+  m->stage_idx ^= 1;
+  m->n_valid = nv;
+  m->t += 1;
+  m->next_fwd = 0;
+  m->next_bwd = -1;
+  m->logits_valid = false;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what) {
+  hydra_status st = check_model(ctx, model, shard);
+  if (st) return st;
+  if (!(what & HYDRA_LOAD_PARAMS) || (what & ~3)) return fail(ctx, HYDRA_E_INVAL, "bad 'what' for load");
+  if ((st = ensure_planned(ctx))) return st;
+  Model *m = ctx->models[model];
+  const int64_t off = m->sh.shard_off[shard], cnt = m->sh.shard_off[shard + 1] - off;
+  ctx->stats.n_loads++;
+  Slot *sl = slot_for(ctx, model, shard);
+  bool copied = false;
+  if (!sl) {
+    int free_i = -1;
+    for (size_t i = 0; i < ctx->slots.size(); ++i)
+      if (ctx->slots[i].model < 0) { free_i = (int)i; break; }
+    if (free_i < 0) {
+      ctx->stats.n_loads--;
+      return fail(ctx, HYDRA_E_NOSLOT, "no free shard buffer");
+    }
+    sl = &ctx->slots[free_i];
+    sl->model = model; sl->shard = shard;
+    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->dirty = false;
+    m->slot_of[shard] = free_i;
+    // the buffer's previous occupant must be done with it
+    if (!ctx->dry) {
+      if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, sl->ev_compute, 0));
+      if (sl->spill_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, sl->ev_spilled, 0));
+    }
+    sl->compute_pending = sl->spill_pending = false;
+  } else if (sl->has_params && (sl->has_opt || !(what & HYDRA_LOAD_OPT))) {
+    ctx->stats.n_load_hits++;
+  }
+  if (!sl->has_params) {
+    if (!ctx->dry)
+      HYDRA_HIP(ctx, hipMemcpyAsync(sl->w, m->host.master + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
+    ctx->stats.bytes_h2d += cnt * 4;
+    sl->has_params = true;
+    copied = true;
+  }
+  if ((what & HYDRA_LOAD_OPT) && !sl->has_opt) {
+    if (!ctx->dry) {
+      HYDRA_HIP(ctx, hipMemcpyAsync(sl->m, m->host.adam_m + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
+      HYDRA_HIP(ctx, hipMemcpyAsync(sl->v, m->host.adam_v + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
+    }
+    ctx->stats.bytes_h2d += cnt * 8;
+    sl->has_opt = true;
+    copied = true;
+  }
+  // a backward visit of shard s >= 1 reads the checkpoint at its input; when
+  // checkpoints live in host DRAM it is promoted together with the shard
+  if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && (what & HYDRA_LOAD_OPT) && shard >= 1 &&
+      m->ckpt_in_buf[(shard - 1) & 1] != shard - 1 && m->next_bwd >= 0) {
+    const int b = shard - 1;
+    const uint64_t bytes = (uint64_t)m->sh.M * m->sh.d * 4;
+    if (!ctx->dry) {
+      if (m->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_last_compute, 0));
+      if (m->ckpt_d2h_pending[b & 1]) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_ckpt_d2h[b & 1], 0));
+      HYDRA_HIP(ctx, hipMemcpyAsync(m->ckpt[b], m->host.ckpt + (uint64_t)b * m->sh.M * m->sh.d, bytes,
+                                    hipMemcpyHostToDevice, ctx->s_h2d));
+      HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_h2d[b & 1], ctx->s_h2d));
+    }
+    m->ckpt_h2d_pending[b & 1] = true;
+    m->ckpt_in_buf[b & 1] = b;
+    ctx->stats.bytes_h2d += bytes;
+  }
+  if (copied) {
+    if (!ctx->dry) HYDRA_HIP(ctx, hipEventRecord(sl->ev_loaded, ctx->s_h2d));
+    sl->need_wait_load = true;
+  }
+  return HYDRA_OK;
+}
+
+hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what) {
+  hydra_status st = check_model(ctx, model, shard);
+  if (st) return st;
+  if (!(what & 3) || (what & ~3)) return fail(ctx, HYDRA_E_INVAL, "bad 'what' for spill");
+  if ((st = ensure_planned(ctx))) return st;
+  Model *m = ctx->models[model];
+  Slot *sl = slot_for(ctx, model, shard);
+  if (!sl) return fail(ctx, HYDRA_E_STATE, "shard is not resident");
+  if ((what & HYDRA_SPILL_EVICT) && sl->dirty && !(what & HYDRA_SPILL_WRITEBACK))
+    return fail(ctx, HYDRA_E_STATE, "evicting a shard whose updated state was not written back");
+  const int64_t off = m->sh.shard_off[shard], cnt = m->sh.shard_off[shard + 1] - off;
+  if ((what & HYDRA_SPILL_WRITEBACK) && sl->dirty) {
+    if (!ctx->dry) {
+      if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
+      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.master + off, sl->w, cnt * 4, hipMemcpyDeviceToHost, ctx->s_d2h));
+      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.adam_m + off, sl->m, cnt * 4, hipMemcpyDeviceToHost, ctx->s_d2h));
+      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.adam_v + off, sl->v, cnt * 4, hipMemcpyDeviceToHost, ctx->s_d2h));
+      HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
+    }
+    sl->spill_pending = true;
+    sl->dirty = false;
+    ctx->stats.bytes_d2h += cnt * 12;
+    ctx->stats.n_writebacks++;
+  }
+  if (what & HYDRA_SPILL_EVICT) {
+    if ((ctx->init.flags & HYDRA_FLAG_POISON) && !ctx->dry) {
+      // runs after everything enqueued so far on the compute stream and after the write-back
+      if (sl->spill_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, sl->ev_spilled, 0));
+      HYDRA_HIP(ctx, launch_fill_u32((uint32_t *)sl->base, 0x7fc07fc0u, (int64_t)(ctx->slot_bytes / 4), ctx->s_compute));
+      HYDRA_HIP(ctx, hipEventRecord(sl->ev_compute, ctx->s_compute));
+      sl->compute_pending = true;
+    }
+    m->slot_of[shard] = -1;
+    sl->model = sl->shard = -1;
+    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = false;
+    ctx->stats.n_evictions++;
+  }
+  return HYDRA_OK;
+}
+
+// common entry of the three compute calls: the shard must have been promoted
+static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out) {
+  hydra_status st = check_model(ctx, model, shard);
+  if (st) return st;
+  if ((st = ensure_planned(ctx))) return st;
+  Slot *sl = slot_for(ctx, model, shard);
+  if (!sl || !sl->has_params) return fail(ctx, HYDRA_E_STATE, "shard was not loaded");
+  if (sl->need_wait_load) {
+    if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, sl->ev_loaded, 0));
+    sl->need_wait_load = false;
+  }
+  *out = sl;
+  return HYDRA_OK;
+}
+
+static hydra_status end_task(hydra_ctx *ctx, Model *m, Slot *sl) {
+  if (!ctx->dry) {
+    HYDRA_HIP(ctx, hipEventRecord(sl->ev_compute, ctx->s_compute));
+    HYDRA_HIP(ctx, hipEventRecord(m->ev_last_compute, ctx->s_compute));
+  }
+  sl->compute_pending = true;
+  m->compute_pending = true;
+  ctx->stats.n_tasks++;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
+  Slot *sl = nullptr;
+  hydra_status st = begin_task(ctx, model, shard, &sl);
+  if (st) return st;
+  Model *m = ctx->models[model];
+  if (m->t == 0) return fail(ctx, HYDRA_E_STATE, "no minibatch set");
+  if (shard != m->next_fwd) return fail(ctx, HYDRA_E_STATE, "forward visits must follow shard order");
+  const bool spill = (ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) != 0;
+  const int S = m->sh.S;
+  if (spill && shard <= S && !ctx->dry && m->ckpt_d2h_pending[shard & 1]) {
+    // the ping-pong buffer about to be overwritten may still be on its way to the host
+    HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, m->ev_ckpt_d2h[shard & 1], 0));
+  }
+  if (!ctx->dry && (st = exec_forward(ctx, m, sl, shard))) return st;
+  if ((st = end_task(ctx, m, sl))) return st;
+  if (spill && shard <= S) {
+    const uint64_t bytes = (uint64_t)m->sh.M * m->sh.d * 4;
+    if (!ctx->dry) {
+      HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, m->ev_last_compute, 0));
+      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.ckpt + (uint64_t)shard * m->sh.M * m->sh.d, m->ckpt[shard], bytes,
+                                    hipMemcpyDeviceToHost, ctx->s_d2h));
+      HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_d2h[shard & 1], ctx->s_d2h));
+    }
+    m->ckpt_d2h_pending[shard & 1] = true;
+    ctx->stats.bytes_d2h += bytes;
+  }
+  m->next_fwd = shard + 1;
+  if (shard <= S) m->ckpt_in_buf[shard & 1] = shard;
+  if (shard == S + 1) {
+    m->next_bwd = S + 1;
+    m->logits_valid = true;
+  }
+  return HYDRA_OK;
+}
+
+hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard) {
+  Slot *sl = nullptr;
+  hydra_status st = begin_task(ctx, model, shard, &sl);
+  if (st) return st;
+  Model *m = ctx->models[model];
+  if (m->next_bwd < 0) return fail(ctx, HYDRA_E_STATE, "backward before the forward pass has finished");
+  if (shard != m->next_bwd) return fail(ctx, HYDRA_E_STATE, "backward visits must follow reverse shard order");
+  if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && shard >= 1) {
+    const int pb = (shard - 1) & 1;
+    if (m->ckpt_in_buf[pb] != shard - 1)
+      return fail(ctx, HYDRA_E_STATE, "input checkpoint not promoted: load the shard with HYDRA_LOAD_OPT first");
+    if (m->ckpt_h2d_pending[pb] && !ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, m->ev_ckpt_h2d[pb], 0));
+    m->ckpt_h2d_pending[pb] = false;
+  }
+  if (!ctx->dry && (st = exec_backward(ctx, m, sl, shard))) return st;
+  sl->grads_valid = true;
+  if ((st = end_task(ctx, m, sl))) return st;
+  m->next_bwd = shard - 1;  // -1 after the embedding shard: minibatch finished
+  return HYDRA_OK;
+}
+
+hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard) {
+  Slot *sl = nullptr;
+  hydra_status st = begin_task(ctx, model, shard, &sl);
+  if (st) return st;
+  Model *m = ctx->models[model];
+  if (!sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients: run the backward visit first");
+  if (!sl->has_opt) return fail(ctx, HYDRA_E_STATE, "Adam state not resident: load with HYDRA_LOAD_OPT");
+  if (!ctx->dry && (st = exec_adam(ctx, m, sl, shard))) return st;
+  sl->grads_valid = false;
+  sl->dirty = true;
+  ctx->stats.n_tasks--;  // the optimizer step belongs to the backward task
+  return end_task(ctx, m, sl);
+}
+
+hydra_status hydra_get_loss(hydra_ctx *ctx, int32_t model, float *loss) {
+  hydra_status st = check_model(ctx, model, 0);
+  if (st) return st;
+  if (!loss) return fail(ctx, HYDRA_E_INVAL, "null output");
+  Model *m = ctx->models[model];
+  if (m->next_fwd != m->sh.S + 2) return fail(ctx, HYDRA_E_STATE, "the HEAD forward visit has not run");
+  if (ctx->dry) {
+    *loss = 0.f;
+    return HYDRA_OK;
+  }
+  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+  HYDRA_HIP(ctx, hipMemcpy(loss, m->loss, 4, hipMemcpyDeviceToHost));
+  return HYDRA_OK;
+}
+
+hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t which, void *host_dst,
+                               uint64_t bytes) {
+  hydra_status st = check_model(ctx, model, shard);
+  if (st) return st;
+  if (!host_dst) return fail(ctx, HYDRA_E_INVAL, "null destination");
+  if ((st = ensure_planned(ctx))) return st;
+  Model *m = ctx->models[model];
+  const ModelShape &s = m->sh;
+  const uint64_t act = (uint64_t)s.M * s.d * 4;
+  if (!ctx->dry) {
+    HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
+    HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
+  }
+  const void *src = nullptr;
+  uint64_t need = 0;
+  switch (which) {
+    case HYDRA_RD_LOGITS: {
+      if (!m->logits_valid || ctx->logits_owner != model)
+        return fail(ctx, HYDRA_E_STATE, "logits of this model are no longer held");
+      need = (uint64_t)s.M * s.V * 4;
+      if (bytes != need) return fail(ctx, HYDRA_E_INVAL, "size mismatch");
+      if (!ctx->dry)
+        HYDRA_HIP(ctx, hipMemcpy2D(host_dst, (size_t)s.V * 4, ctx->logits, (size_t)s.Vpad * 4, (size_t)s.V * 4, s.M,
+                                   hipMemcpyDeviceToHost));
+      return HYDRA_OK;
+    }
+    case HYDRA_RD_GRADS:
+    case HYDRA_RD_PARAMS:
+    case HYDRA_RD_ADAM_M:
+    case HYDRA_RD_ADAM_V: {
+      Slot *sl = slot_for(ctx, model, shard);
+      if (!sl) return fail(ctx, HYDRA_E_STATE, "shard is not resident");
+      if (which == HYDRA_RD_GRADS && !sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients held");
+      if ((which == HYDRA_RD_ADAM_M || which == HYDRA_RD_ADAM_V) && !sl->has_opt)
+        return fail(ctx, HYDRA_E_STATE, "Adam state not resident");
+      src = which == HYDRA_RD_GRADS ? sl->g : which == HYDRA_RD_PARAMS ? sl->w : which == HYDRA_RD_ADAM_M ? sl->m : sl->v;
+      need = (uint64_t)(s.shard_off[shard + 1] - s.shard_off[shard]) * 4;
+      break;
+    }
+    case HYDRA_RD_CKPT:
+      if (shard > s.S) return fail(ctx, HYDRA_E_INVAL, "no boundary after the HEAD shard");
+      src = m->ckpt[shard];
+      need = act;
+      break;
+    case HYDRA_RD_DBOUND:
+      src = m->dbound[m->dcur];
+      need = act;
+      break;
+    default:
+      return fail(ctx, HYDRA_E_INVAL, "unknown 'which'");
+  }
+  if (bytes != need) return fail(ctx, HYDRA_E_INVAL, "size mismatch");
+  if (!ctx->dry) HYDRA_HIP(ctx, hipMemcpy(host_dst, src, need, hipMemcpyDeviceToHost));
+  return HYDRA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,559 @@
+// Memory-bound kernels of the decoder shard: embedding, LayerNorm, causal
+// softmax, cross-entropy, Adam, casts and column reductions.  One wavefront
+// (64 lanes) owns one row wherever a row reduction is needed; reductions over
+// rows (bias / gain gradients) are done in two passes with a fixed summation
+// order so that results do not depend on scheduling.
+#include "kernels.h"
+
+namespace hydra {
+
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float ldv(const T *p, int64_t i);
+template <> __device__ __forceinline__ float ldv<float>(const float *p, int64_t i) { return p[i]; }
+template <> __device__ __forceinline__ float ldv<bf16_t>(const bf16_t *p, int64_t i) { return bf2f(p[i]); }
+template <typename T> __device__ __forceinline__ void stv(T *p, int64_t i, float v);
+template <> __device__ __forceinline__ void stv<float>(float *p, int64_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void stv<bf16_t>(bf16_t *p, int64_t i, float v) { p[i] = f2bf(v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ------------------------------------------------------------------ embedding
+__global__ void embed_fwd_kernel(const int32_t *__restrict__ tok, const float *__restrict__ wte,
+                                 const float *__restrict__ wpe, float *__restrict__ x0, int M, int T, int d) {
+  const int m = blockIdx.x;
+  const int64_t id = tok[m];
+  const int t = m % T;
+  for (int c = threadIdx.x * 4; c < d; c += blockDim.x * 4) {
+    const float4 a = *(const float4 *)(wte + id * d + c);
+    const float4 b = *(const float4 *)(wpe + (int64_t)t * d + c);
+    float4 o;
+    o.x = a.x + b.x; o.y = a.y + b.y; o.z = a.z + b.z; o.w = a.w + b.w;
+    *(float4 *)(x0 + (int64_t)m * d + c) = o;
+  }
+}
+
+// One block per position m.  The block that holds the first occurrence of a
+// token id marks all later occurrences in a bitmap, then sums their rows in
+// ascending m and writes the token's gradient row once; other blocks leave.
+// dwte was zeroed before.
+constexpr int EMB_MAXW = 1024;  // bitmap words: up to 32768 positions
+__global__ __launch_bounds__(256) void embed_bwd_wte_kernel(const int32_t *__restrict__ tok,
+                                                            const float *__restrict__ dx0, float *__restrict__ dwte,
+                                                            int M, int d) {
+  const int m = blockIdx.x;
+  const int id = tok[m];
+  __shared__ int earlier;
+  __shared__ uint32_t bits[EMB_MAXW];
+  if (threadIdx.x == 0) earlier = 0;
+  const int nw = (M + 31) / 32;
+  for (int w = threadIdx.x; w < nw; w += blockDim.x) bits[w] = 0u;
+  __syncthreads();
+  int found = 0;
+  for (int j = threadIdx.x; j < m; j += blockDim.x) found |= (tok[j] == id);
+  if (found) earlier = 1;
+  __syncthreads();
+  if (earlier) return;
+  for (int j = m + 1 + threadIdx.x; j < M; j += blockDim.x)
+    if (tok[j] == id) atomicOr(&bits[j >> 5], 1u << (j & 31));
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float acc = dx0[(int64_t)m * d + c];
+    for (int w = m >> 5; w < nw; ++w) {
+      uint32_t b = bits[w];
+      while (b) {
+        const int j = (w << 5) + __ffs(b) - 1;
+        b &= b - 1;
+        acc += dx0[(int64_t)j * d + c];
+      }
+    }
+    dwte[(int64_t)id * d + c] = acc;
+  }
+}
+
+__global__ void embed_bwd_wpe_kernel(const float *__restrict__ dx0, float *__restrict__ dwpe, int B, int T, int d) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // over T*d
+  if (i >= (int64_t)T * d) return;
+  float acc = 0.f;
+  for (int b = 0; b < B; ++b) acc += dx0[(int64_t)b * T * d + i];
+  dwpe[i] = acc;
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
+  int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  for (; i < n; i += stride) {
+    if (i + 4 <= n && ((((uintptr_t)p) & 15) == 0)) {
+      *(uint4 *)(p + i) = make_uint4(v, v, v, v);
+    } else {
+      for (int64_t j = i; j < n && j < i + 4; ++j) p[j] = v;
+    }
+  }
+}
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n / 4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, value, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *wpe, float *x0, int M, int T, int d,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3(M), dim3(128), 0, s, tok, wte, wpe, x0, M, T, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, float *dwpe, int B, int T, int d, int V,
+                            hipStream_t s) {
+  if (B * T > EMB_MAXW * 32) return hipErrorInvalidValue;
+  hipError_t e = launch_fill_u32((uint32_t *)dwte, 0u, (int64_t)V * d, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(B * T), dim3(256), 0, s, tok, dx0, dwte, B * T, d);
+  const int64_t n = (int64_t)T * d;
+  hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dx0, dwpe, B, T, d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ LayerNorm
+// One wavefront per row, four rows per block.  Mean, then centred variance
+// (two passes, as in the definition), then the affine output.
+template <typename OutT>
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float *__restrict__ x, const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta, OutT *__restrict__ y,
+                                                            float *__restrict__ mean, float *__restrict__ rstd, int M,
+                                                            int d) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= M) return;
+  const float *xr = x + (int64_t)row * d;
+  float s = 0.f;
+  for (int c = lane * 4; c < d; c += 256) {
+    const float4 v = *(const float4 *)(xr + c);
+    s += (v.x + v.y) + (v.z + v.w);
+  }
+  const float mu = wave_sum(s) / (float)d;
+  float q = 0.f;
+  for (int c = lane * 4; c < d; c += 256) {
+    const float4 v = *(const float4 *)(xr + c);
+    const float a = v.x - mu, b = v.y - mu, e = v.z - mu, f = v.w - mu;
+    q += (a * a + b * b) + (e * e + f * f);
+  }
+  const float rs = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  OutT *yr = y + (int64_t)row * d;
+  for (int c = lane * 4; c < d; c += 256) {
+    const float4 v = *(const float4 *)(xr + c);
+    const float4 gm = *(const float4 *)(gamma + c);
+    const float4 bt = *(const float4 *)(beta + c);
+    stv<OutT>(yr, c + 0, (v.x - mu) * rs * gm.x + bt.x);
+    stv<OutT>(yr, c + 1, (v.y - mu) * rs * gm.y + bt.y);
+    stv<OutT>(yr, c + 2, (v.z - mu) * rs * gm.z + bt.z);
+    stv<OutT>(yr, c + 3, (v.w - mu) * rs * gm.w + bt.w);
+  }
+}
+
+hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, const float *beta, void *y, float *mean,
+                                float *rstd, int M, int d, hipStream_t s) {
+  dim3 grid((M + 3) / 4), block(256);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(layernorm_fwd_kernel<bf16_t>, grid, block, 0, s, x, gamma, beta, (bf16_t *)y, mean, rstd, M, d);
+  else
+    hipLaunchKernelGGL(layernorm_fwd_kernel<float>, grid, block, 0, s, x, gamma, beta, (float *)y, mean, rstd, M, d);
+  return hipGetLastError();
+}
+
+// dx = rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)) [+ dres], dxhat = dy * gamma
+__global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__restrict__ dy, const float *__restrict__ x,
+                                                               const float *__restrict__ mean,
+                                                               const float *__restrict__ rstd,
+                                                               const float *__restrict__ gamma,
+                                                               const float *__restrict__ dres, float *__restrict__ dx,
+                                                               int M, int d) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= M) return;
+  const float *xr = x + (int64_t)row * d, *dyr = dy + (int64_t)row * d;
+  const float mu = mean[row], rs = rstd[row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane * 4; c < d; c += 256) {
+    const float4 v = *(const float4 *)(xr + c);
+    const float4 g = *(const float4 *)(dyr + c);
+    const float4 gm = *(const float4 *)(gamma + c);
+    const float h0 = g.x * gm.x, h1 = g.y * gm.y, h2 = g.z * gm.z, h3 = g.w * gm.w;
+    s1 += (h0 + h1) + (h2 + h3);
+    s2 += (h0 * ((v.x - mu) * rs) + h1 * ((v.y - mu) * rs)) + (h2 * ((v.z - mu) * rs) + h3 * ((v.w - mu) * rs));
+  }
+  const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
+  for (int c = lane * 4; c < d; c += 256) {
+    const float4 v = *(const float4 *)(xr + c);
+    const float4 g = *(const float4 *)(dyr + c);
+    const float4 gm = *(const float4 *)(gamma + c);
+    float4 o;
+    o.x = rs * (g.x * gm.x - m1 - (v.x - mu) * rs * m2);
+    o.y = rs * (g.y * gm.y - m1 - (v.y - mu) * rs * m2);
+    o.z = rs * (g.z * gm.z - m1 - (v.z - mu) * rs * m2);
+    o.w = rs * (g.w * gm.w - m1 - (v.w - mu) * rs * m2);
+    if (dres) {
+      const float4 r = *(const float4 *)(dres + (int64_t)row * d + c);
+      o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
+    }
+    *(float4 *)(dx + (int64_t)row * d + c) = o;
+  }
+}
+
+hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
+                                   const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s) {
+  hipLaunchKernelGGL(layernorm_bwd_dx_kernel, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma, dres, dx, M,
+                     d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------- column reductions
+// pass 1: block (64 columns x 4 row lanes) sums a chunk of CH rows; pass 2 adds
+// the chunk partials in ascending chunk order.
+constexpr int CH = 128;
+int colsum_chunks(int M) { return (M + CH - 1) / CH; }
+
+template <typename T, int MODE>  // MODE 0: plain column sum; 1: LayerNorm dgamma/dbeta
+__global__ __launch_bounds__(256) void colsum_pass1_kernel(const T *__restrict__ in, int64_t ld,
+                                                           const float *__restrict__ x, const float *__restrict__ mean,
+                                                           const float *__restrict__ rstd, float *__restrict__ part,
+                                                           int M, int N) {
+  __shared__ float sh[2][4][64];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + cx;
+  const int r0 = blockIdx.y * CH, r1 = min(M, r0 + CH);
+  float a = 0.f, b = 0.f;
+  if (col < N) {
+    for (int r = r0 + ry; r < r1; r += 4) {
+      const float v = ldv<T>(in, (int64_t)r * ld + col);
+      if (MODE == 1) {
+        a += v * ((x[(int64_t)r * ld + col] - mean[r]) * rstd[r]);
+        b += v;
+      } else {
+        a += v;
+      }
+    }
+  }
+  sh[0][ry][cx] = a;
+  sh[1][ry][cx] = b;
+  __syncthreads();
+  if (ry == 0 && col < N) {
+    const int nch = gridDim.y;
+    part[(int64_t)blockIdx.y * N + col] = (sh[0][0][cx] + sh[0][1][cx]) + (sh[0][2][cx] + sh[0][3][cx]);
+    if (MODE == 1)
+      part[(int64_t)(nch + blockIdx.y) * N + col] = (sh[1][0][cx] + sh[1][1][cx]) + (sh[1][2][cx] + sh[1][3][cx]);
+  }
+}
+
+__global__ void colsum_pass2_kernel(const float *__restrict__ part, float *__restrict__ out0, float *__restrict__ out1,
+                                    int nch, int N) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= N) return;
+  float a = 0.f;
+  for (int c = 0; c < nch; ++c) a += part[(int64_t)c * N + col];
+  out0[col] = a;
+  if (out1) {
+    float b = 0.f;
+    for (int c = 0; c < nch; ++c) b += part[(int64_t)(nch + c) * N + col];
+    out1[col] = b;
+  }
+}
+
+hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N,
+                         hipStream_t s) {
+  const int nch = colsum_chunks(M);
+  dim3 grid((N + 63) / 64, nch);
+  if (in_dtype == DT_BF16)
+    hipLaunchKernelGGL((colsum_pass1_kernel<bf16_t, 0>), grid, dim3(256), 0, s, (const bf16_t *)in, ld, nullptr,
+                       nullptr, nullptr, scratch, M, N);
+  else
+    hipLaunchKernelGGL((colsum_pass1_kernel<float, 0>), grid, dim3(256), 0, s, (const float *)in, ld, nullptr, nullptr,
+                       nullptr, scratch, M, N);
+  hipLaunchKernelGGL(colsum_pass2_kernel, dim3((N + 255) / 256), dim3(256), 0, s, scratch, out, nullptr, nch, N);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const float *mean, const float *rstd,
+                                       float *dgamma, float *dbeta, float *scratch, int M, int d, hipStream_t s) {
+  const int nch = colsum_chunks(M);
+  dim3 grid((d + 63) / 64, nch);
+  hipLaunchKernelGGL((colsum_pass1_kernel<float, 1>), grid, dim3(256), 0, s, dy, (int64_t)d, x, mean, rstd, scratch, M,
+                     d);
+  hipLaunchKernelGGL(colsum_pass2_kernel, dim3((d + 255) / 256), dim3(256), 0, s, scratch, dgamma, dbeta, nch, d);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ softmax
+// One wavefront per row i of one [T,T] score matrix; only j <= i is read.
+// Entries i < j < min(T, roundup(i+1, 256)) are written as exact zeros so that
+// tile-granular GEMMs over the lower triangle read zeros beyond the diagonal.
+__device__ __forceinline__ int causal_zero_end(int i, int T) { return min(T, ((i + 256) / 256) * 256); }
+
+template <typename OutT>
+__global__ __launch_bounds__(256) void softmax_causal_fwd_kernel(const float *__restrict__ S, OutT *__restrict__ P,
+                                                                 int64_t rows, int T) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const int i = (int)(row % T);
+  const float *sr = S + row * T;
+  OutT *pr = P + row * T;
+  float mx = -INFINITY;
+  for (int j = lane; j <= i; j += 64) mx = fmaxf(mx, sr[j]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int j = lane; j <= i; j += 64) sum += expf(sr[j] - mx);
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+  const int zend = causal_zero_end(i, T);
+  for (int j = lane; j < zend; j += 64) stv<OutT>(pr, j, j <= i ? expf(sr[j] - mx) * inv : 0.f);
+}
+
+template <typename ActT>
+__global__ __launch_bounds__(256) void softmax_causal_bwd_kernel(const ActT *__restrict__ P, const float *__restrict__ dP,
+                                                                 ActT *__restrict__ dS, int64_t rows, int T) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const int i = (int)(row % T);
+  const ActT *pr = P + row * T;
+  const float *dpr = dP + row * T;
+  float dot = 0.f;
+  for (int j = lane; j <= i; j += 64) dot += ldv<ActT>(pr, j) * dpr[j];
+  dot = wave_sum(dot);
+  const int zend = causal_zero_end(i, T);
+  for (int j = lane; j < zend; j += 64) stv<ActT>(dS + row * T, j, j <= i ? ldv<ActT>(pr, j) * (dpr[j] - dot) : 0.f);
+}
+
+hipError_t launch_softmax_causal_fwd(int dtype, const float *S, void *P, int n_mat, int T, hipStream_t s) {
+  const int64_t rows = (int64_t)n_mat * T;
+  dim3 grid((unsigned)((rows + 3) / 4));
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(softmax_causal_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, S, (bf16_t *)P, rows, T);
+  else
+    hipLaunchKernelGGL(softmax_causal_fwd_kernel<float>, grid, dim3(256), 0, s, S, (float *)P, rows, T);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_causal_bwd(int dtype, const void *P, const float *dP, void *dS, int n_mat, int T,
+                                     hipStream_t s) {
+  const int64_t rows = (int64_t)n_mat * T;
+  dim3 grid((unsigned)((rows + 3) / 4));
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(softmax_causal_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)P, dP, (bf16_t *)dS,
+                       rows, T);
+  else
+    hipLaunchKernelGGL(softmax_causal_bwd_kernel<float>, grid, dim3(256), 0, s, (const float *)P, dP, (float *)dS, rows,
+                       T);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------ cross-entropy
+// One block per row: running (max, sum) per thread in one pass, combined over
+// the block, then dlogits = (softmax - onehot) * inv_n in a second pass.  Rows
+// whose target is negative contribute no loss and a zero gradient.  Columns
+// V..ld-1 of dlogits are written as zeros.
+template <typename OutT>
+__global__ __launch_bounds__(256) void cross_entropy_kernel(const float *__restrict__ logits,
+                                                            const int32_t *__restrict__ targets,
+                                                            float *__restrict__ row_loss, OutT *__restrict__ dlogits,
+                                                            int V, int64_t ld, float inv_n) {
+  __shared__ float shm[4], shs[4];
+  const int row = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float *lr = logits + (int64_t)row * ld;
+  OutT *dr = dlogits + (int64_t)row * ld;
+  const int tgt = targets[row];
+  if (tgt < 0) {
+    for (int c = tid; c < ld; c += 256) stv<OutT>(dr, c, 0.f);
+    if (tid == 0) row_loss[row] = 0.f;
+    return;
+  }
+  float mx = -INFINITY, sum = 0.f;
+  for (int c = tid; c < V; c += 256) {
+    const float v = lr[c];
+    if (v > mx) { sum = sum * expf(mx - v) + 1.f; mx = v; } else { sum += expf(v - mx); }
+  }
+  const float wmx = wave_max(mx);
+  sum = wave_sum(mx == -INFINITY ? 0.f : sum * expf(mx - wmx));
+  if (lane == 0) { shm[wave] = wmx; shs[wave] = sum; }
+  __syncthreads();
+  const float bmx = fmaxf(fmaxf(shm[0], shm[1]), fmaxf(shm[2], shm[3]));
+  float bsum = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (shm[w] != -INFINITY) bsum += shs[w] * expf(shm[w] - bmx);
+  const float inv = 1.0f / bsum;
+  if (tid == 0) row_loss[row] = (logf(bsum) + bmx) - lr[tgt];
+  for (int c = tid; c < ld; c += 256) {
+    float g = 0.f;
+    if (c < V) g = (expf(lr[c] - bmx) * inv - (c == tgt ? 1.f : 0.f)) * inv_n;
+    stv<OutT>(dr, c, g);
+  }
+}
+
+hipError_t launch_cross_entropy(int dtype, const float *logits, const int32_t *targets, float *row_loss, void *dlogits,
+                                int M, int V, int64_t ld, float inv_n, hipStream_t s) {
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(cross_entropy_kernel<bf16_t>, dim3(M), dim3(256), 0, s, logits, targets, row_loss,
+                       (bf16_t *)dlogits, V, ld, inv_n);
+  else
+    hipLaunchKernelGGL(cross_entropy_kernel<float>, dim3(M), dim3(256), 0, s, logits, targets, row_loss,
+                       (float *)dlogits, V, ld, inv_n);
+  return hipGetLastError();
+}
+
+// single block; thread t sums rows t, t+256, ... in double, then a fixed tree
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float *__restrict__ row_loss, float *__restrict__ loss,
+                                                          int M, float inv_n) {
+  __shared__ double sh[256];
+  double a = 0.0;
+  for (int i = threadIdx.x; i < M; i += 256) a += (double)row_loss[i];
+  sh[threadIdx.x] = a;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) loss[0] = (float)(sh[0] * (double)inv_n);
+}
+
+hipError_t launch_loss_reduce(const float *row_loss, float *loss, int M, float inv_n, hipStream_t s) {
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, s, row_loss, loss, M, inv_n);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ Adam
+// m <- b1 m + (1-b1) g ; v <- b2 v + (1-b2) g^2 ; w <- w - lr (m/c1) / (sqrt(v/c2) + eps)
+// 16 B read and 12 B (+2 B bf16 copy) written per parameter.
+__global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float *__restrict__ m, float *__restrict__ v,
+                                                   const float *__restrict__ g, bf16_t *__restrict__ shadow, int64_t n,
+                                                   float lr, float b1, float b2, float eps, float c1, float c2) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  const float ob1 = 1.f - b1, ob2 = 1.f - b2;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 4 <= n) {
+      float4 W = *(float4 *)(w + i), Mm = *(float4 *)(m + i), Vv = *(float4 *)(v + i);
+      const float4 G = *(const float4 *)(g + i);
+      float *pw = (float *)&W, *pm = (float *)&Mm, *pv = (float *)&Vv;
+      const float *pg = (const float *)&G;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        pm[k] = b1 * pm[k] + ob1 * pg[k];
+        pv[k] = b2 * pv[k] + ob2 * (pg[k] * pg[k]);
+        pw[k] = pw[k] - lr * (pm[k] / c1) / (sqrtf(pv[k] / c2) + eps);
+      }
+      *(float4 *)(w + i) = W;
+      *(float4 *)(m + i) = Mm;
+      *(float4 *)(v + i) = Vv;
+      if (shadow) {
+        uint2 o;
+        o.x = (uint32_t)f2bf(pw[0]) | ((uint32_t)f2bf(pw[1]) << 16);
+        o.y = (uint32_t)f2bf(pw[2]) | ((uint32_t)f2bf(pw[3]) << 16);
+        *(uint2 *)(shadow + i) = o;
+      }
+    } else {
+      for (int64_t j = i; j < n; ++j) {
+        const float gg = g[j];
+        const float mm = b1 * m[j] + ob1 * gg;
+        const float vv = b2 * v[j] + ob2 * (gg * gg);
+        const float ww = w[j] - lr * (mm / c1) / (sqrtf(vv / c2) + eps);
+        m[j] = mm; v[j] = vv; w[j] = ww;
+        if (shadow) shadow[j] = f2bf(ww);
+      }
+    }
+  }
+}
+
+hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *shadow, int64_t n, float lr, float beta1,
+                       float beta2, float eps, float corr1, float corr2, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n / 4 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(adam_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, m, v, g, shadow, n, lr, beta1, beta2, eps,
+                     corr1, corr2);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ casts
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out,
+                                                        int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 4 <= n) {
+      const float4 a = *(const float4 *)(in + i);
+      uint2 o;
+      o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+      o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+      *(uint2 *)(out + i) = o;
+    } else {
+      for (int64_t j = i; j < n; ++j) out[j] = f2bf(in[j]);
+    }
+  }
+}
+
+hipError_t launch_cast_bf16(const float *in, bf16_t *out, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n / 4 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in, out, n);
+  return hipGetLastError();
+}
+
+// 64x64 tile through LDS: coalesced reads along C, coalesced writes along R
+__global__ __launch_bounds__(256) void cast_transpose_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out,
+                                                                  int R, int C) {
+  __shared__ float t[64][65];
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4)
+    t[r][tx] = (r0 + r < R && c0 + tx < C) ? in[(int64_t)(r0 + r) * C + c0 + tx] : 0.f;
+  __syncthreads();
+  for (int c = ty; c < 64; c += 4)
+    if (c0 + c < C && r0 + tx < R) out[(int64_t)(c0 + c) * R + r0 + tx] = f2bf(t[tx][c]);
+}
+
+hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C, hipStream_t s) {
+  hipLaunchKernelGGL(cast_transpose_bf16_kernel, dim3((C + 63) / 64, (R + 63) / 64), dim3(256), 0, s, in, out, R, C);
+  return hipGetLastError();
+}
+
+template <typename OutT>
+__global__ void cast_act_kernel(const float *__restrict__ in, int64_t ld_in, OutT *__restrict__ out, int64_t ld_out, int R,
+                                int C) {
+  const int r = blockIdx.y;
+  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < C; c += gridDim.x * blockDim.x)
+    stv<OutT>(out, (int64_t)r * ld_out + c, in[(int64_t)r * ld_in + c]);
+}
+
+hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C,
+                           hipStream_t s) {
+  dim3 grid(min(64, (C + 255) / 256), R);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(cast_act_kernel<bf16_t>, grid, dim3(256), 0, s, in, ld_in, (bf16_t *)out, ld_out, R, C);
+  else
+    hipLaunchKernelGGL(cast_act_kernel<float>, grid, dim3(256), 0, s, in, ld_in, (float *)out, ld_out, R, C);
+  return hipGetLastError();
+}
+
+}  // namespace hydra

@@ -1,0 +1,433 @@
+// Shard executor: the kernel sequence of a forward visit, a backward visit
+// (recompute from the boundary checkpoint, then back-propagate; paper Section
+// 2.3) and the Adam step of one shard, all enqueued on the compute stream.
+#include <algorithm>
+#include <cmath>
+
+#include "hydra_internal.h"
+
+namespace hydra {
+
+static inline uint64_t up256(uint64_t x) { return (x + 255) / 256 * 256; }
+
+namespace {
+
+// Bump allocator over the shared workspace; one task at a time uses it.
+struct Bump {
+  char *base;
+  uint64_t cap, used = 0;
+  bool ok = true;
+  template <typename T> T *take(uint64_t count, uint64_t elem = sizeof(T)) {
+    const uint64_t bytes = up256(count * elem);
+    if (used + bytes > cap) {
+      ok = false;
+      return nullptr;
+    }
+    T *p = (T *)(base + used);
+    used += bytes;
+    return p;
+  }
+};
+
+struct LayerActs {  // what the backward visit keeps of one block's forward
+  float *x1, *mean1, *rstd1, *mean2, *rstd2;
+  void *a, *qkv, *P, *o, *c, *u, *g;
+};
+
+struct BlockW {  // pointers into a shard buffer for one block
+  const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc, *b_proj;
+  const void *w_qkv, *w_o, *w_fc, *w_proj;  // operand dtype (bf16 working copy, or the fp32 master itself)
+  float *G;                                  // gradient base of the block
+};
+
+uint64_t layer_act_bytes(const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  const uint64_t P = (uint64_t)s.B * s.H * s.T * s.T * e;
+  return up256(M * d * 4) + 4 * up256(M * 4) + 3 * up256(M * d * e) + up256(M * 3 * d * e) + up256(P) +
+         2 * up256(M * F * e);
+}
+
+LayerActs take_layer(Bump &b, const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  LayerActs A;
+  A.x1 = b.take<float>(M * d);
+  A.mean1 = b.take<float>(M); A.rstd1 = b.take<float>(M);
+  A.mean2 = b.take<float>(M); A.rstd2 = b.take<float>(M);
+  A.a = b.take<char>(M * d * e);
+  A.qkv = b.take<char>(M * 3 * d * e);
+  A.P = b.take<char>((uint64_t)s.B * s.H * s.T * s.T * e);
+  A.o = b.take<char>(M * d * e);
+  A.c = b.take<char>(M * d * e);
+  A.u = b.take<char>(M * F * e);
+  A.g = b.take<char>(M * F * e);
+  return A;
+}
+
+BlockW block_ptrs(const ModelShape &s, const Slot *sl, int dt, int j) {
+  const BlockOffsets &o = s.bo;
+  const int64_t base = (int64_t)j * o.size;
+  const float *w = sl->w + base;
+  BlockW B;
+  B.ln1_g = w + o.ln1_g; B.ln1_b = w + o.ln1_b; B.b_qkv = w + o.b_qkv; B.b_o = w + o.b_o;
+  B.ln2_g = w + o.ln2_g; B.ln2_b = w + o.ln2_b; B.b_fc = w + o.b_fc; B.b_proj = w + o.b_proj;
+  if (dt == DT_BF16) {
+    const bf16_t *h = sl->wb + base;
+    B.w_qkv = h + o.w_qkv; B.w_o = h + o.w_o; B.w_fc = h + o.w_fc; B.w_proj = h + o.w_proj;
+  } else {
+    B.w_qkv = w + o.w_qkv; B.w_o = w + o.w_o; B.w_fc = w + o.w_fc; B.w_proj = w + o.w_proj;
+  }
+  B.G = sl->g + base;
+  return B;
+}
+
+inline const void *off_act(const void *p, int64_t elems, int dt) { return (const char *)p + elems * (int64_t)dt_size(dt); }
+inline void *off_act(void *p, int64_t elems, int dt) { return (char *)p + elems * (int64_t)dt_size(dt); }
+
+// y = x*W + b : X [M,K] operand dtype, W [K,N]
+hipError_t linear(int dt, int M, int N, int K, const void *X, const void *W, const float *bias, const float *resid,
+                  float *out_f32, void *out_act, int epi, void *out_act2, hipStream_t st) {
+  GemmDesc g;
+  g.dtype = dt; g.ta = 0; g.tb = 1; g.M = M; g.N = N; g.K = K;
+  g.A = X; g.lda = K; g.B = W; g.ldb = N; g.ldc = N;
+  g.bias = bias; g.resid = resid; g.out_f32 = out_f32; g.out_act = out_act; g.epi = epi; g.out_act2 = out_act2;
+  return launch_gemm(g, st);
+}
+// dx = dy*W^T : dY [M,N], W [K,N] -> [M,K]
+hipError_t linear_dx(int dt, int M, int N, int K, const void *dY, const void *W, float *out_f32, void *out_act, int epi,
+                     const void *aux, hipStream_t st) {
+  GemmDesc g;
+  g.dtype = dt; g.ta = 0; g.tb = 0; g.M = M; g.N = K; g.K = N;
+  g.A = dY; g.lda = N; g.B = W; g.ldb = N; g.ldc = K;
+  g.out_f32 = out_f32; g.out_act = out_act; g.epi = epi; g.aux = aux;
+  return launch_gemm(g, st);
+}
+// dW = x^T*dy : X [M,K] (ldx), dY [M,N] (ldy) -> fp32 [K,N]
+hipError_t linear_dw(int dt, int M, int N, int K, const void *X, int64_t ldx, const void *dY, int64_t ldy, float *dW,
+                     hipStream_t st) {
+  GemmDesc g;
+  g.dtype = dt; g.ta = 1; g.tb = 1; g.M = K; g.N = N; g.K = M;
+  g.A = X; g.lda = ldx; g.B = dY; g.ldb = ldy; g.ldc = N;
+  g.out_f32 = dW;
+  return launch_gemm(g, st);
+}
+
+#define CK(call)                                \
+  do {                                          \
+    hipError_t e__ = (call);                    \
+    if (e__ != hipSuccess) return e__;          \
+  } while (0)
+
+// batched attention GEMM over (sample, head)
+GemmDesc attn_desc(const ModelShape &s, int dt) {
+  GemmDesc g;
+  g.dtype = dt;
+  g.nb1 = s.B; g.nb2 = s.H;
+  return g;
+}
+
+hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, float *x_out,
+                         const LayerActs &A, float *Sbuf, hipStream_t st) {
+  const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
+  const int64_t TT = (int64_t)T * T;
+  CK(launch_layernorm_fwd(dt, x_in, W.ln1_g, W.ln1_b, A.a, A.mean1, A.rstd1, M, d, st));
+  CK(linear(dt, M, 3 * d, d, A.a, W.w_qkv, W.b_qkv, nullptr, nullptr, A.qkv, EPI_NONE, nullptr, st));
+  {  // scores = q k^T / sqrt(dh), lower triangle
+    GemmDesc g = attn_desc(s, dt);
+    g.ta = 0; g.tb = 0; g.M = T; g.N = T; g.K = dh; g.alpha = 1.0f / sqrtf((float)dh);
+    g.A = A.qkv; g.lda = 3 * d; g.sA1 = (int64_t)T * 3 * d; g.sA2 = dh;
+    g.B = off_act(A.qkv, d, dt); g.ldb = 3 * d; g.sB1 = (int64_t)T * 3 * d; g.sB2 = dh;
+    g.out_f32 = Sbuf; g.ldc = T; g.sC1 = s.H * TT; g.sC2 = TT;
+    g.causal = CAUSAL_SKIP_UPPER;
+    CK(launch_gemm(g, st));
+  }
+  CK(launch_softmax_causal_fwd(dt, Sbuf, A.P, s.B * s.H, T, st));
+  {  // o = p v, heads merged
+    GemmDesc g = attn_desc(s, dt);
+    g.ta = 0; g.tb = 1; g.M = T; g.N = dh; g.K = T;
+    g.A = A.P; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
+    g.B = off_act(A.qkv, 2 * d, dt); g.ldb = 3 * d; g.sB1 = (int64_t)T * 3 * d; g.sB2 = dh;
+    g.out_act = A.o; g.ldc = d; g.sC1 = (int64_t)T * d; g.sC2 = dh;
+    g.causal = CAUSAL_K_END;
+    CK(launch_gemm(g, st));
+  }
+  CK(linear(dt, M, d, d, A.o, W.w_o, W.b_o, x_in, A.x1, nullptr, EPI_NONE, nullptr, st));
+  CK(launch_layernorm_fwd(dt, A.x1, W.ln2_g, W.ln2_b, A.c, A.mean2, A.rstd2, M, d, st));
+  CK(linear(dt, M, F, d, A.c, W.w_fc, W.b_fc, nullptr, nullptr, A.u, EPI_GELU, A.g, st));
+  CK(linear(dt, M, d, F, A.g, W.w_proj, W.b_proj, A.x1, x_out, nullptr, EPI_NONE, nullptr, st));
+  return hipSuccess;
+}
+
+struct BwdScratch {
+  float *dP;    // [B,H,T,T] fp32 (also the score buffer of the recomputation)
+  void *dS;     // [B,H,T,T] operand dtype
+  void *dact;   // [M,d] operand-dtype copy of a residual-stream gradient
+  void *du;     // [M,F]
+  void *d_o;    // [M,d]
+  void *dqkv;   // [M,3d]
+  float *dtmp;  // [M,d] fp32 (dc, then da)
+  float *dx1;   // [M,d] fp32
+  float *red;   // column-reduction partials
+};
+
+// fp32 -> operand dtype view of an [M,d] gradient (no copy in the fp32 path)
+hipError_t act_view(int dt, const float *src, void *scratch, int M, int d, const void **out, hipStream_t st) {
+  if (dt == DT_F32) {
+    *out = src;
+    return hipSuccess;
+  }
+  *out = scratch;
+  return launch_cast_act(dt, src, d, scratch, d, M, d, st);
+}
+
+hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, const LayerActs &A,
+                          const float *dx2, float *dx_out, const BwdScratch &Z, hipStream_t st) {
+  const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
+  const int64_t TT = (int64_t)T * T;
+  const BlockOffsets &o = s.bo;
+  const float scale = 1.0f / sqrtf((float)dh);
+  const void *dx2a;
+  CK(act_view(dt, dx2, Z.dact, M, d, &dx2a, st));
+  // MLP down projection
+  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, st));
+  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, st));
+  CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, Z.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
+  // MLP up projection
+  CK(launch_colsum(dt, Z.du, F, W.G + o.b_fc, Z.red, M, F, st));
+  CK(linear_dw(dt, M, F, d, A.c, d, Z.du, F, W.G + o.w_fc, st));
+  CK(linear_dx(dt, M, F, d, Z.du, W.w_fc, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // dc
+  CK(launch_layernorm_bwd_params(Z.dtmp, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, st));
+  CK(launch_layernorm_bwd_dx(Z.dtmp, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, Z.dx1, M, d, st));
+  // attention output projection
+  const void *dx1a;
+  CK(act_view(dt, Z.dx1, Z.dact, M, d, &dx1a, st));
+  CK(launch_colsum(DT_F32, Z.dx1, d, W.G + o.b_o, Z.red, M, d, st));
+  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, st));
+  CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
+  // attention core
+  const void *q = A.qkv, *k = off_act((const void *)A.qkv, d, dt), *v = off_act((const void *)A.qkv, 2 * d, dt);
+  const int64_t sQ1 = (int64_t)T * 3 * d;
+  {  // dP = dO V^T
+    GemmDesc g = attn_desc(s, dt);
+    g.ta = 0; g.tb = 0; g.M = T; g.N = T; g.K = dh;
+    g.A = Z.d_o; g.lda = d; g.sA1 = (int64_t)T * d; g.sA2 = dh;
+    g.B = v; g.ldb = 3 * d; g.sB1 = sQ1; g.sB2 = dh;
+    g.out_f32 = Z.dP; g.ldc = T; g.sC1 = s.H * TT; g.sC2 = TT;
+    g.causal = CAUSAL_SKIP_UPPER;
+    CK(launch_gemm(g, st));
+  }
+  {  // dV = P^T dO
+    GemmDesc g = attn_desc(s, dt);
+    g.ta = 1; g.tb = 1; g.M = T; g.N = dh; g.K = T;
+    g.A = A.P; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
+    g.B = Z.d_o; g.ldb = d; g.sB1 = (int64_t)T * d; g.sB2 = dh;
+    g.out_act = off_act(Z.dqkv, 2 * d, dt); g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
+    g.causal = CAUSAL_K_BEGIN;
+    CK(launch_gemm(g, st));
+  }
+  CK(launch_softmax_causal_bwd(dt, A.P, Z.dP, Z.dS, s.B * s.H, T, st));
+  {  // dQ = dS K / sqrt(dh)
+    GemmDesc g = attn_desc(s, dt);
+    g.ta = 0; g.tb = 1; g.M = T; g.N = dh; g.K = T; g.alpha = scale;
+    g.A = Z.dS; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
+    g.B = k; g.ldb = 3 * d; g.sB1 = sQ1; g.sB2 = dh;
+    g.out_act = Z.dqkv; g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
+    g.causal = CAUSAL_K_END;
+    CK(launch_gemm(g, st));
+  }
+  {  // dK = dS^T Q / sqrt(dh)
+    GemmDesc g = attn_desc(s, dt);
+    g.ta = 1; g.tb = 1; g.M = T; g.N = dh; g.K = T; g.alpha = scale;
+    g.A = Z.dS; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
+    g.B = q; g.ldb = 3 * d; g.sB1 = sQ1; g.sB2 = dh;
+    g.out_act = off_act(Z.dqkv, d, dt); g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
+    g.causal = CAUSAL_K_BEGIN;
+    CK(launch_gemm(g, st));
+  }
+  // QKV projection
+  CK(launch_colsum(dt, Z.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, st));
+  CK(linear_dw(dt, M, 3 * d, d, A.a, d, Z.dqkv, 3 * d, W.G + o.w_qkv, st));
+  CK(linear_dx(dt, M, 3 * d, d, Z.dqkv, W.w_qkv, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // da
+  CK(launch_layernorm_bwd_params(Z.dtmp, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, st));
+  CK(launch_layernorm_bwd_dx(Z.dtmp, x_in, A.mean1, A.rstd1, W.ln1_g, Z.dx1, dx_out, M, d, st));
+  return hipSuccess;
+}
+
+uint64_t red_elems(const ModelShape &s) {
+  const uint64_t widest = (uint64_t)(3 * s.d > s.F ? 3 * s.d : s.F);
+  return 2 * (uint64_t)colsum_chunks((int)s.M) * widest;
+}
+
+uint64_t bwd_scratch_bytes(const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  const uint64_t PP = (uint64_t)s.B * s.H * s.T * s.T;
+  return up256(PP * 4) + up256(PP * e) + up256(M * d * e) + up256(M * F * e) + up256(M * d * e) + up256(M * 3 * d * e) +
+         2 * up256(M * d * 4) + up256(red_elems(s) * 4);
+}
+
+BwdScratch take_bwd(Bump &b, const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  const uint64_t PP = (uint64_t)s.B * s.H * s.T * s.T;
+  BwdScratch Z;
+  Z.dP = b.take<float>(PP);
+  Z.dS = b.take<char>(PP * e);
+  Z.dact = b.take<char>(M * d * e);
+  Z.du = b.take<char>(M * F * e);
+  Z.d_o = b.take<char>(M * d * e);
+  Z.dqkv = b.take<char>(M * 3 * d * e);
+  Z.dtmp = b.take<float>(M * d);
+  Z.dx1 = b.take<float>(M * d);
+  Z.red = b.take<float>(red_elems(s));
+  return Z;
+}
+
+uint64_t head_bytes(const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d;
+  return up256(M * s.Vpad * 4) + up256(M * d * e) + 2 * up256(M * 4) + up256(M * d * 4) + up256(red_elems(s) * 4);
+}
+
+}  // namespace
+
+uint64_t workspace_need(const ModelShape &s, int dtype) {
+  const uint64_t act = up256((uint64_t)s.M * s.d * 4);
+  // backward visit: k kept layers + k-1 inter-layer activations + backward scratch + ping-pong gradients
+  const uint64_t bwd = (uint64_t)s.k * layer_act_bytes(s, dtype) + (uint64_t)s.k * act + bwd_scratch_bytes(s, dtype) + 2 * act;
+  const uint64_t head = head_bytes(s, dtype);
+  return (bwd > head ? bwd : head) + 4096;
+}
+
+// make the operand-dtype copy of a shard's matrices current
+static hipError_t ensure_working_copy(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
+  if (mm->dtype != DT_BF16 || sl->wb_valid) return hipSuccess;
+  const ModelShape &s = mm->sh;
+  hipStream_t st = ctx->s_compute;
+  if (shard >= 1 && shard <= s.S) {
+    CK(launch_cast_bf16(sl->w, sl->wb, s.shard_off[shard + 1] - s.shard_off[shard], st));
+  } else if (shard == s.S + 1) {
+    // LM head kept transposed [V,d] so that the odd vocabulary size never is a leading dimension
+    CK(launch_cast_transpose_bf16(sl->w + 2 * s.d, sl->wb + 2 * s.d, s.d, s.V, st));
+  }
+  sl->wb_valid = true;
+  return hipSuccess;
+}
+
+hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
+  const ModelShape &s = mm->sh;
+  const int dt = mm->dtype;
+  hipStream_t st = ctx->s_compute;
+  const int M = (int)s.M, d = s.d;
+  HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
+  Bump b{ctx->ws, ctx->ws_bytes};
+  if (shard == 0) {
+    HYDRA_HIP(ctx, launch_embed_fwd(mm->tok, sl->w, sl->w + (int64_t)s.V * d, mm->ckpt[0], M, s.T, d, st));
+    return HYDRA_OK;
+  }
+  if (shard <= s.S) {
+    ctx->logits_owner = -1;  // the shared workspace is about to be overwritten
+    LayerActs A = take_layer(b, s, dt);
+    float *Sbuf = b.take<float>((uint64_t)s.B * s.H * s.T * s.T);
+    float *pp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
+    if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (forward)");
+    const float *x = mm->ckpt[shard - 1];
+    for (int j = 0; j < s.k; ++j) {
+      float *y = (j == s.k - 1) ? mm->ckpt[shard] : pp[j & 1];
+      HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), x, y, A, Sbuf, st));
+      x = y;
+    }
+    return HYDRA_OK;
+  }
+  // HEAD: final LayerNorm, logits, loss and d(loss)/d(logits)
+  float *logits = b.take<float>((uint64_t)M * s.Vpad);
+  void *z = b.take<char>((uint64_t)M * d * dt_size(dt));
+  float *mean = b.take<float>(M), *rstd = b.take<float>(M);
+  if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (head)");
+  HYDRA_HIP(ctx, launch_layernorm_fwd(dt, mm->ckpt[s.S], sl->w, sl->w + d, z, mean, rstd, M, d, st));
+  GemmDesc g;
+  g.dtype = dt; g.M = M; g.N = s.V; g.K = d; g.A = z; g.lda = d; g.ta = 0;
+  if (dt == DT_BF16) { g.tb = 0; g.B = sl->wb + 2 * d; g.ldb = d; }
+  else { g.tb = 1; g.B = sl->w + 2 * d; g.ldb = s.V; }
+  g.out_f32 = logits; g.ldc = s.Vpad;
+  HYDRA_HIP(ctx, launch_gemm(g, st));
+  const float inv_n = 1.0f / (float)mm->n_valid;
+  HYDRA_HIP(ctx, launch_cross_entropy(dt, logits, mm->tgt, mm->row_loss, mm->dlogits, M, s.V, s.Vpad, inv_n, st));
+  HYDRA_HIP(ctx, launch_loss_reduce(mm->row_loss, mm->loss, M, inv_n, st));
+  ctx->logits = logits;
+  ctx->logits_owner = (int)(std::find(ctx->models.begin(), ctx->models.end(), mm) - ctx->models.begin());
+  for (Model *o : ctx->models)
+    if (o != mm) o->logits_valid = false;
+  return HYDRA_OK;
+}
+
+hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
+  const ModelShape &s = mm->sh;
+  const int dt = mm->dtype;
+  hipStream_t st = ctx->s_compute;
+  const int M = (int)s.M, d = s.d;
+  HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
+  Bump b{ctx->ws, ctx->ws_bytes};
+  if (shard == s.S + 1) {
+    // the logits of the forward visit were turned into dlogits there; only the
+    // normalised input z is recomputed
+    if (ctx->logits_owner >= 0 && ctx->models[ctx->logits_owner] == mm)
+      b.take<float>((uint64_t)M * s.Vpad);  // leave this model's logits readable
+    else
+      ctx->logits_owner = -1;
+    void *z = b.take<char>((uint64_t)M * d * dt_size(dt));
+    float *mean = b.take<float>(M), *rstd = b.take<float>(M);
+    float *dz = b.take<float>((uint64_t)M * d);
+    float *red = b.take<float>(red_elems(s));
+    if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (head backward)");
+    const float *x = mm->ckpt[s.S];
+    HYDRA_HIP(ctx, launch_layernorm_fwd(dt, x, sl->w, sl->w + d, z, mean, rstd, M, d, st));
+    HYDRA_HIP(ctx, linear_dw(dt, M, s.V, d, z, d, mm->dlogits, s.Vpad, sl->g + 2 * d, st));
+    GemmDesc g;
+    g.dtype = dt; g.M = M; g.N = d; g.K = s.V; g.A = mm->dlogits; g.lda = s.Vpad; g.ta = 0;
+    if (dt == DT_BF16) { g.tb = 1; g.B = sl->wb + 2 * d; g.ldb = d; }
+    else { g.tb = 0; g.B = sl->w + 2 * d; g.ldb = s.V; }
+    g.out_f32 = dz; g.ldc = d;
+    HYDRA_HIP(ctx, launch_gemm(g, st));
+    HYDRA_HIP(ctx, launch_layernorm_bwd_params(dz, x, mean, rstd, sl->g, sl->g + d, red, M, d, st));
+    mm->dcur = 0;
+    HYDRA_HIP(ctx, launch_layernorm_bwd_dx(dz, x, mean, rstd, sl->w, nullptr, mm->dbound[0], M, d, st));
+    return HYDRA_OK;
+  }
+  if (shard >= 1) {
+    ctx->logits_owner = -1;  // the shared workspace is about to be overwritten
+    std::vector<LayerActs> acts(s.k);
+    std::vector<float *> xs(s.k + 1);
+    for (int j = 0; j < s.k; ++j) acts[j] = take_layer(b, s, dt);
+    for (int j = 1; j <= s.k; ++j) xs[j] = b.take<float>((uint64_t)M * d);
+    BwdScratch Z = take_bwd(b, s, dt);
+    float *gpp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
+    if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (backward)");
+    xs[0] = mm->ckpt[shard - 1];
+    for (int j = 0; j < s.k; ++j)
+      HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), xs[j], xs[j + 1], acts[j], Z.dP, st));
+    const float *dx = mm->dbound[mm->dcur];
+    for (int j = s.k - 1; j >= 0; --j) {
+      float *out = (j == 0) ? mm->dbound[mm->dcur ^ 1] : gpp[j & 1];
+      HYDRA_HIP(ctx, block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, out, Z, st));
+      dx = out;
+    }
+    mm->dcur ^= 1;
+    return HYDRA_OK;
+  }
+  // EMBED
+  HYDRA_HIP(ctx, launch_embed_bwd(mm->tok, mm->dbound[mm->dcur], sl->g, sl->g + (int64_t)s.V * d, s.B, s.T, d, s.V, st));
+  return HYDRA_OK;
+}
+
+hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
+  const ModelShape &s = mm->sh;
+  const hydra_model_desc &h = mm->desc;
+  const int64_t n = s.shard_off[shard + 1] - s.shard_off[shard];
+  const double c1 = 1.0 - std::pow((double)h.beta1, (double)mm->t);
+  const double c2 = 1.0 - std::pow((double)h.beta2, (double)mm->t);
+  // block shards keep their bf16 working copy current for the next visit
+  bf16_t *shadow = (mm->dtype == DT_BF16 && shard >= 1 && shard <= s.S) ? sl->wb : nullptr;
+  HYDRA_HIP(ctx, launch_adam(sl->w, sl->m, sl->v, sl->g, shadow, n, h.lr, h.beta1, h.beta2, h.eps, (float)c1, (float)c2,
+                             ctx->s_compute));
+  sl->wb_valid = shadow != nullptr;
+  return HYDRA_OK;
+}
+
+}  // namespace hydra

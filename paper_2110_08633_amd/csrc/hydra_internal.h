@@ -1,0 +1,122 @@
+// Internal host-side structures of the library (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/hydra.h"
+#include "kernels.h"
+
+namespace hydra {
+
+struct TensorInfo {
+  std::string name;
+  int64_t off, rows, cols;
+  int shard;
+};
+
+// Offsets (in elements, relative to the start of a block) of a block's tensors.
+struct BlockOffsets {
+  int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_fc, b_fc, w_proj, b_proj, size;
+};
+
+struct ModelShape {
+  int L, d, H, F, V, T, B, k, S, dh;
+  int64_t M;     // tokens per minibatch
+  int64_t Vpad;  // leading dimension of logits / dlogits
+  BlockOffsets bo;
+  int64_t n_params;
+  std::vector<int64_t> shard_off;  // S+3 entries
+  int64_t max_shard;               // largest shard, elements
+};
+
+hydra_status build_shape(const hydra_model_desc *d, ModelShape *out, std::string *err);
+void list_tensors(const ModelShape &s, std::vector<TensorInfo> *out);
+
+struct Slot {
+  char *base = nullptr;
+  float *w = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
+  bf16_t *wb = nullptr;
+  int model = -1, shard = -1;
+  bool has_params = false, has_opt = false, wb_valid = false, grads_valid = false, dirty = false;
+  bool need_wait_load = false;  // a copy into this slot was enqueued since the compute stream last waited
+  hipEvent_t ev_loaded = nullptr, ev_compute = nullptr, ev_spilled = nullptr;
+  bool compute_pending = false, spill_pending = false;
+};
+
+struct Model {
+  hydra_model_desc desc;
+  hydra_host_state host;
+  ModelShape sh;
+  int dtype;
+  // device state carved from the arena
+  int32_t *tok = nullptr, *tgt = nullptr;
+  std::vector<float *> ckpt;  // boundary b -> buffer (ping-pong pair when checkpoints are spilled)
+  float *dbound[2] = {nullptr, nullptr};
+  int dcur = 0;
+  void *dlogits = nullptr;
+  float *row_loss = nullptr, *loss = nullptr;
+  // pinned staging for tokens / targets (two minibatches deep)
+  int32_t *stage = nullptr;
+  int stage_idx = 0;
+  hipEvent_t ev_stage[2] = {nullptr, nullptr};
+  bool stage_used[2] = {false, false};
+  hipEvent_t ev_ckpt_d2h[2] = {nullptr, nullptr};
+  bool ckpt_d2h_pending[2] = {false, false};
+  hipEvent_t ev_ckpt_h2d[2] = {nullptr, nullptr};
+  bool ckpt_h2d_pending[2] = {false, false};
+  int ckpt_in_buf[2] = {-1, -1};  // spilled checkpoints: boundary index held by each ping-pong buffer
+  hipEvent_t ev_last_compute = nullptr;
+  bool compute_pending = false;
+  int64_t t = 0;        // minibatches handed over = Adam step of the current minibatch
+  int64_t n_valid = 0;  // targets >= 0 in the current minibatch
+  int next_fwd = 0;     // next forward visit expected
+  int next_bwd = -1;    // next backward visit expected (-1: none)
+  bool logits_valid = false;
+  std::vector<int> slot_of;  // shard -> slot index or -1
+};
+
+}  // namespace hydra
+
+struct hydra_ctx {
+  hydra_init_desc init;
+  bool dry = false;
+  bool planned = false;
+  hipStream_t s_compute = nullptr, s_h2d = nullptr, s_d2h = nullptr;
+  char *arena = nullptr;
+  uint64_t arena_bytes = 0, arena_used = 0;
+  std::vector<hydra::Model *> models;
+  std::vector<hydra::Slot> slots;
+  uint64_t slot_bytes = 0, slot_elems = 0;
+  char *ws = nullptr;  // workspace shared by all tasks (one task runs at a time on the compute stream)
+  uint64_t ws_bytes = 0, ws_used = 0;
+  int logits_owner = -1;
+  float *logits = nullptr;  // inside the workspace; valid for logits_owner until the next HEAD forward
+  hydra_stats stats;
+  std::string err;
+};
+
+namespace hydra {
+
+hydra_status fail(hydra_ctx *ctx, hydra_status code, const std::string &msg);
+hydra_status hipfail(hydra_ctx *ctx, hipError_t e, const char *what);
+void set_global_error(const std::string &msg);
+const char *global_error();
+hydra_status ensure_planned(hydra_ctx *ctx);
+Slot *slot_for(hydra_ctx *ctx, int model, int shard);
+
+// executor (exec.cpp): enqueue the kernels of one visit on the compute stream
+hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
+hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
+hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
+uint64_t workspace_need(const ModelShape &s, int dtype);
+
+}  // namespace hydra
+
+#define HYDRA_HIP(ctx, call)                                     \
+  do {                                                           \
+    hipError_t e__ = (call);                                     \
+    if (e__ != hipSuccess) return hydra::hipfail(ctx, e__, #call); \
+  } while (0)

@@ -1,0 +1,89 @@
+// Launchers of the gfx950 kernels.  Host-callable, all pointers are device
+// pointers unless stated; every launcher only enqueues on the given stream.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hydra {
+
+typedef uint16_t bf16_t;  // raw bfloat16 storage
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_DGELU = 2 };
+// causal structure of a batched [T,T] attention operand / result
+enum {
+  CAUSAL_NONE = 0,
+  CAUSAL_SKIP_UPPER = 1,  // result is [T,T]: tiles entirely above the diagonal are not computed
+  CAUSAL_K_END = 2,       // A is lower-triangular [i,j]: contraction stops at the row tile's end
+  CAUSAL_K_BEGIN = 3      // A^T is used (A stored [i,j], rows of the result are j): contraction starts at the row tile
+};
+
+static inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+struct GemmDesc {
+  int dtype = DT_BF16;
+  int ta = 0, tb = 0;  // ta: A stored [K,M]; tb: B stored [K,N] (else [N,K])
+  int M = 0, N = 0, K = 0;
+  float alpha = 1.f;
+  const void *A = nullptr;
+  int64_t lda = 0;
+  const void *B = nullptr;
+  int64_t ldb = 0;
+  int64_t ldc = 0;
+  int nb1 = 1, nb2 = 1;  // batch = nb1*nb2, matrix (i1,i2) at offset i1*s?1 + i2*s?2 elements
+  int64_t sA1 = 0, sA2 = 0, sB1 = 0, sB2 = 0, sC1 = 0, sC2 = 0;
+  const float *bias = nullptr;   // [N]
+  const float *resid = nullptr;  // fp32, same shape/ld/batching as C
+  float *out_f32 = nullptr;
+  void *out_act = nullptr;   // operand-dtype output
+  int epi = EPI_NONE;
+  void *out_act2 = nullptr;  // EPI_GELU: gelu(value); out_act then holds the pre-activation
+  const void *aux = nullptr; // EPI_DGELU: pre-activation u (operand dtype, ld = ldc)
+  int causal = CAUSAL_NONE;
+};
+
+hipError_t launch_gemm(const GemmDesc &g, hipStream_t s);
+
+// x0[m,:] = wte[tok[m],:] + wpe[m % T,:]
+hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *wpe, float *x0, int M, int T, int d,
+                            hipStream_t s);
+// dwte = 0 then rows of present tokens accumulate dx0 in ascending m; dwpe[t] = sum_b dx0[b*T+t]
+hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, float *dwpe, int B, int T, int d, int V,
+                            hipStream_t s);
+
+hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, const float *beta, void *y, float *mean,
+                                float *rstd, int M, int d, hipStream_t s);
+// dx = dres + LN'(dy) (dres may be null); dy is fp32
+hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
+                                   const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s);
+// dgamma[n] = sum_m dy*xhat, dbeta[n] = sum_m dy ; scratch: fp32 [2 * colsum_chunks(M) * d]
+hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const float *mean, const float *rstd,
+                                       float *dgamma, float *dbeta, float *scratch, int M, int d, hipStream_t s);
+int colsum_chunks(int M);
+// out[n] = sum_m in[m,n]; in has operand dtype (or fp32 when in_dtype == DT_F32); scratch fp32 [colsum_chunks(M)*N]
+hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N,
+                         hipStream_t s);
+
+// P[z,i,j] = softmax_j<=i S[z,i,j]; zero for i < j < min(T, roundup(i+1,256)); nothing written beyond
+hipError_t launch_softmax_causal_fwd(int dtype, const float *S, void *P, int n_mat, int T, hipStream_t s);
+// dS = P * (dP - rowsum(dP*P)), same zero-fill rule; dP fp32
+hipError_t launch_softmax_causal_bwd(int dtype, const void *P, const float *dP, void *dS, int n_mat, int T,
+                                     hipStream_t s);
+
+hipError_t launch_cross_entropy(int dtype, const float *logits, const int32_t *targets, float *row_loss, void *dlogits,
+                                int M, int V, int64_t ld, float inv_n, hipStream_t s);
+// loss[0] = (sum_m row_loss[m]) * inv_n, summed in double in a fixed order
+hipError_t launch_loss_reduce(const float *row_loss, float *loss, int M, float inv_n, hipStream_t s);
+
+hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *shadow, int64_t n, float lr, float beta1,
+                       float beta2, float eps, float corr1, float corr2, hipStream_t s);
+
+hipError_t launch_cast_bf16(const float *in, bf16_t *out, int64_t n, hipStream_t s);
+// out[c, r] = bf16(in[r, c]) ; in is [R, C] row-major, out is [C, R]
+hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C, hipStream_t s);
+// fp32 [R,C] (ld_in) -> operand dtype [R,C] (ld_out)
+hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C,
+                           hipStream_t s);
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s);
+
+}  // namespace hydra

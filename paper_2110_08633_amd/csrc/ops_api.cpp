@@ -1,0 +1,53 @@
+// Single-kernel entry points of the C ABI, used by parity tests and by the
+// roofline measurements.  All pointers are device pointers.
+#include "hydra_internal.h"
+
+using namespace hydra;
+
+static hydra_status ret(hipError_t e, const char *what) {
+  if (e == hipSuccess) return HYDRA_OK;
+  return hipfail(nullptr, e, what);
+}
+
+extern "C" {
+
+hydra_status hydra_op_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int32_t N, int32_t K, float alpha,
+                           const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias,
+                           const float *resid, float *out_f32, void *out_act, int64_t ldc, void *stream) {
+  if ((dtype != 0 && dtype != 1) || M < 0 || N < 0 || K < 0 || !A || !B || (!out_f32 && !out_act))
+    return fail(nullptr, HYDRA_E_INVAL, "bad GEMM argument");
+  GemmDesc g;
+  g.dtype = dtype; g.ta = ta != 0; g.tb = tb != 0; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.ldc = ldc;
+  g.bias = bias; g.resid = resid; g.out_f32 = out_f32; g.out_act = out_act;
+  return ret(launch_gemm(g, (hipStream_t)stream), "gemm");
+}
+
+hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *shadow_bf16, int64_t n, float lr,
+                           float beta1, float beta2, float eps, float corr1, float corr2, void *stream) {
+  if (!w || !m || !v || !g || n < 0) return fail(nullptr, HYDRA_E_INVAL, "bad Adam argument");
+  return ret(launch_adam(w, m, v, g, (bf16_t *)shadow_bf16, n, lr, beta1, beta2, eps, corr1, corr2, (hipStream_t)stream),
+             "adam");
+}
+
+hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *gamma, const float *beta, void *y,
+                                    float *mean, float *rstd, int32_t M, int32_t d, void *stream) {
+  if (!x || !gamma || !beta || !y || !mean || !rstd || M < 0 || d <= 0 || (d & 7))
+    return fail(nullptr, HYDRA_E_INVAL, "bad LayerNorm argument");
+  return ret(launch_layernorm_fwd(dtype, x, gamma, beta, y, mean, rstd, M, d, (hipStream_t)stream), "layernorm");
+}
+
+hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T, void *stream) {
+  if (!S || !P || n_mat < 0 || T <= 0) return fail(nullptr, HYDRA_E_INVAL, "bad softmax argument");
+  return ret(launch_softmax_causal_fwd(dtype, S, P, n_mat, T, (hipStream_t)stream), "softmax");
+}
+
+hydra_status hydra_op_cross_entropy(int32_t dtype, const float *logits, const int32_t *targets, float *row_loss,
+                                    void *dlogits, int32_t M, int32_t V, int64_t ld, float inv_n, void *stream) {
+  if (!logits || !targets || !row_loss || !dlogits || M < 0 || V <= 0 || ld < V)
+    return fail(nullptr, HYDRA_E_INVAL, "bad cross-entropy argument");
+  return ret(launch_cross_entropy(dtype, logits, targets, row_loss, dlogits, M, V, ld, inv_n, (hipStream_t)stream),
+             "cross_entropy");
+}
+
+}  // extern "C"

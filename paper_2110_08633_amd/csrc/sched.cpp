@@ -1,0 +1,206 @@
+// Sharded-LRTF scheduler (paper Section 2.4) for one device, and the driver
+// that runs its decisions through the swap engine with one task of prefetch
+// (double buffering, Section 2.3).
+//
+// Decision rule: after every shard task, the next task is taken from the model
+// whose remaining total time is largest; a shard task is atomic.  Remaining
+// time = summed cost of the model's tasks that have not been started; ties go
+// to the lowest model index.  The decisions depend only on the cost table, not
+// on wall-clock time, so the whole order is computed up front - this also gives
+// the buffer manager exact knowledge of future uses.
+#include <algorithm>
+
+#include "hydra_internal.h"
+
+struct hydra_sched {
+  hydra_ctx *ctx = nullptr;
+  int n_models = 0;
+  std::vector<int> model_id, S, n_mb;
+  std::vector<hydra_task> order;  // complete decision sequence; model = index into model_id
+  size_t cursor = 0;
+};
+
+using namespace hydra;
+
+namespace {
+
+struct Chain {
+  std::vector<hydra_task> tasks;
+  std::vector<int64_t> cost;
+};
+
+void build_order(hydra_sched *s, const int64_t *const *task_cost) {
+  std::vector<Chain> ch(s->n_models);
+  std::vector<int64_t> remaining(s->n_models, 0);
+  for (int m = 0; m < s->n_models; ++m) {
+    const int ns = s->S[m] + 2;
+    for (int mb = 0; mb < s->n_mb[m]; ++mb) {
+      for (int sh = 0; sh < ns; ++sh) {
+        ch[m].tasks.push_back({m, sh, 0, mb});
+        ch[m].cost.push_back(task_cost[m][sh]);
+      }
+      for (int sh = ns - 1; sh >= 0; --sh) {
+        ch[m].tasks.push_back({m, sh, 1, mb});
+        ch[m].cost.push_back(task_cost[m][ns + sh]);
+      }
+    }
+    for (int64_t c : ch[m].cost) remaining[m] += c;
+  }
+  std::vector<size_t> cur(s->n_models, 0);
+  for (;;) {
+    int best = -1;
+    for (int m = 0; m < s->n_models; ++m)
+      if (cur[m] < ch[m].tasks.size() && (best < 0 || remaining[m] > remaining[best])) best = m;
+    if (best < 0) break;
+    s->order.push_back(ch[best].tasks[cur[best]]);
+    remaining[best] -= ch[best].cost[cur[best]];
+    cur[best]++;
+  }
+}
+
+// index of the next task at or after 'from' that uses (model, shard); large if none
+size_t next_use(const hydra_sched *s, size_t from, int model, int shard) {
+  for (size_t i = from; i < s->order.size(); ++i)
+    if (s->order[i].model == model && s->order[i].shard == shard) return i;
+  return (size_t)-1;
+}
+
+// Promote the shard of task i.  When no buffer is free, the resident shard
+// whose next use lies furthest in the future is demoted first.
+hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
+  hydra_ctx *ctx = s->ctx;
+  const hydra_task &t = s->order[i];
+  const int mid = s->model_id[t.model];
+  const int what = t.phase == 1 ? (HYDRA_LOAD_PARAMS | HYDRA_LOAD_OPT) : HYDRA_LOAD_PARAMS;
+  hydra_status st = ensure_planned(ctx);
+  if (st) return st;
+  if (!slot_for(ctx, mid, t.shard)) {
+    bool has_free = false;
+    for (const Slot &sl : ctx->slots) has_free |= sl.model < 0;
+    if (!has_free) {
+      int victim = -1;
+      size_t far = 0;
+      for (size_t j = 0; j < ctx->slots.size(); ++j) {
+        const Slot &sl = ctx->slots[j];
+        if (sl.model == keep_model && sl.shard == keep_shard) continue;  // in use by the running task
+        int local = -1;
+        for (int m = 0; m < s->n_models; ++m)
+          if (s->model_id[m] == sl.model) local = m;
+        const size_t nu = local < 0 ? (size_t)-1 : next_use(s, i, local, sl.shard);
+        if (victim < 0 || nu > far) { victim = (int)j; far = nu; }
+      }
+      if (victim < 0) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the prefetch");
+      const Slot &v = ctx->slots[victim];
+      st = hydra_shard_spill(ctx, v.model, v.shard, HYDRA_SPILL_WRITEBACK | HYDRA_SPILL_EVICT);
+      if (st) return st;
+    }
+  }
+  return hydra_shard_load_async(ctx, mid, t.shard, what);
+}
+
+}  // namespace
+
+extern "C" {
+
+hydra_status hydra_sched_create(hydra_ctx *ctx, int32_t n_models, const int32_t *model_ids,
+                                const int32_t *n_block_shards, const int32_t *n_minibatches,
+                                const int64_t *const *task_cost, hydra_sched **out) {
+  if (n_models <= 0 || !n_minibatches || !task_cost || !out) return fail(ctx, HYDRA_E_INVAL, "bad scheduler argument");
+  if (ctx && !model_ids) return fail(ctx, HYDRA_E_INVAL, "model ids required with a context");
+  if (!ctx && !n_block_shards) return fail(ctx, HYDRA_E_INVAL, "shard counts required without a context");
+  hydra_sched *s = new hydra_sched();
+  s->ctx = ctx;
+  s->n_models = n_models;
+  for (int m = 0; m < n_models; ++m) {
+    int S;
+    if (ctx) {
+      if (model_ids[m] < 0 || model_ids[m] >= (int)ctx->models.size()) {
+        delete s;
+        return fail(ctx, HYDRA_E_INVAL, "unknown model id");
+      }
+      S = ctx->models[model_ids[m]]->sh.S;
+    } else {
+      S = n_block_shards[m];
+    }
+    if (S < 1 || n_minibatches[m] < 0 || !task_cost[m]) {
+      delete s;
+      return fail(ctx, HYDRA_E_INVAL, "bad per-model scheduler argument");
+    }
+    for (int i = 0; i < 2 * (S + 2); ++i)
+      if (task_cost[m][i] < 0) {
+        delete s;
+        return fail(ctx, HYDRA_E_INVAL, "negative task cost");
+      }
+    s->model_id.push_back(ctx ? model_ids[m] : m);
+    s->S.push_back(S);
+    s->n_mb.push_back(n_minibatches[m]);
+  }
+  build_order(s, task_cost);
+  *out = s;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_sched_destroy(hydra_sched *s) {
+  delete s;
+  return HYDRA_OK;
+}
+
+hydra_status hydra_sched_next(hydra_sched *s, hydra_task *out) {
+  if (!s || !out) return fail(nullptr, HYDRA_E_INVAL, "null argument");
+  if (s->cursor >= s->order.size()) return 1;
+  *out = s->order[s->cursor++];
+  out->model = s->model_id[out->model];
+  return HYDRA_OK;
+}
+
+hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const int32_t *const *targets,
+                             hydra_task *trace, int64_t trace_cap, int64_t *n_executed) {
+  if (!s || !s->ctx) return fail(nullptr, HYDRA_E_INVAL, "scheduler has no context");
+  hydra_ctx *ctx = s->ctx;
+  if (!tokens || !targets) return fail(ctx, HYDRA_E_INVAL, "null batch arrays");
+  hydra_status st = ensure_planned(ctx);
+  if (st) return st;
+  size_t total_shards = 0;
+  for (Model *m : ctx->models) total_shards += m->sh.S + 2;
+  const bool all_fit = ctx->slots.size() >= total_shards;
+  int64_t done = 0;
+  if (s->cursor < s->order.size() && (st = promote(s, s->cursor, -1, -1))) return st;
+  while (s->cursor < s->order.size()) {
+    const size_t i = s->cursor;
+    const hydra_task t = s->order[i];
+    const int mid = s->model_id[t.model];
+    Model *mm = ctx->models[mid];
+    // prefetch the next task's shard while this one runs
+    if (i + 1 < s->order.size() && ctx->slots.size() > 1) {
+      if ((st = promote(s, i + 1, mid, t.shard))) return st;
+    }
+    if (t.phase == 0 && t.shard == 0) {
+      const int64_t per = mm->sh.M;
+      if ((st = hydra_set_batch(ctx, mid, tokens[t.model] + t.minibatch * per, targets[t.model] + t.minibatch * per)))
+        return st;
+    }
+    if (t.phase == 0) {
+      if ((st = hydra_shard_forward(ctx, mid, t.shard))) return st;
+    } else {
+      if ((st = hydra_shard_backward(ctx, mid, t.shard))) return st;
+      if ((st = hydra_shard_adam_step(ctx, mid, t.shard))) return st;
+      // when shards do not all fit, start the write-back right away so that it
+      // overlaps the following tasks instead of delaying the next promote
+      if (!all_fit && (st = hydra_shard_spill(ctx, mid, t.shard, HYDRA_SPILL_WRITEBACK))) return st;
+    }
+    if (ctx->slots.size() == 1 && i + 1 < s->order.size()) {
+      // single buffer: no double buffering possible, promote after the task
+      if ((st = promote(s, i + 1, -1, -1))) return st;
+    }
+    if (trace && done < trace_cap) {
+      trace[done] = t;
+      trace[done].model = mid;
+    }
+    ++done;
+    s->cursor++;
+  }
+  if (n_executed) *n_executed = done;
+  return HYDRA_OK;
+}
+
+}  // extern "C"

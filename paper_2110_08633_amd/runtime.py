@@ -1,0 +1,144 @@
+"""Plumbing around the C ABI: device arena, pinned host state, streams.
+
+torch is used only to allocate memory and create streams; every computation
+happens inside libhydra.so.  With dry_run=True no GPU is touched (host-only
+state machine tests).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import hydra as H
+
+
+class Session:
+    """One hydra context with its arena, three streams and registered models."""
+
+    def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False):
+        self.dry = dry_run
+        self.models = []      # dicts: desc, cfg, master, m, v, ckpt, id, names
+        if dry_run:
+            flags |= H.FLAG_DRY_RUN
+            self.arena = None
+            self.streams = (None, None, None)
+            arena_ptr = 256
+        else:
+            import torch
+            self.torch = torch
+            self.arena = torch.empty(arena_bytes + 256, dtype=torch.uint8, device="cuda:0")
+            arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
+            self.streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+        self.ctx = H.hydra_init(arena_ptr, arena_bytes, *self.streams, flags=flags,
+                                shard_buffer_cap_bytes=shard_buffer_cap_bytes, max_slots=max_slots)
+        self.flags = flags
+
+    def _host(self, n, dtype=np.float32):
+        if self.dry:
+            return np.zeros(n, dtype)
+        t = self.torch.zeros(n, dtype=self.torch.float32, pin_memory=True)
+        self._keep = getattr(self, "_keep", []) + [t]
+        return t.numpy()
+
+    def add_model(self, cfg, weights, lr, dtype=None):
+        """weights: dict name -> float32 array (names as given by hydra_model_tensor)."""
+        desc = H.model_desc(cfg, lr, dtype)
+        lay = H.hydra_model_layout(desc)
+        master, m, v = self._host(lay.n_params), self._host(lay.n_params), self._host(lay.n_params)
+        tensors = {}
+        for i in range(lay.n_tensors):
+            name, off, rows, cols, shard = H.hydra_model_tensor(desc, i)
+            tensors[name] = (off, rows, cols, shard)
+            if weights is not None:
+                master[off:off + rows * cols] = np.asarray(weights[name], np.float32).reshape(-1)
+        ckpt = None
+        if self.flags & H.FLAG_CKPT_SPILL:
+            ckpt = self._host((lay.n_block_shards + 1) * cfg["B"] * cfg["T"] * cfg["d"])
+        mid = H.hydra_register_model(self.ctx, desc, master, m, v, ckpt)
+        rec = dict(id=mid, desc=desc, cfg=cfg, layout=lay, master=master, m=m, v=v, ckpt=ckpt, tensors=tensors,
+                   S=lay.n_block_shards)
+        self.models.append(rec)
+        return rec
+
+    def unpack(self, rec, flat):
+        """dict name -> array view of a flat array in canonical layout."""
+        return {n: flat[o:o + r * c].reshape((r, c) if c > 1 else (r,)) for n, (o, r, c, _) in rec["tensors"].items()}
+
+    def read_shard(self, rec, shard, which):
+        off, cnt = H.hydra_shard_range(rec["desc"], shard)
+        out = np.empty(cnt, np.float32)
+        H.hydra_read_device(self.ctx, rec["id"], shard, which, out)
+        return out
+
+    def read_logits(self, rec):
+        cfg = rec["cfg"]
+        out = np.empty((cfg["B"] * cfg["T"], cfg["V"]), np.float32)
+        H.hydra_read_device(self.ctx, rec["id"], 0, H.RD_LOGITS, out)
+        return out
+
+    def read_act(self, rec, shard, which):
+        cfg = rec["cfg"]
+        out = np.empty((cfg["B"] * cfg["T"], cfg["d"]), np.float32)
+        H.hydra_read_device(self.ctx, rec["id"], shard, which, out)
+        return out
+
+    def train_step_manual(self, rec, tokens, targets, collect=True, spill=True):
+        """One minibatch of one model through the low-level calls, shard by
+        shard.  Returns logits, loss and a dict of gradients (read back before
+        each shard's Adam step) when collect is set."""
+        ctx, mid, S = self.ctx, rec["id"], rec["S"]
+        H.hydra_set_batch(ctx, mid, np.ascontiguousarray(tokens, np.int32), np.ascontiguousarray(targets, np.int32))
+        for s in range(S + 2):
+            H.hydra_shard_load_async(ctx, mid, s, H.LOAD_PARAMS)
+            H.hydra_shard_forward(ctx, mid, s)
+            if spill and s != S + 1:
+                H.hydra_shard_spill(ctx, mid, s, H.SPILL_EVICT)
+        out = {}
+        if collect:
+            out["logits"] = self.read_logits(rec)
+        out["loss"] = H.hydra_get_loss(ctx, mid)
+        gflat = np.zeros(rec["layout"].n_params, np.float32)
+        for s in range(S + 1, -1, -1):
+            H.hydra_shard_load_async(ctx, mid, s, H.LOAD_PARAMS | H.LOAD_OPT)
+            H.hydra_shard_backward(ctx, mid, s)
+            if collect:
+                off, cnt = H.hydra_shard_range(rec["desc"], s)
+                gflat[off:off + cnt] = self.read_shard(rec, s, H.RD_GRADS)
+            H.hydra_shard_adam_step(ctx, mid, s)
+            if spill:
+                H.hydra_shard_spill(ctx, mid, s, H.SPILL_WRITEBACK | H.SPILL_EVICT)
+        if collect:
+            out["grads"] = self.unpack(rec, gflat)
+        return out
+
+    def flush(self):
+        """Write every resident shard's changed state back to the host arrays."""
+        for rec in self.models:
+            for s in range(rec["S"] + 2):
+                try:
+                    H.hydra_shard_spill(self.ctx, rec["id"], s, H.SPILL_WRITEBACK)
+                except H.HydraError as e:
+                    if e.code != H.E_STATE:
+                        raise
+        H.hydra_sync(self.ctx)
+
+    def close(self):
+        if self.ctx is not None:
+            H.hydra_destroy(self.ctx)
+            self.ctx = None
+
+
+def arena_bytes_for(cfgs, n_slots, ckpt_spill=False):
+    """Generous arena size for a list of model configs and a number of shard buffers."""
+    total, ws, max_shard = 0, 0, 0
+    for c in cfgs:
+        M, d, F, V, T, B, k = c["B"] * c["T"], c["d"], c["F"], c["V"], c["T"], c["B"], c["k"]
+        S = c["L"] // k
+        act = M * d * 4
+        vpad = (V + 63) // 64 * 64
+        total += (2 if ckpt_spill else S + 1) * act + 2 * act + M * vpad * 4 + 64 * M + (1 << 16)
+        layer = 5 * act + 3 * M * d * 4 + M * 3 * d * 4 + B * c["H"] * T * T * 4 + 2 * M * F * 4
+        scratch = 2 * B * c["H"] * T * T * 4 + 4 * act + M * F * 4 + M * 3 * d * 4 + 4 * act
+        ws = max(ws, k * layer + k * act + scratch + 2 * act + (1 << 20), M * vpad * 4 + 4 * act + (1 << 20))
+        blk = 12 * d * d + 13 * d if F == 4 * d else 4 * d * d + 2 * d * F + 9 * d + F
+        max_shard = max(max_shard, V * d + T * d, k * blk, 2 * d + d * V)
+    return int(total + ws + n_slots * (max_shard * 18 + 4096) + (64 << 20))

@@ -1,0 +1,196 @@
+"""Host-side logic of the library, exercised without a GPU: exported symbols,
+layout, scheduler decisions, and the shard-buffer state machine in dry-run mode
+(no HIP call is made)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth_inputs as SI
+from oracle import spilled as SP
+from paper_2110_08633_amd import hydra as H
+from paper_2110_08633_amd.runtime import Session
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    text = open(os.path.join(ROOT, "include", "hydra.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(hydra_[a-z0-9_]+)\s*\(", text))
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(H.lib, n), n
+        assert n in H.SIGNATURES, n
+    assert set(H.SIGNATURES) == names
+
+
+@pytest.mark.parametrize("name,total,per_block", [("gpt2s", 162643968, 7087872), ("gpt2m", 406286336, 12596224),
+                                                  ("gpt2xl", 1638022400, 30740800), ("gpt6b", 6055714816, 201379840),
+                                                  ("tiny", 536064, 198272)])
+def test_layout_matches_shapes_and_counts(name, total, per_block):
+    cfg = SI.CONFIGS[name]
+    desc = H.model_desc(cfg, 1e-4)
+    lay = H.hydra_model_layout(desc)
+    assert lay.n_params == total == SI.n_params(cfg)
+    assert lay.params_per_block == per_block
+    assert lay.n_shards == cfg["L"] // cfg["k"] + 2
+    shapes = SI.tensor_shapes(cfg)
+    assert lay.n_tensors == len(shapes)
+    off = 0
+    for i in (list(range(0, 16)) + list(range(lay.n_tensors - 16, lay.n_tensors))):
+        nm, o, r, c, sh = H.hydra_model_tensor(desc, i)
+        assert nm == shapes[i][0]
+        assert r * c == int(np.prod(shapes[i][1]))
+        assert o == sum(int(np.prod(s[1])) for s in shapes[:i])
+    so = [H.hydra_shard_range(desc, s) for s in range(lay.n_shards)]
+    assert so[0][0] == 0 and so[-1][0] + so[-1][1] == total
+    for a, b in zip(so[:-1], so[1:]):
+        assert a[0] + a[1] == b[0]
+
+
+def test_bad_descriptions_are_rejected():
+    base = dict(SI.small_cfg())
+    for bad in (dict(d=20), dict(k=3, L=4), dict(T=9), dict(H=3), dict(F=30), dict(L=0)):
+        c = dict(base)
+        c.update(bad)
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_model_layout(H.model_desc(c, 1e-3))
+        assert e.value.code == H.E_INVAL
+
+
+def _costs(cfg):
+    fc, bc = SI.task_costs(cfg)
+    return list(fc) + list(bc)
+
+
+def test_scheduler_decisions_equal_oracle_on_random_cost_tables():
+    rng = np.random.default_rng(0)
+    for trial in range(40):
+        n = int(rng.integers(1, 5))
+        S = [int(rng.integers(1, 5)) for _ in range(n)]
+        nmb = [int(rng.integers(1, 4)) for _ in range(n)]
+        tab = [[int(x) for x in rng.integers(0, 9, 2 * (s + 2))] for s in S]
+        sch = H.hydra_sched_create(None, None, nmb, tab, n_block_shards=S)
+        got = []
+        while (t := H.hydra_sched_next(sch)) is not None:
+            got.append(t)
+        H.hydra_sched_destroy(sch)
+        chains, costs = [], []
+        for m in range(n):
+            ch = SP.model_task_chain(dict(L=S[m], k=1), nmb[m])
+            chains.append(ch)
+            costs.append([tab[m][s] if ph == SP.FWD else tab[m][S[m] + 2 + s] for s, ph in ch])
+        order = SP.sharded_lrtf(chains, costs)
+        per = [2 * (s + 2) for s in S]
+        exp = [(m, chains[m][i][0], chains[m][i][1], i // per[m]) for m, i in order]
+        assert got == exp
+
+
+def _dry_session(n_models=2, max_slots=0, flags=0, cfg=None):
+    cfg = cfg or SI.small_cfg(L=4, k=2)
+    s = Session(1 << 34, flags=flags, max_slots=max_slots, dry_run=True)
+    for m in range(n_models):
+        s.add_model(cfg, None, 1e-3)
+    return s, cfg
+
+
+def test_dry_run_error_codes_and_state_machine():
+    s, cfg = _dry_session(1, max_slots=2)
+    ctx = s.ctx
+    tok, tgt = SI.make_batch(cfg, 1)
+
+    def code(fn, *a):
+        with pytest.raises(H.HydraError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(H.hydra_shard_forward, ctx, 0, 0) == H.E_STATE            # not loaded
+    H.hydra_shard_load_async(ctx, 0, 0, H.LOAD_PARAMS)
+    assert code(H.hydra_shard_forward, ctx, 0, 0) == H.E_STATE            # no minibatch yet
+    H.hydra_set_batch(ctx, 0, tok, tgt)
+    assert code(H.hydra_shard_load_async, ctx, 0, 9, H.LOAD_PARAMS) == H.E_INVAL
+    assert code(H.hydra_shard_load_async, ctx, 3, 0, H.LOAD_PARAMS) == H.E_INVAL
+    assert code(H.hydra_shard_load_async, ctx, 0, 1, H.LOAD_OPT) == H.E_INVAL
+    H.hydra_shard_load_async(ctx, 0, 1, H.LOAD_PARAMS)
+    assert code(H.hydra_shard_load_async, ctx, 0, 2, H.LOAD_PARAMS) == H.E_NOSLOT
+    assert code(H.hydra_shard_forward, ctx, 0, 1) == H.E_STATE            # out of order
+    H.hydra_shard_forward(ctx, 0, 0)
+    assert code(H.hydra_shard_backward, ctx, 0, 0) == H.E_STATE           # forward pass not finished
+    assert code(H.hydra_shard_adam_step, ctx, 0, 0) == H.E_STATE          # no gradients
+    assert code(H.hydra_shard_spill, ctx, 0, 2, 3) == H.E_STATE           # not resident
+    H.hydra_shard_spill(ctx, 0, 0, H.SPILL_EVICT)
+    H.hydra_shard_forward(ctx, 0, 1)
+    H.hydra_shard_load_async(ctx, 0, 2, H.LOAD_PARAMS)
+    H.hydra_shard_forward(ctx, 0, 2)
+    H.hydra_shard_spill(ctx, 0, 1, H.SPILL_EVICT)
+    H.hydra_shard_load_async(ctx, 0, 3, H.LOAD_PARAMS)
+    assert code(H.hydra_get_loss, ctx, 0) == H.E_STATE
+    H.hydra_shard_forward(ctx, 0, 3)
+    assert H.hydra_get_loss(ctx, 0) == 0.0
+    assert code(H.hydra_shard_backward, ctx, 0, 2) == H.E_STATE           # reverse order starts at the head
+    H.hydra_shard_backward(ctx, 0, 3)
+    assert code(H.hydra_shard_adam_step, ctx, 0, 3) == H.E_STATE          # m, v not resident
+    H.hydra_shard_load_async(ctx, 0, 3, H.LOAD_PARAMS | H.LOAD_OPT)      # fetches only m, v
+    H.hydra_shard_adam_step(ctx, 0, 3)
+    assert code(H.hydra_shard_spill, ctx, 0, 3, H.SPILL_EVICT) == H.E_STATE   # dirty, no write-back requested
+    H.hydra_shard_spill(ctx, 0, 3, H.SPILL_WRITEBACK | H.SPILL_EVICT)
+    st = H.hydra_get_stats(ctx)
+    rng = [H.hydra_shard_range(s.models[0]["desc"], i)[1] for i in range(4)]
+    assert st["bytes_h2d"] == 4 * sum(rng) + 8 * rng[3]
+    assert st["bytes_d2h"] == 12 * rng[3]
+    assert st["n_slots"] == 2 and st["n_writebacks"] == 1
+    assert code(H.hydra_register_model, ctx, s.models[0]["desc"], s.models[0]["master"], s.models[0]["m"],
+                s.models[0]["v"]) == H.E_STATE
+    s.close()
+
+
+@pytest.mark.parametrize("max_slots", [1, 2, 3, 0])
+def test_dry_sched_run_trace_equals_oracle_and_traffic(max_slots):
+    n_models, nmb = 3, 2
+    s, cfg = _dry_session(n_models, max_slots=max_slots)
+    S = cfg["L"] // cfg["k"]
+    tab = [_costs(cfg)] * n_models
+    sch = H.hydra_sched_create(s.ctx, [0, 1, 2], [nmb] * n_models, tab)
+    toks = [np.stack([SI.make_batch(cfg, 10 * m + i)[0] for i in range(nmb)]) for m in range(n_models)]
+    tgts = [np.stack([SI.make_batch(cfg, 10 * m + i)[1] for i in range(nmb)]) for m in range(n_models)]
+    trace, done = H.hydra_sched_run(sch, toks, tgts, s.ctx, trace_cap=1000)
+    chains = [SP.model_task_chain(cfg, nmb) for _ in range(n_models)]
+    costs = [[tab[m][sh] if ph == SP.FWD else tab[m][S + 2 + sh] for sh, ph in ch] for m, ch in enumerate(chains)]
+    order = SP.sharded_lrtf(chains, costs)
+    per = 2 * (S + 2)
+    assert done == len(order) == n_models * nmb * per
+    assert trace == [(m, chains[m][i][0], chains[m][i][1], i // per) for m, i in order]
+    st = H.hydra_get_stats(s.ctx)
+    assert st["n_tasks"] == done
+    sizes = [H.hydra_shard_range(s.models[0]["desc"], i)[1] for i in range(S + 2)]
+    per_model_params = sum(sizes)
+    if max_slots == 0:      # everything fits: each shard's state crosses the link exactly once, nothing comes back
+        assert st["n_slots"] == n_models * (S + 2)
+        assert st["bytes_h2d"] == n_models * per_model_params * 12
+        assert st["bytes_d2h"] == 0 and st["n_evictions"] == 0
+    else:
+        # every shard is promoted for each of its two visits per minibatch (paper Section 2.3), except where the
+        # buffer manager finds it still resident; Adam state goes back after every backward visit
+        assert st["bytes_d2h"] == n_models * nmb * per_model_params * 12
+        assert st["bytes_h2d"] <= n_models * nmb * per_model_params * 16
+        assert st["bytes_h2d"] >= n_models * nmb * per_model_params * 12
+        assert st["n_slots"] == max_slots
+    s.flush()
+    s.close()
+
+
+def test_dry_checkpoint_spill_traffic_and_ordering_guard():
+    cfg = SI.small_cfg(L=4, k=2)
+    s, _ = _dry_session(1, max_slots=2, flags=H.FLAG_CKPT_SPILL, cfg=cfg)
+    S = 2
+    sch = H.hydra_sched_create(s.ctx, [0], [1], [_costs(cfg)])
+    tok, tgt = SI.make_batch(cfg, 3)
+    H.hydra_sched_run(sch, [tok[None]], [tgt[None]], s.ctx)
+    st = H.hydra_get_stats(s.ctx)
+    act = cfg["B"] * cfg["T"] * cfg["d"] * 4
+    n = s.models[0]["layout"].n_params
+    assert st["bytes_d2h"] == 12 * n + (S + 1) * act          # S+1 boundaries written to the host
+    assert st["bytes_h2d"] >= 12 * n + S * act                # and the S inputs of the block shards read back
+    s.close()
