@@ -104,7 +104,8 @@ typedef struct {
   int32_t n_layer, d_model, n_head, d_ff, vocab, seq, batch;
   int32_t layers_per_shard; /* must divide n_layer                                        */
   int32_t dtype;            /* 0 = fp32 compute; 1 = bf16 MFMA compute, fp32 master/Adam  */
-  float lr, beta1, beta2, eps;
+  int32_t reserved;
+  double lr, beta1, beta2, eps; /* Adam hyper-parameters of this model (doubles so that 1-beta is exact) */
 } hydra_model_desc;
 
 typedef struct {
@@ -232,11 +233,11 @@ hydra_status hydra_op_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int
                            float alpha, const void *A, int64_t lda, const void *B, int64_t ldb,
                            const float *bias, const float *resid, float *out_f32, void *out_act,
                            int64_t ldc, void *stream);
-/* Fused Adam on n elements (Kingma & Ba update without weight decay, bias
- * corrections passed in as 1-beta1^t and 1-beta2^t); shadow_bf16 may be NULL. */
+/* Fused Adam on n elements, step t >= 1 (update without weight decay; 1-beta
+ * and the bias corrections 1-beta^t are evaluated in double on the host);
+ * shadow_bf16 (bf16 copy of the new weights) may be NULL. */
 hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *shadow_bf16, int64_t n,
-                           float lr, float beta1, float beta2, float eps, float corr1, float corr2,
-                           void *stream);
+                           double lr, double beta1, double beta2, double eps, int64_t t, void *stream);
 /* Row LayerNorm: y (dtype) [M,d], mean/rstd fp32 [M]. */
 hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *gamma, const float *beta,
                                     void *y, float *mean, float *rstd, int32_t M, int32_t d, void *stream);

@@ -3,6 +3,8 @@
 // (64 lanes) owns one row wherever a row reduction is needed; reductions over
 // rows (bias / gain gradients) are done in two passes with a fixed summation
 // order so that results do not depend on scheduling.
+#include <cmath>
+
 #include "kernels.h"
 
 namespace hydra {
@@ -236,16 +238,16 @@ __global__ __launch_bounds__(256) void colsum_pass1_kernel(const T *__restrict__
                                                            const float *__restrict__ x, const float *__restrict__ mean,
                                                            const float *__restrict__ rstd, float *__restrict__ part,
                                                            int M, int N) {
-  __shared__ float sh[2][4][64];
+  __shared__ double sh[2][4][64];
   const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
   const int col = blockIdx.x * 64 + cx;
   const int r0 = blockIdx.y * CH, r1 = min(M, r0 + CH);
-  float a = 0.f, b = 0.f;
+  double a = 0.0, b = 0.0;  // fp64 adds are free in a memory-bound reduction
   if (col < N) {
     for (int r = r0 + ry; r < r1; r += 4) {
       const float v = ldv<T>(in, (int64_t)r * ld + col);
       if (MODE == 1) {
-        a += v * ((x[(int64_t)r * ld + col] - mean[r]) * rstd[r]);
+        a += (double)(v * ((x[(int64_t)r * ld + col] - mean[r]) * rstd[r]));
         b += v;
       } else {
         a += v;
@@ -257,9 +259,10 @@ __global__ __launch_bounds__(256) void colsum_pass1_kernel(const T *__restrict__
   __syncthreads();
   if (ry == 0 && col < N) {
     const int nch = gridDim.y;
-    part[(int64_t)blockIdx.y * N + col] = (sh[0][0][cx] + sh[0][1][cx]) + (sh[0][2][cx] + sh[0][3][cx]);
+    part[(int64_t)blockIdx.y * N + col] = (float)((sh[0][0][cx] + sh[0][1][cx]) + (sh[0][2][cx] + sh[0][3][cx]));
     if (MODE == 1)
-      part[(int64_t)(nch + blockIdx.y) * N + col] = (sh[1][0][cx] + sh[1][1][cx]) + (sh[1][2][cx] + sh[1][3][cx]);
+      part[(int64_t)(nch + blockIdx.y) * N + col] =
+          (float)((sh[1][0][cx] + sh[1][1][cx]) + (sh[1][2][cx] + sh[1][3][cx]));
   }
 }
 
@@ -267,13 +270,13 @@ __global__ void colsum_pass2_kernel(const float *__restrict__ part, float *__res
                                     int nch, int N) {
   const int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= N) return;
-  float a = 0.f;
-  for (int c = 0; c < nch; ++c) a += part[(int64_t)c * N + col];
-  out0[col] = a;
+  double a = 0.0;
+  for (int c = 0; c < nch; ++c) a += (double)part[(int64_t)c * N + col];
+  out0[col] = (float)a;
   if (out1) {
-    float b = 0.f;
-    for (int c = 0; c < nch; ++c) b += part[(int64_t)(nch + c) * N + col];
-    out1[col] = b;
+    double b = 0.0;
+    for (int c = 0; c < nch; ++c) b += (double)part[(int64_t)(nch + c) * N + col];
+    out1[col] = (float)b;
   }
 }
 
@@ -446,9 +449,9 @@ hipError_t launch_loss_reduce(const float *row_loss, float *loss, int M, float i
 // 16 B read and 12 B (+2 B bf16 copy) written per parameter.
 __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float *__restrict__ m, float *__restrict__ v,
                                                    const float *__restrict__ g, bf16_t *__restrict__ shadow, int64_t n,
-                                                   float lr, float b1, float b2, float eps, float c1, float c2) {
+                                                   float lr, float b1, float b2, float ob1, float ob2, float eps,
+                                                   float c1, float c2) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x * 4;
-  const float ob1 = 1.f - b1, ob2 = 1.f - b2;
   for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
     if (i + 4 <= n) {
       float4 W = *(float4 *)(w + i), Mm = *(float4 *)(m + i), Vv = *(float4 *)(v + i);
@@ -483,14 +486,15 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float 
   }
 }
 
-hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *shadow, int64_t n, float lr, float beta1,
-                       float beta2, float eps, float corr1, float corr2, hipStream_t s) {
+hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *shadow, int64_t n, double lr, double beta1,
+                       double beta2, double eps, int64_t t, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  const float corr1 = (float)(1.0 - pow(beta1, (double)t)), corr2 = (float)(1.0 - pow(beta2, (double)t));
   int64_t blocks = (n / 4 + 255) / 256;
   if (blocks > 8192) blocks = 8192;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(adam_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, m, v, g, shadow, n, lr, beta1, beta2, eps,
-                     corr1, corr2);
+  hipLaunchKernelGGL(adam_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, m, v, g, shadow, n, (float)lr, (float)beta1,
+                     (float)beta2, (float)(1.0 - beta1), (float)(1.0 - beta2), (float)eps, corr1, corr2);
   return hipGetLastError();
 }
 

@@ -420,12 +420,9 @@ hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const ModelShape &s = mm->sh;
   const hydra_model_desc &h = mm->desc;
   const int64_t n = s.shard_off[shard + 1] - s.shard_off[shard];
-  const double c1 = 1.0 - std::pow((double)h.beta1, (double)mm->t);
-  const double c2 = 1.0 - std::pow((double)h.beta2, (double)mm->t);
   // block shards keep their bf16 working copy current for the next visit
   bf16_t *shadow = (mm->dtype == DT_BF16 && shard >= 1 && shard <= s.S) ? sl->wb : nullptr;
-  HYDRA_HIP(ctx, launch_adam(sl->w, sl->m, sl->v, sl->g, shadow, n, h.lr, h.beta1, h.beta2, h.eps, (float)c1, (float)c2,
-                             ctx->s_compute));
+  HYDRA_HIP(ctx, launch_adam(sl->w, sl->m, sl->v, sl->g, shadow, n, h.lr, h.beta1, h.beta2, h.eps, mm->t, ctx->s_compute));
   sl->wb_valid = shadow != nullptr;
   return HYDRA_OK;
 }

@@ -75,8 +75,9 @@ hipError_t launch_cross_entropy(int dtype, const float *logits, const int32_t *t
 // loss[0] = (sum_m row_loss[m]) * inv_n, summed in double in a fixed order
 hipError_t launch_loss_reduce(const float *row_loss, float *loss, int M, float inv_n, hipStream_t s);
 
-hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *shadow, int64_t n, float lr, float beta1,
-                       float beta2, float eps, float corr1, float corr2, hipStream_t s);
+// hyper-parameters in double; the kernel receives beta, 1-beta and 1-beta^t each rounded once to fp32
+hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *shadow, int64_t n, double lr, double beta1,
+                       double beta2, double eps, int64_t t, hipStream_t s);
 
 hipError_t launch_cast_bf16(const float *in, bf16_t *out, int64_t n, hipStream_t s);
 // out[c, r] = bf16(in[r, c]) ; in is [R, C] row-major, out is [C, R]

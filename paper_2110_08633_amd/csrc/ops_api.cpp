@@ -23,11 +23,10 @@ hydra_status hydra_op_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int
   return ret(launch_gemm(g, (hipStream_t)stream), "gemm");
 }
 
-hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *shadow_bf16, int64_t n, float lr,
-                           float beta1, float beta2, float eps, float corr1, float corr2, void *stream) {
-  if (!w || !m || !v || !g || n < 0) return fail(nullptr, HYDRA_E_INVAL, "bad Adam argument");
-  return ret(launch_adam(w, m, v, g, (bf16_t *)shadow_bf16, n, lr, beta1, beta2, eps, corr1, corr2, (hipStream_t)stream),
-             "adam");
+hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *shadow_bf16, int64_t n, double lr,
+                           double beta1, double beta2, double eps, int64_t t, void *stream) {
+  if (!w || !m || !v || !g || n < 0 || t < 1) return fail(nullptr, HYDRA_E_INVAL, "bad Adam argument");
+  return ret(launch_adam(w, m, v, g, (bf16_t *)shadow_bf16, n, lr, beta1, beta2, eps, t, (hipStream_t)stream), "adam");
 }
 
 hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *gamma, const float *beta, void *y,

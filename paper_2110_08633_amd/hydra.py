@@ -8,6 +8,11 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# torch owns the device memory and the streams handed to the library, so both must
+# use the same HIP runtime: importing torch first makes libhydra.so bind to the
+# libamdhip64 that torch has already loaded instead of bringing in a second copy.
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhydra.so")
 if not os.path.exists(LIB_PATH):
@@ -31,8 +36,8 @@ class InitDesc(C.Structure):
 class ModelDesc(C.Structure):
     _fields_ = [("n_layer", C.c_int32), ("d_model", C.c_int32), ("n_head", C.c_int32), ("d_ff", C.c_int32),
                 ("vocab", C.c_int32), ("seq", C.c_int32), ("batch", C.c_int32), ("layers_per_shard", C.c_int32),
-                ("dtype", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float)]
+                ("dtype", C.c_int32), ("reserved", C.c_int32), ("lr", C.c_double), ("beta1", C.c_double),
+                ("beta2", C.c_double), ("eps", C.c_double)]
 
 
 class HostState(C.Structure):
@@ -57,7 +62,7 @@ class Stats(C.Structure):
 
 
 _P = C.POINTER
-_vp, _i32, _i64, _u64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+_vp, _i32, _i64, _u64, _f32, _f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
 
 # name -> (restype, argtypes); every symbol declared in include/hydra.h
 SIGNATURES = {
@@ -84,7 +89,7 @@ SIGNATURES = {
     "hydra_sched_run": (_i32, [_vp, _P(_vp), _P(_vp), _P(Task), _i64, _P(_i64)]),
     "hydra_op_gemm": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp,
                              _i64, _vp]),
-    "hydra_op_adam": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _f32, _f32, _vp]),
+    "hydra_op_adam": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _f64, _f64, _f64, _f64, _i64, _vp]),
     "hydra_op_layernorm_fwd": (_i32, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_softmax_causal": (_i32, [_i32, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_cross_entropy": (_i32, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _f32, _vp]),
@@ -125,7 +130,7 @@ def model_desc(cfg, lr, dtype=None, beta1=0.9, beta2=0.999, eps=1e-8):
     """ModelDesc from a config dict with keys L, d, H, F, V, T, B, k, dtype."""
     dt = cfg["dtype"] if dtype is None else dtype
     return ModelDesc(cfg["L"], cfg["d"], cfg["H"], cfg["F"], cfg["V"], cfg["T"], cfg["B"], cfg["k"],
-                     1 if dt == "bf16" else 0, lr, beta1, beta2, eps)
+                     1 if dt == "bf16" else 0, 0, lr, beta1, beta2, eps)
 
 
 # ---- thin wrappers, same names as the C functions --------------------------
@@ -259,9 +264,9 @@ def hydra_op_gemm(dtype, ta, tb, M, N, K, alpha, A, lda, B, ldb, bias, resid, ou
                                     _ptr(resid), _ptr(out_f32), _ptr(out_act), ldc, _stream(stream)))
 
 
-def hydra_op_adam(w, m, v, g, shadow, n, lr, beta1, beta2, eps, corr1, corr2, stream=None):
+def hydra_op_adam(w, m, v, g, shadow, n, lr, beta1, beta2, eps, t, stream=None):
     return _check(lib.hydra_op_adam(_ptr(w), _ptr(m), _ptr(v), _ptr(g), _ptr(shadow), n, lr, beta1, beta2, eps,
-                                    corr1, corr2, _stream(stream)))
+                                    t, _stream(stream)))
 
 
 def hydra_op_layernorm_fwd(dtype, x, gamma, beta, y, mean, rstd, M, d, stream=None):

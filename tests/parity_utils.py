@@ -6,6 +6,8 @@ def rel_errs(a, b):
     """(max-norm relative error, l2 relative error) of a against reference b."""
     a = np.asarray(a, np.float64)
     b = np.asarray(b, np.float64)
+    if b.size == 0:
+        return 0.0, 0.0
     den_m = max(np.abs(b).max(), 1e-30)
     den_2 = max(np.linalg.norm(b.ravel()), 1e-30)
     return np.abs(a - b).max() / den_m, np.linalg.norm((a - b).ravel()) / den_2

@@ -74,7 +74,7 @@ def test_adam_kernel_against_oracle(H, n):
     t, lr = 5, 3e-4
     dw, dm, dv, dg = dev(w), dev(m), dev(v), dev(g)
     shadow = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
-    H.hydra_op_adam(dw, dm, dv, dg, shadow, n, lr, 0.9, 0.999, 1e-8, 1 - 0.9 ** t, 1 - 0.999 ** t)
+    H.hydra_op_adam(dw, dm, dv, dg, shadow, n, lr, 0.9, 0.999, 1e-8, t)
     torch.cuda.synchronize()
     rw, rm, rv = D.adam_update(w.astype(np.float64), m.astype(np.float64), v.astype(np.float64),
                                g.astype(np.float64), t, lr)
@@ -85,7 +85,7 @@ def test_adam_kernel_against_oracle(H, n):
     # closed form: first step from zero state moves by -lr * g / (|g| + eps); zero gradient moves nothing
     z = torch.zeros(n, device="cuda")
     dw2, dm2, dv2 = dev(w), z.clone(), z.clone()
-    H.hydra_op_adam(dw2, dm2, dv2, dg, None, n, lr, 0.9, 0.999, 1e-8, 1 - 0.9, 1 - 0.999)
+    H.hydra_op_adam(dw2, dm2, dv2, dg, None, n, lr, 0.9, 0.999, 1e-8, 1)
     torch.cuda.synchronize()
     w2 = dw2.cpu().numpy()
     assert (w2[g == 0] == w[g == 0]).all()

@@ -36,26 +36,44 @@ def oracle_steps(cfg, W, lr, batches, dtype=np.float64):
     return outs, P, Mo, Vo
 
 
-def check_step(cfg, got, ref, after_gpu, tol, bf16):
+# Adam's first steps move a weight by about lr * g / |g|: where the gradient of an element is at the noise level of
+# the arithmetic (e.g. the key bias, whose exact gradient is zero), the step is decided by rounding noise on either
+# side.  The gradient check admits an absolute error of tol * max|g| per element, so elements whose oracle gradient is
+# below FLOOR = 5 * tol times max|g| of their tensor at any step so far are called ill-conditioned: they may differ by
+# a full Adam step; all other elements must meet the tolerance.
+FLOOR = {"f32": 5e-4, "bf16": 1e-1}
+DELTA_TOL = {"f32": 2e-3, "bf16": 5e-2}
+
+
+def update_ill(ill, grads, dtype):
+    for name, g in grads.items():
+        a = np.abs(g)
+        bad = a < FLOOR[dtype] * a.max()
+        ill[name] = bad if name not in ill else (ill[name] | bad)
+    return ill
+
+
+def check_weights(after_gpu, ref_after, ref_before_first, ill, lr, steps, dtype, what=""):
+    tol = TOL[dtype]
+    for name, ref in ref_after.items():
+        got = after_gpu[name].astype(np.float64)
+        assert np.isfinite(got).all(), f"{what}weight {name}: non-finite"
+        err = np.abs(got - ref)
+        allowed = tol * np.abs(ref).max() + np.where(ill[name], 2.5 * lr * steps, 0.0)
+        assert (err <= allowed).all(), f"{what}weight {name}: max excess {(err - allowed).max():.3e}"
+        well = ~ill[name]
+        if well.any():
+            dref = (ref - ref_before_first[name])[well]
+            dgot = (got - ref_before_first[name])[well]
+            em, e2 = rel_errs(dgot, dref)
+            assert e2 <= DELTA_TOL[dtype], f"{what}delta {name}: l2-rel {e2:.3e} (max-rel {em:.3e})"
+
+
+def check_step(cfg, got, ref, tol):
     assert_close(got["logits"], ref["logits"], tol, "logits")
     assert abs(got["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), ("loss", got["loss"], ref["loss"])
     for name, g in ref["grads"].items():
         assert_close(got["grads"][name], g, tol, f"grad {name}")
-    for name in ref["after"]:
-        assert_close(after_gpu[name], ref["after"][name], tol, f"weight {name}")
-        dref = ref["after"][name] - ref["before"][name]
-        dgot = after_gpu[name].astype(np.float64) - ref["before"][name]
-        if not bf16:
-            # w_new - w_old carries fp32 rounding of w (|w| ~ 2e-2, ulp ~ 2e-9) against |dw| ~ lr
-            assert_close(dgot, dref, 2e-3, f"delta {name}")
-        else:
-            # first steps move every weight by about lr*sign(g); bf16 noise flips tiny gradients, so compare the
-            # update only where the oracle's gradient is clearly non-zero
-            g = np.abs(ref["grads"][name])
-            sel = g > 0.05 * np.sqrt((g * g).mean())
-            if sel.any():
-                em, e2 = rel_errs(dgot[sel], dref[sel])
-                assert e2 <= 0.25, f"delta {name}: l2-rel {e2:.3e}"
 
 
 def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False):
@@ -67,11 +85,14 @@ def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False):
     sess = R.Session(R.arena_bytes_for([cfg], 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags, max_slots=max_slots or 4)
     rec = sess.add_model(cfg, W, lr)
     bf16 = cfg["dtype"] == "bf16"
+    ill = {}
     for i, (tok, tgt) in enumerate(batches):
         got = sess.train_step_manual(rec, tok, tgt)
         H.hydra_sync(sess.ctx)
         after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
-        check_step(cfg, got, refs[i], after, TOL[cfg["dtype"]], bf16)
+        check_step(cfg, got, refs[i], TOL[cfg["dtype"]])
+        update_ill(ill, refs[i]["grads"], cfg["dtype"])
+        check_weights(after, refs[i]["after"], refs[0]["before"], ill, lr, i + 1, cfg["dtype"], f"step {i}: ")
     if not bf16:
         for name, a in sess.unpack(rec, rec["m"]).items():
             assert_close(a, Mo[name], 1e-4, f"adam m {name}")
@@ -94,7 +115,7 @@ def test_tiny_config_fp32_three_steps(rt):
 ])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ragged_shapes(rt, kw, dtype):
-    cfg = SI.small_cfg(dtype=dtype, lrs=[1e-3], **kw)
+    cfg = SI.small_cfg(dtype=dtype, lrs=[1e-4], **kw)       # the learning rate of the reference workloads
     run_manual(rt, cfg, 2)
 
 
@@ -163,11 +184,14 @@ def test_scheduled_multi_model_run_matches_oracle(rt, max_slots, dtype):
     for m in range(n):
         assert abs(H.hydra_get_loss(sess.ctx, recs[m]["id"]) - oracle[m].loss) <= tol * oracle[m].loss
         after = sess.unpack(recs[m], recs[m]["master"])
-        for name, ref in oracle[m].P.items():
-            assert_close(after[name], ref, tol, f"model {m} weight {name}")
-            if dtype == "f32":
-                assert_close(after[name].astype(np.float64) - Ws[m][name], ref - Ws[m][name], 5e-3,
-                             f"model {m} delta {name}")
+        # gradients of every step from the plain (unsharded) oracle, to mark ill-conditioned elements
+        refs, P, _, _ = oracle_steps(cfg, Ws[m], cfg["lrs"][m], batches[m])
+        ill = {}
+        for r in refs:
+            update_ill(ill, r["grads"], dtype)
+        for name in P:
+            assert (P[name] == oracle[m].P[name]).all()       # interleaved spilled oracle == plain oracle
+        check_weights(after, oracle[m].P, refs[0]["before"], ill, cfg["lrs"][m], nmb[m], dtype, f"model {m} ")
     st = H.hydra_get_stats(sess.ctx)
     assert st["n_tasks"] == done == len(order)
     H.hydra_sched_destroy(sch)
