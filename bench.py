@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Throughput of spilled, shard-alternated training on one MI355X.
+
+Workload (BASELINE config 2): two GPT-2-small-shaped models (12 layers, d 768,
+12 heads, MLP 3072, vocab 50257, seq 512, batch 4; bf16 compute with fp32
+master weights; lr 1e-4 / 3e-5) whose 2-layer shards are alternated by the
+Sharded-LRTF scheduler.  One step = one minibatch of every model through the
+whole path: promote shard, forward visit, checkpoint, backward visit with
+recomputation, Adam, demote.
+
+Default mode "spill": three shard buffers, so every shard's state streams in
+from pinned host DRAM before each visit and the updated state streams back.
+Mode "resident": as many buffers as shards (state crosses the link once).
+
+Prints ONE JSON line.  `value` is tokens/s over all models with all inputs
+(weights in pinned host memory, token batches) prepared before the timed
+region.  `roofline` describes the kernel with the largest share of GPU time,
+timed with HIP events on its own stream in a second pass over the same work.
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as SI  # noqa: E402
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBPS = 8000.0
+
+
+def make_session(cfg, n_models, mode, timing, R, H):
+    n_shards = n_models * (cfg["L"] // cfg["k"] + 2)
+    slots = 3 if mode == "spill" else n_shards
+    flags = H.FLAG_TIMING if timing else 0
+    sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots), flags=flags, max_slots=slots)
+    recs = []
+    for m in range(n_models):
+        W = SI.make_weights(cfg, SI.model_seed(cfg, m))
+        recs.append(sess.add_model(cfg, W, cfg["lrs"][m]))
+        del W
+    return sess, recs
+
+
+def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
+    n = len(recs)
+    fc, bc = SI.task_costs(cfg)
+    toks = [np.stack([SI.make_batch(cfg, SI.batch_seed(cfg, m, first_step + i))[0] for i in range(n_mb)]) for m in range(n)]
+    tgts = [np.stack([SI.make_batch(cfg, SI.batch_seed(cfg, m, first_step + i))[1] for i in range(n_mb)]) for m in range(n)]
+    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [n_mb] * n, [list(fc) + list(bc)] * n)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    H.hydra_sched_run(sch, toks, tgts, sess.ctx)
+    H.hydra_sync(sess.ctx)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    H.hydra_sched_destroy(sch)
+    return dt
+
+
+def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch):
+    sess, recs = make_session(cfg, n_models, mode, timing, R, H)
+    if warmup:
+        run_steps(sess, recs, cfg, warmup, 0, H, torch)
+    if timing:
+        H.hydra_kernel_stats_reset(sess.ctx)
+    st0 = H.hydra_get_stats(sess.ctx)
+    dt = run_steps(sess, recs, cfg, steps, warmup, H, torch)
+    st1 = H.hydra_get_stats(sess.ctx)
+    kst = H.hydra_kernel_stats(sess.ctx) if timing else None
+    losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
+    sess.close()
+    del sess
+    torch.cuda.empty_cache()
+    return dict(seconds=dt, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
+                n_slots=st1["n_slots"], kernels=kst, losses=losses)
+
+
+def cpu_baseline(cfg):
+    """The CPU oracle (float32 instance) on one model-minibatch of the same workload."""
+    from oracle import decoder as D
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    W = SI.make_weights(cfg, SI.model_seed(cfg, 0))
+    P = D.cast_params(W, np.float32)
+    Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
+    tok, tgt = SI.make_batch(cfg, SI.batch_seed(cfg, 0, 0))
+    t0 = time.perf_counter()
+    out = D.train_step(P, Mo, Vo, tok, tgt, cfg, cfg["lrs"][0], 1)
+    dt = time.perf_counter() - t0
+    return dict(value=cfg["B"] * cfg["T"] / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample="1 model x 1 minibatch (2048 tokens) of the same workload, float32 numpy oracle, "
+                       f"unsharded step, {dt:.1f} s; loss {out['loss']:.4f}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--mode", choices=["spill", "resident"], default="spill")
+    ap.add_argument("--config", default="gpt2s")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the second mode and the timing pass")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the method shards over host DRAM, not over GPUs); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2110_08633_amd import hydra as H, runtime as R
+    assert torch.cuda.is_available(), "no GPU visible"
+    cfg = SI.CONFIGS[args.config]
+    n_models = cfg["n_models"]
+    tokens_per_step = n_models * cfg["B"] * cfg["T"]
+
+    main_run = measure(cfg, n_models, args.mode, args.steps, args.warmup, False, R, H, torch)
+    value = tokens_per_step * args.steps / main_run["seconds"]
+    out = {
+        "metric": "training tokens/sec (all models, 1 MI355X)", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * main_run["seconds"] / args.steps, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: {n_models} GPT-2-small-shaped models (12L d768 H12 F3072 V50257), "
+                               f"B{cfg['B']} T{cfg['T']}, 2-layer shards alternated by Sharded-LRTF, bf16 MFMA + fp32 "
+                               "master/Adam, seeded N(0,0.02) weights, uniform tokens",
+                   "mode": args.mode, "shard_buffers": main_run["n_slots"],
+                   "tokens_per_step": tokens_per_step},
+        "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),
+                 "d2h_GB_per_step": round(main_run["d2h"] / args.steps / 1e9, 3),
+                 "h2d_GBps_over_wall": round(main_run["h2d"] / main_run["seconds"] / 1e9, 2),
+                 "d2h_GBps_over_wall": round(main_run["d2h"] / main_run["seconds"] / 1e9, 2)},
+        "final_losses": [round(x, 4) for x in main_run["losses"]],
+    }
+    if not args.no_extra:
+        other = "resident" if args.mode == "spill" else "spill"
+        o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch)
+        out[other] = {"value": round(tokens_per_step * args.steps / o["seconds"], 1), "unit": "tokens/s",
+                      "ms_per_step": round(1e3 * o["seconds"] / args.steps, 3), "shard_buffers": o["n_slots"]}
+        # per-kernel HIP-event timing over the same steps (resident buffers so that copies do not perturb kernels)
+        t = measure(cfg, n_models, "resident", args.steps, args.warmup, True, R, H, torch)
+        ks = sorted(t["kernels"], key=lambda k: -k["ms"])
+        total_ms = sum(k["ms"] for k in ks)
+        dom = ks[0]
+        if dom["flops"] > 0:
+            ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+            out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                               "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                               "kernel": dom["name"], "launches": dom["launches"],
+                               "avg_us": round(1e3 * dom["ms"] / dom["launches"], 2)}
+        else:
+            ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+            out["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                               "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": dom["name"],
+                               "launches": dom["launches"], "avg_us": round(1e3 * dom["ms"] / dom["launches"], 2)}
+        out["kernels"] = [
+            {"name": k["name"], "launches": k["launches"], "ms_per_step": round(k["ms"] / args.steps, 4),
+             "share": round(k["ms"] / total_ms, 4),
+             **({"TFLOPs": round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 1)} if k["flops"] > 0 else
+                {"GBps": round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1)})}
+            for k in ks]
+        gemm = [k for k in ks if k["flops"] > 0]
+        out["gemm_aggregate"] = {"TFLOPs": round(sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12, 1),
+                                 "frac_of_mfma_peak": round(sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                 "kernel_ms_per_step": round(total_ms / args.steps, 3)}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

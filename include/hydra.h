@@ -65,7 +65,7 @@ enum {
   HYDRA_FLAG_DRY_RUN = 1,    /* no HIP call is made: state machine, slot table and traces only (host tests) */
   HYDRA_FLAG_CKPT_SPILL = 2, /* boundary activations travel through host DRAM between visits                */
   HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
-  HYDRA_FLAG_TIMING = 8      /* record device-side start/stop events per task for hydra_get_stats            */
+  HYDRA_FLAG_TIMING = 8      /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
 };
 
 /* 'what' of hydra_shard_load_async */
@@ -139,7 +139,7 @@ typedef struct {
   int32_t n_slots;
   int32_t reserved;
   uint64_t slot_bytes, workspace_bytes, model_state_bytes;
-  double compute_ms, h2d_ms, d2h_ms; /* device time per stream, only with HYDRA_FLAG_TIMING  */
+  double reserved_ms[3];
 } hydra_stats;
 
 /* ---- context ------------------------------------------------------------ */
@@ -153,6 +153,15 @@ hydra_status hydra_sync(hydra_ctx *ctx);
  * functions that take no context). Never NULL. */
 const char *hydra_last_error(const hydra_ctx *ctx);
 hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out);
+
+/* Per-kernel timing (context created with HYDRA_FLAG_TIMING): entry 'index' of
+ * the table of kernels launched since the last reset - name, number of
+ * launches, summed HIP-event time on the launching stream, and the summed
+ * algorithmic flops and bytes of those launches.  Synchronises.  Returns 1 when
+ * index is past the end. */
+hydra_status hydra_kernel_stats(hydra_ctx *ctx, int32_t index, char name[64], uint64_t *launches,
+                                double *total_ms, double *flops, double *bytes);
+hydra_status hydra_kernel_stats_reset(hydra_ctx *ctx);
 
 /* ---- layout (pure functions of the model description) ------------------- */
 hydra_status hydra_model_layout(const hydra_model_desc *desc, hydra_layout *out);

@@ -124,6 +124,10 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
       return fail(nullptr, HYDRA_E_HIP, "no HIP device available");
     }
   }
+  if (!ctx->dry && (desc->flags & HYDRA_FLAG_TIMING)) {
+    ctx->prof = prof_create();
+    prof_activate(ctx->prof);
+  }
   *out = ctx;
   return HYDRA_OK;
 }
@@ -134,6 +138,7 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->s_compute);
     (void)hipStreamSynchronize(ctx->s_h2d);
     (void)hipStreamSynchronize(ctx->s_d2h);
+    prof_destroy(ctx->prof);
     for (Slot &s : ctx->slots) {
       if (s.ev_loaded) (void)hipEventDestroy(s.ev_loaded);
       if (s.ev_compute) (void)hipEventDestroy(s.ev_compute);

@@ -109,6 +109,7 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
 
 hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  ProfScope ps("fill_u32", s, 0, 4.0 * n);
   int64_t blocks = (n / 4 + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
@@ -118,6 +119,7 @@ hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s
 
 hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *wpe, float *x0, int M, int T, int d,
                             hipStream_t s) {
+  ProfScope ps("embed_fwd", s, 0, 12.0 * M * d);
   hipLaunchKernelGGL(embed_fwd_kernel, dim3(M), dim3(128), 0, s, tok, wte, wpe, x0, M, T, d);
   return hipGetLastError();
 }
@@ -127,6 +129,7 @@ hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, f
   if (B * T > EMB_MAXW * 32) return hipErrorInvalidValue;
   hipError_t e = launch_fill_u32((uint32_t *)dwte, 0u, (int64_t)V * d, s);
   if (e != hipSuccess) return e;
+  ProfScope ps("embed_bwd", s, 0, 8.0 * B * T * d + 4.0 * T * d);
   hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(B * T), dim3(256), 0, s, tok, dx0, dwte, B * T, d);
   const int64_t n = (int64_t)T * d;
   hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dx0, dwpe, B, T, d);
@@ -174,6 +177,7 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float *__restr
 hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, const float *beta, void *y, float *mean,
                                 float *rstd, int M, int d, hipStream_t s) {
   dim3 grid((M + 3) / 4), block(256);
+  ProfScope ps("layernorm_fwd", s, 0, (double)M * d * (4.0 + dt_size(dtype)) + 8.0 * M);
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(layernorm_fwd_kernel<bf16_t>, grid, block, 0, s, x, gamma, beta, (bf16_t *)y, mean, rstd, M, d);
   else
@@ -222,6 +226,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__re
 
 hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
                                    const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s) {
+  ProfScope ps("layernorm_bwd_dx", s, 0, (double)M * d * (dres ? 16.0 : 12.0));
   hipLaunchKernelGGL(layernorm_bwd_dx_kernel, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma, dres, dx, M,
                      d);
   return hipGetLastError();
@@ -284,6 +289,7 @@ hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, f
                          hipStream_t s) {
   const int nch = colsum_chunks(M);
   dim3 grid((N + 63) / 64, nch);
+  ProfScope ps("colsum", s, 0, (double)M * N * dt_size(in_dtype));
   if (in_dtype == DT_BF16)
     hipLaunchKernelGGL((colsum_pass1_kernel<bf16_t, 0>), grid, dim3(256), 0, s, (const bf16_t *)in, ld, nullptr,
                        nullptr, nullptr, scratch, M, N);
@@ -298,6 +304,7 @@ hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const fl
                                        float *dgamma, float *dbeta, float *scratch, int M, int d, hipStream_t s) {
   const int nch = colsum_chunks(M);
   dim3 grid((d + 63) / 64, nch);
+  ProfScope ps("layernorm_bwd_params", s, 0, 8.0 * M * d);
   hipLaunchKernelGGL((colsum_pass1_kernel<float, 1>), grid, dim3(256), 0, s, dy, (int64_t)d, x, mean, rstd, scratch, M,
                      d);
   hipLaunchKernelGGL(colsum_pass2_kernel, dim3((d + 255) / 256), dim3(256), 0, s, scratch, dgamma, dbeta, nch, d);
@@ -348,6 +355,7 @@ __global__ __launch_bounds__(256) void softmax_causal_bwd_kernel(const ActT *__r
 
 hipError_t launch_softmax_causal_fwd(int dtype, const float *S, void *P, int n_mat, int T, hipStream_t s) {
   const int64_t rows = (int64_t)n_mat * T;
+  ProfScope ps("softmax_causal_fwd", s, 0, (double)n_mat * (0.5 * T * (T + 1.0)) * (4.0 + dt_size(dtype)));
   dim3 grid((unsigned)((rows + 3) / 4));
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(softmax_causal_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, S, (bf16_t *)P, rows, T);
@@ -359,6 +367,7 @@ hipError_t launch_softmax_causal_fwd(int dtype, const float *S, void *P, int n_m
 hipError_t launch_softmax_causal_bwd(int dtype, const void *P, const float *dP, void *dS, int n_mat, int T,
                                      hipStream_t s) {
   const int64_t rows = (int64_t)n_mat * T;
+  ProfScope ps("softmax_causal_bwd", s, 0, (double)n_mat * (0.5 * T * (T + 1.0)) * (4.0 + 2.0 * dt_size(dtype)));
   dim3 grid((unsigned)((rows + 3) / 4));
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(softmax_causal_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)P, dP, (bf16_t *)dS,
@@ -415,6 +424,7 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float *__restr
 
 hipError_t launch_cross_entropy(int dtype, const float *logits, const int32_t *targets, float *row_loss, void *dlogits,
                                 int M, int V, int64_t ld, float inv_n, hipStream_t s) {
+  ProfScope ps("cross_entropy", s, 0, (double)M * V * (4.0 + dt_size(dtype)));
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(cross_entropy_kernel<bf16_t>, dim3(M), dim3(256), 0, s, logits, targets, row_loss,
                        (bf16_t *)dlogits, V, ld, inv_n);
@@ -490,6 +500,7 @@ hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *sha
                        double beta2, double eps, int64_t t, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   const float corr1 = (float)(1.0 - pow(beta1, (double)t)), corr2 = (float)(1.0 - pow(beta2, (double)t));
+  ProfScope ps("adam", s, 0, (double)n * (shadow ? 30.0 : 28.0));
   int64_t blocks = (n / 4 + 255) / 256;
   if (blocks > 8192) blocks = 8192;
   if (blocks < 1) blocks = 1;
@@ -517,6 +528,7 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict_
 
 hipError_t launch_cast_bf16(const float *in, bf16_t *out, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  ProfScope ps("cast_bf16", s, 0, 6.0 * n);
   int64_t blocks = (n / 4 + 255) / 256;
   if (blocks > 8192) blocks = 8192;
   if (blocks < 1) blocks = 1;
@@ -538,6 +550,7 @@ __global__ __launch_bounds__(256) void cast_transpose_bf16_kernel(const float *_
 }
 
 hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C, hipStream_t s) {
+  ProfScope ps("cast_transpose_bf16", s, 0, 6.0 * R * C);
   hipLaunchKernelGGL(cast_transpose_bf16_kernel, dim3((C + 63) / 64, (R + 63) / 64), dim3(256), 0, s, in, out, R, C);
   return hipGetLastError();
 }
@@ -553,6 +566,7 @@ __global__ void cast_act_kernel(const float *__restrict__ in, int64_t ld_in, Out
 hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C,
                            hipStream_t s) {
   dim3 grid(min(64, (C + 255) / 256), R);
+  ProfScope ps("cast_act", s, 0, (double)R * C * (4.0 + dt_size(dtype)));
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(cast_act_kernel<bf16_t>, grid, dim3(256), 0, s, in, ld_in, (bf16_t *)out, ld_out, R, C);
   else

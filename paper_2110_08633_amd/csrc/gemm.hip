@@ -323,6 +323,23 @@ static hipError_t launch_bf16_cfg(const GemmArgs &a, int ta, int tb, dim3 grid, 
   return hipGetLastError();
 }
 
+// algorithmic flops of a launch: causal products only count the triangle
+static double gemm_flops(const GemmDesc &d) {
+  const double nb = (double)d.nb1 * d.nb2;
+  if (d.causal == CAUSAL_SKIP_UPPER) return nb * 2.0 * d.K * (0.5 * d.M * (d.M + 1.0));
+  if (d.causal == CAUSAL_K_END || d.causal == CAUSAL_K_BEGIN) return nb * 2.0 * d.N * (0.5 * d.M * (d.M + 1.0));
+  return nb * 2.0 * d.M * d.N * d.K;
+}
+
+static const char *gemm_name(int dtype, int bn, int ta, int tb) {
+  static const char *n128[4] = {"gemm_bf16_128x128_nt", "gemm_bf16_128x128_nn", "gemm_bf16_128x128_tt",
+                                "gemm_bf16_128x128_tn"};
+  static const char *n64[4] = {"gemm_bf16_128x64_nt", "gemm_bf16_128x64_nn", "gemm_bf16_128x64_tt",
+                               "gemm_bf16_128x64_tn"};
+  if (dtype == DT_F32) return "gemm_f32_64x64";
+  return (bn == 128 ? n128 : n64)[ta * 2 + tb];
+}
+
 hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   if (d.M <= 0 || d.N <= 0 || d.nb1 * d.nb2 <= 0) return hipSuccess;
   GemmArgs a;
@@ -338,6 +355,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
     a.tiles_m = (d.M + FBM - 1) / FBM;
     a.tiles_n = (d.N + FBN - 1) / FBN;
     dim3 grid(a.tiles_m * a.tiles_n, nbatch);
+    ProfScope ps(gemm_name(DT_F32, 0, 0, 0), s, gemm_flops(d), 0);
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, a, d.ta, d.tb);
     return hipGetLastError();
   }
@@ -348,9 +366,11 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128) * nbatch;
   if (d.N > 64 && t128 >= 256) {
     a.tiles_m = (d.M + 127) / 128; a.tiles_n = (d.N + 127) / 128;
+    ProfScope ps(gemm_name(DT_BF16, 128, d.ta, d.tb), s, gemm_flops(d), 0);
     return launch_bf16_cfg<128, 128, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
   }
   a.tiles_m = (d.M + 127) / 128; a.tiles_n = (d.N + 63) / 64;
+  ProfScope ps(gemm_name(DT_BF16, 64, d.ta, d.tb), s, gemm_flops(d), 0);
   return launch_bf16_cfg<128, 64, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
 }
 

@@ -11,6 +11,13 @@
 
 namespace hydra {
 
+struct Profiler;
+Profiler *prof_create();
+void prof_destroy(Profiler *p);
+void prof_activate(Profiler *p);
+void prof_collect(Profiler *p);
+void prof_reset(Profiler *p);
+
 struct TensorInfo {
   std::string name;
   int64_t off, rows, cols;
@@ -95,6 +102,7 @@ struct hydra_ctx {
   int logits_owner = -1;
   float *logits = nullptr;  // inside the workspace; valid for logits_owner until the next HEAD forward
   hydra_stats stats;
+  hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
   std::string err;
 };
 

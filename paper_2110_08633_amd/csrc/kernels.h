@@ -20,6 +20,15 @@ enum {
 
 static inline size_t dt_size(int dt) { return dt == DT_BF16 ? 2 : 4; }
 
+// Brackets one kernel launch with two events when per-kernel timing is active
+// (no-op otherwise).  flops / bytes: algorithmic work of the launch.
+struct ProfScope {
+  ProfScope(const char *name, hipStream_t s, double flops, double bytes);
+  ~ProfScope();
+  hipStream_t stream_;
+  long idx_;
+};
+
 struct GemmDesc {
   int dtype = DT_BF16;
   int ta = 0, tb = 0;  // ta: A stored [K,M]; tb: B stored [K,N] (else [N,K])

@@ -58,7 +58,7 @@ class Stats(C.Structure):
                 ("n_load_hits", C.c_uint64), ("n_evictions", C.c_uint64), ("n_writebacks", C.c_uint64),
                 ("n_tasks", C.c_uint64), ("n_slots", C.c_int32), ("reserved", C.c_int32),
                 ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("model_state_bytes", C.c_uint64),
-                ("compute_ms", C.c_double), ("h2d_ms", C.c_double), ("d2h_ms", C.c_double)]
+                ("reserved_ms", C.c_double * 3)]
 
 
 _P = C.POINTER
@@ -71,6 +71,8 @@ SIGNATURES = {
     "hydra_sync": (_i32, [_vp]),
     "hydra_last_error": (C.c_char_p, [_vp]),
     "hydra_get_stats": (_i32, [_vp, _P(Stats)]),
+    "hydra_kernel_stats": (_i32, [_vp, _i32, C.c_char_p, _P(_u64), _P(_f64), _P(_f64), _P(_f64)]),
+    "hydra_kernel_stats_reset": (_i32, [_vp]),
     "hydra_model_layout": (_i32, [_P(ModelDesc), _P(Layout)]),
     "hydra_model_tensor": (_i32, [_P(ModelDesc), _i32, C.c_char_p, _P(_i64), _P(_i64), _P(_i64), _P(_i32)]),
     "hydra_shard_range": (_i32, [_P(ModelDesc), _i32, _P(_i64), _P(_i64)]),
@@ -159,7 +161,24 @@ def hydra_last_error(ctx=None):
 def hydra_get_stats(ctx):
     s = Stats()
     _check(lib.hydra_get_stats(ctx, C.byref(s)), ctx)
-    return {n: getattr(s, n) for n, _ in Stats._fields_}
+    return {n: getattr(s, n) for n, _ in Stats._fields_ if not n.startswith("reserved")}
+
+
+def hydra_kernel_stats(ctx):
+    """List of dicts(name, launches, ms, flops, bytes) since the last reset."""
+    out, i = [], 0
+    while True:
+        name = C.create_string_buffer(64)
+        n, ms, fl, by = _u64(), _f64(), _f64(), _f64()
+        r = _check(lib.hydra_kernel_stats(ctx, i, name, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)), ctx)
+        if r == 1:
+            return out
+        out.append(dict(name=name.value.decode(), launches=n.value, ms=ms.value, flops=fl.value, bytes=by.value))
+        i += 1
+
+
+def hydra_kernel_stats_reset(ctx):
+    return _check(lib.hydra_kernel_stats_reset(ctx), ctx)
 
 
 def hydra_model_layout(desc):
