@@ -75,98 +75,199 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs &g, int64_t coff, 
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.  256 threads = 4 wavefronts arranged WM x WN over a
-// BM x BN tile; K is consumed in slices of BK = 64 staged through LDS in
-// K-contiguous form [row][BK + 8] (the 16-byte pad makes the 128-bit operand
-// reads conflict-free).  Operands that are stored with the contraction index
-// strided (ta / tb) are transposed in registers on their way into LDS.
+// BM x BN tile of C.  K is consumed in slices of BK = 32:
+//   global -> registers : 16-byte loads, issued three slices ahead
+//   registers -> LDS    : one slice ahead, two LDS buffers, one barrier per slice
+//   LDS -> MFMA operands: ds_read_b128 for operands whose contraction index is
+//                         contiguous in memory, ds_read_tr16_b64 (transposing
+//                         read) for operands stored with it strided, so both
+//                         kinds sit in LDS exactly as they sit in memory
+// LDS tiles carry no padding; their 16-byte chunks are XOR-swizzled so that the
+// operand reads of 16 neighbouring lanes fall into distinct banks.
+// The MFMA is issued with the B fragment as first operand, which leaves every
+// lane with runs of 4 consecutive columns of one row of C: the epilogue then
+// stores 16-byte (fp32) or 8-byte (bf16) vectors.
 // ---------------------------------------------------------------------------
-constexpr int BK = 64;
-constexpr int LDSP = BK + 8;  // row pitch in elements
+constexpr int BK = 32;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-// K-contiguous source: rows x BK tile, 16-byte chunks
-template <int ROWS>
-struct TileKC {
-  static constexpr int NCH = ROWS * (BK / 8) / 256;  // chunks per thread
-  u32x4_t r[NCH];
-  __device__ __forceinline__ void load(const bf16_t *__restrict__ base, int64_t ld, int row0, int rows, int k0, int kend,
-                                       int tid) {
+// operands live in global memory: say so, or the loads become flat loads that also count as LDS traffic
+typedef const __attribute__((address_space(1))) u32x4_t *gvec_ptr;
+
+template <int R> __device__ __forceinline__ int rc_swz(int k) {
+  return (R / 8 >= 16) ? ((k & 3) << 2) : (((k >> 1) & 1) << 2);
+}
+
+// Global -> register -> LDS mover of one operand.  All per-thread addressing is
+// computed once: a slice load is base (uniform) + 32-bit per-thread offset.
+//   RCL = 0: memory is [rows][K] (contraction contiguous): LDS [row][32], chunk kc of row r at slot r*4 + (kc ^ ((r>>2)&3))
+//   RCL = 1: memory is [K][rows] (rows contiguous):        LDS [k][R],    chunk c of slice row k at slot k*(R/8) + (c ^ swz(k))
+// Rows beyond the matrix are redirected to a valid row: they only feed rows /
+// columns of C that are never stored.  The contraction tail is zero-filled.
+template <int R, int RCL>
+struct Mover {
+  static constexpr int N = R * 4 / 256;  // 16-byte chunks per thread and slice
+  static constexpr int CPK = R / 8;
+  const bf16_t *base;   // uniform: element (row0, kbeg) of the operand
+  int64_t kstep;        // uniform: elements per slice
+  uint32_t off[N];      // per-thread element offset inside a slice
+  int kloc[N];          // first contraction index of the chunk inside a slice
+  int slot[N];          // LDS element offset
+  __device__ __forceinline__ void init(const bf16_t *mat, int64_t ld, int row0, int rows, int kbeg, int tid) {
+    if (!RCL) {
+      base = mat + (int64_t)row0 * ld + kbeg;
+      kstep = BK;
+    } else {
+      base = mat + (int64_t)kbeg * ld + row0;
+      kstep = (int64_t)BK * ld;
+    }
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
+    for (int i = 0; i < N; ++i) {
       const int id = tid + i * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
+      if (!RCL) {
+        int row = id >> 2;
+        const int kc = id & 3;
+        slot[i] = (row * 4 + (kc ^ ((row >> 2) & 3))) * 8;
+        if (row0 + row >= rows) row = 0;
+        off[i] = (uint32_t)(row * ld + kc * 8);
+        kloc[i] = kc * 8;
+      } else {
+        const int k = id / CPK;
+        int c = id % CPK;
+        slot[i] = (k * CPK + (c ^ rc_swz<R>(k))) * 8;
+        if (row0 + c * 8 >= rows) c = 0;
+        off[i] = (uint32_t)(k * ld + c * 8);
+        kloc[i] = k;
+      }
+    }
+  }
+  // slice t (0-based from kbeg), known to lie entirely inside the contraction range
+  __device__ __forceinline__ void load_full(u32x4_t (&r)[N], int t) const {
+    const bf16_t *b = base + t * kstep;
+#pragma unroll
+    for (int i = 0; i < N; ++i) r[i] = *(gvec_ptr)(b + off[i]);
+  }
+  // any slice; krem = contraction steps left at the start of the slice
+  __device__ __forceinline__ void load_tail(u32x4_t (&r)[N], int t, int krem) const {
+    const bf16_t *b = base + t * kstep;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
       u32x4_t v = {0u, 0u, 0u, 0u};
-      if (row0 + row < rows && k0 + kc < kend) v = *(const u32x4_t *)(base + (int64_t)(row0 + row) * ld + k0 + kc);
+      if (kloc[i] < krem) v = *(gvec_ptr)(b + off[i]);
       r[i] = v;
     }
   }
-  __device__ __forceinline__ void store(bf16_t *lds, int tid) const {
+  __device__ __forceinline__ void store(const u32x4_t (&r)[N], bf16_t *lds) const {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int id = tid + i * 256;
-      const int row = id >> 3, kc = (id & 7) * 8;
-      *(u32x4_t *)(lds + row * LDSP + kc) = r[i];
-    }
+    for (int i = 0; i < N; ++i) *(u32x4_t *)(lds + slot[i]) = r[i];
   }
 };
 
-// row-contiguous source (stored [K][rows]): BK x ROWS tile read as 4(k) x 8(row)
-// blocks, transposed in registers, written as 8-byte pieces [row][4 k]
-template <int ROWS>
-struct TileRC {
-  static constexpr int TOTAL = (BK / 4) * (ROWS / 8);
-  static constexpr int NBLK = (TOTAL + 255) / 256;
-  static constexpr int RB = ROWS / 8;  // blocks along the row dimension
-  u32x4_t r[NBLK][4];
-  __device__ __forceinline__ void load(const bf16_t *__restrict__ base, int64_t ld, int row0, int rows, int k0, int kend,
-                                       int tid) {
-#pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      const int id = tid + i * 256;
-      const int rb = id % RB, kb = id / RB;
-      const bool rok = (TOTAL % 256 == 0 || id < TOTAL) && row0 + rb * 8 < rows;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int k = k0 + kb * 4 + q;
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (rok && k < kend) v = *(const u32x4_t *)(base + (int64_t)k * ld + row0 + rb * 8);
-        r[i][q] = v;
-      }
-    }
+// LDS element offsets of the MFMA operand for 32 rows starting at rb and the 16 contraction steps
+// kk16*16..+15 of a slice: lane L holds row rb + L%32, steps (L/32)*8 .. +7
+template <int R, int RCL>
+__device__ __forceinline__ void fragment_offsets(int rb, int kk16, int lane, int &o0, int &o1) {
+  if (!RCL) {
+    const int row = rb + (lane & 31), kc = kk16 * 2 + (lane >> 5);
+    o0 = (row * 4 + (kc ^ ((row >> 2) & 3))) * 8;
+    o1 = 0;
+  } else {
+    // transposing read: within each group of 16 lanes, lane i receives element i%4 of the 8 bytes
+    // addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of the group
+    constexpr int CPK = R / 8;
+    const int G = lane >> 4, sl = lane & 15;
+    const int k = kk16 * 16 + (G >> 1) * 8 + (sl >> 2);
+    const int m = rb + 16 * (G & 1) + 4 * (sl & 3);
+    const int c = m >> 3, half = (m >> 2) & 1;
+    o0 = (k * CPK + (c ^ rc_swz<R>(k))) * 8 + half * 4;
+    o1 = ((k + 4) * CPK + (c ^ rc_swz<R>(k + 4))) * 8 + half * 4;
   }
-  __device__ __forceinline__ void store(bf16_t *lds, int tid) const {
-#pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      const int id = tid + i * 256;
-      if (TOTAL % 256 != 0 && id >= TOTAL) continue;
-      const int rb = id % RB, kb = id / RB;
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        // dword a of each source row holds rows (2a, 2a+1) of the block for one k
-        u32x2_t lo, hi;
-        lo.x = __builtin_amdgcn_perm(r[i][1][a], r[i][0][a], 0x05040100u);
-        lo.y = __builtin_amdgcn_perm(r[i][3][a], r[i][2][a], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(r[i][1][a], r[i][0][a], 0x07060302u);
-        hi.y = __builtin_amdgcn_perm(r[i][3][a], r[i][2][a], 0x07060302u);
-        *(u32x2_t *)(lds + (rb * 8 + 2 * a) * LDSP + kb * 4) = lo;
-        *(u32x2_t *)(lds + (rb * 8 + 2 * a + 1) * LDSP + kb * 4) = hi;
-      }
-    }
+}
+
+template <int RCL>
+__device__ __forceinline__ bf16x8_t fragment(const bf16_t *lds, int o0, int o1) {
+  if (!RCL) {
+    return *(const bf16x8_t *)(lds + o0);
+  } else {
+    const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(lds + o0));
+    const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(lds + o1));
+    union { s16x4_t h[2]; bf16x8_t f; } u;
+    u.h[0] = v0;
+    u.h[1] = v1;
+    return u.f;
   }
-};
+}
 
-template <int ROWS, int T> struct TileSel { typedef TileKC<ROWS> type; };
-template <int ROWS> struct TileSel<ROWS, 1> { typedef TileRC<ROWS> type; };
+// 4 consecutive columns of one row of C
+template <typename ActT>
+__device__ __forceinline__ void epilogue_store4(const GemmArgs &g, int64_t coff, int row, int col, const float *acc,
+                                                bool vec) {
+  if (!vec || col + 3 >= g.N) {
+#pragma unroll 1
+    for (int e = 0; e < 4; ++e)
+      if (col + e < g.N) epilogue_store<ActT>(g, coff, row, col + e, acc[e]);
+    return;
+  }
+  float v[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = acc[e] * g.alpha;
+  if (g.bias) {
+    const f32x4_t b = *(const f32x4_t *)(g.bias + col);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += b[e];
+  }
+  const int64_t idx = coff + (int64_t)row * g.ldc + col;
+  if (g.epi == EPI_GELU) {
+    u32x2_t u, h;
+    u.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+    u.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+    h.x = (uint32_t)f2bf(gelu_f(v[0])) | ((uint32_t)f2bf(gelu_f(v[1])) << 16);
+    h.y = (uint32_t)f2bf(gelu_f(v[2])) | ((uint32_t)f2bf(gelu_f(v[3])) << 16);
+    *(u32x2_t *)((bf16_t *)g.out_act + idx) = u;
+    *(u32x2_t *)((bf16_t *)g.out_act2 + idx) = h;
+    return;
+  }
+  if (g.epi == EPI_DGELU) {
+    const u32x2_t a = *(const u32x2_t *)((const bf16_t *)g.aux + idx);
+    v[0] *= dgelu_f(__uint_as_float(a.x << 16));
+    v[1] *= dgelu_f(__uint_as_float(a.x & 0xffff0000u));
+    v[2] *= dgelu_f(__uint_as_float(a.y << 16));
+    v[3] *= dgelu_f(__uint_as_float(a.y & 0xffff0000u));
+  }
+  if (g.resid) {
+    const f32x4_t r = *(const f32x4_t *)(g.resid + idx);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += r[e];
+  }
+  if (g.out_f32) {
+    f32x4_t o = {v[0], v[1], v[2], v[3]};
+    *(f32x4_t *)(g.out_f32 + idx) = o;
+  }
+  if (g.out_act) {
+    u32x2_t o;
+    o.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+    o.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+    *(u32x2_t *)((bf16_t *)g.out_act + idx) = o;
+  }
+}
 
-template <int BM, int BN, int WM, int WN, int TA, int TB>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
-  constexpr int MI = BM / WM / 32, NJ = BN / WN / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDSP];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDSP];
+template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
+  static_assert(D == 2 || D == 4, "slices in flight");
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int MI = WTM / 32, NJ = WTN / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * BK];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int tile = blockIdx.x;
+  // consecutive workgroup ids are dealt round-robin to the 8 XCDs; renumber so that each XCD (own L2)
+  // works on a contiguous run of tiles, which share operand rows
+  const int nt = gridDim.x, bid = blockIdx.x;
+  const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
+  const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
   const int tm = tile / g.tiles_n, tn = tile % g.tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
   if (g.causal == CAUSAL_SKIP_UPPER && n0 > m0 + BM - 1) return;
@@ -177,10 +278,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
 
   int kbeg = 0, kend = g.K;
   if (g.causal == CAUSAL_K_END) kend = min(g.K, m0 + BM);
-  if (g.causal == CAUSAL_K_BEGIN) kbeg = (m0 / BK) * BK;
+  if (g.causal == CAUSAL_K_BEGIN) kbeg = m0;
+  const int nk = (kend - kbeg + BK - 1) / BK;
 
-  typename TileSel<BM, TA>::type ta;
-  typename TileSel<BN, TB>::type tb;
+  Mover<BM, TA> ma;
+  Mover<BN, TB> mb;
+  ma.init(A, g.lda, m0, g.M, kbeg, tid);
+  mb.init(B, g.ldb, n0, g.N, kbeg, tid);
+  u32x4_t ra[D][Mover<BM, TA>::N], rb[D][Mover<BN, TB>::N];
+
+  int ao[MI][BK / 16][2], bo[NJ][BK / 16][2];
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) fragment_offsets<BM, TA>(wm * WTM + i * 32, kk, lane, ao[i][kk][0], ao[i][kk][1]);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) fragment_offsets<BN, TB>(wn * WTN + j * 32, kk, lane, bo[j][kk][0], bo[j][kk][1]);
+  }
 
   f32x16_t acc[MI][NJ];
 #pragma unroll
@@ -190,56 +304,78 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = (kend - kbeg + BK - 1) / BK;
-  if (nk > 0) {
-    ta.load(A, g.lda, m0, g.M, kbeg, kend, tid);
-    tb.load(B, g.ldb, n0, g.N, kbeg, kend, tid);
-    ta.store(As[0], tid);
-    tb.store(Bs[0], tid);
-  }
-  __syncthreads();
-  const int arow = (wm * (BM / WM) + (lane & 31)) * LDSP + (lane >> 5) * 8;
-  const int brow = (wn * (BN / WN) + (lane & 31)) * LDSP + (lane >> 5) * 8;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      ta.load(A, g.lda, m0, g.M, kbeg + (kt + 1) * BK, kend, tid);
-      tb.load(B, g.ldb, n0, g.N, kbeg + (kt + 1) * BK, kend, tid);
-    }
-    const bf16_t *as = As[cur], *bs = Bs[cur];
+  const int klen = kend - kbeg;
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
+  for (int p = 0; p < D; ++p) {
+    ma.load_tail(ra[p], p, klen - p * BK);
+    mb.load_tail(rb[p], p, klen - p * BK);
+  }
+  ma.store(ra[0], As[0]);
+  mb.store(rb[0], Bs[0]);
+  __syncthreads();
+
+  auto compute = [&](const bf16_t *as, const bf16_t *bs) {
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8_t af[MI], bfr[NJ];
 #pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t *)(as + arow + i * 32 * LDSP + kk);
+      for (int i = 0; i < MI; ++i) af[i] = fragment<TA>(as, ao[i][kk][0], ao[i][kk][1]);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) bfr[j] = *(const bf16x8_t *)(bs + brow + j * 32 * LDSP + kk);
+      for (int j = 0; j < NJ; ++j) bfr[j] = fragment<TB>(bs, bo[j][kk][0], bo[j][kk][1]);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) {
-      ta.store(As[cur ^ 1], tid);
-      tb.store(Bs[cur ^ 1], tid);
+  };
+
+  // Step for slice u = t + j: request slice u + D into the register set that slice u left, move slice u + 1 from
+  // registers to the other LDS buffer, multiply slice u out of LDS buffer u & 1.  D slices are in flight.  Both
+  // loops are free of conditions around the MFMAs, so the accumulators never move; the drain loop zero-fills
+  // slices past the end of the contraction range (at most D - 1 all-zero slices are multiplied).
+  int t = 0;
+  for (; t + 2 * D + 1 <= nk; t += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      ma.load_full(ra[j], t + j + D);
+      mb.load_full(rb[j], t + j + D);
+      ma.store(ra[(j + 1) % D], As[(j + 1) & 1]);
+      mb.store(rb[(j + 1) % D], Bs[(j + 1) & 1]);
+      compute(As[j & 1], Bs[j & 1]);
+      __syncthreads();
     }
-    __syncthreads();
+  }
+  for (; t < nk; t += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      ma.load_tail(ra[j], t + j + D, klen - (t + j + D) * BK);
+      mb.load_tail(rb[j], t + j + D, klen - (t + j + D) * BK);
+      ma.store(ra[(j + 1) % D], As[(j + 1) & 1]);
+      mb.store(rb[(j + 1) % D], Bs[(j + 1) & 1]);
+      compute(As[j & 1], Bs[j & 1]);
+      __syncthreads();
+    }
   }
 
-  // accumulator element r of a 32x32 result: row (r/4)*8 + (lane/32)*4 + r%4, column lane%32
+  // lane L of a 32x32 result (B fragment first): row of C = L%32, columns (r/4)*8 + (L/32)*4 + r%4
+  const bool vec = ((g.ldc & 3) == 0) && ((coff & 3) == 0) &&
+                   ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
+                   ((((uintptr_t)g.out_act | (uintptr_t)g.out_act2 | (uintptr_t)g.aux) & 7) == 0);
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+  for (int i = 0; i < MI; ++i) {
+    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
+    if (row >= g.M) continue;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const int col = n0 + wn * (BN / WN) + j * 32 + (lane & 31);
-      if (col >= g.N) continue;
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * (BM / WM) + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row < g.M) epilogue_store<bf16_t>(g, coff, row, col, acc[i][j][r]);
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn * WTN + j * 32 + q * 8 + (lane >> 5) * 4;
+        if (col >= g.N) continue;
+        float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        epilogue_store4<bf16_t>(g, coff, row, col, v, vec);
       }
-    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -314,12 +450,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g, int ta,
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int D>
 static hipError_t launch_bf16_cfg(const GemmArgs &a, int ta, int tb, dim3 grid, hipStream_t s) {
-  if (ta == 0 && tb == 0) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 0, 0>), grid, dim3(256), 0, s, a);
-  else if (ta == 0 && tb == 1) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 0, 1>), grid, dim3(256), 0, s, a);
-  else if (ta == 1 && tb == 1) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 1, 1>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 1, 0>), grid, dim3(256), 0, s, a);
+  if (ta == 0 && tb == 0) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 0, 0, D>), grid, dim3(256), 0, s, a);
+  else if (ta == 0 && tb == 1) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 0, 1, D>), grid, dim3(256), 0, s, a);
+  else if (ta == 1 && tb == 1) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 1, 1, D>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 1, 0, D>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
@@ -367,11 +503,13 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   if (d.N > 64 && t128 >= 256) {
     a.tiles_m = (d.M + 127) / 128; a.tiles_n = (d.N + 127) / 128;
     ProfScope ps(gemm_name(DT_BF16, 128, d.ta, d.tb), s, gemm_flops(d), 0);
-    return launch_bf16_cfg<128, 128, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
+    if (d.K <= 4 * BK) return launch_bf16_cfg<128, 128, 2, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
+    return launch_bf16_cfg<128, 128, 2, 2, 4>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
   }
   a.tiles_m = (d.M + 127) / 128; a.tiles_n = (d.N + 63) / 64;
   ProfScope ps(gemm_name(DT_BF16, 64, d.ta, d.tb), s, gemm_flops(d), 0);
-  return launch_bf16_cfg<128, 64, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
+  if (d.K <= 4 * BK) return launch_bf16_cfg<128, 64, 2, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
+  return launch_bf16_cfg<128, 64, 2, 2, 4>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
 }
 
 }  // namespace hydra
