@@ -8,7 +8,7 @@ Sharded-LRTF scheduler.  One step = one minibatch of every model through the
 whole path: promote shard, forward visit, checkpoint, backward visit with
 recomputation, Adam, demote.
 
-Default mode "spill": three shard buffers, so every shard's state streams in
+Default mode "spill": four shard buffers (one computing, one filling, two draining), so every shard's state streams in
 from pinned host DRAM before each visit and the updated state streams back.
 Mode "resident": as many buffers as shards (state crosses the link once).
 
@@ -35,10 +35,14 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBPS = 8000.0
 
 
+SPILL_SLOTS = 4
+EXTRA_FLAGS = 0
+
+
 def make_session(cfg, n_models, mode, timing, R, H):
     n_shards = n_models * (cfg["L"] // cfg["k"] + 2)
-    slots = 3 if mode == "spill" else n_shards
-    flags = H.FLAG_TIMING if timing else 0
+    slots = SPILL_SLOTS if mode == "spill" else n_shards
+    flags = (H.FLAG_TIMING if timing else 0) | EXTRA_FLAGS
     sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots), flags=flags, max_slots=slots)
     recs = []
     for m in range(n_models):
@@ -57,6 +61,7 @@ def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     H.hydra_sched_run(sch, toks, tgts, sess.ctx)
+    run_steps.enqueue_s = time.perf_counter() - t0
     H.hydra_sync(sess.ctx)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -78,7 +83,7 @@ def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch):
     sess.close()
     del sess
     torch.cuda.empty_cache()
-    return dict(seconds=dt, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
+    return dict(seconds=dt, enqueue_seconds=run_steps.enqueue_s, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
                 n_slots=st1["n_slots"], kernels=kst, losses=losses)
 
 
@@ -111,7 +116,11 @@ def main():
     ap.add_argument("--config", default="gpt2s")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the second mode and the timing pass")
+    ap.add_argument("--slots", type=int, default=4, help="shard buffers in spill mode")
+    ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
     args = ap.parse_args()
+    global SPILL_SLOTS, EXTRA_FLAGS
+    SPILL_SLOTS = args.slots
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the method shards over host DRAM, not over GPUs); "
               "use --gpus 1", file=sys.stderr)
@@ -119,6 +128,8 @@ def main():
     import torch
     from paper_2110_08633_amd import hydra as H, runtime as R
     assert torch.cuda.is_available(), "no GPU visible"
+    if args.d2h_memcpy:
+        EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
     cfg = SI.CONFIGS[args.config]
     n_models = cfg["n_models"]
     tokens_per_step = n_models * cfg["B"] * cfg["T"]
@@ -128,7 +139,8 @@ def main():
     out = {
         "metric": "training tokens/sec (all models, 1 MI355X)", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(1e3 * main_run["seconds"] / args.steps, 3), "higher_is_better": True,
+        "ms_per_step": round(1e3 * main_run["seconds"] / args.steps, 3),
+        "host_enqueue_ms_per_step": round(1e3 * main_run["enqueue_seconds"] / args.steps, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: {n_models} GPT-2-small-shaped models (12L d768 H12 F3072 V50257), "
                                f"B{cfg['B']} T{cfg['T']}, 2-layer shards alternated by Sharded-LRTF, bf16 MFMA + fp32 "

@@ -65,7 +65,8 @@ enum {
   HYDRA_FLAG_DRY_RUN = 1,    /* no HIP call is made: state machine, slot table and traces only (host tests) */
   HYDRA_FLAG_CKPT_SPILL = 2, /* boundary activations travel through host DRAM between visits                */
   HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
-  HYDRA_FLAG_TIMING = 8      /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
+  HYDRA_FLAG_TIMING = 8,     /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
+  HYDRA_FLAG_D2H_MEMCPY = 16 /* demote with hipMemcpyAsync instead of the library's own copy kernel             */
 };
 
 /* 'what' of hydra_shard_load_async */

@@ -36,6 +36,30 @@ Slot *slot_for(hydra_ctx *ctx, int model, int shard) {
   return i < 0 ? nullptr : &ctx->slots[i];
 }
 
+hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes) {
+  if (ctx->dry) return HYDRA_OK;
+  if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)
+    HYDRA_HIP(ctx, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, ctx->s_d2h));
+  else
+    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, ctx->s_d2h));
+  return HYDRA_OK;
+}
+
+// device-side address of caller memory that must be page-locked and mapped
+static hydra_status mapped_pointer(hydra_ctx *ctx, const void *host, const char *what, float **out) {
+  *out = (float *)host;
+  if (ctx->dry || !host) return HYDRA_OK;
+  hipPointerAttribute_t at;
+  hipError_t e = hipPointerGetAttributes(&at, host);
+  if (e != hipSuccess || at.type != hipMemoryTypeHost || !at.devicePointer) {
+    (void)hipGetLastError();
+    return fail(ctx, HYDRA_E_INVAL, std::string(what) + " is not page-locked host memory");
+  }
+  if (((uintptr_t)at.devicePointer) & 15) return fail(ctx, HYDRA_E_INVAL, std::string(what) + " must be 16-byte aligned");
+  *out = (float *)at.devicePointer;
+  return HYDRA_OK;
+}
+
 static hydra_status make_event(hydra_ctx *ctx, hipEvent_t *ev) {
   if (ctx->dry) return HYDRA_OK;
   HYDRA_HIP(ctx, hipEventCreateWithFlags(ev, hipEventDisableTiming));
@@ -196,6 +220,13 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   }
   m->desc = *desc;
   m->host = *host;
+  if ((st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master)) ||
+      (st = mapped_pointer(ctx, host->adam_m, "adam_m", &m->host_dev.adam_m)) ||
+      (st = mapped_pointer(ctx, host->adam_v, "adam_v", &m->host_dev.adam_v)) ||
+      (st = mapped_pointer(ctx, host->ckpt, "ckpt", &m->host_dev.ckpt))) {
+    delete m;
+    return st;
+  }
   m->dtype = desc->dtype;
   const ModelShape &s = m->sh;
   const uint64_t act = (uint64_t)s.M * s.d * 4;
@@ -361,9 +392,11 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
   if ((what & HYDRA_SPILL_WRITEBACK) && sl->dirty) {
     if (!ctx->dry) {
       if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
-      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.master + off, sl->w, cnt * 4, hipMemcpyDeviceToHost, ctx->s_d2h));
-      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.adam_m + off, sl->m, cnt * 4, hipMemcpyDeviceToHost, ctx->s_d2h));
-      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.adam_v + off, sl->v, cnt * 4, hipMemcpyDeviceToHost, ctx->s_d2h));
+      hydra_status cs;
+      if ((cs = copy_d2h(ctx, m->host.master + off, m->host_dev.master + off, sl->w, cnt * 4)) ||
+          (cs = copy_d2h(ctx, m->host.adam_m + off, m->host_dev.adam_m + off, sl->m, cnt * 4)) ||
+          (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4)))
+        return cs;
       HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
     }
     sl->spill_pending = true;
@@ -408,6 +441,7 @@ static hydra_status end_task(hydra_ctx *ctx, Model *m, Slot *sl) {
     HYDRA_HIP(ctx, hipEventRecord(m->ev_last_compute, ctx->s_compute));
   }
   sl->compute_pending = true;
+  sl->last_use = ++ctx->use_counter;
   m->compute_pending = true;
   ctx->stats.n_tasks++;
   return HYDRA_OK;
@@ -432,8 +466,9 @@ hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
     const uint64_t bytes = (uint64_t)m->sh.M * m->sh.d * 4;
     if (!ctx->dry) {
       HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, m->ev_last_compute, 0));
-      HYDRA_HIP(ctx, hipMemcpyAsync(m->host.ckpt + (uint64_t)shard * m->sh.M * m->sh.d, m->ckpt[shard], bytes,
-                                    hipMemcpyDeviceToHost, ctx->s_d2h));
+      const uint64_t eo = (uint64_t)shard * m->sh.M * m->sh.d;
+      hydra_status cs = copy_d2h(ctx, m->host.ckpt + eo, m->host_dev.ckpt + eo, m->ckpt[shard], bytes);
+      if (cs) return cs;
       HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_d2h[shard & 1], ctx->s_d2h));
     }
     m->ckpt_d2h_pending[shard & 1] = true;

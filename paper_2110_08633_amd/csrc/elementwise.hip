@@ -509,6 +509,33 @@ hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *sha
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------ link copy
+// Streams a device buffer into page-locked host memory (mapped into the device
+// address space) with plain 16-byte vector stores.  A small grid suffices: the
+// host link, not the CUs, bounds it; the rest of the chip stays free for the
+// compute stream.
+__global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                           int64_t n16, uint8_t *dst_tail, const uint8_t *src_tail,
+                                                           int tail) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  if (blockIdx.x == 0 && threadIdx.x < tail) dst_tail[threadIdx.x] = src_tail[threadIdx.x];
+}
+
+hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if ((((uintptr_t)dst_mapped) | ((uintptr_t)src)) & 15) return hipErrorInvalidValue;
+  const int64_t n16 = (int64_t)(bytes / 16);
+  const int tail = (int)(bytes % 16);
+  int64_t blocks = (n16 + 255) / 256;
+  if (blocks > 128) blocks = 128;
+  if (blocks < 1) blocks = 1;
+  ProfScope ps("copy_to_host", s, 0, (double)bytes);
+  hipLaunchKernelGGL(copy_to_host_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4 *)dst_mapped, (const uint4 *)src,
+                     n16, (uint8_t *)dst_mapped + n16 * 16, (const uint8_t *)src + n16 * 16, tail);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ casts
 __global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out,
                                                         int64_t n) {

@@ -51,11 +51,13 @@ struct Slot {
   bool need_wait_load = false;  // a copy into this slot was enqueued since the compute stream last waited
   hipEvent_t ev_loaded = nullptr, ev_compute = nullptr, ev_spilled = nullptr;
   bool compute_pending = false, spill_pending = false;
+  uint64_t last_use = 0;  // value of the context's task counter when a task last ran on this buffer
 };
 
 struct Model {
   hydra_model_desc desc;
   hydra_host_state host;
+  hydra_host_state host_dev;  // device-side mappings of the same page-locked arrays
   ModelShape sh;
   int dtype;
   // device state carved from the arena
@@ -102,6 +104,7 @@ struct hydra_ctx {
   int logits_owner = -1;
   float *logits = nullptr;  // inside the workspace; valid for logits_owner until the next HEAD forward
   hydra_stats stats;
+  uint64_t use_counter = 0;
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
   std::string err;
 };
@@ -114,6 +117,8 @@ void set_global_error(const std::string &msg);
 const char *global_error();
 hydra_status ensure_planned(hydra_ctx *ctx);
 Slot *slot_for(hydra_ctx *ctx, int model, int shard);
+// device -> host copy on the d2h stream: own copy kernel, or hipMemcpyAsync with HYDRA_FLAG_D2H_MEMCPY
+hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes);
 
 // executor (exec.cpp): enqueue the kernels of one visit on the compute stream
 hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);

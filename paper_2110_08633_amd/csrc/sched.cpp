@@ -78,8 +78,13 @@ hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
     bool has_free = false;
     for (const Slot &sl : ctx->slots) has_free |= sl.model < 0;
     if (!has_free) {
-      int victim = -1;
+      // Candidates are the buffers not needed again soon; among them the one idle longest goes first, because its
+      // write-back has had the most time to finish (the promote waits for it).  If every buffer is needed soon, the
+      // one whose next use is furthest away is taken.
+      int victim = -1, oldest = -1;
       size_t far = 0;
+      uint64_t oldest_use = ~0ull;
+      const size_t soon = 2 * ctx->slots.size();
       for (size_t j = 0; j < ctx->slots.size(); ++j) {
         const Slot &sl = ctx->slots[j];
         if (sl.model == keep_model && sl.shard == keep_shard) continue;  // in use by the running task
@@ -88,7 +93,9 @@ hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
           if (s->model_id[m] == sl.model) local = m;
         const size_t nu = local < 0 ? (size_t)-1 : next_use(s, i, local, sl.shard);
         if (victim < 0 || nu > far) { victim = (int)j; far = nu; }
+        if ((nu == (size_t)-1 || nu - i > soon) && sl.last_use < oldest_use) { oldest = (int)j; oldest_use = sl.last_use; }
       }
+      if (oldest >= 0) victim = oldest;
       if (victim < 0) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the prefetch");
       const Slot &v = ctx->slots[victim];
       st = hydra_shard_spill(ctx, v.model, v.shard, HYDRA_SPILL_WRITEBACK | HYDRA_SPILL_EVICT);
