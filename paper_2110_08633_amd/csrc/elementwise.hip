@@ -4,6 +4,7 @@
 // rows (bias / gain gradients) are done in two passes with a fixed summation
 // order so that results do not depend on scheduling.
 #include <cmath>
+#include <cstdlib>
 
 #include "kernels.h"
 
@@ -528,7 +529,12 @@ hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, 
   const int64_t n16 = (int64_t)(bytes / 16);
   const int tail = (int)(bytes % 16);
   int64_t blocks = (n16 + 255) / 256;
-  if (blocks > 128) blocks = 128;
+  static const int max_blocks = [] {
+    const char *e = getenv("HYDRA_COPY_BLOCKS");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 128;
+  }();
+  if (blocks > max_blocks) blocks = max_blocks;
   if (blocks < 1) blocks = 1;
   ProfScope ps("copy_to_host", s, 0, (double)bytes);
   hipLaunchKernelGGL(copy_to_host_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4 *)dst_mapped, (const uint4 *)src,

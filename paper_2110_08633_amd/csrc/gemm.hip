@@ -5,6 +5,8 @@
 // The linear layers of a block (y = x*W + b), their input gradients
 // (dx = dy*W^T) and weight gradients (dW = x^T*dy) and the batched attention
 // products are all instances of C = alpha * op(A) * op(B) with a row-major C.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace hydra {
@@ -75,7 +77,7 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs &g, int64_t coff, 
 
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel.  256 threads = 4 wavefronts arranged WM x WN over a
-// BM x BN tile of C.  K is consumed in slices of BK = 32:
+// BM x BN tile of C.  K is consumed in slices of BK = 64:
 //   global -> registers : 16-byte loads, issued three slices ahead
 //   registers -> LDS    : one slice ahead, two LDS buffers, one barrier per slice
 //   LDS -> MFMA operands: ds_read_b128 for operands whose contraction index is
@@ -88,7 +90,10 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs &g, int64_t coff, 
 // lane with runs of 4 consecutive columns of one row of C: the epilogue then
 // stores 16-byte (fp32) or 8-byte (bf16) vectors.
 // ---------------------------------------------------------------------------
-constexpr int BK = 32;
+constexpr int BK = 64;
+constexpr int CPR = BK / 8;  // 16-byte chunks per row of a contraction-contiguous tile
+// swizzle of a contraction-contiguous tile: 16 neighbouring rows must land in 16 distinct 16-byte bank groups
+__device__ __forceinline__ int kc_swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
@@ -101,13 +106,13 @@ template <int R> __device__ __forceinline__ int rc_swz(int k) {
 
 // Global -> register -> LDS mover of one operand.  All per-thread addressing is
 // computed once: a slice load is base (uniform) + 32-bit per-thread offset.
-//   RCL = 0: memory is [rows][K] (contraction contiguous): LDS [row][32], chunk kc of row r at slot r*4 + (kc ^ ((r>>2)&3))
+//   RCL = 0: memory is [rows][K] (contraction contiguous): LDS [row][BK], chunk kc of row r at slot r*CPR + (kc ^ kc_swz(r))
 //   RCL = 1: memory is [K][rows] (rows contiguous):        LDS [k][R],    chunk c of slice row k at slot k*(R/8) + (c ^ swz(k))
 // Rows beyond the matrix are redirected to a valid row: they only feed rows /
 // columns of C that are never stored.  The contraction tail is zero-filled.
 template <int R, int RCL>
 struct Mover {
-  static constexpr int N = R * 4 / 256;  // 16-byte chunks per thread and slice
+  static constexpr int N = R * CPR / 256;  // 16-byte chunks per thread and slice
   static constexpr int CPK = R / 8;
   const bf16_t *base;   // uniform: element (row0, kbeg) of the operand
   int64_t kstep;        // uniform: elements per slice
@@ -126,9 +131,9 @@ struct Mover {
     for (int i = 0; i < N; ++i) {
       const int id = tid + i * 256;
       if (!RCL) {
-        int row = id >> 2;
-        const int kc = id & 3;
-        slot[i] = (row * 4 + (kc ^ ((row >> 2) & 3))) * 8;
+        int row = id / CPR;
+        const int kc = id % CPR;
+        slot[i] = (row * CPR + (kc ^ kc_swz(row))) * 8;
         if (row0 + row >= rows) row = 0;
         off[i] = (uint32_t)(row * ld + kc * 8);
         kloc[i] = kc * 8;
@@ -170,7 +175,7 @@ template <int R, int RCL>
 __device__ __forceinline__ void fragment_offsets(int rb, int kk16, int lane, int &o0, int &o1) {
   if (!RCL) {
     const int row = rb + (lane & 31), kc = kk16 * 2 + (lane >> 5);
-    o0 = (row * 4 + (kc ^ ((row >> 2) & 3))) * 8;
+    o0 = (row * CPR + (kc ^ kc_swz(row))) * 8;
     o1 = 0;
   } else {
     // transposing read: within each group of 16 lanes, lane i receives element i%4 of the 8 bytes
@@ -252,13 +257,31 @@ __device__ __forceinline__ void epilogue_store4(const GemmArgs &g, int64_t coff,
   }
 }
 
+#ifdef HYDRA_GEMM_TRACE
+__device__ unsigned long long g_gemm_trace[8192];
+#define TRACE_STAMP(slot)                                                                     \
+  do {                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && trace_n < 8190)             \
+      g_gemm_trace[trace_n++] = ((unsigned long long)(slot) << 56) | (__builtin_amdgcn_s_memtime() & 0xffffffffffffffull); \
+    __builtin_amdgcn_sched_barrier(0);                                                        \
+  } while (0)
+#else
+#define TRACE_STAMP(slot)
+#endif
+
 template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
-  static_assert(D == 2 || D == 4, "slices in flight");
+#ifdef HYDRA_GEMM_TRACE
+  int trace_n = 0;
+#endif
+  static_assert(D >= 2 && D % 2 == 0, "slices in flight");
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int MI = WTM / 32, NJ = WTN / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * BK];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * BK];
+  // one LDS block: two buffers per operand during the K loop, per-wavefront staging of C in the epilogue
+  __shared__ __attribute__((aligned(16))) bf16_t lds_all[2 * (BM + BN) * BK];
+  bf16_t *const As[2] = {lds_all, lds_all + BM * BK};
+  bf16_t *const Bs[2] = {lds_all + 2 * BM * BK, lds_all + 2 * BM * BK + BN * BK};
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -314,20 +337,25 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   mb.store(rb[0], Bs[0]);
   __syncthreads();
 
+  // All operand fragments of a slice are requested from LDS before the first MFMA: with one wavefront per SIMD
+  // nothing else hides the LDS latency, and LDS returns data in order, so the MFMAs start as the first arrive.
   auto compute = [&](const bf16_t *as, const bf16_t *bs) {
+    bf16x8_t af[BK / 16][MI], bfr[BK / 16][NJ];
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[MI], bfr[NJ];
 #pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = fragment<TA>(as, ao[i][kk][0], ao[i][kk][1]);
+      for (int i = 0; i < MI; ++i) af[kk][i] = fragment<TA>(as, ao[i][kk][0], ao[i][kk][1]);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) bfr[j] = fragment<TB>(bs, bo[j][kk][0], bo[j][kk][1]);
+      for (int j = 0; j < NJ; ++j) bfr[kk][j] = fragment<TB>(bs, bo[j][kk][0], bo[j][kk][1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the scheduler from sinking the reads between the MFMAs
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk)
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-    }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
   };
 
   // Step for slice u = t + j: request slice u + D into the register set that slice u left, move slice u + 1 from
@@ -335,15 +363,24 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   // loops are free of conditions around the MFMAs, so the accumulators never move; the drain loop zero-fills
   // slices past the end of the contraction range (at most D - 1 all-zero slices are multiplied).
   int t = 0;
+  if (nk <= 1) {  // a single slice (the head-width contractions of attention): nothing to pipeline
+    compute(As[0], Bs[0]);
+    t = nk;
+  }
   for (; t + 2 * D + 1 <= nk; t += D) {
 #pragma unroll
     for (int j = 0; j < D; ++j) {
+      TRACE_STAMP(1);
       ma.load_full(ra[j], t + j + D);
       mb.load_full(rb[j], t + j + D);
+      TRACE_STAMP(2);
       ma.store(ra[(j + 1) % D], As[(j + 1) & 1]);
       mb.store(rb[(j + 1) % D], Bs[(j + 1) & 1]);
+      TRACE_STAMP(3);
       compute(As[j & 1], Bs[j & 1]);
+      TRACE_STAMP(4);
       __syncthreads();
+      TRACE_STAMP(5);
     }
   }
   for (; t < nk; t += D) {
@@ -358,24 +395,50 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
     }
   }
 
-  // lane L of a 32x32 result (B fragment first): row of C = L%32, columns (r/4)*8 + (L/32)*4 + r%4
+  TRACE_STAMP(6);
+  // Epilogue through LDS.  Lane L of a 32x32 result (B fragment first) holds row L%32 and columns
+  // (r/4)*8 + (L/32)*4 + r%4: storing that directly would touch 32 different rows per instruction.  Each
+  // wavefront instead parks 32 rows of its sub-tile in a private LDS patch [32][WTN + 4] (fp32) and reads it
+  // back row-wise, so every store instruction covers whole row segments of C.
   const bool vec = ((g.ldc & 3) == 0) && ((coff & 3) == 0) &&
                    ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
                    ((((uintptr_t)g.out_act | (uintptr_t)g.out_act2 | (uintptr_t)g.aux) & 7) == 0);
+  constexpr int SP = WTN + 4;                 // patch pitch in floats
+  constexpr int LPR = WTN / 4;                // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;               // rows per read instruction
+  static_assert(4 * 32 * SP * 4 <= 2 * (BM + BN) * BK * 2, "staging patches must fit the operand buffers");
+  float *const patch = (float *)lds_all + wave * 32 * SP;
+  // every wavefront has passed the last barrier of the K loop, so nobody reads the operand buffers any more
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
-    const int row = m0 + wm * WTM + i * 32 + (lane & 31);
-    if (row >= g.M) continue;
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = n0 + wn * WTN + j * 32 + q * 8 + (lane >> 5) * 4;
-        if (col >= g.N) continue;
-        float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        f32x4_t v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        *(f32x4_t *)(patch + (lane & 31) * SP + j * 32 + q * 8 + (lane >> 5) * 4) = v;
+      }
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the patch is written (LDS serves a wavefront in order)
+    __builtin_amdgcn_wave_barrier();
+    // deliberately a rolled loop: one copy of the epilogue code keeps the kernel small enough for the
+    // instruction cache (the unrolled form spent thousands of cycles per block fetching cold code)
+#pragma unroll 1
+    for (int p = 0; p < 32 / RPI; ++p) {
+      const int r = p * RPI + lane / LPR, c = (lane % LPR) * 4;
+      const f32x4_t v4 = *(const f32x4_t *)(patch + r * SP + c);
+      const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + c;
+      if (row < g.M && col < g.N) {
+        float v[4] = {v4[0], v4[1], v4[2], v4[3]};
         epilogue_store4<bf16_t>(g, coff, row, col, v, vec);
       }
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
   }
+  TRACE_STAMP(7);
+#ifdef HYDRA_GEMM_TRACE
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_gemm_trace[8191] = trace_n;
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -450,6 +513,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g, int ta,
     }
 }
 
+#ifdef HYDRA_GEMM_TRACE
+extern "C" int hydra_debug_gemm_trace(unsigned long long *host_out) {
+  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gemm_trace), sizeof(unsigned long long) * 8192);
+}
+#endif
+
 template <int BM, int BN, int WM, int WN, int D>
 static hipError_t launch_bf16_cfg(const GemmArgs &a, int ta, int tb, dim3 grid, hipStream_t s) {
   if (ta == 0 && tb == 0) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, 0, 0, D>), grid, dim3(256), 0, s, a);
@@ -470,8 +539,7 @@ static double gemm_flops(const GemmDesc &d) {
 static const char *gemm_name(int dtype, int bn, int ta, int tb) {
   static const char *n128[4] = {"gemm_bf16_128x128_nt", "gemm_bf16_128x128_nn", "gemm_bf16_128x128_tt",
                                 "gemm_bf16_128x128_tn"};
-  static const char *n64[4] = {"gemm_bf16_128x64_nt", "gemm_bf16_128x64_nn", "gemm_bf16_128x64_tt",
-                               "gemm_bf16_128x64_tn"};
+  static const char *n64[4] = {"gemm_bf16_x64_nt", "gemm_bf16_x64_nn", "gemm_bf16_x64_tt", "gemm_bf16_x64_tn"};
   if (dtype == DT_F32) return "gemm_f32_64x64";
   return (bn == 128 ? n128 : n64)[ta * 2 + tb];
 }
@@ -498,18 +566,33 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   // operand alignment the vector loads rely on
   if ((d.lda & 7) || (d.ldb & 7) || (((uintptr_t)d.A) & 15) || (((uintptr_t)d.B) & 15)) return hipErrorInvalidValue;
   if ((d.sA1 & 7) || (d.sA2 & 7) || (d.sB1 & 7) || (d.sB2 & 7)) return hipErrorInvalidValue;
-  // tile choice: 128x128 when the grid still covers the chip, else narrower tiles
+  // experimental overrides (tile / slices in flight)
+  static const int force_tile = getenv("HYDRA_GEMM_TILE") ? atoi(getenv("HYDRA_GEMM_TILE")) : 0;
+  static const int force_d = getenv("HYDRA_GEMM_D") ? atoi(getenv("HYDRA_GEMM_D")) : 0;
+  // tile choice: 128x128 only for problems of many waves of tiles (the LM head); at a few thousand tokens per
+  // visit the block GEMMs have 100-400 tiles and the narrower tile measured faster on every one of them
   const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128) * nbatch;
-  if (d.N > 64 && t128 >= 256) {
-    a.tiles_m = (d.M + 127) / 128; a.tiles_n = (d.N + 127) / 128;
-    ProfScope ps(gemm_name(DT_BF16, 128, d.ta, d.tb), s, gemm_flops(d), 0);
-    if (d.K <= 4 * BK) return launch_bf16_cfg<128, 128, 2, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
-    return launch_bf16_cfg<128, 128, 2, 2, 4>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
+  int tile = (d.N > 64 && t128 >= 2048) ? 1 : 2;
+  if (force_tile) tile = force_tile;
+  int D = 2;
+  if (force_d && d.K > 4 * BK) D = force_d;
+#define HYDRA_LAUNCH(BM_, BN_, DD_)                                                                      \
+  do {                                                                                                    \
+    a.tiles_m = (d.M + BM_ - 1) / BM_;                                                                    \
+    a.tiles_n = (d.N + BN_ - 1) / BN_;                                                                    \
+    ProfScope ps(gemm_name(DT_BF16, BN_, d.ta, d.tb), s, gemm_flops(d), 0);                              \
+    return launch_bf16_cfg<BM_, BN_, 2, 2, DD_>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s); \
+  } while (0)
+  if (tile == 1) {
+    HYDRA_LAUNCH(128, 128, 2);
   }
-  a.tiles_m = (d.M + 127) / 128; a.tiles_n = (d.N + 63) / 64;
-  ProfScope ps(gemm_name(DT_BF16, 64, d.ta, d.tb), s, gemm_flops(d), 0);
-  if (d.K <= 4 * BK) return launch_bf16_cfg<128, 64, 2, 2, 2>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
-  return launch_bf16_cfg<128, 64, 2, 2, 4>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s);
+  if (tile == 3) {
+    if (D == 4) HYDRA_LAUNCH(64, 64, 4);
+    HYDRA_LAUNCH(64, 64, 2);
+  }
+  if (D == 4) HYDRA_LAUNCH(128, 64, 4);
+  HYDRA_LAUNCH(128, 64, 2);
+#undef HYDRA_LAUNCH
 }
 
 }  // namespace hydra
