@@ -37,13 +37,15 @@ HBM_PEAK_GBPS = 8000.0
 
 SPILL_SLOTS = 4
 EXTRA_FLAGS = 0
+LANES = 2
 
 
 def make_session(cfg, n_models, mode, timing, R, H):
     n_shards = n_models * (cfg["L"] // cfg["k"] + 2)
     slots = SPILL_SLOTS if mode == "spill" else n_shards
     flags = (H.FLAG_TIMING if timing else 0) | EXTRA_FLAGS
-    sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots), flags=flags, max_slots=slots)
+    lanes = 1 if timing else LANES      # per-kernel timing wants kernels one at a time
+    sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots, lanes=lanes), flags=flags, max_slots=slots, lanes=lanes)
     recs = []
     for m in range(n_models):
         W = SI.make_weights(cfg, SI.model_seed(cfg, m))
@@ -118,9 +120,11 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the second mode and the timing pass")
     ap.add_argument("--slots", type=int, default=4, help="shard buffers in spill mode")
     ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
+    ap.add_argument("--lanes", type=int, default=2, help="compute lanes (streams); models are spread over them")
     args = ap.parse_args()
-    global SPILL_SLOTS, EXTRA_FLAGS
+    global SPILL_SLOTS, EXTRA_FLAGS, LANES
     SPILL_SLOTS = args.slots
+    LANES = args.lanes
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the method shards over host DRAM, not over GPUs); "
               "use --gpus 1", file=sys.stderr)
@@ -145,7 +149,7 @@ def main():
         "config": {"workload": f"{args.config}: {n_models} GPT-2-small-shaped models (12L d768 H12 F3072 V50257), "
                                f"B{cfg['B']} T{cfg['T']}, 2-layer shards alternated by Sharded-LRTF, bf16 MFMA + fp32 "
                                "master/Adam, seeded N(0,0.02) weights, uniform tokens",
-                   "mode": args.mode, "shard_buffers": main_run["n_slots"],
+                   "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes,
                    "tokens_per_step": tokens_per_step},
         "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),
                  "d2h_GB_per_step": round(main_run["d2h"] / args.steps / 1e9, 3),

@@ -99,6 +99,9 @@ typedef struct {
   void *compute_stream;            /* hipStream_t handles; NULL = the null stream             */
   void *h2d_stream;
   void *d2h_stream;
+  int32_t compute_lanes;           /* 0 or 1: every task on compute_stream.  n > 1: model i runs on lane i % n;   */
+  int32_t reserved;                /* lanes 1.. use streams (default priority) and workspaces of the library's    */
+                                   /* own, so that tasks of different models overlap on the device               */
 } hydra_init_desc;
 
 typedef struct {

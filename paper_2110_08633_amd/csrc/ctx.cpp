@@ -79,8 +79,10 @@ hydra_status ensure_planned(hydra_ctx *ctx) {
   }
   ctx->stats.model_state_bytes = ctx->arena_used;
   ctx->ws_bytes = align_up(ws, 256);
-  ctx->ws = arena_take(ctx, ctx->ws_bytes);
-  if (!ctx->ws) return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the workspace");
+  for (hydra_ctx::Lane &ln : ctx->lanes) {
+    ln.ws = arena_take(ctx, ctx->ws_bytes);
+    if (!ln.ws) return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the workspace");
+  }
   // a slot: fp32 master, m, v, grad and a bf16 working copy of the largest shard
   ctx->slot_elems = align_up(max_shard, 64);
   ctx->slot_bytes = align_up(ctx->slot_elems * 18, 256);
@@ -109,7 +111,7 @@ hydra_status ensure_planned(hydra_ctx *ctx) {
   }
   ctx->stats.n_slots = (int32_t)n;
   ctx->stats.slot_bytes = ctx->slot_bytes;
-  ctx->stats.workspace_bytes = ctx->ws_bytes;
+  ctx->stats.workspace_bytes = ctx->ws_bytes * ctx->lanes.size();
   ctx->planned = true;
   return HYDRA_OK;
 }
@@ -134,7 +136,13 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
   hydra_ctx *ctx = new hydra_ctx();
   ctx->init = *desc;
   ctx->dry = (desc->flags & HYDRA_FLAG_DRY_RUN) != 0;
-  ctx->s_compute = (hipStream_t)desc->compute_stream;
+  const int n_lanes = desc->compute_lanes > 0 ? desc->compute_lanes : 1;
+  if (n_lanes > 8) {
+    delete ctx;
+    return fail(nullptr, HYDRA_E_INVAL, "at most 8 compute lanes");
+  }
+  ctx->lanes.resize(n_lanes);
+  ctx->lanes[0].stream = (hipStream_t)desc->compute_stream;
   ctx->s_h2d = (hipStream_t)desc->h2d_stream;
   ctx->s_d2h = (hipStream_t)desc->d2h_stream;
   ctx->arena = (char *)desc->dev_arena;
@@ -148,6 +156,13 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
       return fail(nullptr, HYDRA_E_HIP, "no HIP device available");
     }
   }
+  for (int i = 1; i < n_lanes && !ctx->dry; ++i) {
+    if (hipStreamCreateWithFlags(&ctx->lanes[i].stream, hipStreamNonBlocking) != hipSuccess) {
+      delete ctx;
+      return fail(nullptr, HYDRA_E_HIP, "cannot create a compute lane stream");
+    }
+    ctx->lanes[i].own_stream = true;
+  }
   if (!ctx->dry && (desc->flags & HYDRA_FLAG_TIMING)) {
     ctx->prof = prof_create();
     prof_activate(ctx->prof);
@@ -159,10 +174,12 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
 hydra_status hydra_destroy(hydra_ctx *ctx) {
   if (!ctx) return HYDRA_OK;
   if (!ctx->dry) {
-    (void)hipStreamSynchronize(ctx->s_compute);
+    for (hydra_ctx::Lane &ln : ctx->lanes) (void)hipStreamSynchronize(ln.stream);
     (void)hipStreamSynchronize(ctx->s_h2d);
     (void)hipStreamSynchronize(ctx->s_d2h);
     prof_destroy(ctx->prof);
+    for (hydra_ctx::Lane &ln : ctx->lanes)
+      if (ln.own_stream) (void)hipStreamDestroy(ln.stream);
     for (Slot &s : ctx->slots) {
       if (s.ev_loaded) (void)hipEventDestroy(s.ev_loaded);
       if (s.ev_compute) (void)hipEventDestroy(s.ev_compute);
@@ -191,7 +208,7 @@ hydra_status hydra_sync(hydra_ctx *ctx) {
   if (!ctx) return fail(nullptr, HYDRA_E_INVAL, "null context");
   if (ctx->dry) return HYDRA_OK;
   HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
-  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+  for (hydra_ctx::Lane &ln : ctx->lanes) HYDRA_HIP(ctx, hipStreamSynchronize(ln.stream));
   HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
   return HYDRA_OK;
 }
@@ -254,6 +271,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
     return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the model's activations");
   }
   m->slot_of.assign(s.S + 2, -1);
+  m->lane = (int)(ctx->models.size() % ctx->lanes.size());
   if (!ctx->dry) {
     hipError_t e = hipHostMalloc((void **)&m->stage, (size_t)s.M * 4 * 4, hipHostMallocDefault);
     if (e != hipSuccess) {
@@ -293,9 +311,10 @@ hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *token
   memcpy(st_tok, tokens, M * 4);
   memcpy(st_tgt, targets, M * 4);
   if (!ctx->dry) {
-    HYDRA_HIP(ctx, hipMemcpyAsync(m->tok, st_tok, M * 4, hipMemcpyHostToDevice, ctx->s_compute));
-    HYDRA_HIP(ctx, hipMemcpyAsync(m->tgt, st_tgt, M * 4, hipMemcpyHostToDevice, ctx->s_compute));
-    HYDRA_HIP(ctx, hipEventRecord(m->ev_stage[si], ctx->s_compute));
+    hipStream_t cs = ctx->lanes[m->lane].stream;
+    HYDRA_HIP(ctx, hipMemcpyAsync(m->tok, st_tok, M * 4, hipMemcpyHostToDevice, cs));
+    HYDRA_HIP(ctx, hipMemcpyAsync(m->tgt, st_tgt, M * 4, hipMemcpyHostToDevice, cs));
+    HYDRA_HIP(ctx, hipEventRecord(m->ev_stage[si], cs));
     m->stage_used[si] = true;
   }
   m->stage_idx ^= 1;
@@ -406,11 +425,11 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
   }
   if (what & HYDRA_SPILL_EVICT) {
     if ((ctx->init.flags & HYDRA_FLAG_POISON) && !ctx->dry) {
-      // runs after everything enqueued so far on the compute stream and after the write-back
-      if (sl->spill_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, sl->ev_spilled, 0));
-      HYDRA_HIP(ctx, launch_fill_u32((uint32_t *)sl->base, 0x7fc07fc0u, (int64_t)(ctx->slot_bytes / 4), ctx->s_compute));
-      HYDRA_HIP(ctx, hipEventRecord(sl->ev_compute, ctx->s_compute));
-      sl->compute_pending = true;
+      // on the d2h stream: after the write-back (same stream) and after the last task that used the buffer
+      if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
+      HYDRA_HIP(ctx, launch_fill_u32((uint32_t *)sl->base, 0x7fc07fc0u, (int64_t)(ctx->slot_bytes / 4), ctx->s_d2h));
+      HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
+      sl->spill_pending = true;
     }
     m->slot_of[shard] = -1;
     sl->model = sl->shard = -1;
@@ -428,7 +447,7 @@ static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out)
   Slot *sl = slot_for(ctx, model, shard);
   if (!sl || !sl->has_params) return fail(ctx, HYDRA_E_STATE, "shard was not loaded");
   if (sl->need_wait_load) {
-    if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, sl->ev_loaded, 0));
+    if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[ctx->models[model]->lane].stream, sl->ev_loaded, 0));
     sl->need_wait_load = false;
   }
   *out = sl;
@@ -437,8 +456,8 @@ static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out)
 
 static hydra_status end_task(hydra_ctx *ctx, Model *m, Slot *sl) {
   if (!ctx->dry) {
-    HYDRA_HIP(ctx, hipEventRecord(sl->ev_compute, ctx->s_compute));
-    HYDRA_HIP(ctx, hipEventRecord(m->ev_last_compute, ctx->s_compute));
+    HYDRA_HIP(ctx, hipEventRecord(sl->ev_compute, ctx->lanes[m->lane].stream));
+    HYDRA_HIP(ctx, hipEventRecord(m->ev_last_compute, ctx->lanes[m->lane].stream));
   }
   sl->compute_pending = true;
   sl->last_use = ++ctx->use_counter;
@@ -458,7 +477,7 @@ hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
   const int S = m->sh.S;
   if (spill && shard <= S && !ctx->dry && m->ckpt_d2h_pending[shard & 1]) {
     // the ping-pong buffer about to be overwritten may still be on its way to the host
-    HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, m->ev_ckpt_d2h[shard & 1], 0));
+    HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_d2h[shard & 1], 0));
   }
   if (!ctx->dry && (st = exec_forward(ctx, m, sl, shard))) return st;
   if ((st = end_task(ctx, m, sl))) return st;
@@ -494,7 +513,7 @@ hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard) 
     const int pb = (shard - 1) & 1;
     if (m->ckpt_in_buf[pb] != shard - 1)
       return fail(ctx, HYDRA_E_STATE, "input checkpoint not promoted: load the shard with HYDRA_LOAD_OPT first");
-    if (m->ckpt_h2d_pending[pb] && !ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_compute, m->ev_ckpt_h2d[pb], 0));
+    if (m->ckpt_h2d_pending[pb] && !ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_h2d[pb], 0));
     m->ckpt_h2d_pending[pb] = false;
   }
   if (!ctx->dry && (st = exec_backward(ctx, m, sl, shard))) return st;
@@ -528,7 +547,7 @@ hydra_status hydra_get_loss(hydra_ctx *ctx, int32_t model, float *loss) {
     *loss = 0.f;
     return HYDRA_OK;
   }
-  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+  HYDRA_HIP(ctx, hipStreamSynchronize(ctx->lanes[m->lane].stream));
   HYDRA_HIP(ctx, hipMemcpy(loss, m->loss, 4, hipMemcpyDeviceToHost));
   return HYDRA_OK;
 }
@@ -544,19 +563,19 @@ hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int
   const uint64_t act = (uint64_t)s.M * s.d * 4;
   if (!ctx->dry) {
     HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
-    HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_compute));
+    for (hydra_ctx::Lane &ln : ctx->lanes) HYDRA_HIP(ctx, hipStreamSynchronize(ln.stream));
     HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
   }
   const void *src = nullptr;
   uint64_t need = 0;
   switch (which) {
     case HYDRA_RD_LOGITS: {
-      if (!m->logits_valid || ctx->logits_owner != model)
+      if (!m->logits_valid || ctx->lanes[m->lane].logits_owner != model)
         return fail(ctx, HYDRA_E_STATE, "logits of this model are no longer held");
       need = (uint64_t)s.M * s.V * 4;
       if (bytes != need) return fail(ctx, HYDRA_E_INVAL, "size mismatch");
       if (!ctx->dry)
-        HYDRA_HIP(ctx, hipMemcpy2D(host_dst, (size_t)s.V * 4, ctx->logits, (size_t)s.Vpad * 4, (size_t)s.V * 4, s.M,
+        HYDRA_HIP(ctx, hipMemcpy2D(host_dst, (size_t)s.V * 4, ctx->lanes[m->lane].logits, (size_t)s.Vpad * 4, (size_t)s.V * 4, s.M,
                                    hipMemcpyDeviceToHost));
       return HYDRA_OK;
     }

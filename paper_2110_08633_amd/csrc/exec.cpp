@@ -299,7 +299,7 @@ uint64_t workspace_need(const ModelShape &s, int dtype) {
 static hipError_t ensure_working_copy(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   if (mm->dtype != DT_BF16 || sl->wb_valid) return hipSuccess;
   const ModelShape &s = mm->sh;
-  hipStream_t st = ctx->s_compute;
+  hipStream_t st = ctx->lanes[mm->lane].stream;
   if (shard >= 1 && shard <= s.S) {
     CK(launch_cast_bf16(sl->w, sl->wb, s.shard_off[shard + 1] - s.shard_off[shard], st));
   } else if (shard == s.S + 1) {
@@ -313,16 +313,17 @@ static hipError_t ensure_working_copy(hydra_ctx *ctx, Model *mm, Slot *sl, int s
 hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const ModelShape &s = mm->sh;
   const int dt = mm->dtype;
-  hipStream_t st = ctx->s_compute;
+  hipStream_t st = ctx->lanes[mm->lane].stream;
   const int M = (int)s.M, d = s.d;
   HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
-  Bump b{ctx->ws, ctx->ws_bytes};
+  hydra_ctx::Lane &ln = ctx->lanes[mm->lane];
+  Bump b{ln.ws, ctx->ws_bytes};
   if (shard == 0) {
     HYDRA_HIP(ctx, launch_embed_fwd(mm->tok, sl->w, sl->w + (int64_t)s.V * d, mm->ckpt[0], M, s.T, d, st));
     return HYDRA_OK;
   }
   if (shard <= s.S) {
-    ctx->logits_owner = -1;  // the shared workspace is about to be overwritten
+    ln.logits_owner = -1;  // the shared workspace is about to be overwritten
     LayerActs A = take_layer(b, s, dt);
     float *Sbuf = b.take<float>((uint64_t)s.B * s.H * s.T * s.T);
     float *pp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
@@ -350,8 +351,8 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const float inv_n = 1.0f / (float)mm->n_valid;
   HYDRA_HIP(ctx, launch_cross_entropy(dt, logits, mm->tgt, mm->row_loss, mm->dlogits, M, s.V, s.Vpad, inv_n, st));
   HYDRA_HIP(ctx, launch_loss_reduce(mm->row_loss, mm->loss, M, inv_n, st));
-  ctx->logits = logits;
-  ctx->logits_owner = (int)(std::find(ctx->models.begin(), ctx->models.end(), mm) - ctx->models.begin());
+  ln.logits = logits;
+  ln.logits_owner = (int)(std::find(ctx->models.begin(), ctx->models.end(), mm) - ctx->models.begin());
   for (Model *o : ctx->models)
     if (o != mm) o->logits_valid = false;
   return HYDRA_OK;
@@ -360,17 +361,18 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
 hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const ModelShape &s = mm->sh;
   const int dt = mm->dtype;
-  hipStream_t st = ctx->s_compute;
+  hipStream_t st = ctx->lanes[mm->lane].stream;
   const int M = (int)s.M, d = s.d;
   HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
-  Bump b{ctx->ws, ctx->ws_bytes};
+  hydra_ctx::Lane &ln = ctx->lanes[mm->lane];
+  Bump b{ln.ws, ctx->ws_bytes};
   if (shard == s.S + 1) {
     // the logits of the forward visit were turned into dlogits there; only the
     // normalised input z is recomputed
-    if (ctx->logits_owner >= 0 && ctx->models[ctx->logits_owner] == mm)
+    if (ln.logits_owner >= 0 && ctx->models[ln.logits_owner] == mm)
       b.take<float>((uint64_t)M * s.Vpad);  // leave this model's logits readable
     else
-      ctx->logits_owner = -1;
+      ln.logits_owner = -1;
     void *z = b.take<char>((uint64_t)M * d * dt_size(dt));
     float *mean = b.take<float>(M), *rstd = b.take<float>(M);
     float *dz = b.take<float>((uint64_t)M * d);
@@ -391,7 +393,7 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     return HYDRA_OK;
   }
   if (shard >= 1) {
-    ctx->logits_owner = -1;  // the shared workspace is about to be overwritten
+    ln.logits_owner = -1;  // the shared workspace is about to be overwritten
     std::vector<LayerActs> acts(s.k);
     std::vector<float *> xs(s.k + 1);
     for (int j = 0; j < s.k; ++j) acts[j] = take_layer(b, s, dt);
@@ -422,7 +424,8 @@ hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const int64_t n = s.shard_off[shard + 1] - s.shard_off[shard];
   // block shards keep their bf16 working copy current for the next visit
   bf16_t *shadow = (mm->dtype == DT_BF16 && shard >= 1 && shard <= s.S) ? sl->wb : nullptr;
-  HYDRA_HIP(ctx, launch_adam(sl->w, sl->m, sl->v, sl->g, shadow, n, h.lr, h.beta1, h.beta2, h.eps, mm->t, ctx->s_compute));
+  HYDRA_HIP(ctx, launch_adam(sl->w, sl->m, sl->v, sl->g, shadow, n, h.lr, h.beta1, h.beta2, h.eps, mm->t,
+                             ctx->lanes[mm->lane].stream));
   sl->wb_valid = shadow != nullptr;
   return HYDRA_OK;
 }

@@ -366,6 +366,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   if (nk <= 1) {  // a single slice (the head-width contractions of attention): nothing to pipeline
     compute(As[0], Bs[0]);
     t = nk;
+    __syncthreads();  // the epilogue reuses the operand buffers: every wavefront must be done reading them
   }
   for (; t + 2 * D + 1 <= nk; t += D) {
 #pragma unroll

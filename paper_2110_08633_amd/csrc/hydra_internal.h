@@ -60,6 +60,7 @@ struct Model {
   hydra_host_state host_dev;  // device-side mappings of the same page-locked arrays
   ModelShape sh;
   int dtype;
+  int lane = 0;
   // device state carved from the arena
   int32_t *tok = nullptr, *tgt = nullptr;
   std::vector<float *> ckpt;  // boundary b -> buffer (ping-pong pair when checkpoints are spilled)
@@ -93,16 +94,23 @@ struct hydra_ctx {
   hydra_init_desc init;
   bool dry = false;
   bool planned = false;
-  hipStream_t s_compute = nullptr, s_h2d = nullptr, s_d2h = nullptr;
+  hipStream_t s_h2d = nullptr, s_d2h = nullptr;
+  // Compute lanes: each has its own stream and workspace; a model always runs on lane (model id % lanes), so
+  // tasks of different models may overlap on the device while every model's own tasks stay in order.
+  struct Lane {
+    hipStream_t stream = nullptr;
+    bool own_stream = false;
+    char *ws = nullptr;
+    int logits_owner = -1;    // model whose logits the lane's workspace still holds
+    float *logits = nullptr;
+  };
+  std::vector<Lane> lanes;
   char *arena = nullptr;
   uint64_t arena_bytes = 0, arena_used = 0;
   std::vector<hydra::Model *> models;
   std::vector<hydra::Slot> slots;
   uint64_t slot_bytes = 0, slot_elems = 0;
-  char *ws = nullptr;  // workspace shared by all tasks (one task runs at a time on the compute stream)
-  uint64_t ws_bytes = 0, ws_used = 0;
-  int logits_owner = -1;
-  float *logits = nullptr;  // inside the workspace; valid for logits_owner until the next HEAD forward
+  uint64_t ws_bytes = 0;  // workspace per lane (one task at a time runs on a lane)
   hydra_stats stats;
   uint64_t use_counter = 0;
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)

@@ -30,7 +30,8 @@ RD_LOGITS, RD_GRADS, RD_PARAMS, RD_ADAM_M, RD_ADAM_V, RD_CKPT, RD_DBOUND = range
 class InitDesc(C.Structure):
     _fields_ = [("dev_arena", C.c_void_p), ("dev_arena_bytes", C.c_uint64),
                 ("shard_buffer_cap_bytes", C.c_uint64), ("max_slots", C.c_int32), ("flags", C.c_int32),
-                ("compute_stream", C.c_void_p), ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
+                ("compute_lanes", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ModelDesc(C.Structure):
@@ -138,9 +139,9 @@ def model_desc(cfg, lr, dtype=None, beta1=0.9, beta2=0.999, eps=1e-8):
 # ---- thin wrappers, same names as the C functions --------------------------
 
 def hydra_init(arena, arena_bytes, compute_stream=None, h2d_stream=None, d2h_stream=None, flags=0,
-               shard_buffer_cap_bytes=0, max_slots=0):
+               shard_buffer_cap_bytes=0, max_slots=0, compute_lanes=1):
     d = InitDesc(arena if isinstance(arena, int) else _ptr(arena), arena_bytes, shard_buffer_cap_bytes, max_slots,
-                 flags, _stream(compute_stream), _stream(h2d_stream), _stream(d2h_stream))
+                 flags, _stream(compute_stream), _stream(h2d_stream), _stream(d2h_stream), compute_lanes, 0)
     out = _vp()
     _check(lib.hydra_init(C.byref(d), C.byref(out)))
     return out

@@ -14,7 +14,7 @@ from . import hydra as H
 class Session:
     """One hydra context with its arena, three streams and registered models."""
 
-    def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False):
+    def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False, lanes=1):
         self.dry = dry_run
         self.models = []      # dicts: desc, cfg, master, m, v, ckpt, id, names
         if dry_run:
@@ -29,7 +29,8 @@ class Session:
             arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
             self.streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
         self.ctx = H.hydra_init(arena_ptr, arena_bytes, *self.streams, flags=flags,
-                                shard_buffer_cap_bytes=shard_buffer_cap_bytes, max_slots=max_slots)
+                                shard_buffer_cap_bytes=shard_buffer_cap_bytes, max_slots=max_slots,
+                                compute_lanes=lanes)
         self.flags = flags
 
     def _host(self, n, dtype=np.float32):
@@ -127,7 +128,7 @@ class Session:
             self.ctx = None
 
 
-def arena_bytes_for(cfgs, n_slots, ckpt_spill=False):
+def arena_bytes_for(cfgs, n_slots, ckpt_spill=False, lanes=1):
     """Generous arena size for a list of model configs and a number of shard buffers."""
     total, ws, max_shard = 0, 0, 0
     for c in cfgs:
@@ -141,4 +142,4 @@ def arena_bytes_for(cfgs, n_slots, ckpt_spill=False):
         ws = max(ws, k * layer + k * act + scratch + 2 * act + (1 << 20), M * vpad * 4 + 4 * act + (1 << 20))
         blk = 12 * d * d + 13 * d if F == 4 * d else 4 * d * d + 2 * d * F + 9 * d + F
         max_shard = max(max_shard, V * d + T * d, k * blk, 2 * d + d * V)
-    return int(total + ws + n_slots * (max_shard * 18 + 4096) + (64 << 20))
+    return int(total + lanes * ws + n_slots * (max_shard * 18 + 4096) + (64 << 20))

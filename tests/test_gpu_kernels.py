@@ -161,3 +161,26 @@ def test_cross_entropy(H, dtype, M, V):
     H.hydra_op_cross_entropy(0, z, dev(tgt), row, torch.zeros((M, ld), device="cuda"), M, V, ld, 1.0 / n)
     torch.cuda.synchronize()
     assert abs(float(row.cpu().numpy().sum()) / n - math.log(V)) < 1e-5
+
+
+def test_single_slice_gemm_under_concurrency(H):
+    """Contractions that fit one K slice (the head-width products of attention) skip the pipelined loop; their
+    epilogue reuses the operand buffers in LDS and must wait for every wavefront of the block.  Two streams keep
+    the device busy so that wavefronts of a block drift apart."""
+    rng = np.random.default_rng(11)
+    M, N, K = 512, 512, 64
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    B = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
+    ref = A.astype(np.float64) @ B.astype(np.float64).T
+    dA, dB = dev(A, torch.bfloat16), dev(B, torch.bfloat16)
+    big = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+    bigC = torch.empty((4096, 4096), device="cuda", dtype=torch.float32)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [torch.zeros((M, N), device="cuda", dtype=torch.float32) for _ in range(40)]
+    torch.cuda.synchronize()
+    for o in outs:
+        H.hydra_op_gemm(1, 0, 0, 4096, 4096, 4096, 1.0, big, 4096, big, 4096, None, None, bigC, None, 4096, s2)
+        H.hydra_op_gemm(1, 0, 0, M, N, K, 1.0, dA, K, dB, K, None, None, o, None, N, s1)
+    torch.cuda.synchronize()
+    for o in outs:
+        assert_close(o.cpu().numpy(), ref, 1e-5, "single-slice gemm")

@@ -152,9 +152,9 @@ def test_embedding_forward_is_bit_exact_and_absent_rows_untouched(rt):
     sess.close()
 
 
-@pytest.mark.parametrize("max_slots", [2, 3, 0])
+@pytest.mark.parametrize("max_slots,lanes", [(2, 1), (3, 1), (0, 1), (3, 2), (0, 3)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_scheduled_multi_model_run_matches_oracle(rt, max_slots, dtype):
+def test_scheduled_multi_model_run_matches_oracle(rt, max_slots, lanes, dtype):
     """Three models with different learning rates and weights, interleaved by the library's scheduler with
     prefetch and write-back, against the oracle's interleaved spilled run; task order must be identical."""
     H, R = rt
@@ -170,7 +170,8 @@ def test_scheduled_multi_model_run_matches_oracle(rt, max_slots, dtype):
     oracle = [SP.SpilledModel(cfg, Ws[m], cfg["lrs"][m], np.float64) for m in range(n)]
     SP.run_interleaved(oracle, batches, order, chains)
 
-    sess = R.Session(R.arena_bytes_for([cfg] * n, 12), max_slots=max_slots)
+    sess = R.Session(R.arena_bytes_for([cfg] * n, 12, lanes=lanes), max_slots=max_slots, lanes=lanes,
+                     flags=H.FLAG_POISON if lanes > 1 else 0)
     recs = [sess.add_model(cfg, Ws[m], cfg["lrs"][m]) for m in range(n)]
     sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, [list(fc) + list(bc)] * n)
     toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
