@@ -575,7 +575,8 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128) * nbatch;
   int tile = (d.N > 64 && t128 >= 2048) ? 1 : 2;
   if (force_tile) tile = force_tile;
-  int D = 2;
+  // slices in flight: a deeper pipeline pays once the contraction is long enough to amortise filling it
+  int D = (d.causal == CAUSAL_NONE && d.K >= 24 * BK) ? 4 : 2;
   if (force_d && d.K > 4 * BK) D = force_d;
 #define HYDRA_LAUNCH(BM_, BN_, DD_)                                                                      \
   do {                                                                                                    \
