@@ -57,8 +57,9 @@ def make_session(cfg, n_models, mode, timing, R, H):
 def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
     n = len(recs)
     fc, bc = SI.task_costs(cfg)
-    toks = [np.stack([SI.make_batch(cfg, SI.batch_seed(cfg, m, first_step + i))[0] for i in range(n_mb)]) for m in range(n)]
-    tgts = [np.stack([SI.make_batch(cfg, SI.batch_seed(cfg, m, first_step + i))[1] for i in range(n_mb)]) for m in range(n)]
+    big = dict(cfg, B=cfg["B"] * cfg.get("n_micro", 1))   # a minibatch holds n_micro micro-batches of B samples
+    toks = [np.stack([SI.make_batch(big, SI.batch_seed(cfg, m, first_step + i))[0] for i in range(n_mb)]) for m in range(n)]
+    tgts = [np.stack([SI.make_batch(big, SI.batch_seed(cfg, m, first_step + i))[1] for i in range(n_mb)]) for m in range(n)]
     sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [n_mb] * n, [list(fc) + list(bc)] * n)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -121,6 +122,10 @@ def main():
     ap.add_argument("--slots", type=int, default=4, help="shard buffers in spill mode")
     ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
     ap.add_argument("--lanes", type=int, default=2, help="compute lanes (streams); models are spread over them")
+    ap.add_argument("--micro", type=int, default=1,
+                    help="micro-batches of B samples per shard visit (1 = the workload as BASELINE states it)")
+    ap.add_argument("--extra-micro", type=int, default=4,
+                    help="also report spill-mode throughput with this many micro-batches per visit (0 = skip)")
     args = ap.parse_args()
     global SPILL_SLOTS, EXTRA_FLAGS, LANES
     SPILL_SLOTS = args.slots
@@ -134,9 +139,11 @@ def main():
     assert torch.cuda.is_available(), "no GPU visible"
     if args.d2h_memcpy:
         EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
-    cfg = SI.CONFIGS[args.config]
+    cfg = dict(SI.CONFIGS[args.config])
+    if args.micro > 1:
+        cfg["n_micro"] = args.micro
     n_models = cfg["n_models"]
-    tokens_per_step = n_models * cfg["B"] * cfg["T"]
+    tokens_per_step = n_models * args.micro * cfg["B"] * cfg["T"]
 
     main_run = measure(cfg, n_models, args.mode, args.steps, args.warmup, False, R, H, torch)
     value = tokens_per_step * args.steps / main_run["seconds"]
@@ -150,7 +157,7 @@ def main():
                                f"B{cfg['B']} T{cfg['T']}, 2-layer shards alternated by Sharded-LRTF, bf16 MFMA + fp32 "
                                "master/Adam, seeded N(0,0.02) weights, uniform tokens",
                    "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes,
-                   "tokens_per_step": tokens_per_step},
+                   "micro_batches_per_visit": args.micro, "tokens_per_step": tokens_per_step},
         "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),
                  "d2h_GB_per_step": round(main_run["d2h"] / args.steps / 1e9, 3),
                  "h2d_GBps_over_wall": round(main_run["h2d"] / main_run["seconds"] / 1e9, 2),
@@ -162,6 +169,16 @@ def main():
         o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch)
         out[other] = {"value": round(tokens_per_step * args.steps / o["seconds"], 1), "unit": "tokens/s",
                       "ms_per_step": round(1e3 * o["seconds"] / args.steps, 3), "shard_buffers": o["n_slots"]}
+        if args.extra_micro > 1 and args.micro == 1:
+            # same models, shards and buffers, but every shard visit runs several micro-batches while the shard is
+            # resident: the state traffic per step is unchanged and serves that many times the tokens
+            mc = dict(cfg, n_micro=args.extra_micro)
+            o = measure(mc, n_models, "spill", max(2, args.steps // 2), 1, False, R, H, torch)
+            steps_m = max(2, args.steps // 2)
+            out[f"spill_micro{args.extra_micro}"] = {
+                "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
+                "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
+                "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"]}
         # per-kernel HIP-event timing over the same steps (resident buffers so that copies do not perturb kernels)
         t = measure(cfg, n_models, "resident", args.steps, args.warmup, True, R, H, torch)
         ks = sorted(t["kernels"], key=lambda k: -k["ms"])

@@ -81,13 +81,13 @@ enum {
 };
 /* 'which' of hydra_read_device */
 enum {
-  HYDRA_RD_LOGITS = 0, /* fp32 [B*T, V] of the model's last HEAD forward            */
+  HYDRA_RD_LOGITS = 0, /* fp32 [B*T, V] of the model's last HEAD forward (its last micro-batch) */
   HYDRA_RD_GRADS = 1,  /* fp32 gradients of a resident shard after its backward     */
   HYDRA_RD_PARAMS = 2, /* fp32 master weights of a resident shard                   */
   HYDRA_RD_ADAM_M = 3,
   HYDRA_RD_ADAM_V = 4,
-  HYDRA_RD_CKPT = 5,   /* fp32 [B*T, d]: output activation of shard 'shard' (0..S)  */
-  HYDRA_RD_DBOUND = 6  /* fp32 [B*T, d]: gradient w.r.t. the input of the last backward visit */
+  HYDRA_RD_CKPT = 5,   /* fp32 [n_micro*B*T, d]: output activation of shard 'shard' (0..S)  */
+  HYDRA_RD_DBOUND = 6  /* fp32 [n_micro*B*T, d]: gradient w.r.t. the input of the last backward visit */
 };
 
 typedef struct {
@@ -108,7 +108,10 @@ typedef struct {
   int32_t n_layer, d_model, n_head, d_ff, vocab, seq, batch;
   int32_t layers_per_shard; /* must divide n_layer                                        */
   int32_t dtype;            /* 0 = fp32 compute; 1 = bf16 MFMA compute, fp32 master/Adam  */
-  int32_t reserved;
+  int32_t n_micro;          /* micro-batches of 'batch' samples per minibatch (0 counts as 1): every visit of  */
+                            /* a shard runs all of them while the shard is resident and sums their gradients,  */
+                            /* so one promotion serves n_micro * batch samples (paper Section 2.3 leaves the   */
+                            /* work done per visit open; activation memory stays that of one micro-batch)      */
   double lr, beta1, beta2, eps; /* Adam hyper-parameters of this model (doubles so that 1-beta is exact) */
 } hydra_model_desc;
 
@@ -117,7 +120,7 @@ typedef struct {
   float *master;  /* [n_params] fp32, canonical flat layout */
   float *adam_m;  /* [n_params]                               */
   float *adam_v;  /* [n_params]                               */
-  float *ckpt;    /* [(S+1) * B*T * d] fp32; only read/written with HYDRA_FLAG_CKPT_SPILL, else may be NULL */
+  float *ckpt;    /* [(S+1) * n_micro*B*T * d] fp32; only read/written with HYDRA_FLAG_CKPT_SPILL, else may be NULL */
 } hydra_host_state;
 
 typedef struct {
@@ -183,9 +186,10 @@ hydra_status hydra_shard_range(const hydra_model_desc *desc, int32_t shard, int6
  * the first load / forward / scheduler call. */
 hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc,
                                   const hydra_host_state *host, int32_t *model_id);
-/* Hands the next minibatch of a model to the library: host int32 [B,T] token
- * ids in [0,V) and targets (id or -1 = ignore).  Copied before returning
- * control of the arrays; advances the model's Adam step counter t. */
+/* Hands the next minibatch of a model to the library: host int32
+ * [n_micro*B, T] token ids in [0,V) and targets (id or -1 = ignore); the loss
+ * is the mean over all valid targets of the minibatch.  Copied before
+ * returning control of the arrays; advances the model's Adam step counter t. */
 hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *tokens, const int32_t *targets);
 
 /* ---- shard tasks (paper Section 2.3) ------------------------------------- */
@@ -228,7 +232,7 @@ hydra_status hydra_sched_destroy(hydra_sched *s);
 hydra_status hydra_sched_next(hydra_sched *s, hydra_task *out);
 /* Runs every remaining task: prefetch of task n+1 is issued before task n is
  * enqueued, dirty shards are written back when their buffer is needed.
- * tokens[m] / targets[m]: host int32 [n_minibatches[m], B, T].  trace (may be
+ * tokens[m] / targets[m]: host int32 [n_minibatches[m], n_micro*B, T].  trace (may be
  * NULL) receives the executed order. Returns after everything is enqueued
  * (call hydra_sync to wait). */
 hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const int32_t *const *targets,

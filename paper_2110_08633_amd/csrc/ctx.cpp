@@ -246,12 +246,12 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   }
   m->dtype = desc->dtype;
   const ModelShape &s = m->sh;
-  const uint64_t act = (uint64_t)s.M * s.d * 4;
+  const uint64_t act = (uint64_t)s.Mt * s.d * 4;  // boundary tensors hold all micro-batches
   const bool spill = (ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) != 0;
   auto take = [&](uint64_t bytes) -> char * { return arena_take(ctx, bytes); };
   bool ok = true;
-  ok &= (m->tok = (int32_t *)take(s.M * 4)) != nullptr;
-  ok &= (m->tgt = (int32_t *)take(s.M * 4)) != nullptr;
+  ok &= (m->tok = (int32_t *)take(s.Mt * 4)) != nullptr;
+  ok &= (m->tgt = (int32_t *)take(s.Mt * 4)) != nullptr;
   m->ckpt.assign(s.S + 1, nullptr);
   if (spill) {
     float *pp[2];
@@ -263,8 +263,8 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   }
   ok &= (m->dbound[0] = (float *)take(act)) != nullptr;
   ok &= (m->dbound[1] = (float *)take(act)) != nullptr;
-  ok &= (m->dlogits = take((uint64_t)s.M * s.Vpad * dt_size(m->dtype))) != nullptr;
-  ok &= (m->row_loss = (float *)take(s.M * 4)) != nullptr;
+  ok &= (m->dlogits = take((uint64_t)s.Mt * s.Vpad * dt_size(m->dtype))) != nullptr;
+  ok &= (m->row_loss = (float *)take(s.Mt * 4)) != nullptr;
   ok &= (m->loss = (float *)take(256)) != nullptr;
   if (!ok) {
     delete m;
@@ -273,7 +273,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   m->slot_of.assign(s.S + 2, -1);
   m->lane = (int)(ctx->models.size() % ctx->lanes.size());
   if (!ctx->dry) {
-    hipError_t e = hipHostMalloc((void **)&m->stage, (size_t)s.M * 4 * 4, hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void **)&m->stage, (size_t)s.Mt * 4 * 4, hipHostMallocDefault);
     if (e != hipSuccess) {
       delete m;
       return hipfail(ctx, e, "hipHostMalloc(token staging)");
@@ -285,7 +285,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
     }
     if ((st = make_event(ctx, &m->ev_last_compute))) return st;
   } else {
-    m->stage = new int32_t[(size_t)s.M * 4];
+    m->stage = new int32_t[(size_t)s.Mt * 4];
   }
   *model_id = (int32_t)ctx->models.size();
   ctx->models.push_back(m);
@@ -297,7 +297,7 @@ hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *token
   if (st) return st;
   if (!tokens || !targets) return fail(ctx, HYDRA_E_INVAL, "null token / target array");
   Model *m = ctx->models[model];
-  const int64_t M = m->sh.M;
+  const int64_t M = m->sh.Mt;
   int64_t nv = 0;
   for (int64_t i = 0; i < M; ++i) {
     if (tokens[i] < 0 || tokens[i] >= m->sh.V) return fail(ctx, HYDRA_E_INVAL, "token id out of range");
@@ -378,11 +378,11 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && (what & HYDRA_LOAD_OPT) && shard >= 1 &&
       m->ckpt_in_buf[(shard - 1) & 1] != shard - 1 && m->next_bwd >= 0) {
     const int b = shard - 1;
-    const uint64_t bytes = (uint64_t)m->sh.M * m->sh.d * 4;
+    const uint64_t bytes = (uint64_t)m->sh.Mt * m->sh.d * 4;
     if (!ctx->dry) {
       if (m->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_last_compute, 0));
       if (m->ckpt_d2h_pending[b & 1]) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_ckpt_d2h[b & 1], 0));
-      HYDRA_HIP(ctx, hipMemcpyAsync(m->ckpt[b], m->host.ckpt + (uint64_t)b * m->sh.M * m->sh.d, bytes,
+      HYDRA_HIP(ctx, hipMemcpyAsync(m->ckpt[b], m->host.ckpt + (uint64_t)b * m->sh.Mt * m->sh.d, bytes,
                                     hipMemcpyHostToDevice, ctx->s_h2d));
       HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_h2d[b & 1], ctx->s_h2d));
     }
@@ -482,10 +482,10 @@ hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
   if (!ctx->dry && (st = exec_forward(ctx, m, sl, shard))) return st;
   if ((st = end_task(ctx, m, sl))) return st;
   if (spill && shard <= S) {
-    const uint64_t bytes = (uint64_t)m->sh.M * m->sh.d * 4;
+    const uint64_t bytes = (uint64_t)m->sh.Mt * m->sh.d * 4;
     if (!ctx->dry) {
       HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, m->ev_last_compute, 0));
-      const uint64_t eo = (uint64_t)shard * m->sh.M * m->sh.d;
+      const uint64_t eo = (uint64_t)shard * m->sh.Mt * m->sh.d;
       hydra_status cs = copy_d2h(ctx, m->host.ckpt + eo, m->host_dev.ckpt + eo, m->ckpt[shard], bytes);
       if (cs) return cs;
       HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_d2h[shard & 1], ctx->s_d2h));
@@ -560,7 +560,7 @@ hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int
   if ((st = ensure_planned(ctx))) return st;
   Model *m = ctx->models[model];
   const ModelShape &s = m->sh;
-  const uint64_t act = (uint64_t)s.M * s.d * 4;
+  const uint64_t act = (uint64_t)s.Mt * s.d * 4;
   if (!ctx->dry) {
     HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
     for (hydra_ctx::Lane &ln : ctx->lanes) HYDRA_HIP(ctx, hipStreamSynchronize(ln.stream));

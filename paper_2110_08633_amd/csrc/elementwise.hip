@@ -52,12 +52,12 @@ __global__ void embed_fwd_kernel(const int32_t *__restrict__ tok, const float *_
 
 // One block per position m.  The block that holds the first occurrence of a
 // token id marks all later occurrences in a bitmap, then sums their rows in
-// ascending m and writes the token's gradient row once; other blocks leave.
-// dwte was zeroed before.
+// ascending m and writes the token's gradient row once (adding to what the row
+// holds when acc is set); other blocks leave.  Without acc dwte was zeroed before.
 constexpr int EMB_MAXW = 1024;  // bitmap words: up to 32768 positions
 __global__ __launch_bounds__(256) void embed_bwd_wte_kernel(const int32_t *__restrict__ tok,
                                                             const float *__restrict__ dx0, float *__restrict__ dwte,
-                                                            int M, int d) {
+                                                            int M, int d, int acc_prev) {
   const int m = blockIdx.x;
   const int id = tok[m];
   __shared__ int earlier;
@@ -84,16 +84,18 @@ __global__ __launch_bounds__(256) void embed_bwd_wte_kernel(const int32_t *__res
         acc += dx0[(int64_t)j * d + c];
       }
     }
+    if (acc_prev) acc = dwte[(int64_t)id * d + c] + acc;
     dwte[(int64_t)id * d + c] = acc;
   }
 }
 
-__global__ void embed_bwd_wpe_kernel(const float *__restrict__ dx0, float *__restrict__ dwpe, int B, int T, int d) {
+__global__ void embed_bwd_wpe_kernel(const float *__restrict__ dx0, float *__restrict__ dwpe, int B, int T, int d,
+                                     int acc_prev) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // over T*d
   if (i >= (int64_t)T * d) return;
   float acc = 0.f;
   for (int b = 0; b < B; ++b) acc += dx0[(int64_t)b * T * d + i];
-  dwpe[i] = acc;
+  dwpe[i] = acc_prev ? dwpe[i] + acc : acc;
 }
 
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
@@ -126,14 +128,16 @@ hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *w
 }
 
 hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, float *dwpe, int B, int T, int d, int V,
-                            hipStream_t s) {
+                            int acc, hipStream_t s) {
   if (B * T > EMB_MAXW * 32) return hipErrorInvalidValue;
-  hipError_t e = launch_fill_u32((uint32_t *)dwte, 0u, (int64_t)V * d, s);
-  if (e != hipSuccess) return e;
+  if (!acc) {
+    hipError_t e = launch_fill_u32((uint32_t *)dwte, 0u, (int64_t)V * d, s);
+    if (e != hipSuccess) return e;
+  }
   ProfScope ps("embed_bwd", s, 0, 8.0 * B * T * d + 4.0 * T * d);
-  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(B * T), dim3(256), 0, s, tok, dx0, dwte, B * T, d);
+  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(B * T), dim3(256), 0, s, tok, dx0, dwte, B * T, d, acc);
   const int64_t n = (int64_t)T * d;
-  hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dx0, dwpe, B, T, d);
+  hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dx0, dwpe, B, T, d, acc);
   return hipGetLastError();
 }
 
@@ -273,20 +277,20 @@ __global__ __launch_bounds__(256) void colsum_pass1_kernel(const T *__restrict__
 }
 
 __global__ void colsum_pass2_kernel(const float *__restrict__ part, float *__restrict__ out0, float *__restrict__ out1,
-                                    int nch, int N) {
+                                    int nch, int N, int acc) {
   const int col = blockIdx.x * blockDim.x + threadIdx.x;
   if (col >= N) return;
-  double a = 0.0;
+  double a = acc ? (double)out0[col] : 0.0;
   for (int c = 0; c < nch; ++c) a += (double)part[(int64_t)c * N + col];
   out0[col] = (float)a;
   if (out1) {
-    double b = 0.0;
+    double b = acc ? (double)out1[col] : 0.0;
     for (int c = 0; c < nch; ++c) b += (double)part[(int64_t)(nch + c) * N + col];
     out1[col] = (float)b;
   }
 }
 
-hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N,
+hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N, int acc,
                          hipStream_t s) {
   const int nch = colsum_chunks(M);
   dim3 grid((N + 63) / 64, nch);
@@ -297,18 +301,19 @@ hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, f
   else
     hipLaunchKernelGGL((colsum_pass1_kernel<float, 0>), grid, dim3(256), 0, s, (const float *)in, ld, nullptr, nullptr,
                        nullptr, scratch, M, N);
-  hipLaunchKernelGGL(colsum_pass2_kernel, dim3((N + 255) / 256), dim3(256), 0, s, scratch, out, nullptr, nch, N);
+  hipLaunchKernelGGL(colsum_pass2_kernel, dim3((N + 255) / 256), dim3(256), 0, s, scratch, out, nullptr, nch, N, acc);
   return hipGetLastError();
 }
 
 hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const float *mean, const float *rstd,
-                                       float *dgamma, float *dbeta, float *scratch, int M, int d, hipStream_t s) {
+                                       float *dgamma, float *dbeta, float *scratch, int M, int d, int acc,
+                                       hipStream_t s) {
   const int nch = colsum_chunks(M);
   dim3 grid((d + 63) / 64, nch);
   ProfScope ps("layernorm_bwd_params", s, 0, 8.0 * M * d);
   hipLaunchKernelGGL((colsum_pass1_kernel<float, 1>), grid, dim3(256), 0, s, dy, (int64_t)d, x, mean, rstd, scratch, M,
                      d);
-  hipLaunchKernelGGL(colsum_pass2_kernel, dim3((d + 255) / 256), dim3(256), 0, s, scratch, dgamma, dbeta, nch, d);
+  hipLaunchKernelGGL(colsum_pass2_kernel, dim3((d + 255) / 256), dim3(256), 0, s, scratch, dgamma, dbeta, nch, d, acc);
   return hipGetLastError();
 }
 

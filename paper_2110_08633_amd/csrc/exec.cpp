@@ -101,13 +101,14 @@ hipError_t linear_dx(int dt, int M, int N, int K, const void *dY, const void *W,
   g.out_f32 = out_f32; g.out_act = out_act; g.epi = epi; g.aux = aux;
   return launch_gemm(g, st);
 }
-// dW = x^T*dy : X [M,K] (ldx), dY [M,N] (ldy) -> fp32 [K,N]
+// dW (+)= x^T*dy : X [M,K] (ldx), dY [M,N] (ldy) -> fp32 [K,N]; acc adds to what dW holds
 hipError_t linear_dw(int dt, int M, int N, int K, const void *X, int64_t ldx, const void *dY, int64_t ldy, float *dW,
-                     hipStream_t st) {
+                     int acc, hipStream_t st) {
   GemmDesc g;
   g.dtype = dt; g.ta = 1; g.tb = 1; g.M = K; g.N = N; g.K = M;
   g.A = X; g.lda = ldx; g.B = dY; g.ldb = ldy; g.ldc = N;
   g.out_f32 = dW;
+  if (acc) g.resid = dW;  // every element is read and then written by the same thread
   return launch_gemm(g, st);
 }
 
@@ -180,7 +181,7 @@ hipError_t act_view(int dt, const float *src, void *scratch, int M, int d, const
 }
 
 hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, const LayerActs &A,
-                          const float *dx2, float *dx_out, const BwdScratch &Z, hipStream_t st) {
+                          const float *dx2, float *dx_out, const BwdScratch &Z, int acc, hipStream_t st) {
   const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
   const int64_t TT = (int64_t)T * T;
   const BlockOffsets &o = s.bo;
@@ -188,20 +189,20 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
   const void *dx2a;
   CK(act_view(dt, dx2, Z.dact, M, d, &dx2a, st));
   // MLP down projection
-  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, st));
-  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, st));
+  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, st));
+  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, st));
   CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, Z.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
   // MLP up projection
-  CK(launch_colsum(dt, Z.du, F, W.G + o.b_fc, Z.red, M, F, st));
-  CK(linear_dw(dt, M, F, d, A.c, d, Z.du, F, W.G + o.w_fc, st));
+  CK(launch_colsum(dt, Z.du, F, W.G + o.b_fc, Z.red, M, F, acc, st));
+  CK(linear_dw(dt, M, F, d, A.c, d, Z.du, F, W.G + o.w_fc, acc, st));
   CK(linear_dx(dt, M, F, d, Z.du, W.w_fc, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // dc
-  CK(launch_layernorm_bwd_params(Z.dtmp, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, st));
+  CK(launch_layernorm_bwd_params(Z.dtmp, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, st));
   CK(launch_layernorm_bwd_dx(Z.dtmp, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, Z.dx1, M, d, st));
   // attention output projection
   const void *dx1a;
   CK(act_view(dt, Z.dx1, Z.dact, M, d, &dx1a, st));
-  CK(launch_colsum(DT_F32, Z.dx1, d, W.G + o.b_o, Z.red, M, d, st));
-  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, st));
+  CK(launch_colsum(DT_F32, Z.dx1, d, W.G + o.b_o, Z.red, M, d, acc, st));
+  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, st));
   CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
   // attention core
   const void *q = A.qkv, *k = off_act((const void *)A.qkv, d, dt), *v = off_act((const void *)A.qkv, 2 * d, dt);
@@ -244,10 +245,10 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
     CK(launch_gemm(g, st));
   }
   // QKV projection
-  CK(launch_colsum(dt, Z.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, st));
-  CK(linear_dw(dt, M, 3 * d, d, A.a, d, Z.dqkv, 3 * d, W.G + o.w_qkv, st));
+  CK(launch_colsum(dt, Z.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, st));
+  CK(linear_dw(dt, M, 3 * d, d, A.a, d, Z.dqkv, 3 * d, W.G + o.w_qkv, acc, st));
   CK(linear_dx(dt, M, 3 * d, d, Z.dqkv, W.w_qkv, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // da
-  CK(launch_layernorm_bwd_params(Z.dtmp, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, st));
+  CK(launch_layernorm_bwd_params(Z.dtmp, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, acc, st));
   CK(launch_layernorm_bwd_dx(Z.dtmp, x_in, A.mean1, A.rstd1, W.ln1_g, Z.dx1, dx_out, M, d, st));
   return hipSuccess;
 }
@@ -315,11 +316,13 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const int dt = mm->dtype;
   hipStream_t st = ctx->lanes[mm->lane].stream;
   const int M = (int)s.M, d = s.d;
+  const int64_t act = (int64_t)M * d;  // elements of one micro-batch's boundary activation
   HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
   hydra_ctx::Lane &ln = ctx->lanes[mm->lane];
   Bump b{ln.ws, ctx->ws_bytes};
   if (shard == 0) {
-    HYDRA_HIP(ctx, launch_embed_fwd(mm->tok, sl->w, sl->w + (int64_t)s.V * d, mm->ckpt[0], M, s.T, d, st));
+    // one launch over every micro-batch: a row's position is its index modulo T
+    HYDRA_HIP(ctx, launch_embed_fwd(mm->tok, sl->w, sl->w + (int64_t)s.V * d, mm->ckpt[0], (int)s.Mt, s.T, d, st));
     return HYDRA_OK;
   }
   if (shard <= s.S) {
@@ -328,11 +331,13 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     float *Sbuf = b.take<float>((uint64_t)s.B * s.H * s.T * s.T);
     float *pp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (forward)");
-    const float *x = mm->ckpt[shard - 1];
-    for (int j = 0; j < s.k; ++j) {
-      float *y = (j == s.k - 1) ? mm->ckpt[shard] : pp[j & 1];
-      HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), x, y, A, Sbuf, st));
-      x = y;
+    for (int u = 0; u < s.nm; ++u) {  // micro-batches share the workspace, one after the other
+      const float *x = mm->ckpt[shard - 1] + u * act;
+      for (int j = 0; j < s.k; ++j) {
+        float *y = (j == s.k - 1) ? mm->ckpt[shard] + u * act : pp[j & 1];
+        HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), x, y, A, Sbuf, st));
+        x = y;
+      }
     }
     return HYDRA_OK;
   }
@@ -341,16 +346,19 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   void *z = b.take<char>((uint64_t)M * d * dt_size(dt));
   float *mean = b.take<float>(M), *rstd = b.take<float>(M);
   if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (head)");
-  HYDRA_HIP(ctx, launch_layernorm_fwd(dt, mm->ckpt[s.S], sl->w, sl->w + d, z, mean, rstd, M, d, st));
-  GemmDesc g;
-  g.dtype = dt; g.M = M; g.N = s.V; g.K = d; g.A = z; g.lda = d; g.ta = 0;
-  if (dt == DT_BF16) { g.tb = 0; g.B = sl->wb + 2 * d; g.ldb = d; }
-  else { g.tb = 1; g.B = sl->w + 2 * d; g.ldb = s.V; }
-  g.out_f32 = logits; g.ldc = s.Vpad;
-  HYDRA_HIP(ctx, launch_gemm(g, st));
-  const float inv_n = 1.0f / (float)mm->n_valid;
-  HYDRA_HIP(ctx, launch_cross_entropy(dt, logits, mm->tgt, mm->row_loss, mm->dlogits, M, s.V, s.Vpad, inv_n, st));
-  HYDRA_HIP(ctx, launch_loss_reduce(mm->row_loss, mm->loss, M, inv_n, st));
+  const float inv_n = 1.0f / (float)mm->n_valid;  // valid targets of the whole minibatch
+  for (int u = 0; u < s.nm; ++u) {
+    HYDRA_HIP(ctx, launch_layernorm_fwd(dt, mm->ckpt[s.S] + u * act, sl->w, sl->w + d, z, mean, rstd, M, d, st));
+    GemmDesc g;
+    g.dtype = dt; g.M = M; g.N = s.V; g.K = d; g.A = z; g.lda = d; g.ta = 0;
+    if (dt == DT_BF16) { g.tb = 0; g.B = sl->wb + 2 * d; g.ldb = d; }
+    else { g.tb = 1; g.B = sl->w + 2 * d; g.ldb = s.V; }
+    g.out_f32 = logits; g.ldc = s.Vpad;
+    HYDRA_HIP(ctx, launch_gemm(g, st));
+    HYDRA_HIP(ctx, launch_cross_entropy(dt, logits, mm->tgt + (int64_t)u * M, mm->row_loss + (int64_t)u * M,
+                                        off_act(mm->dlogits, (int64_t)u * M * s.Vpad, dt), M, s.V, s.Vpad, inv_n, st));
+  }
+  HYDRA_HIP(ctx, launch_loss_reduce(mm->row_loss, mm->loss, (int)s.Mt, inv_n, st));
   ln.logits = logits;
   ln.logits_owner = (int)(std::find(ctx->models.begin(), ctx->models.end(), mm) - ctx->models.begin());
   for (Model *o : ctx->models)
@@ -363,6 +371,7 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   const int dt = mm->dtype;
   hipStream_t st = ctx->lanes[mm->lane].stream;
   const int M = (int)s.M, d = s.d;
+  const int64_t act = (int64_t)M * d;
   HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
   hydra_ctx::Lane &ln = ctx->lanes[mm->lane];
   Bump b{ln.ws, ctx->ws_bytes};
@@ -378,18 +387,21 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     float *dz = b.take<float>((uint64_t)M * d);
     float *red = b.take<float>(red_elems(s));
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (head backward)");
-    const float *x = mm->ckpt[s.S];
-    HYDRA_HIP(ctx, launch_layernorm_fwd(dt, x, sl->w, sl->w + d, z, mean, rstd, M, d, st));
-    HYDRA_HIP(ctx, linear_dw(dt, M, s.V, d, z, d, mm->dlogits, s.Vpad, sl->g + 2 * d, st));
-    GemmDesc g;
-    g.dtype = dt; g.M = M; g.N = d; g.K = s.V; g.A = mm->dlogits; g.lda = s.Vpad; g.ta = 0;
-    if (dt == DT_BF16) { g.tb = 1; g.B = sl->wb + 2 * d; g.ldb = d; }
-    else { g.tb = 0; g.B = sl->w + 2 * d; g.ldb = s.V; }
-    g.out_f32 = dz; g.ldc = d;
-    HYDRA_HIP(ctx, launch_gemm(g, st));
-    HYDRA_HIP(ctx, launch_layernorm_bwd_params(dz, x, mean, rstd, sl->g, sl->g + d, red, M, d, st));
     mm->dcur = 0;
-    HYDRA_HIP(ctx, launch_layernorm_bwd_dx(dz, x, mean, rstd, sl->w, nullptr, mm->dbound[0], M, d, st));
+    for (int u = 0; u < s.nm; ++u) {  // gradients of the shard's tensors add up over micro-batches
+      const float *x = mm->ckpt[s.S] + u * act;
+      const void *dl = off_act((const void *)mm->dlogits, (int64_t)u * M * s.Vpad, dt);
+      HYDRA_HIP(ctx, launch_layernorm_fwd(dt, x, sl->w, sl->w + d, z, mean, rstd, M, d, st));
+      HYDRA_HIP(ctx, linear_dw(dt, M, s.V, d, z, d, dl, s.Vpad, sl->g + 2 * d, u > 0, st));
+      GemmDesc g;
+      g.dtype = dt; g.M = M; g.N = d; g.K = s.V; g.A = dl; g.lda = s.Vpad; g.ta = 0;
+      if (dt == DT_BF16) { g.tb = 1; g.B = sl->wb + 2 * d; g.ldb = d; }
+      else { g.tb = 0; g.B = sl->w + 2 * d; g.ldb = s.V; }
+      g.out_f32 = dz; g.ldc = d;
+      HYDRA_HIP(ctx, launch_gemm(g, st));
+      HYDRA_HIP(ctx, launch_layernorm_bwd_params(dz, x, mean, rstd, sl->g, sl->g + d, red, M, d, u > 0, st));
+      HYDRA_HIP(ctx, launch_layernorm_bwd_dx(dz, x, mean, rstd, sl->w, nullptr, mm->dbound[0] + u * act, M, d, st));
+    }
     return HYDRA_OK;
   }
   if (shard >= 1) {
@@ -401,20 +413,24 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     BwdScratch Z = take_bwd(b, s, dt);
     float *gpp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (backward)");
-    xs[0] = mm->ckpt[shard - 1];
-    for (int j = 0; j < s.k; ++j)
-      HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), xs[j], xs[j + 1], acts[j], Z.dP, st));
-    const float *dx = mm->dbound[mm->dcur];
-    for (int j = s.k - 1; j >= 0; --j) {
-      float *out = (j == 0) ? mm->dbound[mm->dcur ^ 1] : gpp[j & 1];
-      HYDRA_HIP(ctx, block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, out, Z, st));
-      dx = out;
+    for (int u = 0; u < s.nm; ++u) {  // recompute and back-propagate one micro-batch at a time
+      xs[0] = mm->ckpt[shard - 1] + u * act;
+      for (int j = 0; j < s.k; ++j)
+        HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), xs[j], xs[j + 1], acts[j], Z.dP, st));
+      const float *dx = mm->dbound[mm->dcur] + u * act;
+      for (int j = s.k - 1; j >= 0; --j) {
+        float *out = (j == 0) ? mm->dbound[mm->dcur ^ 1] + u * act : gpp[j & 1];
+        HYDRA_HIP(ctx, block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, out, Z, u > 0, st));
+        dx = out;
+      }
     }
     mm->dcur ^= 1;
     return HYDRA_OK;
   }
   // EMBED
-  HYDRA_HIP(ctx, launch_embed_bwd(mm->tok, mm->dbound[mm->dcur], sl->g, sl->g + (int64_t)s.V * d, s.B, s.T, d, s.V, st));
+  for (int u = 0; u < s.nm; ++u)
+    HYDRA_HIP(ctx, launch_embed_bwd(mm->tok + (int64_t)u * M, mm->dbound[mm->dcur] + u * act, sl->g,
+                                    sl->g + (int64_t)s.V * d, s.B, s.T, d, s.V, u > 0, st));
   return HYDRA_OK;
 }
 

@@ -31,7 +31,9 @@ struct BlockOffsets {
 
 struct ModelShape {
   int L, d, H, F, V, T, B, k, S, dh;
-  int64_t M;     // tokens per minibatch
+  int nm;        // micro-batches per minibatch
+  int64_t M;     // tokens per micro-batch
+  int64_t Mt;    // tokens per minibatch = nm * M
   int64_t Vpad;  // leading dimension of logits / dlogits
   BlockOffsets bo;
   int64_t n_params;

@@ -57,7 +57,9 @@ hipError_t launch_gemm(const GemmDesc &g, hipStream_t s);
 hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *wpe, float *x0, int M, int T, int d,
                             hipStream_t s);
 // dwte = 0 then rows of present tokens accumulate dx0 in ascending m; dwpe[t] = sum_b dx0[b*T+t]
+// acc != 0 adds to the gradients already held (a later micro-batch of the same minibatch)
 hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, float *dwpe, int B, int T, int d, int V,
+                            int acc,
                             hipStream_t s);
 
 hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, const float *beta, void *y, float *mean,
@@ -65,12 +67,12 @@ hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, c
 // dx = dres + LN'(dy) (dres may be null); dy is fp32
 hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
                                    const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s);
-// dgamma[n] = sum_m dy*xhat, dbeta[n] = sum_m dy ; scratch: fp32 [2 * colsum_chunks(M) * d]
+// dgamma[n] = sum_m dy*xhat, dbeta[n] = sum_m dy ; scratch: fp32 [2 * colsum_chunks(M) * d]; acc != 0 adds to the outputs
 hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const float *mean, const float *rstd,
-                                       float *dgamma, float *dbeta, float *scratch, int M, int d, hipStream_t s);
+                                       float *dgamma, float *dbeta, float *scratch, int M, int d, int acc, hipStream_t s);
 int colsum_chunks(int M);
-// out[n] = sum_m in[m,n]; in has operand dtype (or fp32 when in_dtype == DT_F32); scratch fp32 [colsum_chunks(M)*N]
-hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N,
+// out[n] (+)= sum_m in[m,n]; in has operand dtype (or fp32 when in_dtype == DT_F32); scratch fp32 [colsum_chunks(M)*N]
+hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N, int acc,
                          hipStream_t s);
 
 // P[z,i,j] = softmax_j<=i S[z,i,j]; zero for i < j < min(T, roundup(i+1,256)); nothing written beyond

@@ -27,9 +27,12 @@ hydra_status build_shape(const hydra_model_desc *d, ModelShape *s, std::string *
   if ((d->d_model / d->n_head) % 8) return bad("head width d_model/n_head must be a multiple of 8");
   if (d->dtype != 0 && d->dtype != 1) return bad("dtype must be 0 (fp32) or 1 (bf16)");
   if ((int64_t)d->batch * d->seq > 32768) return bad("batch*seq above 32768 tokens is not supported");
+  if (d->n_micro < 0 || d->n_micro > 4096) return bad("n_micro must be in 0..4096");
   s->L = d->n_layer; s->d = d->d_model; s->H = d->n_head; s->F = d->d_ff; s->V = d->vocab;
   s->T = d->seq; s->B = d->batch; s->k = d->layers_per_shard; s->S = s->L / s->k; s->dh = s->d / s->H;
   s->M = (int64_t)s->B * s->T;
+  s->nm = d->n_micro > 0 ? d->n_micro : 1;
+  s->Mt = s->M * s->nm;
   s->Vpad = ((int64_t)s->V + 63) / 64 * 64;
   const int64_t dd = s->d, F = s->F;
   BlockOffsets &b = s->bo;

@@ -182,7 +182,7 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
       if ((st = promote(s, i + 1, mid, t.shard))) return st;
     }
     if (t.phase == 0 && t.shard == 0) {
-      const int64_t per = mm->sh.M;
+      const int64_t per = mm->sh.Mt;
       if ((st = hydra_set_batch(ctx, mid, tokens[t.model] + t.minibatch * per, targets[t.model] + t.minibatch * per)))
         return st;
     }

@@ -53,7 +53,7 @@ class Session:
                 master[off:off + rows * cols] = np.asarray(weights[name], np.float32).reshape(-1)
         ckpt = None
         if self.flags & H.FLAG_CKPT_SPILL:
-            ckpt = self._host((lay.n_block_shards + 1) * cfg["B"] * cfg["T"] * cfg["d"])
+            ckpt = self._host((lay.n_block_shards + 1) * cfg.get("n_micro", 1) * cfg["B"] * cfg["T"] * cfg["d"])
         mid = H.hydra_register_model(self.ctx, desc, master, m, v, ckpt)
         rec = dict(id=mid, desc=desc, cfg=cfg, layout=lay, master=master, m=m, v=v, ckpt=ckpt, tensors=tensors,
                    S=lay.n_block_shards)
@@ -71,6 +71,7 @@ class Session:
         return out
 
     def read_logits(self, rec):
+        """Logits of the last micro-batch of the model's last HEAD forward."""
         cfg = rec["cfg"]
         out = np.empty((cfg["B"] * cfg["T"], cfg["V"]), np.float32)
         H.hydra_read_device(self.ctx, rec["id"], 0, H.RD_LOGITS, out)
@@ -78,7 +79,7 @@ class Session:
 
     def read_act(self, rec, shard, which):
         cfg = rec["cfg"]
-        out = np.empty((cfg["B"] * cfg["T"], cfg["d"]), np.float32)
+        out = np.empty((cfg.get("n_micro", 1) * cfg["B"] * cfg["T"], cfg["d"]), np.float32)
         H.hydra_read_device(self.ctx, rec["id"], shard, which, out)
         return out
 
@@ -136,7 +137,8 @@ def arena_bytes_for(cfgs, n_slots, ckpt_spill=False, lanes=1):
         S = c["L"] // k
         act = M * d * 4
         vpad = (V + 63) // 64 * 64
-        total += (2 if ckpt_spill else S + 1) * act + 2 * act + M * vpad * 4 + 64 * M + (1 << 16)
+        nm = c.get("n_micro", 1)
+        total += nm * ((2 if ckpt_spill else S + 1) * act + 2 * act + M * vpad * 4 + 64 * M) + (1 << 16)
         layer = 5 * act + 3 * M * d * 4 + M * 3 * d * 4 + B * c["H"] * T * T * 4 + 2 * M * F * 4
         scratch = 2 * B * c["H"] * T * T * 4 + 4 * act + M * F * 4 + M * 3 * d * 4 + 4 * act
         ws = max(ws, k * layer + k * act + scratch + 2 * act + (1 << 20), M * vpad * 4 + 4 * act + (1 << 20))

@@ -218,3 +218,67 @@ def test_sharding_does_not_change_gpu_results(rt):
         assert (o[0] == outs[0][0]).all() and o[1] == outs[0][1]
         for name in o[2]:
             assert (o[2][name] == outs[0][2][name]).all(), name
+
+
+@pytest.mark.parametrize("nm,flags", [(2, 0), (3, 6), (4, 0)])   # 6 = checkpoint spilling + poisoned buffers
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_micro_batches_equal_one_large_minibatch(rt, nm, flags, dtype):
+    """A minibatch run as nm micro-batches per shard visit (gradients summed while the shard is resident) equals
+    the oracle's single step on all nm*B samples: loss over all valid targets, every gradient, weights after
+    two steps.  Micro-batches carry different numbers of valid targets, so averaging per micro-batch would fail."""
+    H, R = rt
+    base = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=72, B=2, k=2, dtype=dtype, lrs=[1e-4])
+    big = dict(base, B=base["B"] * nm)
+    cfg = dict(base, n_micro=nm)
+    W = SI.make_weights(base, 77)
+    batches = []
+    for i in range(2):
+        tok, tgt = SI.make_batch(big, 900 + i, zipf=(i == 1))
+        tgt[: base["B"], 5:] = -1          # the first micro-batch has few valid targets
+        batches.append((tok, tgt))
+    refs, P, Mo, Vo = oracle_steps(big, W, 1e-4, batches)
+    sess = R.Session(R.arena_bytes_for([cfg], 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags, max_slots=3)
+    rec = sess.add_model(cfg, W, 1e-4)
+    ill, tol, M = {}, TOL[dtype], base["B"] * base["T"]
+    for i, (tok, tgt) in enumerate(batches):
+        got = sess.train_step_manual(rec, tok, tgt)
+        H.hydra_sync(sess.ctx)
+        assert_close(got["logits"], refs[i]["logits"][-M:], tol, "logits of the last micro-batch")
+        assert abs(got["loss"] - refs[i]["loss"]) <= tol * abs(refs[i]["loss"])
+        for name, g in refs[i]["grads"].items():
+            assert_close(got["grads"][name], g, tol, f"grad {name}")
+        update_ill(ill, refs[i]["grads"], dtype)
+        after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
+        check_weights(after, refs[i]["after"], refs[0]["before"], ill, 1e-4, i + 1, dtype, f"step {i}: ")
+    sess.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scheduled_run_with_micro_batches(rt, dtype):
+    """Two models, one with 3 micro-batches per visit and one with 1, through the scheduler on two lanes with
+    three shard buffers; weights after two minibatches each against the oracle on the full minibatches."""
+    H, R = rt
+    base = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=2, lrs=[1e-4, 3e-4])
+    nms = [3, 1]
+    cfgs = [dict(base, n_micro=nm) for nm in nms]
+    bigs = [dict(base, B=base["B"] * nm) for nm in nms]
+    Ws = [SI.make_weights(base, 50 + m) for m in range(2)]
+    batches = [[SI.make_batch(bigs[m], 800 + 10 * m + i) for i in range(2)] for m in range(2)]
+    fc, bc = SI.task_costs(base)
+    sess = R.Session(R.arena_bytes_for(cfgs, 3, lanes=2), max_slots=3, lanes=2, flags=H.FLAG_POISON)
+    recs = [sess.add_model(cfgs[m], Ws[m], base["lrs"][m]) for m in range(2)]
+    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [2, 2], [list(fc) + list(bc)] * 2)
+    toks = [np.stack([b[0] for b in batches[m]]) for m in range(2)]
+    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(2)]
+    H.hydra_sched_run(sch, toks, tgts, sess.ctx)
+    sess.flush()
+    for m in range(2):
+        refs, P, _, _ = oracle_steps(bigs[m], Ws[m], base["lrs"][m], batches[m])
+        ill = {}
+        for r in refs:
+            update_ill(ill, r["grads"], dtype)
+        assert abs(H.hydra_get_loss(sess.ctx, recs[m]["id"]) - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
+        check_weights(sess.unpack(recs[m], recs[m]["master"]), P, refs[0]["before"], ill, base["lrs"][m], 2, dtype,
+                      f"model {m} ")
+    H.hydra_sched_destroy(sch)
+    sess.close()

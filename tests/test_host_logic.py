@@ -52,7 +52,7 @@ def test_layout_matches_shapes_and_counts(name, total, per_block):
 
 def test_bad_descriptions_are_rejected():
     base = dict(SI.small_cfg())
-    for bad in (dict(d=20), dict(k=3, L=4), dict(T=9), dict(H=3), dict(F=30), dict(L=0)):
+    for bad in (dict(d=20), dict(k=3, L=4), dict(T=9), dict(H=3), dict(F=30), dict(L=0), dict(n_micro=-1)):
         c = dict(base)
         c.update(bad)
         with pytest.raises(H.HydraError) as e:
@@ -181,15 +181,19 @@ def test_dry_sched_run_trace_equals_oracle_and_traffic(max_slots):
     s.close()
 
 
-def test_dry_checkpoint_spill_traffic_and_ordering_guard():
+@pytest.mark.parametrize("nm", [1, 3])
+def test_dry_checkpoint_spill_traffic_and_ordering_guard(nm):
+    """Checkpoint traffic grows with the micro-batch count, state traffic does not."""
     cfg = SI.small_cfg(L=4, k=2)
+    if nm > 1:
+        cfg = dict(cfg, n_micro=nm)
     s, _ = _dry_session(1, max_slots=2, flags=H.FLAG_CKPT_SPILL, cfg=cfg)
     S = 2
     sch = H.hydra_sched_create(s.ctx, [0], [1], [_costs(cfg)])
-    tok, tgt = SI.make_batch(cfg, 3)
+    tok, tgt = SI.make_batch(dict(cfg, B=cfg["B"] * nm), 3)
     H.hydra_sched_run(sch, [tok[None]], [tgt[None]], s.ctx)
     st = H.hydra_get_stats(s.ctx)
-    act = cfg["B"] * cfg["T"] * cfg["d"] * 4
+    act = nm * cfg["B"] * cfg["T"] * cfg["d"] * 4
     n = s.models[0]["layout"].n_params
     assert st["bytes_d2h"] == 12 * n + (S + 1) * act          # S+1 boundaries written to the host
     assert st["bytes_h2d"] >= 12 * n + S * act                # and the S inputs of the block shards read back
