@@ -6,6 +6,7 @@
 // (dx = dy*W^T) and weight gradients (dW = x^T*dy) and the batched attention
 // products are all instances of C = alpha * op(A) * op(B) with a row-major C.
 #include <cstdlib>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -22,13 +23,14 @@ struct GemmArgs {
   int64_t lda, ldb, ldc;
   int nb2;
   int64_t sA1, sA2, sB1, sB2, sC1, sC2;
-  float alpha;
   const float *bias, *resid;
   float *out_f32;
   void *out_act, *out_act2;
   const void *aux;
   int epi, causal;
   int tiles_m, tiles_n;
+  float alpha;  // kept among the 32-bit fields: next to a pointer the compiler fused both into one 16-byte load and
+  int pad_;     // parked it in scratch memory, and a kernel that uses scratch pays microseconds per launch
 };
 
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
@@ -206,12 +208,16 @@ __device__ __forceinline__ bf16x8_t fragment(const bf16_t *lds, int o0, int o1) 
 
 // 4 consecutive columns of one row of C
 template <typename ActT>
-__device__ __forceinline__ void epilogue_store4(const GemmArgs &g, int64_t coff, int row, int col, const float *acc,
+__device__ __forceinline__ void epilogue_store4(const GemmArgs &g, int64_t coff, int row, int col, const f32x4_t acc,
                                                 bool vec) {
   if (!vec || col + 3 >= g.N) {
 #pragma unroll 1
-    for (int e = 0; e < 4; ++e)
-      if (col + e < g.N) epilogue_store<ActT>(g, coff, row, col + e, acc[e]);
+    for (int e = 0; e < 4; ++e) {
+      // chosen by comparison, not by address: an indexed local array would live in scratch memory, and a kernel
+      // that uses scratch pays several microseconds per launch for its set-up
+      const float x = e == 0 ? acc[0] : e == 1 ? acc[1] : e == 2 ? acc[2] : acc[3];
+      if (col + e < g.N) epilogue_store<ActT>(g, coff, row, col + e, x);
+    }
     return;
   }
   float v[4];
@@ -254,6 +260,130 @@ __device__ __forceinline__ void epilogue_store4(const GemmArgs &g, int64_t coff,
     o.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
     o.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
     *(u32x2_t *)((bf16_t *)g.out_act + idx) = o;
+  }
+}
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+// two fp32 -> packed bf16, round to nearest even (one instruction on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  const f32x2_t v = {a, b};
+  union { bf16x2_t h; uint32_t u; } x;
+  x.h = __builtin_convertvector(v, bf16x2_t);
+  return x.u;
+}
+// tanh(x) = 1 - 2 / (exp(2x) + 1): exact limits at both infinities; the absolute error of about 1e-7 near zero
+// is far below what a bf16 result keeps
+__device__ __forceinline__ float tanh_fast(float x) {
+  return 1.f - 2.f * __builtin_amdgcn_rcpf(__expf(2.f * x) + 1.f);
+}
+__device__ __forceinline__ float gelu_fast(float u) {
+  const float c = 0.7978845608028654f;
+  return 0.5f * u * (1.f + tanh_fast(c * (u + 0.044715f * u * u * u)));
+}
+__device__ __forceinline__ float dgelu_fast(float u) {
+  const float c = 0.7978845608028654f;
+  const float t = tanh_fast(c * (u + 0.044715f * u * u * u));
+  const float dt = (1.f - t * t) * c * (1.f + 3.f * 0.044715f * u * u);
+  return 0.5f * (1.f + t) + 0.5f * u * dt;
+}
+
+// Row-wise write-out of a wavefront's staged [32][WTN] fp32 patch (LDS, pitch WTN + 4) to rows row0.. and columns
+// col0.. of C.  LPR lanes cover a row with 4 columns each, so one instruction stores whole row segments.  With one
+// wavefront per SIMD nothing hides latency here, so the work is batched: the epilogue kind is a template
+// parameter, addresses advance by addition, and the rows are handled four instructions' worth at a time - all LDS
+// reads and all global loads (residual, GELU pre-activation) of a batch are issued before the first is used, and
+// all its stores follow together (a load issued after a store has to wait until that store has completed).
+// bf16 packing is the hardware conversion.  Needs: 16-byte aligned fp32 pointers, 8-byte aligned bf16 pointers,
+// ldc % 4 == 0, col0 + WTN <= N, row0 + 32 <= M.
+template <int WTN, int EPI>
+__device__ __forceinline__ void store_patch_rows(const GemmArgs &g, int64_t coff, const float *patch, int row0,
+                                                 int col0, int lane) {
+  constexpr int SP = WTN + 4, LPR = WTN / 4, RPI = 64 / LPR, NIT = 32 / RPI, U = NIT < 4 ? NIT : 4;
+  const int c = (lane % LPR) * 4, r0 = lane / LPR;
+  const int col = col0 + c;
+  f32x4_t b4 = {0.f, 0.f, 0.f, 0.f};
+  if (g.bias) b4 = *(const f32x4_t *)(g.bias + col);
+  const float alpha = g.alpha;
+  int64_t idx = coff + (int64_t)(row0 + r0) * g.ldc + col;
+  const int64_t step = (int64_t)RPI * g.ldc;
+  const float *pp = patch + r0 * SP + c;
+  const bool has_resid = g.resid != nullptr, has_f32 = g.out_f32 != nullptr, has_act = g.out_act != nullptr;
+#pragma unroll 1
+  for (int p0 = 0; p0 < NIT; p0 += U, idx += U * step, pp += U * RPI * SP) {
+    f32x4_t v[U], r[U];
+    u32x2_t a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = *(const f32x4_t *)(pp + u * RPI * SP);
+    if (EPI == EPI_DGELU) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) a[u] = *(const u32x2_t *)((const bf16_t *)g.aux + idx + u * step);
+    }
+    if (EPI != EPI_GELU && has_resid) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) r[u] = *(const f32x4_t *)(g.resid + idx + u * step);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = v[u] * alpha + b4;
+    if (EPI == EPI_GELU) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        u32x2_t o, h;
+        o.x = pack_bf16(v[u][0], v[u][1]);
+        o.y = pack_bf16(v[u][2], v[u][3]);
+        h.x = pack_bf16(gelu_fast(v[u][0]), gelu_fast(v[u][1]));
+        h.y = pack_bf16(gelu_fast(v[u][2]), gelu_fast(v[u][3]));
+        *(u32x2_t *)((bf16_t *)g.out_act + idx + u * step) = o;
+        *(u32x2_t *)((bf16_t *)g.out_act2 + idx + u * step) = h;
+      }
+      continue;
+    }
+    if (EPI == EPI_DGELU) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        v[u][0] *= dgelu_fast(__uint_as_float(a[u].x << 16));
+        v[u][1] *= dgelu_fast(__uint_as_float(a[u].x & 0xffff0000u));
+        v[u][2] *= dgelu_fast(__uint_as_float(a[u].y << 16));
+        v[u][3] *= dgelu_fast(__uint_as_float(a[u].y & 0xffff0000u));
+      }
+    }
+    if (has_resid) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] += r[u];
+    }
+    if (has_f32) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) *(f32x4_t *)(g.out_f32 + idx + u * step) = v[u];
+    }
+    if (has_act) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        u32x2_t o;
+        o.x = pack_bf16(v[u][0], v[u][1]);
+        o.y = pack_bf16(v[u][2], v[u][3]);
+        *(u32x2_t *)((bf16_t *)g.out_act + idx + u * step) = o;
+      }
+    }
+  }
+}
+
+template <int WTN>
+__device__ __forceinline__ void store_patch(const GemmArgs &g, int64_t coff, const float *patch, int row0, int col0,
+                                            int lane, bool vec) {
+  if (vec && col0 + WTN <= g.N && row0 + 32 <= g.M) {  // uniform over the wavefront
+    if (g.epi == EPI_GELU) store_patch_rows<WTN, EPI_GELU>(g, coff, patch, row0, col0, lane);
+    else if (g.epi == EPI_DGELU) store_patch_rows<WTN, EPI_DGELU>(g, coff, patch, row0, col0, lane);
+    else store_patch_rows<WTN, EPI_NONE>(g, coff, patch, row0, col0, lane);
+    return;
+  }
+  // ragged edge or unaligned operands: element-wise, one copy of the code
+  constexpr int SP = WTN + 4, LPR = WTN / 4, RPI = 64 / LPR;
+#pragma unroll 1
+  for (int p = 0; p < 32 / RPI; ++p) {
+    const int r = p * RPI + lane / LPR, c = (lane % LPR) * 4;
+    const f32x4_t v4 = *(const f32x4_t *)(patch + r * SP + c);
+    const int row = row0 + r, col = col0 + c;
+    if (row < g.M && col < g.N) epilogue_store4<bf16_t>(g, coff, row, col, v4, vec);
   }
 }
 
@@ -421,18 +551,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
       }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the patch is written (LDS serves a wavefront in order)
     __builtin_amdgcn_wave_barrier();
-    // deliberately a rolled loop: one copy of the epilogue code keeps the kernel small enough for the
-    // instruction cache (the unrolled form spent thousands of cycles per block fetching cold code)
-#pragma unroll 1
-    for (int p = 0; p < 32 / RPI; ++p) {
-      const int r = p * RPI + lane / LPR, c = (lane % LPR) * 4;
-      const f32x4_t v4 = *(const f32x4_t *)(patch + r * SP + c);
-      const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + c;
-      if (row < g.M && col < g.N) {
-        float v[4] = {v4[0], v4[1], v4[2], v4[3]};
-        epilogue_store4<bf16_t>(g, coff, row, col, v, vec);
-      }
-    }
+    store_patch<WTN>(g, coff, patch, m0 + wm * WTM + i * 32, n0 + wn * WTN, lane, vec);
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_wave_barrier();
   }
@@ -440,6 +559,301 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
 #ifdef HYDRA_GEMM_TRACE
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_gemm_trace[8191] = trace_n;
 #endif
+}
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA kernel for plain products (one matrix, no causal short-cut, K a
+// multiple of the slice width) with large tiles.
+//
+// Two per-CU rates bound a bf16 GEMM on this chip besides the MFMA rate (about
+// 4096 flop per clock and CU): the vector-memory path delivers 64 bytes per
+// clock, so a tile needs 2*BM*BN/(BM+BN) >= 64 flop per operand byte just to
+// keep up (128x128 tiles sit exactly on that line, 256x256 tiles need half of
+// it), and LDS serves every byte once on its way in and once per wavefront that
+// multiplies it.  Hence
+//   - a wavefront owns (BM/2) x (BN/2) results (up to 128x128, accumulators in
+//     up to 256 registers), one block per CU;
+//   - operand slices go from global memory straight into LDS (16 bytes per
+//     lane; lane l of a wavefront fills LDS base + 16*l), so nothing is staged
+//     in registers and no LDS store is issued; the XOR swizzle of the tiles is
+//     applied on the global side (which 16 bytes a lane fetches);
+//   - S LDS stages of BKT contraction steps each.  The loads of a slice are
+//     spread one by one between groups of MFMAs (issued in a burst they stall
+//     the wavefront for as long as the memory path needs to take them);
+//   - the only barrier of a slice sits before its last contraction step: by
+//     then every wavefront has read that slice completely, so its stage is
+//     handed to the loads of slice t + S, and the first fragments of slice
+//     t + 1 are read while the last MFMAs of slice t run;
+//   - fragments for step kk + 1 are read while the MFMAs of step kk run (one
+//     wavefront per SIMD: the overlap has to come from inside it).
+// Tiles of C are numbered so that each XCD (own L2) works through groups of up
+// to 8 tile rows column by column: the operand panels of a group stay in L2.
+// ---------------------------------------------------------------------------
+template <int BKT> __device__ __forceinline__ int kc_swz_t(int row) {
+  return BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+
+template <int R, int RCL, int BKT>
+struct DirectMover {
+  static constexpr int CPRT = BKT / 8;             // 16-byte chunks per row of a contraction-contiguous tile
+  static constexpr int N = R * CPRT / 256;         // chunks per thread and slice
+  static constexpr int CPK = R / 8;
+  const bf16_t *base;
+  int64_t kstep;
+  uint32_t off[N];
+  __device__ __forceinline__ void init(const bf16_t *mat, int64_t ld, int row0, int rows, int tid) {
+    const int lane = tid & 63, wave = tid >> 6;
+    if (!RCL) {
+      base = mat + (int64_t)row0 * ld;
+      kstep = BKT;
+    } else {
+      base = mat + row0;
+      kstep = (int64_t)BKT * ld;
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int p = (i * 4 + wave) * 64 + lane;  // LDS chunk this lane fills
+      if (!RCL) {
+        int row = p / CPRT;
+        const int kc = (p % CPRT) ^ kc_swz_t<BKT>(row);
+        if (row0 + row >= rows) row = 0;
+        off[i] = (uint32_t)(row * ld + kc * 8);
+      } else {
+        const int k = p / CPK;
+        int c = (p % CPK) ^ rc_swz<R>(k);
+        if (row0 + c * 8 >= rows) c = 0;
+        off[i] = (uint32_t)(k * ld + c * 8);
+      }
+    }
+  }
+  // chunk i of slice t into the operand's tile at lds
+  __device__ __forceinline__ void issue(int i, int t, bf16_t *lds, int wave) const {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + t * kstep + off[i]),
+                                     (__attribute__((address_space(3))) void *)(lds + (i * 4 + wave) * 64 * 8), 16, 0, 0);
+  }
+};
+
+// LDS addresses of a wavefront's operand fragments: NF groups of 32 rows from row rb0 on.  Only NF or BKT/16
+// per-lane offsets are kept; the other index enters as a compile-time constant.
+template <int R, int RCL, int NF, int BKT>
+struct FragAddr {
+  static constexpr int CPRT = BKT / 8;
+  static constexpr int CPK = R / 8;
+  static constexpr int NO = RCL ? NF : BKT / 16;
+  int o[NO];
+  __device__ __forceinline__ void init(int rb0, int lane) {
+    if (!RCL) {
+      const int row = rb0 + (lane & 31), s = kc_swz_t<BKT>(row), hi = lane >> 5;
+#pragma unroll
+      for (int kk = 0; kk < BKT / 16; ++kk) o[kk] = (row * CPRT + ((kk * 2 + hi) ^ s)) * 8;
+    } else {
+      const int G = lane >> 4, sl = lane & 15;
+      const int k0 = (G >> 1) * 8 + (sl >> 2);
+      const int m0 = rb0 + 16 * (G & 1) + 4 * (sl & 3);
+#pragma unroll
+      for (int f = 0; f < NF; ++f) {
+        const int m = m0 + f * 32;
+        o[f] = (k0 * CPK + ((m >> 3) ^ rc_swz<R>(k0))) * 8 + ((m >> 2) & 1) * 4;
+      }
+    }
+  }
+  __device__ __forceinline__ bf16x8_t get(const bf16_t *lds, int f, int kk) const {
+    if (!RCL) return fragment<0>(lds, o[kk] + f * 32 * CPRT * 8, 0);
+    const int b = o[f] + kk * 16 * CPK * 8;  // 16 further contraction steps leave the swizzle unchanged
+    return fragment<1>(lds, b, b + 4 * CPK * 8);
+  }
+};
+
+template <int n> __device__ __forceinline__ void wait_loads_le() {
+  // vmcnt (outstanding vector-memory loads) is split over bits 3:0 and 15:14; lgkmcnt(0): this wavefront's LDS
+  // reads have returned; expcnt is left alone
+  static_assert(n >= 0 && n <= 63, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0070);
+}
+
+template <int BM, int BN, int TA, int TB, int BKT, int S, int OCC>
+__global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs g) {
+  constexpr int WTM = BM / 2, WTN = BN / 2;
+  constexpr int MI = WTM / 32, NJ = WTN / 32;
+  constexpr int KS = BKT / 16;                   // contraction steps of one MFMA per slice
+  constexpr int STAGE = (BM + BN) * BKT;         // elements per stage
+  constexpr int NLA = DirectMover<BM, TA, BKT>::N, NLB = DirectMover<BN, TB, BKT>::N, NL = NLA + NLB;
+  constexpr int G = KS * MI;                     // groups of NJ MFMAs per slice
+  constexpr int QB = (KS - 1) * MI;              // the barrier sits before this group
+  static_assert(KS % 2 == 0 && NL <= G && S >= 2, "pipeline shape");
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds_dyn[];
+#ifdef HYDRA_GEMM_TRACE
+  int trace_n = 0;
+#endif
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int nt = gridDim.x, bid = blockIdx.x;
+  const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
+  const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
+  // groups of up to 8 tile rows, walked column by column
+  const int gsz = 8 * g.tiles_n;
+  const int grp = tile / gsz, in_grp = tile - grp * gsz;
+  const int rows_in_grp = min(8, g.tiles_m - grp * 8);
+  const int tm = grp * 8 + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int nk = g.K / BKT;
+
+  DirectMover<BM, TA, BKT> ma;
+  DirectMover<BN, TB, BKT> mb;
+  ma.init((const bf16_t *)g.A, g.lda, m0, g.M, tid);
+  mb.init((const bf16_t *)g.B, g.ldb, n0, g.N, tid);
+  FragAddr<BM, TA, MI, BKT> fa;
+  FragAddr<BN, TB, NJ, BKT> fb;
+  fa.init(wm * WTM, lane);
+  fb.init(wn * WTN, lane);
+
+  // load l (0..NL-1: first A's chunks, then B's) of slice sl into stage sg
+  auto issue = [&](int l, int sl, int sg) {
+    bf16_t *base = lds_dyn + sg * STAGE;
+    if (l < NLA) ma.issue(l, sl, base, wave);
+    else mb.issue(l - NLA, sl, base + BM * BKT, wave);
+  };
+
+  f32x16_t acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // prologue: slices 0 .. S-2 completely and the head of slice S-1 (what the steady state issues after a barrier)
+  constexpr int HEAD = (G - QB) < NL ? (G - QB) : NL;
+#pragma unroll
+  for (int p = 0; p < S - 1; ++p)
+    if (p < nk) {
+#pragma unroll
+      for (int l = 0; l < NL; ++l) issue(l, p, p);
+    }
+  if (S - 1 < nk) {
+#pragma unroll
+    for (int l = 0; l < HEAD; ++l) issue(l, S - 1, S - 1);
+  }
+  if (nk >= S) wait_loads_le<(S - 2) * NL + HEAD>();
+  else wait_loads_le<0>();
+  __builtin_amdgcn_s_barrier();
+  bf16x8_t af[2][MI], bfr[2][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) af[0][i] = fa.get(lds_dyn, i, 0);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) bfr[0][j] = fb.get(lds_dyn + BM * BKT, j, 0);
+
+  // One slice.  GUARD = false: steady state (slices t + S - 1 and t + S exist, so every load is issued and the
+  // number of loads in flight at the barrier is known); GUARD = true: the last S slices.
+  auto slice = [&](int t, int st, auto guard) {
+    constexpr bool GUARD = decltype(guard)::value;
+    const bf16_t *as = lds_dyn + st * STAGE, *bs = as + BM * BKT;
+    const int st_prev = (st == 0) ? S - 1 : st - 1;   // stage of slice t + S - 1
+    const int st_next = (st + 1 == S) ? 0 : st + 1;   // stage of slice t + 1
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      if (kk + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[(kk + 1) & 1][i] = fa.get(as, i, kk + 1);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) bfr[(kk + 1) & 1][j] = fb.get(bs, j, kk + 1);
+      } else if (!GUARD || t + 1 < nk) {
+        TRACE_STAMP(1);
+        // slice t + 1 must have landed (S - 2 younger slices may stay in flight) and this wavefront's reads of
+        // slice t must be complete before anybody overwrites its stage
+        if (!GUARD) wait_loads_le<(S - 2) * NL>();
+        else wait_loads_le<0>();
+        TRACE_STAMP(2);
+        __builtin_amdgcn_s_barrier();
+        TRACE_STAMP(3);
+        const bf16_t *an = lds_dyn + st_next * STAGE, *bn = an + BM * BKT;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[0][i] = fa.get(an, i, 0);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) bfr[0][j] = fb.get(bn, j, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        const int q = kk * MI + i;
+        if (q >= QB) {  // after the barrier: the head of slice t + S goes into the stage slice t just left
+          if (q - QB < NL && (!GUARD || t + S < nk)) issue(q - QB, t + S, st);
+        } else {        // before it: the rest of slice t + S - 1
+          if (q + (G - QB) < NL && (!GUARD || t + S - 1 < nk)) issue(q + (G - QB), t + S - 1, st_prev);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+
+  int t = 0, st = 0;
+  for (; t + S < nk; ++t) {
+    slice(t, st, std::false_type{});
+    if (++st == S) st = 0;
+  }
+  for (; t < nk; ++t) {
+    slice(t, st, std::true_type{});
+    if (++st == S) st = 0;
+  }
+  TRACE_STAMP(5);
+  wait_loads_le<0>();
+  __builtin_amdgcn_s_barrier();  // the epilogue reuses the stages
+  TRACE_STAMP(6);
+
+  const bool vec = ((g.ldc & 3) == 0) &&
+                   ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
+                   ((((uintptr_t)g.out_act | (uintptr_t)g.out_act2 | (uintptr_t)g.aux) & 7) == 0);
+  constexpr int SP = WTN + 4;
+  constexpr int LPR = WTN / 4;
+  constexpr int RPI = 64 / LPR;
+  static_assert(4 * 32 * SP * 4 <= S * STAGE * 2, "staging patches must fit the stages");
+  float *const patch = (float *)lds_dyn + wave * 32 * SP;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4_t v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        *(f32x4_t *)(patch + (lane & 31) * SP + j * 32 + q * 8 + (lane >> 5) * 4) = v;
+      }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+    store_patch<WTN>(g, 0, patch, m0 + wm * WTM + i * 32, n0 + wn * WTN, lane, vec);
+    TRACE_STAMP(9);
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+  }
+  TRACE_STAMP(7);
+#ifdef HYDRA_GEMM_TRACE
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_gemm_trace[8191] = trace_n;
+#endif
+}
+
+template <int BM, int BN, int BKT, int S, int OCC>
+static hipError_t launch_bf16_big(const GemmArgs &a, int ta, int tb, int ntiles, hipStream_t s) {
+  constexpr size_t lds = (size_t)S * (BM + BN) * BKT * 2;
+  static_assert(lds <= 160 * 1024, "LDS per CU");
+#define HYDRA_BIG(TA_, TB_)                                                                                   \
+  do {                                                                                                         \
+    auto kern = gemm_bf16_big_kernel<BM, BN, TA_, TB_, BKT, S, OCC>;                                           \
+    static hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                 (int)lds);                                                    \
+    if (attr != hipSuccess) return attr;                                                                       \
+    hipLaunchKernelGGL(kern, dim3(ntiles), dim3(256), lds, s, a);                                              \
+  } while (0)
+  if (ta == 0 && tb == 0) HYDRA_BIG(0, 0);
+  else if (ta == 0 && tb == 1) HYDRA_BIG(0, 1);
+  else if (ta == 1 && tb == 1) HYDRA_BIG(1, 1);
+  else HYDRA_BIG(1, 0);
+#undef HYDRA_BIG
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -573,7 +987,12 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   // tile choice: 128x128 only for problems of many waves of tiles (the LM head); at a few thousand tokens per
   // visit the block GEMMs have 100-400 tiles and the narrower tile measured faster on every one of them
   const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128) * nbatch;
+  const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
   int tile = (d.N > 64 && t128 >= 2048) ? 1 : 2;
+  // plain products whose operands both have the contraction index contiguous go to the direct-to-LDS kernel:
+  // 256x256 tiles once they fill three quarters of the CUs, else 128x64 tiles.  Operands stored the other way
+  // round need two half-rate transposing LDS reads per fragment, which takes the advantage away (measured).
+  if (d.ta == 0 && d.tb == 0) tile = t256 >= 192 ? 4 : 10;
   if (force_tile) tile = force_tile;
   // slices in flight: a deeper pipeline pays once the contraction is long enough to amortise filling it
   int D = (d.causal == CAUSAL_NONE && d.K >= 24 * BK) ? 4 : 2;
@@ -585,6 +1004,25 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
     ProfScope ps(gemm_name(DT_BF16, BN_, d.ta, d.tb), s, gemm_flops(d), 0);                              \
     return launch_bf16_cfg<BM_, BN_, 2, 2, DD_>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s); \
   } while (0)
+  const bool plain = d.causal == CAUSAL_NONE && nbatch == 1 && d.K % BK == 0 && d.K >= 2 * BK;
+#define HYDRA_LAUNCH_BIG(BM_, BN_, BK_, S_, OCC_, NAME_)                                       \
+  do {                                                                                          \
+    a.tiles_m = (d.M + BM_ - 1) / BM_;                                                          \
+    a.tiles_n = (d.N + BN_ - 1) / BN_;                                                          \
+    static const char *names[4] = {NAME_ "_nt", NAME_ "_nn", NAME_ "_tt", NAME_ "_tn"};         \
+    ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
+    return launch_bf16_big<BM_, BN_, BK_, S_, OCC_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s);   \
+  } while (0)
+  if (plain && tile == 4) HYDRA_LAUNCH_BIG(256, 256, 32, 4, 1, "gemm_bf16_256x256");
+  if (plain && tile == 5) HYDRA_LAUNCH_BIG(256, 128, 32, 5, 1, "gemm_bf16_256x128");
+  if (plain && tile == 6) HYDRA_LAUNCH_BIG(128, 128, 32, 4, 2, "gemm_bf16_d128x128");
+  if (plain && tile == 7) HYDRA_LAUNCH_BIG(256, 256, 32, 5, 1, "gemm_bf16_256x256s5");
+  if (plain && tile == 8) HYDRA_LAUNCH_BIG(256, 256, 64, 2, 1, "gemm_bf16_256x256k64");
+  if (plain && tile == 9) HYDRA_LAUNCH_BIG(128, 64, 32, 4, 2, "gemm_bf16_d128x64");
+  if (plain && tile == 10) HYDRA_LAUNCH_BIG(128, 64, 64, 3, 2, "gemm_bf16_d128x64k64");
+  if (plain && tile == 11) HYDRA_LAUNCH_BIG(128, 128, 64, 3, 1, "gemm_bf16_d128x128k64");
+#undef HYDRA_LAUNCH_BIG
+  if (tile >= 4) tile = 2;
   if (tile == 1) {
     HYDRA_LAUNCH(128, 128, 2);
   }
