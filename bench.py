@@ -72,8 +72,13 @@ def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
     return dt
 
 
-def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch):
+def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch, pilot=False):
     sess, recs = make_session(cfg, n_models, mode, timing, R, H)
+    pilot_ns = None
+    if pilot:   # the partitioner's pilot pass: measured cost of every shard task of model 0 (updates discarded)
+        big = dict(cfg, B=cfg["B"] * cfg.get("n_micro", 1))
+        tok, tgt = SI.make_batch(big, SI.batch_seed(cfg, 0, 0))
+        pilot_ns = H.hydra_pilot_costs(sess.ctx, recs[0]["id"], tok, tgt, cfg["L"] // cfg["k"] + 2)
     if warmup:
         run_steps(sess, recs, cfg, warmup, 0, H, torch)
     if timing:
@@ -87,7 +92,7 @@ def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch):
     del sess
     torch.cuda.empty_cache()
     return dict(seconds=dt, enqueue_seconds=run_steps.enqueue_s, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
-                n_slots=st1["n_slots"], kernels=kst, losses=losses)
+                n_slots=st1["n_slots"], kernels=kst, losses=losses, pilot_ns=pilot_ns)
 
 
 def cpu_baseline(cfg):
@@ -166,7 +171,15 @@ def main():
     }
     if not args.no_extra:
         other = "resident" if args.mode == "spill" else "spill"
-        o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch)
+        o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch, pilot=True)
+        n_sh = cfg["L"] // cfg["k"] + 2
+        out["pilot_costs_us"] = {"forward": [round(x / 1e3, 1) for x in o["pilot_ns"][:n_sh]],
+                                 "backward_with_adam": [round(x / 1e3, 1) for x in o["pilot_ns"][n_sh:]],
+                                 "shards": "EMBED, block shards 1..S, HEAD; model 0, each task alone on the device"}
+        fp = [H.hydra_shard_footprint(H.model_desc(cfg, 1e-4), n) for n in range(0, cfg["L"] + 1)]
+        out["partitioner"] = {"footprint_MB_by_layers_in_shard": [round(x / 1e6, 1) for x in fp[1:]],
+                              "embed_head_MB": round(fp[0] / 1e6, 1),
+                              "cuts_at_bound_of_2_layer_shard": H.hydra_partition(H.model_desc(cfg, 1e-4), max(fp[2], fp[0]))[0]}
         out[other] = {"value": round(tokens_per_step * args.steps / o["seconds"], 1), "unit": "tokens/s",
                       "ms_per_step": round(1e3 * o["seconds"] / args.steps, 3), "shard_buffers": o["n_slots"]}
         if args.extra_micro > 1 and args.micro == 1:

@@ -238,6 +238,42 @@ hydra_status hydra_sched_next(hydra_sched *s, hydra_task *out);
 hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const int32_t *const *targets,
                              hydra_task *trace, int64_t trace_cap, int64_t *n_executed);
 
+/* ---- partitioner and pilot pass (paper Section 2.2, Algorithm 1) ----------
+ * The paper finds cut points by running layer after layer on the GPU until
+ * memory runs out.  This library knows the device footprint of a shard in
+ * closed form, so the same walk runs on the host: open a shard at layer 0;
+ * when adding layer i to the open shard would exceed the bound, cut before i
+ * and open a new shard with layer i. */
+
+/* Device bytes a backward visit of a shard of n_layers blocks needs: its shard
+ * buffer (fp32 weights, Adam m, v, gradients, bf16 working copy) plus the
+ * visit's workspace (kept activations of the recomputation and scratch).
+ * n_layers = 0: the larger of the EMBED / HEAD shards.  desc->n_layer and
+ * desc->layers_per_shard are ignored. */
+hydra_status hydra_shard_footprint(const hydra_model_desc *desc, int32_t n_layers, uint64_t *bytes);
+
+/* Greedy walk over desc->n_layer blocks against mem_bound_bytes.  cuts (host,
+ * capacity cuts_cap, may be NULL with cuts_cap 0) receives the first layer of
+ * every shard, *n_shards their number, *layers_per_shard the largest divisor of
+ * n_layer that is not above the shortest closed shard of the walk (the executor
+ * runs equal shards; use it as desc->layers_per_shard).  HYDRA_E_NOMEM when a
+ * single block, or the EMBED / HEAD shard, exceeds the bound.
+ * desc->layers_per_shard is ignored. */
+hydra_status hydra_partition(const hydra_model_desc *desc, uint64_t mem_bound_bytes, int32_t *cuts,
+                             int32_t cuts_cap, int32_t *n_shards, int32_t *layers_per_shard);
+
+/* Pilot pass: runs one minibatch (host int32 [n_micro*B, T] tokens / targets)
+ * of a registered model shard by shard, each task alone on the device, twice
+ * (the first round absorbs one-time costs such as code loading), and writes
+ * the second round's measured duration in nanoseconds of the forward visits of shards
+ * 0..S+1, then of the backward visits (with their Adam step) of shards 0..S+1,
+ * to costs_ns (host, 2*(S+2) entries): the cost table hydra_sched_create takes.
+ * Every update of the pass is discarded and the Adam step counter is left as it
+ * was: the model's host arrays are not written.  Needs no updated state of the
+ * model pending on the device (HYDRA_E_STATE otherwise); blocks until done. */
+hydra_status hydra_pilot_costs(hydra_ctx *ctx, int32_t model, const int32_t *tokens, const int32_t *targets,
+                               int64_t *costs_ns);
+
 /* ---- single kernels, exposed for parity tests and roofline measurement ----
  * All pointers are DEVICE pointers, 'stream' a hipStream_t (NULL = null
  * stream).  dtype: 0 = fp32 operands, 1 = bf16 operands (fp32 accumulate). */

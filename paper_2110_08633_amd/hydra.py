@@ -88,6 +88,9 @@ SIGNATURES = {
     "hydra_read_device": (_i32, [_vp, _i32, _i32, _i32, _vp, _u64]),
     "hydra_sched_create": (_i32, [_vp, _i32, _P(_i32), _P(_i32), _P(_i32), _P(_P(_i64)), _P(_vp)]),
     "hydra_sched_destroy": (_i32, [_vp]),
+    "hydra_shard_footprint": (_i32, [_P(ModelDesc), _i32, _P(_u64)]),
+    "hydra_partition": (_i32, [_P(ModelDesc), _u64, _P(_i32), _i32, _P(_i32), _P(_i32)]),
+    "hydra_pilot_costs": (_i32, [_vp, _i32, _vp, _vp, _P(_i64)]),
     "hydra_sched_next": (_i32, [_vp, _P(Task)]),
     "hydra_sched_run": (_i32, [_vp, _P(_vp), _P(_vp), _P(Task), _i64, _P(_i64)]),
     "hydra_op_gemm": (_i32, [_i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _vp,
@@ -255,6 +258,29 @@ def hydra_sched_create(ctx, model_ids, n_minibatches, task_costs, n_block_shards
     out = _vp()
     _check(lib.hydra_sched_create(ctx, n, ids, nbs, nmb, tab, C.byref(out)), ctx)
     return out
+
+
+def hydra_shard_footprint(desc, n_layers):
+    out = _u64()
+    _check(lib.hydra_shard_footprint(C.byref(desc), n_layers, C.byref(out)))
+    return out.value
+
+
+def hydra_partition(desc, mem_bound_bytes):
+    """Returns (cuts, layers_per_shard): first layer of every shard of the greedy walk, and the equal shard size
+    the executor can run."""
+    cap = desc.n_layer + 1
+    cuts = (_i32 * cap)()
+    n, k = _i32(), _i32()
+    _check(lib.hydra_partition(C.byref(desc), mem_bound_bytes, cuts, cap, C.byref(n), C.byref(k)))
+    return [cuts[i] for i in range(n.value)], k.value
+
+
+def hydra_pilot_costs(ctx, model, tokens, targets, n_shards):
+    """Measured cost table (ns) of one model: forward visits of shards 0..S+1, then backward visits."""
+    out = (_i64 * (2 * n_shards))()
+    _check(lib.hydra_pilot_costs(ctx, model, _ptr(tokens), _ptr(targets), out), ctx)
+    return [out[i] for i in range(2 * n_shards)]
 
 
 def hydra_sched_destroy(s):

@@ -282,3 +282,91 @@ def test_scheduled_run_with_micro_batches(rt, dtype):
                       f"model {m} ")
     H.hydra_sched_destroy(sch)
     sess.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pilot_pass_measures_costs_and_leaves_the_model_untouched(rt, dtype):
+    """Pilot pass (paper Section 2.2): per-task durations for the scheduler; nothing of the pass may survive - the
+    host arrays stay bit-identical and the first real step still equals the oracle's step 1.  The scheduler then
+    runs two models on the measured tables and its order equals the oracle's Sharded-LRTF on the same numbers."""
+    H, R = rt
+    cfg = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=2, lrs=[1e-3, 3e-4])
+    S, n = 2, 4
+    Ws = [SI.make_weights(cfg, 60 + m) for m in range(2)]
+    sess = R.Session(R.arena_bytes_for([cfg] * 2, 3), max_slots=3)
+    recs = [sess.add_model(cfg, Ws[m], cfg["lrs"][m]) for m in range(2)]
+    tables = []
+    for m in range(2):
+        before = [recs[m][k].copy() for k in ("master", "m", "v")]
+        tok, tgt = SI.make_batch(cfg, 990 + m)
+        costs = H.hydra_pilot_costs(sess.ctx, recs[m]["id"], tok, tgt, n)
+        assert len(costs) == 2 * n and all(c > 0 for c in costs)
+        assert sum(costs[n:]) > sum(costs[:n])                    # backward visits recompute, back-propagate, step
+        for k, b in zip(("master", "m", "v"), before):
+            assert (recs[m][k] == b).all()
+        tables.append(costs)
+    # scheduler on the measured tables: same decisions as the oracle
+    nmb = [2, 1]
+    chains = [SP.model_task_chain(cfg, nmb[m]) for m in range(2)]
+    costs = [[tables[m][s if ph == SP.FWD else n + s] for s, ph in chains[m]] for m in range(2)]
+    order = SP.sharded_lrtf(chains, costs)
+    batches = [[SI.make_batch(cfg, 700 + 10 * m + i) for i in range(nmb[m])] for m in range(2)]
+    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, tables)
+    toks = [np.stack([b[0] for b in batches[m]]) for m in range(2)]
+    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(2)]
+    trace, done = H.hydra_sched_run(sch, toks, tgts, sess.ctx, trace_cap=256)
+    sess.flush()
+    per = 2 * n
+    assert trace == [(m, chains[m][i][0], chains[m][i][1], i // per) for m, i in order]
+    for m in range(2):
+        refs, P, _, _ = oracle_steps(cfg, Ws[m], cfg["lrs"][m], batches[m])   # Adam step counter starts at 1
+        ill = {}
+        for r in refs:
+            update_ill(ill, r["grads"], dtype)
+        check_weights(sess.unpack(recs[m], recs[m]["master"]), P, refs[0]["before"], ill, cfg["lrs"][m], nmb[m], dtype,
+                      f"model {m} ")
+    H.hydra_sched_destroy(sch)
+    sess.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_heterogeneous_models_in_one_job(rt, dtype):
+    """Three models of different depth, width, batch, sequence length, shard size and micro-batch count in one
+    scheduled run on two lanes with four shard buffers (paper Section 2.4: the scheduler exists for unequal
+    models).  Order against the oracle's Sharded-LRTF (and it is not round-robin); weights against the oracle."""
+    H, R = rt
+    cfgs = [SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, lrs=[1e-4]),
+            SI.small_cfg(L=2, d=128, H=4, F=512, V=300, T=72, B=1, k=1, dtype=dtype, lrs=[3e-4]),
+            dict(SI.small_cfg(L=6, d=32, H=2, F=128, V=97, T=40, B=2, k=3, dtype=dtype, lrs=[1e-4]), n_micro=2)]
+    bigs = [dict(c, B=c["B"] * c.get("n_micro", 1)) for c in cfgs]
+    nmb = [1, 2, 2]
+    n = len(cfgs)
+    Ws = [SI.make_weights(cfgs[m], 70 + m) for m in range(n)]
+    batches = [[SI.make_batch(bigs[m], 600 + 10 * m + i) for i in range(nmb[m])] for m in range(n)]
+    tabs = [SI.task_costs(c) for c in cfgs]
+    chains = [SP.model_task_chain(cfgs[m], nmb[m]) for m in range(n)]
+    costs = [[(tabs[m][0] if ph == SP.FWD else tabs[m][1])[s] for s, ph in chains[m]] for m in range(n)]
+    order = SP.sharded_lrtf(chains, costs)
+    sess = R.Session(R.arena_bytes_for(cfgs, 4, lanes=2), max_slots=4, lanes=2, flags=H.FLAG_POISON)
+    recs = [sess.add_model(cfgs[m], Ws[m], cfgs[m]["lrs"][0]) for m in range(n)]
+    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, [list(t[0]) + list(t[1]) for t in tabs])
+    toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
+    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
+    trace, done = H.hydra_sched_run(sch, toks, tgts, sess.ctx, trace_cap=4096)
+    sess.flush()
+    want = []
+    for m, i in order:
+        per = 2 * (cfgs[m]["L"] // cfgs[m]["k"] + 2)
+        want.append((m, chains[m][i][0], chains[m][i][1], i // per))
+    assert trace == want
+    assert [t[0] for t in trace[:n]] != list(range(n))            # not a round-robin start
+    for m in range(n):
+        refs, P, _, _ = oracle_steps(bigs[m], Ws[m], cfgs[m]["lrs"][0], batches[m])
+        ill = {}
+        for r in refs:
+            update_ill(ill, r["grads"], dtype)
+        assert abs(H.hydra_get_loss(sess.ctx, recs[m]["id"]) - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
+        check_weights(sess.unpack(recs[m], recs[m]["master"]), P, refs[0]["before"], ill, cfgs[m]["lrs"][0], nmb[m],
+                      dtype, f"model {m} ")
+    H.hydra_sched_destroy(sch)
+    sess.close()
