@@ -303,6 +303,17 @@ hydra_status hydra_op_cross_entropy(int32_t dtype, const float *logits, const in
                                     float *row_loss, void *dlogits, int32_t M, int32_t V, int64_t ld,
                                     float inv_n, void *stream);
 
+/* Fused causal self-attention, bf16 operands, head width dh = 64 or 128, T % 8 == 0, d = H*dh.
+ * qkv [B*T, 3d] holds q | k | v (head h at columns h*dh of each part);
+ * o [B*T, d] = softmax_{j<=i}(q_i.k_j / sqrt(dh)) v; lse fp32 [B*H*T] = log-sum-exp of every score row. */
+hydra_status hydra_op_attention_fwd(const void *qkv, void *o, float *lse, int32_t B, int32_t H, int32_t T,
+                                    int32_t dh, void *stream);
+/* Its backward: d_o [B*T, d] -> dqkv [B*T, 3d] (dq | dk | dv); o and lse from the forward call;
+ * dsum fp32 [B*H*T] is scratch the call fills. */
+hydra_status hydra_op_attention_bwd(const void *qkv, const void *o, const void *d_o, const float *lse,
+                                    float *dsum, void *dqkv, int32_t B, int32_t H, int32_t T, int32_t dh,
+                                    void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhydra.so")
-SOURCES = ["gemm.hip", "elementwise.hip", "layout.cpp", "ctx.cpp", "exec.cpp", "sched.cpp", "ops_api.cpp", "prof.cpp", "partition.cpp"]
+SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "layout.cpp", "ctx.cpp", "exec.cpp", "sched.cpp", "ops_api.cpp", "prof.cpp", "partition.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

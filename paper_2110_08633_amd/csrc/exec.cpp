@@ -32,7 +32,12 @@ struct Bump {
 struct LayerActs {  // what the backward visit keeps of one block's forward
   float *x1, *mean1, *rstd1, *mean2, *rstd2;
   void *a, *qkv, *P, *o, *c, *u, *g;
+  float *lse;  // fused attention: log-sum-exp per score row instead of the probabilities P
 };
+
+// fused attention kernels serve the bf16 path at head widths 64 and 128; everything else runs the products and
+// the softmax as separate kernels with the T x T matrices in the workspace
+inline bool fused_attn(const ModelShape &s, int dt) { return attention_fused_supported(dt, s.dh); }
 
 struct BlockW {  // pointers into a shard buffer for one block
   const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc, *b_proj;
@@ -42,7 +47,7 @@ struct BlockW {  // pointers into a shard buffer for one block
 
 uint64_t layer_act_bytes(const ModelShape &s, int dt) {
   const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
-  const uint64_t P = (uint64_t)s.B * s.H * s.T * s.T * e;
+  const uint64_t P = fused_attn(s, dt) ? (uint64_t)s.B * s.H * s.T * 4 : (uint64_t)s.B * s.H * s.T * s.T * e;
   return up256(M * d * 4) + 4 * up256(M * 4) + 3 * up256(M * d * e) + up256(M * 3 * d * e) + up256(P) +
          2 * up256(M * F * e);
 }
@@ -55,7 +60,13 @@ LayerActs take_layer(Bump &b, const ModelShape &s, int dt) {
   A.mean2 = b.take<float>(M); A.rstd2 = b.take<float>(M);
   A.a = b.take<char>(M * d * e);
   A.qkv = b.take<char>(M * 3 * d * e);
-  A.P = b.take<char>((uint64_t)s.B * s.H * s.T * s.T * e);
+  if (fused_attn(s, dt)) {
+    A.P = nullptr;
+    A.lse = b.take<float>((uint64_t)s.B * s.H * s.T);
+  } else {
+    A.P = b.take<char>((uint64_t)s.B * s.H * s.T * s.T * e);
+    A.lse = nullptr;
+  }
   A.o = b.take<char>(M * d * e);
   A.c = b.take<char>(M * d * e);
   A.u = b.take<char>(M * F * e);
@@ -132,6 +143,9 @@ hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const flo
   const int64_t TT = (int64_t)T * T;
   CK(launch_layernorm_fwd(dt, x_in, W.ln1_g, W.ln1_b, A.a, A.mean1, A.rstd1, M, d, st));
   CK(linear(dt, M, 3 * d, d, A.a, W.w_qkv, W.b_qkv, nullptr, nullptr, A.qkv, EPI_NONE, nullptr, st));
+  if (fused_attn(s, dt)) {
+    CK(launch_attention_fwd(A.qkv, A.o, A.lse, s.B, s.H, T, dh, st));
+  } else {
   {  // scores = q k^T / sqrt(dh), lower triangle
     GemmDesc g = attn_desc(s, dt);
     g.ta = 0; g.tb = 0; g.M = T; g.N = T; g.K = dh; g.alpha = 1.0f / sqrtf((float)dh);
@@ -151,6 +165,7 @@ hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const flo
     g.causal = CAUSAL_K_END;
     CK(launch_gemm(g, st));
   }
+  }
   CK(linear(dt, M, d, d, A.o, W.w_o, W.b_o, x_in, A.x1, nullptr, EPI_NONE, nullptr, st));
   CK(launch_layernorm_fwd(dt, A.x1, W.ln2_g, W.ln2_b, A.c, A.mean2, A.rstd2, M, d, st));
   CK(linear(dt, M, F, d, A.c, W.w_fc, W.b_fc, nullptr, nullptr, A.u, EPI_GELU, A.g, st));
@@ -168,6 +183,7 @@ struct BwdScratch {
   float *dtmp;  // [M,d] fp32 (dc, then da)
   float *dx1;   // [M,d] fp32
   float *red;   // column-reduction partials
+  float *dsum;  // fused attention: row sums of dO * O
 };
 
 // fp32 -> operand dtype view of an [M,d] gradient (no copy in the fp32 path)
@@ -207,6 +223,9 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
   // attention core
   const void *q = A.qkv, *k = off_act((const void *)A.qkv, d, dt), *v = off_act((const void *)A.qkv, 2 * d, dt);
   const int64_t sQ1 = (int64_t)T * 3 * d;
+  if (fused_attn(s, dt)) {
+    CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, Z.dqkv, s.B, s.H, T, dh, st));
+  } else {
   {  // dP = dO V^T
     GemmDesc g = attn_desc(s, dt);
     g.ta = 0; g.tb = 0; g.M = T; g.N = T; g.K = dh;
@@ -244,6 +263,7 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
     g.causal = CAUSAL_K_BEGIN;
     CK(launch_gemm(g, st));
   }
+  }
   // QKV projection
   CK(launch_colsum(dt, Z.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, st));
   CK(linear_dw(dt, M, 3 * d, d, A.a, d, Z.dqkv, 3 * d, W.G + o.w_qkv, acc, st));
@@ -260,17 +280,20 @@ uint64_t red_elems(const ModelShape &s) {
 
 uint64_t bwd_scratch_bytes(const ModelShape &s, int dt) {
   const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
-  const uint64_t PP = (uint64_t)s.B * s.H * s.T * s.T;
+  const bool fused = fused_attn(s, dt);
+  const uint64_t PP = fused ? (uint64_t)s.B * s.H * s.T : (uint64_t)s.B * s.H * s.T * s.T;
   return up256(PP * 4) + up256(PP * e) + up256(M * d * e) + up256(M * F * e) + up256(M * d * e) + up256(M * 3 * d * e) +
          2 * up256(M * d * 4) + up256(red_elems(s) * 4);
 }
 
 BwdScratch take_bwd(Bump &b, const ModelShape &s, int dt) {
   const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
-  const uint64_t PP = (uint64_t)s.B * s.H * s.T * s.T;
+  const bool fused = fused_attn(s, dt);
+  const uint64_t PP = fused ? (uint64_t)s.B * s.H * s.T : (uint64_t)s.B * s.H * s.T * s.T;
   BwdScratch Z;
-  Z.dP = b.take<float>(PP);
+  Z.dP = b.take<float>(PP);   // fused: serves as dsum
   Z.dS = b.take<char>(PP * e);
+  Z.dsum = Z.dP;
   Z.dact = b.take<char>(M * d * e);
   Z.du = b.take<char>(M * F * e);
   Z.d_o = b.take<char>(M * d * e);
@@ -328,7 +351,7 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   if (shard <= s.S) {
     ln.logits_owner = -1;  // the shared workspace is about to be overwritten
     LayerActs A = take_layer(b, s, dt);
-    float *Sbuf = b.take<float>((uint64_t)s.B * s.H * s.T * s.T);
+    float *Sbuf = fused_attn(s, dt) ? nullptr : b.take<float>((uint64_t)s.B * s.H * s.T * s.T);
     float *pp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (forward)");
     for (int u = 0; u < s.nm; ++u) {  // micro-batches share the workspace, one after the other

@@ -75,6 +75,14 @@ int colsum_chunks(int M);
 hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N, int acc,
                          hipStream_t s);
 
+// Fused causal attention (bf16 operands, head width 64 or 128).  qkv [B*T, 3d] (q | k | v, head h at columns
+// h*dh of each part), o [B*T, d], lse [B*H*T] = log-sum-exp of every score row.  Backward: d_o [B*T, d] -> dqkv
+// [B*T, 3d]; dsum [B*H*T] is scratch (row sums of dO * O).
+bool attention_fused_supported(int dtype, int dh);
+hipError_t launch_attention_fwd(const void *qkv, void *o, float *lse, int B, int H, int T, int dh, hipStream_t s);
+hipError_t launch_attention_bwd(const void *qkv, const void *o, const void *d_o, const float *lse, float *dsum,
+                                void *dqkv, int B, int H, int T, int dh, hipStream_t s);
+
 // P[z,i,j] = softmax_j<=i S[z,i,j]; zero for i < j < min(T, roundup(i+1,256)); nothing written beyond
 hipError_t launch_softmax_causal_fwd(int dtype, const float *S, void *P, int n_mat, int T, hipStream_t s);
 // dS = P * (dP - rowsum(dP*P)), same zero-fill rule; dP fp32

@@ -49,4 +49,19 @@ hydra_status hydra_op_cross_entropy(int32_t dtype, const float *logits, const in
              "cross_entropy");
 }
 
+hydra_status hydra_op_attention_fwd(const void *qkv, void *o, float *lse, int32_t B, int32_t H, int32_t T, int32_t dh,
+                                    void *stream) {
+  if (!qkv || !o || !lse || B <= 0 || H <= 0 || T <= 0 || (T & 7) || !attention_fused_supported(DT_BF16, dh))
+    return fail(nullptr, HYDRA_E_INVAL, "bad attention argument (bf16 only, head width 64 or 128, T % 8 == 0)");
+  return ret(launch_attention_fwd(qkv, o, lse, B, H, T, dh, (hipStream_t)stream), "attention_fwd");
+}
+
+hydra_status hydra_op_attention_bwd(const void *qkv, const void *o, const void *d_o, const float *lse, float *dsum,
+                                    void *dqkv, int32_t B, int32_t H, int32_t T, int32_t dh, void *stream) {
+  if (!qkv || !o || !d_o || !lse || !dsum || !dqkv || B <= 0 || H <= 0 || T <= 0 || (T & 7) ||
+      !attention_fused_supported(DT_BF16, dh))
+    return fail(nullptr, HYDRA_E_INVAL, "bad attention argument (bf16 only, head width 64 or 128, T % 8 == 0)");
+  return ret(launch_attention_bwd(qkv, o, d_o, lse, dsum, dqkv, B, H, T, dh, (hipStream_t)stream), "attention_bwd");
+}
+
 }  // extern "C"

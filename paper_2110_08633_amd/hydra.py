@@ -88,6 +88,8 @@ SIGNATURES = {
     "hydra_read_device": (_i32, [_vp, _i32, _i32, _i32, _vp, _u64]),
     "hydra_sched_create": (_i32, [_vp, _i32, _P(_i32), _P(_i32), _P(_i32), _P(_P(_i64)), _P(_vp)]),
     "hydra_sched_destroy": (_i32, [_vp]),
+    "hydra_op_attention_fwd": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
+    "hydra_op_attention_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
     "hydra_shard_footprint": (_i32, [_P(ModelDesc), _i32, _P(_u64)]),
     "hydra_partition": (_i32, [_P(ModelDesc), _u64, _P(_i32), _i32, _P(_i32), _P(_i32)]),
     "hydra_pilot_costs": (_i32, [_vp, _i32, _vp, _vp, _P(_i64)]),
@@ -327,3 +329,12 @@ def hydra_op_softmax_causal(dtype, S, P, n_mat, T, stream=None):
 def hydra_op_cross_entropy(dtype, logits, targets, row_loss, dlogits, M, V, ld, inv_n, stream=None):
     return _check(lib.hydra_op_cross_entropy(dtype, _ptr(logits), _ptr(targets), _ptr(row_loss), _ptr(dlogits), M,
                                              V, ld, inv_n, _stream(stream)))
+
+
+def hydra_op_attention_fwd(qkv, o, lse, B, H, T, dh, stream=None):
+    return _check(lib.hydra_op_attention_fwd(_ptr(qkv), _ptr(o), _ptr(lse), B, H, T, dh, _stream(stream)))
+
+
+def hydra_op_attention_bwd(qkv, o, d_o, lse, dsum, dqkv, B, H, T, dh, stream=None):
+    return _check(lib.hydra_op_attention_bwd(_ptr(qkv), _ptr(o), _ptr(d_o), _ptr(lse), _ptr(dsum), _ptr(dqkv),
+                                             B, H, T, dh, _stream(stream)))

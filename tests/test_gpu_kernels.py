@@ -184,3 +184,39 @@ def test_single_slice_gemm_under_concurrency(H):
     torch.cuda.synchronize()
     for o in outs:
         assert_close(o.cpu().numpy(), ref, 1e-5, "single-slice gemm")
+
+
+@pytest.mark.parametrize("B,Hh,T,dh", [(2, 3, 72, 64), (1, 2, 264, 64), (2, 1, 136, 128), (1, 4, 512, 64), (1, 1, 8, 64)])
+def test_fused_attention_forward_and_backward(H, B, Hh, T, dh):
+    """Fused causal attention (scores, mask, softmax, PV in one kernel; backward without a stored probability
+    matrix) against the oracle's attention on the same bf16-rounded operands: sequence lengths that are no
+    multiple of the 64-key tile or the 128-row block, both head widths, several heads and samples."""
+    rng = np.random.default_rng(B * 1000 + T + dh)
+    d = Hh * dh
+    M = B * T
+    qkv = bf16_round(rng.standard_normal((M, 3 * d)).astype(np.float32))
+    do = bf16_round(rng.standard_normal((M, d)).astype(np.float32) * 0.5)
+    o_ref, cache = D.attention_fwd(qkv.astype(np.float64), B, T, Hh)
+    q, k, v, p, scale = cache
+    s = (q @ k.transpose(0, 1, 3, 2)) * scale
+    s = np.where(np.tril(np.ones((T, T), dtype=bool)), s, -np.inf)
+    smax = s.max(axis=-1)
+    lse_ref = smax + np.log(np.exp(s - smax[..., None]).sum(axis=-1))          # [B,H,T]
+    dqkv_ref = D.attention_bwd(do.astype(np.float64), cache, B, T, Hh)
+
+    qkv_d = dev(qkv, torch.bfloat16)
+    o_d = torch.full((M, d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    lse_d = torch.full((B * Hh * T,), float("nan"), device="cuda")
+    H.hydra_op_attention_fwd(qkv_d, o_d, lse_d, B, Hh, T, dh)
+    torch.cuda.synchronize()
+    assert_close(o_d.float().cpu().numpy(), o_ref, 2e-2, "attention output")
+    assert_close(lse_d.cpu().numpy().reshape(B, Hh, T), lse_ref, 1e-3, "log-sum-exp")
+
+    do_d = dev(do, torch.bfloat16)
+    dsum_d = torch.zeros(B * Hh * T, device="cuda")
+    dqkv_d = torch.full((M, 3 * d), float("nan"), device="cuda", dtype=torch.bfloat16)
+    H.hydra_op_attention_bwd(qkv_d, o_d, do_d, lse_d, dsum_d, dqkv_d, B, Hh, T, dh)
+    torch.cuda.synchronize()
+    got = dqkv_d.float().cpu().numpy()
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert_close(got[:, sl], dqkv_ref[:, sl], 2e-2, name)

@@ -112,6 +112,8 @@ def test_tiny_config_fp32_three_steps(rt):
     dict(L=2, d=72, H=3, F=136, V=1001, T=72, B=3, k=2),          # ragged everywhere, odd vocabulary
     dict(L=4, d=64, H=8, F=256, V=300, T=264, B=1, k=2),          # T crosses the 256-wide diagonal block
     dict(L=1, d=8, H=1, F=8, V=9, T=8, B=1, k=1),                 # smallest legal shapes
+    dict(L=2, d=128, H=2, F=256, V=211, T=200, B=2, k=1),         # head width 64: fused attention on the bf16 path
+    dict(L=2, d=128, H=1, F=128, V=97, T=72, B=1, k=2),           # head width 128
 ])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ragged_shapes(rt, kw, dtype):
