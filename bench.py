@@ -95,6 +95,20 @@ def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch, pilot=False
                 n_slots=st1["n_slots"], kernels=kst, losses=losses, pilot_ns=pilot_ns)
 
 
+def measured_traffic(config, kernel):
+    """HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs of this script, scaled by kernels of known traffic); None when the summary has no line for it."""
+    path = os.path.join(ROOT, "profiles", f"bench_{config}_hbm_counters.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == "traffic_per_launch_bytes" and f[1] == kernel:
+                return int(f[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg):
     """The CPU oracle (float32 instance) on one model-minibatch of the same workload."""
     from oracle import decoder as D
@@ -200,13 +214,15 @@ def main():
         if dom["flops"] > 0:
             ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
             out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                               "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                               "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
+                               "traffic": measured_traffic(args.config, dom["name"]),
                                "kernel": dom["name"], "launches": dom["launches"],
                                "avg_us": round(1e3 * dom["ms"] / dom["launches"], 2)}
         else:
             ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
             out["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                               "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": dom["name"],
+                               "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.config, dom["name"]),
+                               "kernel": dom["name"],
                                "launches": dom["launches"], "avg_us": round(1e3 * dom["ms"] / dom["launches"], 2)}
         out["kernels"] = [
             {"name": k["name"], "launches": k["launches"], "ms_per_step": round(k["ms"] / args.steps, 4),
