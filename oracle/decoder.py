@@ -220,15 +220,23 @@ def block_bwd(P, l, dx2, cache, B, T, H):
 
 
 def head_fwd(P, x):
+    """Final LayerNorm and logits.  A model without "w_lm" ties the LM head to the
+    token embedding: logits = z @ wte^T."""
     z, lnf = layernorm_fwd(x, P["lnf_g"], P["lnf_b"])
-    logits = linear_fwd(z, P["w_lm"])
+    logits = linear_fwd(z, P["w_lm"] if "w_lm" in P else P["wte"].T)
     return logits, (z, lnf)
 
 
 def head_bwd(P, dlogits, cache):
+    """Tied head: the gradient of wte through the logits comes back as
+    G["wte_head"] ([V, d]); the caller adds the embedding lookup's part."""
     z, lnf = cache
     G = {}
-    dz, G["w_lm"], _ = linear_bwd(dlogits, z, P["w_lm"], has_bias=False)
+    if "w_lm" in P:
+        dz, G["w_lm"], _ = linear_bwd(dlogits, z, P["w_lm"], has_bias=False)
+    else:
+        dz, gw, _ = linear_bwd(dlogits, z, P["wte"].T, has_bias=False)
+        G["wte_head"] = np.ascontiguousarray(gw.T)
     dx, G["lnf_g"], G["lnf_b"] = layernorm_bwd(dz, P["lnf_g"], lnf)
     return dx, G
 
@@ -281,6 +289,8 @@ def forward_backward(P, tokens, targets, cfg):
         dx, g = block_bwd(P, l, dx, caches[l], B, T, H)
         G.update(g)
     G["wte"], G["wpe"] = embed_bwd(dx, tokens, V)
+    if "wte_head" in G:
+        G["wte"] = G.pop("wte_head") + G["wte"]
     return dict(logits=logits, loss=loss, grads=G)
 
 

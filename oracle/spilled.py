@@ -38,7 +38,7 @@ def shard_tensor_names(cfg, s):
     if s == 0:
         return ["wte", "wpe"]
     if s == S + 1:
-        return ["lnf_g", "lnf_b", "w_lm"]
+        return ["lnf_g", "lnf_b"] if cfg.get("tie") else ["lnf_g", "lnf_b", "w_lm"]
     return [f"h{l}.{n}" for l in range((s - 1) * k, s * k) for n in D.BLOCK_TENSORS]
 
 
@@ -85,6 +85,7 @@ class SpilledModel:
         self.ckpt = {}                  # boundary index -> activation; boundary b = output of shard b
         self.dbound = None              # gradient flowing into the next backward visit
         self.dlogits = None
+        self.dwte_head = None
         self.loss = None
         self.logits = None
         self.grads = {}                 # last gradients, kept only for inspection by tests
@@ -117,6 +118,8 @@ class SpilledModel:
             logits, hc = D.head_fwd(P, self.ckpt[self.S])
             _, dlogits = D.cross_entropy(logits, self.targets)
             self.dbound, G = D.head_bwd(P, dlogits, hc)
+            # tied head: its part of the wte gradient waits for the embedding shard's backward visit
+            self.dwte_head = G.pop("wte_head", None)
         elif s >= 1:
             x = self.ckpt[s - 1]
             caches = []
@@ -131,6 +134,8 @@ class SpilledModel:
             self.dbound = dx
         else:
             G["wte"], G["wpe"] = D.embed_bwd(self.dbound, self.tokens, cfg["V"])
+            if self.dwte_head is not None:
+                G["wte"] = self.dwte_head + G["wte"]
             self.dbound = None
         if s == self.S + 1:
             self.t += 1                 # first backward visit of a minibatch opens step t

@@ -286,7 +286,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   const int nt = gridDim.x, bid = blockIdx.x;
   const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
   const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
-  const int tm = tile / g.tiles_n, tn = tile % g.tiles_n;
+  // ... and within the run, groups of up to 8 tile rows are walked column by column: the tiles an XCD works on at
+  // any time then share a few row panels of A and a few column panels of B instead of one A panel and all of B
+  const int gsz = 8 * g.tiles_n;
+  const int grp = tile / gsz, in_grp = tile - grp * gsz;
+  const int rows_in_grp = min(8, g.tiles_m - grp * 8);
+  const int tm = grp * 8 + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
   const int m0 = tm * BM, n0 = tn * BN;
   if (g.causal == CAUSAL_SKIP_UPPER && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / g.nb2, z2 = z % g.nb2;
@@ -858,6 +863,8 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   // 256x256 tiles once they fill three quarters of the CUs, else 128x64 tiles.  Operands stored the other way
   // round need two half-rate transposing LDS reads per fragment, which takes the advantage away (measured).
   if (d.ta == 0 && d.tb == 0) tile = t256 >= 192 ? 4 : 10;
+  // too few 128x64 tiles to occupy half the CUs (the d x d weight gradient): 64x64 tiles measured a third faster
+  else if (tile == 2 && (long)((d.M + 127) / 128) * ((d.N + 63) / 64) * nbatch < 128 && d.M > 64) tile = 3;
   if (force_tile) tile = force_tile;
   // slices in flight: a deeper pipeline pays once the contraction is long enough to amortise filling it
   int D = (d.causal == CAUSAL_NONE && d.K >= 24 * BK) ? 4 : 2;

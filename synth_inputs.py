@@ -40,7 +40,8 @@ def tensor_shapes(cfg):
 
     kind is "matrix" (weights, embeddings), "bias" or "gain"; the order is the
     canonical one: embeddings, blocks in depth order, final LayerNorm, LM head.
-    All matrices are [in, out] so that y = x @ W + b.
+    All matrices are [in, out] so that y = x @ W + b.  With cfg["tie"] the LM
+    head has no matrix of its own: logits = z @ wte^T.
     """
     L, d, F, V, T = cfg["L"], cfg["d"], cfg["F"], cfg["V"], cfg["T"]
     out = [("wte", (V, d), "matrix"), ("wpe", (T, d), "matrix")]
@@ -54,7 +55,9 @@ def tensor_shapes(cfg):
             (p + "w_fc", (d, F), "matrix"), (p + "b_fc", (F,), "bias"),
             (p + "w_proj", (F, d), "matrix"), (p + "b_proj", (d,), "bias"),
         ]
-    out += [("lnf_g", (d,), "gain"), ("lnf_b", (d,), "bias"), ("w_lm", (d, V), "matrix")]
+    out += [("lnf_g", (d,), "gain"), ("lnf_b", (d,), "bias")]
+    if not cfg.get("tie"):
+        out += [("w_lm", (d, V), "matrix")]
     return out
 
 

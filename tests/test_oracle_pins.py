@@ -21,8 +21,10 @@ def _setup(dtype=np.float64, **kw):
 
 
 # ---------------------------------------------------------------- P-FD
-def test_finite_differences_every_tensor():
-    cfg, P, tok, tgt = _setup()
+@pytest.mark.parametrize("tie", [False, True])
+def test_finite_differences_every_tensor(tie):
+    cfg, P, tok, tgt = _setup(tie=tie)
+    assert ("w_lm" in P) != tie
     out = D.forward_backward(P, tok, tgt, cfg)
     rng = np.random.default_rng(0)
     h = 1e-5
@@ -70,13 +72,14 @@ def _torch_model(Pt, tok, tgt, cfg):
         u = c @ g("w_fc") + g("b_fc")
         x = x + TF.gelu(u, approximate="tanh") @ g("w_proj") + g("b_proj")
     z = TF.layer_norm(x, (d,), Pt["lnf_g"], Pt["lnf_b"], eps=1e-5)
-    logits = z @ Pt["w_lm"]
+    logits = z @ (Pt["w_lm"] if "w_lm" in Pt else Pt["wte"].T)
     loss = TF.cross_entropy(logits.view(B * T, -1),
                             torch.as_tensor(tgt, dtype=torch.long).view(-1), ignore_index=-1)
     return logits, loss
 
 
-@pytest.mark.parametrize("kw", [dict(), dict(L=3, d=24, H=3, F=40, V=50, T=12, B=3)])
+@pytest.mark.parametrize("kw", [dict(), dict(L=3, d=24, H=3, F=40, V=50, T=12, B=3),
+                                dict(L=2, d=16, H=2, F=32, V=40, T=8, B=2, tie=True)])
 def test_against_torch_autograd_and_adam(kw):
     cfg, P, tok, tgt = _setup(**kw)
     Pt = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in P.items()}
@@ -257,10 +260,11 @@ def test_adam_closed_forms():
 
 
 # ---------------------------------------------------------------- P-shard / P-models
+@pytest.mark.parametrize("tie", [False, True])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("k", [1, 2, 4])
-def test_sharded_equals_unsharded_bitwise(dtype, k):
-    cfg = SI.small_cfg(L=4, k=k)
+def test_sharded_equals_unsharded_bitwise(dtype, k, tie):
+    cfg = SI.small_cfg(L=4, k=k, tie=tie)
     W = SI.make_weights(cfg, 11)
     P = D.cast_params(W, dtype)
     Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
@@ -308,3 +312,23 @@ def test_interleaved_models_equal_models_alone_bitwise():
     assert a.loss == b.loss
     assert all((a.grads[n] == b.grads[n]).all() for n in a.grads)
     assert any((a.P[n] != b.P[n]).any() for n in a.P)
+
+
+def test_tied_head_gradient_is_the_sum_of_the_two_untied_gradients():
+    """Tying the LM head to the token embedding (logits = z wte^T): same logits and loss as an untied model whose
+    head matrix happens to equal wte^T, and the gradient of wte is the embedding part plus the transposed head
+    part of that untied model."""
+    cfg_t = SI.small_cfg(L=2, d=16, H=2, F=32, V=40, T=8, B=2, tie=True)
+    cfg_u = dict(cfg_t, tie=False)
+    Pt = D.cast_params(SI.make_weights(cfg_t, 5), np.float64)
+    Pu = dict(Pt)
+    Pu["w_lm"] = np.ascontiguousarray(Pt["wte"].T)
+    tok, tgt = SI.make_batch(cfg_t, 6)
+    ot = D.forward_backward(Pt, tok, tgt, cfg_t)
+    ou = D.forward_backward(Pu, tok, tgt, cfg_u)
+    assert np.array_equal(ot["logits"], ou["logits"]) and ot["loss"] == ou["loss"]
+    np.testing.assert_allclose(ot["grads"]["wte"], ou["grads"]["wte"] + ou["grads"]["w_lm"].T, rtol=1e-12, atol=1e-15)
+    for name in ot["grads"]:
+        if name != "wte":
+            np.testing.assert_allclose(ot["grads"][name], ou["grads"][name], rtol=1e-12, atol=1e-15, err_msg=name)
+    assert SI.n_params(cfg_u) - SI.n_params(cfg_t) == cfg_t["d"] * cfg_t["V"]
