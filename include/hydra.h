@@ -112,6 +112,10 @@ typedef struct {
                             /* a shard runs all of them while the shard is resident and sums their gradients,  */
                             /* so one promotion serves n_micro * batch samples (paper Section 2.3 leaves the   */
                             /* work done per visit open; activation memory stays that of one micro-batch)      */
+  int32_t tie_embeddings;   /* 0: own LM head matrix w_lm[d,V].  1: logits = z * wte^T; the HEAD shard then owns   */
+                            /* only the final LayerNorm, keeps a device copy of wte while resident, and hands its   */
+                            /* part of the wte gradient to the EMBED shard's backward visit                        */
+  int32_t reserved;
   double lr, beta1, beta2, eps; /* Adam hyper-parameters of this model (doubles so that 1-beta is exact) */
 } hydra_model_desc;
 

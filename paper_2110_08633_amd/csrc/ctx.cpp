@@ -194,6 +194,8 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
         if (m->ev_ckpt_h2d[i]) (void)hipEventDestroy(m->ev_ckpt_h2d[i]);
       }
       if (m->ev_last_compute) (void)hipEventDestroy(m->ev_last_compute);
+      for (hipEvent_t e : m->ev_wb)
+        if (e) (void)hipEventDestroy(e);
       if (m->stage) (void)hipHostFree(m->stage);
     } else {
       delete[] m->stage;
@@ -266,11 +268,13 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   ok &= (m->dlogits = take((uint64_t)s.Mt * s.Vpad * dt_size(m->dtype))) != nullptr;
   ok &= (m->row_loss = (float *)take(s.Mt * 4)) != nullptr;
   ok &= (m->loss = (float *)take(256)) != nullptr;
+  if (s.tie) ok &= (m->tied_g = (float *)take((uint64_t)s.V * s.d * 4)) != nullptr;
   if (!ok) {
     delete m;
     return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the model's activations");
   }
   m->slot_of.assign(s.S + 2, -1);
+  m->wb_pending.assign(s.S + 2, 0);
   m->lane = (int)(ctx->models.size() % ctx->lanes.size());
   if (!ctx->dry) {
     hipError_t e = hipHostMalloc((void **)&m->stage, (size_t)s.Mt * 4 * 4, hipHostMallocDefault);
@@ -284,6 +288,9 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
         return st;
     }
     if ((st = make_event(ctx, &m->ev_last_compute))) return st;
+    m->ev_wb.assign(s.S + 2, nullptr);
+    for (hipEvent_t &e : m->ev_wb)
+      if ((st = make_event(ctx, &e))) return st;
   } else {
     m->stage = new int32_t[(size_t)s.Mt * 4];
   }
@@ -346,7 +353,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     }
     sl = &ctx->slots[free_i];
     sl->model = model; sl->shard = shard;
-    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->dirty = false;
+    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->dirty = sl->tied_valid = false;
     m->slot_of[shard] = free_i;
     // the buffer's previous occupant must be done with it
     if (!ctx->dry) {
@@ -357,11 +364,40 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   } else if (sl->has_params && (sl->has_opt || !(what & HYDRA_LOAD_OPT))) {
     ctx->stats.n_load_hits++;
   }
+  // the host arrays of a shard are read only after its last write-back has landed (the buffer it was written
+  // back from may be a different one)
+  if ((!sl->has_params || ((what & HYDRA_LOAD_OPT) && !sl->has_opt)) && m->wb_pending[shard]) {
+    if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_wb[shard], 0));
+    m->wb_pending[shard] = 0;
+  }
   if (!sl->has_params) {
     if (!ctx->dry)
       HYDRA_HIP(ctx, hipMemcpyAsync(sl->w, m->host.master + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
     ctx->stats.bytes_h2d += cnt * 4;
     sl->has_params = true;
+    copied = true;
+  }
+  if (m->sh.tie && shard == m->sh.S + 1 && !sl->tied_valid) {
+    // tied LM head: the buffer keeps a copy of wte behind the final LayerNorm's parameters.  Taken from the EMBED
+    // shard's buffer when that is resident (it may hold an update not yet written back), else from the host.
+    const uint64_t bytes = (uint64_t)m->sh.V * m->sh.d * 4;
+    Slot *e = slot_for(ctx, model, 0);
+    if (e && e->has_params) {
+      if (!ctx->dry) {
+        if (e->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, e->ev_compute, 0));
+        HYDRA_HIP(ctx, hipMemcpyAsync(sl->w + 2 * m->sh.d, e->w, bytes, hipMemcpyDeviceToDevice, ctx->s_h2d));
+      }
+    } else {
+      if (m->wb_pending[0]) {
+        if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_wb[0], 0));
+        m->wb_pending[0] = 0;
+      }
+      if (!ctx->dry)
+        HYDRA_HIP(ctx, hipMemcpyAsync(sl->w + 2 * m->sh.d, m->host.master, bytes, hipMemcpyHostToDevice, ctx->s_h2d));
+      ctx->stats.bytes_h2d += bytes;
+    }
+    sl->tied_valid = true;
+    sl->wb_valid = false;
     copied = true;
   }
   if ((what & HYDRA_LOAD_OPT) && !sl->has_opt) {
@@ -417,7 +453,9 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
           (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4)))
         return cs;
       HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
+      HYDRA_HIP(ctx, hipEventRecord(m->ev_wb[shard], ctx->s_d2h));
     }
+    m->wb_pending[shard] = 1;
     sl->spill_pending = true;
     sl->dirty = false;
     ctx->stats.bytes_d2h += cnt * 12;
@@ -433,7 +471,7 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     }
     m->slot_of[shard] = -1;
     sl->model = sl->shard = -1;
-    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = false;
+    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->tied_valid = false;
     ctx->stats.n_evictions++;
   }
   return HYDRA_OK;
@@ -446,6 +484,8 @@ static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out)
   if ((st = ensure_planned(ctx))) return st;
   Slot *sl = slot_for(ctx, model, shard);
   if (!sl || !sl->has_params) return fail(ctx, HYDRA_E_STATE, "shard was not loaded");
+  if (ctx->models[model]->sh.tie && shard == ctx->models[model]->sh.S + 1 && !sl->tied_valid)
+    return fail(ctx, HYDRA_E_STATE, "tied LM head: load the shard again after the embedding shard's update");
   if (sl->need_wait_load) {
     if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[ctx->models[model]->lane].stream, sl->ev_loaded, 0));
     sl->need_wait_load = false;
@@ -533,6 +573,10 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
   if (!ctx->dry && (st = exec_adam(ctx, m, sl, shard))) return st;
   sl->grads_valid = false;
   sl->dirty = true;
+  if (m->sh.tie && shard == 0) {  // the HEAD shard's copy of wte is now out of date
+    Slot *hs = slot_for(ctx, model, m->sh.S + 1);
+    if (hs) hs->tied_valid = hs->wb_valid = false;
+  }
   ctx->stats.n_tasks--;  // the optimizer step belongs to the backward task
   return end_task(ctx, m, sl);
 }

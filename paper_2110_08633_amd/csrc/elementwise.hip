@@ -128,16 +128,16 @@ hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *w
 }
 
 hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, float *dwpe, int B, int T, int d, int V,
-                            int acc, hipStream_t s) {
+                            int acc_wte, int acc_wpe, hipStream_t s) {
   if (B * T > EMB_MAXW * 32) return hipErrorInvalidValue;
-  if (!acc) {
+  if (!acc_wte) {
     hipError_t e = launch_fill_u32((uint32_t *)dwte, 0u, (int64_t)V * d, s);
     if (e != hipSuccess) return e;
   }
   ProfScope ps("embed_bwd", s, 0, 8.0 * B * T * d + 4.0 * T * d);
-  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(B * T), dim3(256), 0, s, tok, dx0, dwte, B * T, d, acc);
+  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(B * T), dim3(256), 0, s, tok, dx0, dwte, B * T, d, acc_wte);
   const int64_t n = (int64_t)T * d;
-  hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dx0, dwpe, B, T, d, acc);
+  hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dx0, dwpe, B, T, d, acc_wpe);
   return hipGetLastError();
 }
 

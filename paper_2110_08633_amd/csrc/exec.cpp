@@ -327,8 +327,10 @@ static hipError_t ensure_working_copy(hydra_ctx *ctx, Model *mm, Slot *sl, int s
   if (shard >= 1 && shard <= s.S) {
     CK(launch_cast_bf16(sl->w, sl->wb, s.shard_off[shard + 1] - s.shard_off[shard], st));
   } else if (shard == s.S + 1) {
-    // LM head kept transposed [V,d] so that the odd vocabulary size never is a leading dimension
-    CK(launch_cast_transpose_bf16(sl->w + 2 * s.d, sl->wb + 2 * s.d, s.d, s.V, st));
+    // LM head kept transposed [V,d] so that the odd vocabulary size never is a leading dimension; a tied head's
+    // copy of wte already is [V,d]
+    if (s.tie) CK(launch_cast_bf16(sl->w + 2 * s.d, sl->wb + 2 * s.d, (int64_t)s.V * s.d, st));
+    else CK(launch_cast_transpose_bf16(sl->w + 2 * s.d, sl->wb + 2 * s.d, s.d, s.V, st));
   }
   sl->wb_valid = true;
   return hipSuccess;
@@ -375,6 +377,7 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     GemmDesc g;
     g.dtype = dt; g.M = M; g.N = s.V; g.K = d; g.A = z; g.lda = d; g.ta = 0;
     if (dt == DT_BF16) { g.tb = 0; g.B = sl->wb + 2 * d; g.ldb = d; }
+    else if (s.tie) { g.tb = 0; g.B = sl->w + 2 * d; g.ldb = d; }  // wte [V,d]: logits = z wte^T
     else { g.tb = 1; g.B = sl->w + 2 * d; g.ldb = s.V; }
     g.out_f32 = logits; g.ldc = s.Vpad;
     HYDRA_HIP(ctx, launch_gemm(g, st));
@@ -415,10 +418,20 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
       const float *x = mm->ckpt[s.S] + u * act;
       const void *dl = off_act((const void *)mm->dlogits, (int64_t)u * M * s.Vpad, dt);
       HYDRA_HIP(ctx, launch_layernorm_fwd(dt, x, sl->w, sl->w + d, z, mean, rstd, M, d, st));
-      HYDRA_HIP(ctx, linear_dw(dt, M, s.V, d, z, d, dl, s.Vpad, sl->g + 2 * d, u > 0, st));
+      if (s.tie) {  // the head's part of the wte gradient, [V,d] = dlogits^T z, kept for the EMBED backward visit
+        GemmDesc w;
+        w.dtype = dt; w.ta = 1; w.tb = 1; w.M = s.V; w.N = d; w.K = M;
+        w.A = dl; w.lda = s.Vpad; w.B = z; w.ldb = d; w.ldc = d;
+        w.out_f32 = mm->tied_g;
+        if (u > 0) w.resid = mm->tied_g;
+        HYDRA_HIP(ctx, launch_gemm(w, st));
+      } else {
+        HYDRA_HIP(ctx, linear_dw(dt, M, s.V, d, z, d, dl, s.Vpad, sl->g + 2 * d, u > 0, st));
+      }
       GemmDesc g;
       g.dtype = dt; g.M = M; g.N = d; g.K = s.V; g.A = dl; g.lda = s.Vpad; g.ta = 0;
       if (dt == DT_BF16) { g.tb = 1; g.B = sl->wb + 2 * d; g.ldb = d; }
+      else if (s.tie) { g.tb = 1; g.B = sl->w + 2 * d; g.ldb = d; }
       else { g.tb = 0; g.B = sl->w + 2 * d; g.ldb = s.V; }
       g.out_f32 = dz; g.ldc = d;
       HYDRA_HIP(ctx, launch_gemm(g, st));
@@ -451,9 +464,11 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     return HYDRA_OK;
   }
   // EMBED
+  if (s.tie)  // start from the LM head's part of the wte gradient
+    HYDRA_HIP(ctx, hipMemcpyAsync(sl->g, mm->tied_g, (size_t)s.V * d * 4, hipMemcpyDeviceToDevice, st));
   for (int u = 0; u < s.nm; ++u)
     HYDRA_HIP(ctx, launch_embed_bwd(mm->tok + (int64_t)u * M, mm->dbound[mm->dcur] + u * act, sl->g,
-                                    sl->g + (int64_t)s.V * d, s.B, s.T, d, s.V, u > 0, st));
+                                    sl->g + (int64_t)s.V * d, s.B, s.T, d, s.V, u > 0 || s.tie, u > 0, st));
   return HYDRA_OK;
 }
 

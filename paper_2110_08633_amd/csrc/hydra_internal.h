@@ -38,7 +38,8 @@ struct ModelShape {
   BlockOffsets bo;
   int64_t n_params;
   std::vector<int64_t> shard_off;  // S+3 entries
-  int64_t max_shard;               // largest shard, elements
+  int64_t max_shard;               // largest shard as held in a shard buffer, elements
+  int tie;                         // LM head tied to the token embedding
 };
 
 hydra_status build_shape(const hydra_model_desc *d, ModelShape *out, std::string *err);
@@ -53,6 +54,7 @@ struct Slot {
   bool need_wait_load = false;  // a copy into this slot was enqueued since the compute stream last waited
   hipEvent_t ev_loaded = nullptr, ev_compute = nullptr, ev_spilled = nullptr;
   bool compute_pending = false, spill_pending = false;
+  bool tied_valid = false;  // HEAD shard of a tied model: the buffer's copy of wte is current
   uint64_t last_use = 0;  // value of the context's task counter when a task last ran on this buffer
 };
 
@@ -88,6 +90,9 @@ struct Model {
   int next_bwd = -1;    // next backward visit expected (-1: none)
   bool logits_valid = false;
   std::vector<int> slot_of;  // shard -> slot index or -1
+  float *tied_g = nullptr;   // tied LM head: its part of the wte gradient [V,d], from HEAD backward to EMBED backward
+  std::vector<hipEvent_t> ev_wb;   // per shard: last write-back to the host arrays
+  std::vector<char> wb_pending;
 };
 
 }  // namespace hydra

@@ -57,9 +57,10 @@ hipError_t launch_gemm(const GemmDesc &g, hipStream_t s);
 hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *wpe, float *x0, int M, int T, int d,
                             hipStream_t s);
 // dwte = 0 then rows of present tokens accumulate dx0 in ascending m; dwpe[t] = sum_b dx0[b*T+t]
-// acc != 0 adds to the gradients already held (a later micro-batch of the same minibatch)
+// acc_wte / acc_wpe != 0: add to the gradient already held (a later micro-batch of the same minibatch; for wte
+// also the tied LM head's part)
 hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, float *dwpe, int B, int T, int d, int V,
-                            int acc,
+                            int acc_wte, int acc_wpe,
                             hipStream_t s);
 
 hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, const float *beta, void *y, float *mean,

@@ -28,6 +28,7 @@ hydra_status build_shape(const hydra_model_desc *d, ModelShape *s, std::string *
   if (d->dtype != 0 && d->dtype != 1) return bad("dtype must be 0 (fp32) or 1 (bf16)");
   if ((int64_t)d->batch * d->seq > 32768) return bad("batch*seq above 32768 tokens is not supported");
   if (d->n_micro < 0 || d->n_micro > 4096) return bad("n_micro must be in 0..4096");
+  if (d->tie_embeddings != 0 && d->tie_embeddings != 1) return bad("tie_embeddings must be 0 or 1");
   s->L = d->n_layer; s->d = d->d_model; s->H = d->n_head; s->F = d->d_ff; s->V = d->vocab;
   s->T = d->seq; s->B = d->batch; s->k = d->layers_per_shard; s->S = s->L / s->k; s->dh = s->d / s->H;
   s->M = (int64_t)s->B * s->T;
@@ -59,10 +60,12 @@ hydra_status build_shape(const hydra_model_desc *d, ModelShape *s, std::string *
     off += b.size * s->k;
   }
   s->shard_off[s->S + 1] = off;
-  off += 2 * dd + dd * (int64_t)s->V;
+  s->tie = d->tie_embeddings != 0;
+  off += 2 * dd + (s->tie ? 0 : dd * (int64_t)s->V);
   s->shard_off[s->S + 2] = off;
   s->n_params = off;
-  s->max_shard = 0;
+  // a tied HEAD shard owns 2d parameters but its buffer also holds a copy of wte
+  s->max_shard = 2 * dd + dd * (int64_t)s->V;
   for (int i = 0; i < s->S + 2; ++i) {
     const int64_t c = s->shard_off[i + 1] - s->shard_off[i];
     if (c > s->max_shard) s->max_shard = c;
@@ -97,7 +100,7 @@ void list_tensors(const ModelShape &s, std::vector<TensorInfo> *out) {
   const int64_t h = s.shard_off[s.S + 1];
   out->push_back({"lnf_g", h, d, 1, s.S + 1});
   out->push_back({"lnf_b", h + d, d, 1, s.S + 1});
-  out->push_back({"w_lm", h + 2 * d, d, s.V, s.S + 1});
+  if (!s.tie) out->push_back({"w_lm", h + 2 * d, d, s.V, s.S + 1});
 }
 
 }  // namespace hydra
@@ -122,7 +125,7 @@ hydra_status hydra_model_layout(const hydra_model_desc *desc, hydra_layout *out)
   out->params_per_block = s.bo.size;
   out->n_block_shards = s.S;
   out->n_shards = s.S + 2;
-  out->n_tensors = 2 + 12 * s.L + 3;
+  out->n_tensors = 2 + 12 * s.L + (s.tie ? 2 : 3);
   out->reserved = 0;
   return HYDRA_OK;
 }

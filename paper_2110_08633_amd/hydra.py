@@ -37,7 +37,8 @@ class InitDesc(C.Structure):
 class ModelDesc(C.Structure):
     _fields_ = [("n_layer", C.c_int32), ("d_model", C.c_int32), ("n_head", C.c_int32), ("d_ff", C.c_int32),
                 ("vocab", C.c_int32), ("seq", C.c_int32), ("batch", C.c_int32), ("layers_per_shard", C.c_int32),
-                ("dtype", C.c_int32), ("n_micro", C.c_int32), ("lr", C.c_double), ("beta1", C.c_double),
+                ("dtype", C.c_int32), ("n_micro", C.c_int32), ("tie_embeddings", C.c_int32), ("reserved", C.c_int32),
+                ("lr", C.c_double), ("beta1", C.c_double),
                 ("beta2", C.c_double), ("eps", C.c_double)]
 
 
@@ -138,7 +139,8 @@ def model_desc(cfg, lr, dtype=None, beta1=0.9, beta2=0.999, eps=1e-8):
     """ModelDesc from a config dict with keys L, d, H, F, V, T, B, k, dtype and, optionally, n_micro."""
     dt = cfg["dtype"] if dtype is None else dtype
     return ModelDesc(cfg["L"], cfg["d"], cfg["H"], cfg["F"], cfg["V"], cfg["T"], cfg["B"], cfg["k"],
-                     1 if dt == "bf16" else 0, int(cfg.get("n_micro", 1)), lr, beta1, beta2, eps)
+                     1 if dt == "bf16" else 0, int(cfg.get("n_micro", 1)), 1 if cfg.get("tie") else 0, 0,
+                     lr, beta1, beta2, eps)
 
 
 # ---- thin wrappers, same names as the C functions --------------------------

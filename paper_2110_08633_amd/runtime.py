@@ -139,6 +139,8 @@ def arena_bytes_for(cfgs, n_slots, ckpt_spill=False, lanes=1):
         vpad = (V + 63) // 64 * 64
         nm = c.get("n_micro", 1)
         total += nm * ((2 if ckpt_spill else S + 1) * act + 2 * act + M * vpad * 4 + 64 * M) + (1 << 16)
+        if c.get("tie"):
+            total += V * d * 4 + 256
         layer = 5 * act + 3 * M * d * 4 + M * 3 * d * 4 + B * c["H"] * T * T * 4 + 2 * M * F * 4
         scratch = 2 * B * c["H"] * T * T * 4 + 4 * act + M * F * 4 + M * 3 * d * 4 + 4 * act
         ws = max(ws, k * layer + k * act + scratch + 2 * act + (1 << 20), M * vpad * 4 + 4 * act + (1 << 20))

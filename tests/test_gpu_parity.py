@@ -372,3 +372,51 @@ def test_heterogeneous_models_in_one_job(rt, dtype):
                       dtype, f"model {m} ")
     H.hydra_sched_destroy(sch)
     sess.close()
+
+
+@pytest.mark.parametrize("mode", ["manual_spill", "resident", "scheduled_micro"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tied_lm_head(rt, dtype, mode):
+    """LM head tied to the token embedding (logits = z wte^T): the HEAD shard owns only the final LayerNorm and
+    works on a copy of wte; the wte gradient is the head's part plus the lookup's part and wte is stepped once,
+    at the EMBED shard's backward visit.  Three minibatches, so that the head's copy has to be refreshed after
+    every update - with every shard spilled between visits, with all shards resident (the update then exists only
+    on the device), and through the scheduler with micro-batches."""
+    H, R = rt
+    base = SI.small_cfg(L=2, d=64, H=2, F=128, V=301, T=40, B=2, k=1, dtype=dtype, lrs=[1e-4], tie=True)
+    nm = 2 if mode == "scheduled_micro" else 1
+    cfg = dict(base, n_micro=nm)
+    big = dict(base, B=base["B"] * nm)
+    W = SI.make_weights(base, 31)
+    assert "w_lm" not in W
+    batches = [SI.make_batch(big, 400 + i, zipf=(i == 1)) for i in range(3)]
+    refs, P, Mo, Vo = oracle_steps(big, W, 1e-4, batches)
+    sess = R.Session(R.arena_bytes_for([cfg], 4), max_slots=2 if mode == "manual_spill" else 4,
+                     flags=H.FLAG_POISON if mode == "manual_spill" else 0)
+    rec = sess.add_model(cfg, W, 1e-4)
+    assert rec["layout"].n_params == SI.n_params(base)
+    ill, tol, M = {}, TOL[dtype], base["B"] * base["T"]
+    if mode == "scheduled_micro":
+        fc, bc = SI.task_costs(base)
+        sch = H.hydra_sched_create(sess.ctx, [rec["id"]], [3], [list(fc) + list(bc)])
+        H.hydra_sched_run(sch, [np.stack([b[0] for b in batches])], [np.stack([b[1] for b in batches])], sess.ctx)
+        sess.flush()
+        H.hydra_sched_destroy(sch)
+        for r in refs:
+            update_ill(ill, r["grads"], dtype)
+        assert abs(H.hydra_get_loss(sess.ctx, rec["id"]) - refs[-1]["loss"]) <= tol * refs[-1]["loss"]
+        check_weights(sess.unpack(rec, rec["master"]), P, refs[0]["before"], ill, 1e-4, 3, dtype)
+    else:
+        for i, (tok, tgt) in enumerate(batches):
+            got = sess.train_step_manual(rec, tok, tgt, spill=(mode == "manual_spill"))
+            H.hydra_sync(sess.ctx)
+            assert_close(got["logits"], refs[i]["logits"][-M:], tol, "logits")
+            assert abs(got["loss"] - refs[i]["loss"]) <= tol * abs(refs[i]["loss"])
+            for name, g in refs[i]["grads"].items():
+                assert_close(got["grads"][name], g, tol, f"grad {name}")
+            update_ill(ill, refs[i]["grads"], dtype)
+            if mode == "resident":
+                sess.flush()
+            after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
+            check_weights(after, refs[i]["after"], refs[0]["before"], ill, 1e-4, i + 1, dtype, f"step {i}: ")
+    sess.close()

@@ -198,3 +198,22 @@ def test_dry_checkpoint_spill_traffic_and_ordering_guard(nm):
     assert st["bytes_d2h"] == 12 * n + (S + 1) * act          # S+1 boundaries written to the host
     assert st["bytes_h2d"] >= 12 * n + S * act                # and the S inputs of the block shards read back
     s.close()
+
+
+def test_tied_layout_drops_the_head_matrix():
+    """Tied LM head: the parameter count falls by d*V (GPT-2 small with 1024 positions then has its published
+    124 439 808 parameters), the HEAD shard owns the final LayerNorm only, and the shard buffer is still sized for
+    the head's working copy of wte."""
+    cfg = dict(SI.CONFIGS["gpt2s"], tie=True)
+    untied = SI.CONFIGS["gpt2s"]
+    desc = H.model_desc(cfg, 1e-4)
+    lay = H.hydra_model_layout(desc)
+    d, V = cfg["d"], cfg["V"]
+    assert lay.n_params == SI.n_params(cfg) == SI.n_params(untied) - d * V
+    assert SI.n_params(dict(cfg, T=1024)) == 124439808
+    assert lay.n_tensors == len(SI.tensor_shapes(cfg))
+    off, cnt = H.hydra_shard_range(desc, lay.n_shards - 1)
+    assert cnt == 2 * d and off + cnt == lay.n_params
+    names = [H.hydra_model_tensor(desc, i)[0] for i in range(lay.n_tensors)]
+    assert names[-2:] == ["lnf_g", "lnf_b"] and "w_lm" not in names
+    assert H.hydra_shard_footprint(desc, 0) >= 18 * (2 * d + d * V)
