@@ -143,8 +143,25 @@ hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, f
 
 // ------------------------------------------------------------------ LayerNorm
 // One wavefront per row, four rows per block.  Mean, then centred variance
-// (two passes, as in the definition), then the affine output.
-template <typename OutT>
+// (two passes, as in the definition), then the affine output.  Rows of up to
+// 64 * 4 * LN_R = 2048 elements are read once and kept in registers; wider rows
+// are re-read (they hit the cache).
+constexpr int LN_R = 8;  // float4 per lane kept in registers
+
+__device__ __forceinline__ void st4(float *p, float a, float b, float c, float e) {
+  *(float4 *)p = make_float4(a, b, c, e);
+}
+__device__ __forceinline__ void st4(bf16_t *p, float a, float b, float c, float e) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf2_t;
+  typedef __attribute__((ext_vector_type(2))) float f2_t;
+  union { bf2_t h[2]; uint2 u; } x;
+  const f2_t lo = {a, b}, hi = {c, e};
+  x.h[0] = __builtin_convertvector(lo, bf2_t);  // round to nearest even, one instruction on gfx950
+  x.h[1] = __builtin_convertvector(hi, bf2_t);
+  *(uint2 *)p = x.u;
+}
+
+template <typename OutT, bool CACHED>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float *__restrict__ x, const float *__restrict__ gamma,
                                                             const float *__restrict__ beta, OutT *__restrict__ y,
                                                             float *__restrict__ mean, float *__restrict__ rstd, int M,
@@ -153,29 +170,53 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const float *__restr
   const int lane = threadIdx.x & 63;
   if (row >= M) return;
   const float *xr = x + (int64_t)row * d;
+  float4 v[LN_R];
   float s = 0.f;
-  for (int c = lane * 4; c < d; c += 256) {
-    const float4 v = *(const float4 *)(xr + c);
-    s += (v.x + v.y) + (v.z + v.w);
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < LN_R; ++i) {
+      const int c = lane * 4 + i * 256;
+      v[i] = c < d ? *(const float4 *)(xr + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < LN_R; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  } else {
+    for (int c = lane * 4; c < d; c += 256) {
+      const float4 w = *(const float4 *)(xr + c);
+      s += (w.x + w.y) + (w.z + w.w);
+    }
   }
   const float mu = wave_sum(s) / (float)d;
   float q = 0.f;
-  for (int c = lane * 4; c < d; c += 256) {
-    const float4 v = *(const float4 *)(xr + c);
-    const float a = v.x - mu, b = v.y - mu, e = v.z - mu, f = v.w - mu;
-    q += (a * a + b * b) + (e * e + f * f);
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < LN_R; ++i)
+      if (lane * 4 + i * 256 < d) {
+        const float a = v[i].x - mu, b = v[i].y - mu, e = v[i].z - mu, f = v[i].w - mu;
+        q += (a * a + b * b) + (e * e + f * f);
+      }
+  } else {
+    for (int c = lane * 4; c < d; c += 256) {
+      const float4 w = *(const float4 *)(xr + c);
+      const float a = w.x - mu, b = w.y - mu, e = w.z - mu, f = w.w - mu;
+      q += (a * a + b * b) + (e * e + f * f);
+    }
   }
   const float rs = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
   OutT *yr = y + (int64_t)row * d;
-  for (int c = lane * 4; c < d; c += 256) {
-    const float4 v = *(const float4 *)(xr + c);
+  auto emit = [&](int c, const float4 w) {
     const float4 gm = *(const float4 *)(gamma + c);
     const float4 bt = *(const float4 *)(beta + c);
-    stv<OutT>(yr, c + 0, (v.x - mu) * rs * gm.x + bt.x);
-    stv<OutT>(yr, c + 1, (v.y - mu) * rs * gm.y + bt.y);
-    stv<OutT>(yr, c + 2, (v.z - mu) * rs * gm.z + bt.z);
-    stv<OutT>(yr, c + 3, (v.w - mu) * rs * gm.w + bt.w);
+    st4(yr + c, (w.x - mu) * rs * gm.x + bt.x, (w.y - mu) * rs * gm.y + bt.y, (w.z - mu) * rs * gm.z + bt.z,
+        (w.w - mu) * rs * gm.w + bt.w);
+  };
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < LN_R; ++i)
+      if (lane * 4 + i * 256 < d) emit(lane * 4 + i * 256, v[i]);
+  } else {
+    for (int c = lane * 4; c < d; c += 256) emit(c, *(const float4 *)(xr + c));
   }
 }
 
@@ -183,14 +224,28 @@ hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, c
                                 float *rstd, int M, int d, hipStream_t s) {
   dim3 grid((M + 3) / 4), block(256);
   ProfScope ps("layernorm_fwd", s, 0, (double)M * d * (4.0 + dt_size(dtype)) + 8.0 * M);
-  if (dtype == DT_BF16)
-    hipLaunchKernelGGL(layernorm_fwd_kernel<bf16_t>, grid, block, 0, s, x, gamma, beta, (bf16_t *)y, mean, rstd, M, d);
-  else
-    hipLaunchKernelGGL(layernorm_fwd_kernel<float>, grid, block, 0, s, x, gamma, beta, (float *)y, mean, rstd, M, d);
+  const bool cached = d <= 256 * LN_R;
+  if (dtype == DT_BF16) {
+    if (cached)
+      hipLaunchKernelGGL((layernorm_fwd_kernel<bf16_t, true>), grid, block, 0, s, x, gamma, beta, (bf16_t *)y, mean, rstd,
+                         M, d);
+    else
+      hipLaunchKernelGGL((layernorm_fwd_kernel<bf16_t, false>), grid, block, 0, s, x, gamma, beta, (bf16_t *)y, mean,
+                         rstd, M, d);
+  } else {
+    if (cached)
+      hipLaunchKernelGGL((layernorm_fwd_kernel<float, true>), grid, block, 0, s, x, gamma, beta, (float *)y, mean, rstd, M,
+                         d);
+    else
+      hipLaunchKernelGGL((layernorm_fwd_kernel<float, false>), grid, block, 0, s, x, gamma, beta, (float *)y, mean, rstd,
+                         M, d);
+  }
   return hipGetLastError();
 }
 
 // dx = rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)) [+ dres], dxhat = dy * gamma
+// One wavefront per row; rows of up to 2048 elements stay in registers between the two phases.
+template <bool CACHED>
 __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__restrict__ dy, const float *__restrict__ x,
                                                                const float *__restrict__ mean,
                                                                const float *__restrict__ rstd,
@@ -202,38 +257,64 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__re
   if (row >= M) return;
   const float *xr = x + (int64_t)row * d, *dyr = dy + (int64_t)row * d;
   const float mu = mean[row], rs = rstd[row];
+  float4 xh[LN_R], h[LN_R];  // normalised input and dy * gamma
   float s1 = 0.f, s2 = 0.f;
-  for (int c = lane * 4; c < d; c += 256) {
+  auto phase1 = [&](int c, float4 &xo, float4 &ho) {
     const float4 v = *(const float4 *)(xr + c);
     const float4 g = *(const float4 *)(dyr + c);
     const float4 gm = *(const float4 *)(gamma + c);
-    const float h0 = g.x * gm.x, h1 = g.y * gm.y, h2 = g.z * gm.z, h3 = g.w * gm.w;
-    s1 += (h0 + h1) + (h2 + h3);
-    s2 += (h0 * ((v.x - mu) * rs) + h1 * ((v.y - mu) * rs)) + (h2 * ((v.z - mu) * rs) + h3 * ((v.w - mu) * rs));
+    xo = make_float4((v.x - mu) * rs, (v.y - mu) * rs, (v.z - mu) * rs, (v.w - mu) * rs);
+    ho = make_float4(g.x * gm.x, g.y * gm.y, g.z * gm.z, g.w * gm.w);
+    s1 += (ho.x + ho.y) + (ho.z + ho.w);
+    s2 += (ho.x * xo.x + ho.y * xo.y) + (ho.z * xo.z + ho.w * xo.w);
+  };
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < LN_R; ++i)
+      if (lane * 4 + i * 256 < d) phase1(lane * 4 + i * 256, xh[i], h[i]);
+  } else {
+    for (int c = lane * 4; c < d; c += 256) {
+      float4 a, b;
+      phase1(c, a, b);
+    }
   }
   const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
-  for (int c = lane * 4; c < d; c += 256) {
-    const float4 v = *(const float4 *)(xr + c);
-    const float4 g = *(const float4 *)(dyr + c);
-    const float4 gm = *(const float4 *)(gamma + c);
+  auto phase2 = [&](int c, const float4 &xo, const float4 &ho) {
     float4 o;
-    o.x = rs * (g.x * gm.x - m1 - (v.x - mu) * rs * m2);
-    o.y = rs * (g.y * gm.y - m1 - (v.y - mu) * rs * m2);
-    o.z = rs * (g.z * gm.z - m1 - (v.z - mu) * rs * m2);
-    o.w = rs * (g.w * gm.w - m1 - (v.w - mu) * rs * m2);
+    o.x = rs * (ho.x - m1 - xo.x * m2);
+    o.y = rs * (ho.y - m1 - xo.y * m2);
+    o.z = rs * (ho.z - m1 - xo.z * m2);
+    o.w = rs * (ho.w - m1 - xo.w * m2);
     if (dres) {
       const float4 r = *(const float4 *)(dres + (int64_t)row * d + c);
       o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
     }
     *(float4 *)(dx + (int64_t)row * d + c) = o;
+  };
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < LN_R; ++i)
+      if (lane * 4 + i * 256 < d) phase2(lane * 4 + i * 256, xh[i], h[i]);
+  } else {
+    for (int c = lane * 4; c < d; c += 256) {
+      const float4 v = *(const float4 *)(xr + c);
+      const float4 g = *(const float4 *)(dyr + c);
+      const float4 gm = *(const float4 *)(gamma + c);
+      phase2(c, make_float4((v.x - mu) * rs, (v.y - mu) * rs, (v.z - mu) * rs, (v.w - mu) * rs),
+             make_float4(g.x * gm.x, g.y * gm.y, g.z * gm.z, g.w * gm.w));
+    }
   }
 }
 
 hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
                                    const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s) {
   ProfScope ps("layernorm_bwd_dx", s, 0, (double)M * d * (dres ? 16.0 : 12.0));
-  hipLaunchKernelGGL(layernorm_bwd_dx_kernel, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma, dres, dx, M,
-                     d);
+  if (d <= 256 * LN_R)
+    hipLaunchKernelGGL(layernorm_bwd_dx_kernel<true>, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma, dres,
+                       dx, M, d);
+  else
+    hipLaunchKernelGGL(layernorm_bwd_dx_kernel<false>, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma,
+                       dres, dx, M, d);
   return hipGetLastError();
 }
 
@@ -254,13 +335,28 @@ __global__ __launch_bounds__(256) void colsum_pass1_kernel(const T *__restrict__
   const int r0 = blockIdx.y * CH, r1 = min(M, r0 + CH);
   double a = 0.0, b = 0.0;  // fp64 adds are free in a memory-bound reduction
   if (col < N) {
-    for (int r = r0 + ry; r < r1; r += 4) {
-      const float v = ldv<T>(in, (int64_t)r * ld + col);
-      if (MODE == 1) {
-        a += (double)(v * ((x[(int64_t)r * ld + col] - mean[r]) * rstd[r]));
-        b += v;
-      } else {
-        a += v;
+    // eight rows' loads are issued before the first is used: the loop is latency-bound otherwise
+    constexpr int U = 8;
+    for (int rb = r0 + ry; rb < r1; rb += 4 * U) {
+      float v[U], xh[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = rb + 4 * u;
+        v[u] = 0.f;
+        xh[u] = 0.f;
+        if (r < r1) {
+          v[u] = ldv<T>(in, (int64_t)r * ld + col);
+          if (MODE == 1) xh[u] = (x[(int64_t)r * ld + col] - mean[r]) * rstd[r];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {  // ascending rows, as before
+        if (MODE == 1) {
+          a += (double)(v[u] * xh[u]);
+          b += v[u];
+        } else {
+          a += v[u];
+        }
       }
     }
   }
