@@ -143,6 +143,9 @@ def main():
     ap.add_argument("--slots", type=int, default=4, help="shard buffers in spill mode")
     ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
     ap.add_argument("--lanes", type=int, default=2, help="compute lanes (streams); models are spread over them")
+    ap.add_argument("--graphs", action="store_true",
+                    help="replay block-shard visits as HIP graphs (halves the host's enqueue time; the device is the "
+                         "bottleneck at this workload, so the throughput does not move)")
     ap.add_argument("--micro", type=int, default=1,
                     help="micro-batches of B samples per shard visit (1 = the workload as BASELINE states it)")
     ap.add_argument("--extra-micro", type=int, default=4,
@@ -160,6 +163,8 @@ def main():
     assert torch.cuda.is_available(), "no GPU visible"
     if args.d2h_memcpy:
         EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
+    if args.graphs:
+        EXTRA_FLAGS |= H.FLAG_GRAPHS
     cfg = dict(SI.CONFIGS[args.config])
     if args.micro > 1:
         cfg["n_micro"] = args.micro
@@ -177,7 +182,7 @@ def main():
         "config": {"workload": f"{args.config}: {n_models} GPT-2-small-shaped models (12L d768 H12 F3072 V50257), "
                                f"B{cfg['B']} T{cfg['T']}, 2-layer shards alternated by Sharded-LRTF, bf16 MFMA + fp32 "
                                "master/Adam, seeded N(0,0.02) weights, uniform tokens",
-                   "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes,
+                   "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes, "hip_graphs": args.graphs,
                    "micro_batches_per_visit": args.micro, "tokens_per_step": tokens_per_step},
         "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),
                  "d2h_GB_per_step": round(main_run["d2h"] / args.steps / 1e9, 3),
@@ -197,7 +202,9 @@ def main():
                               "embed_head_MB": round(fp[0] / 1e6, 1),
                               "cuts_at_bound_of_2_layer_shard": H.hydra_partition(H.model_desc(cfg, 1e-4), max(fp[2], fp[0]))[0]}
         out[other] = {"value": round(tokens_per_step * args.steps / o["seconds"], 1), "unit": "tokens/s",
-                      "ms_per_step": round(1e3 * o["seconds"] / args.steps, 3), "shard_buffers": o["n_slots"]}
+                      "ms_per_step": round(1e3 * o["seconds"] / args.steps, 3),
+                      "host_enqueue_ms_per_step": round(1e3 * o["enqueue_seconds"] / args.steps, 3),
+                      "shard_buffers": o["n_slots"]}
         if args.extra_micro > 1 and args.micro == 1:
             # same models, shards and buffers, but every shard visit runs several micro-batches while the shard is
             # resident: the state traffic per step is unchanged and serves that many times the tokens
@@ -208,6 +215,14 @@ def main():
                 "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
                 "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
                 "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"]}
+            # the same 4x tokens per shard visit as ONE micro-batch of 4x the samples: activation memory grows
+            # fourfold (no issue on a 288 GB part), the GEMMs become four times larger and fill the chip
+            bc = dict(cfg, B=cfg["B"] * args.extra_micro)
+            o = measure(bc, n_models, "spill", steps_m, 1, False, R, H, torch)
+            out[f"spill_batch_x{args.extra_micro}"] = {
+                "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
+                "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
+                "batch": bc["B"], "shard_buffers": o["n_slots"]}
         # per-kernel HIP-event timing over the same steps (resident buffers so that copies do not perturb kernels)
         t = measure(cfg, n_models, "resident", args.steps, args.warmup, True, R, H, torch)
         ks = sorted(t["kernels"], key=lambda k: -k["ms"])

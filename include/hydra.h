@@ -66,7 +66,10 @@ enum {
   HYDRA_FLAG_CKPT_SPILL = 2, /* boundary activations travel through host DRAM between visits                */
   HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
   HYDRA_FLAG_TIMING = 8,     /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
-  HYDRA_FLAG_D2H_MEMCPY = 16 /* demote with hipMemcpyAsync instead of the library's own copy kernel             */
+  HYDRA_FLAG_D2H_MEMCPY = 16, /* demote with hipMemcpyAsync instead of the library's own copy kernel            */
+  HYDRA_FLAG_GRAPHS = 32     /* block-shard visits are captured as HIP graphs on their second run with a given  */
+                             /* shard buffer and replayed from then on (one graph launch instead of dozens of   */
+                             /* kernel launches: the host is the bottleneck otherwise); ignored with TIMING     */
 };
 
 /* 'what' of hydra_shard_load_async */
@@ -150,7 +153,8 @@ typedef struct {
   int32_t n_slots;
   int32_t reserved;
   uint64_t slot_bytes, workspace_bytes, model_state_bytes;
-  double reserved_ms[3];
+  uint64_t n_graph_launches;       /* block-shard visits replayed as HIP graphs (HYDRA_FLAG_GRAPHS)       */
+  double reserved_ms[2];
 } hydra_stats;
 
 /* ---- context ------------------------------------------------------------ */

@@ -178,6 +178,8 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->s_h2d);
     (void)hipStreamSynchronize(ctx->s_d2h);
     prof_destroy(ctx->prof);
+    for (auto &kv : ctx->graphs)
+      if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
     for (hydra_ctx::Lane &ln : ctx->lanes)
       if (ln.own_stream) (void)hipStreamDestroy(ln.stream);
     for (Slot &s : ctx->slots) {
@@ -220,6 +222,7 @@ const char *hydra_last_error(const hydra_ctx *ctx) { return ctx ? ctx->err.c_str
 hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out) {
   if (!ctx || !out) return fail(ctx, HYDRA_E_INVAL, "null argument");
   *out = ctx->stats;
+  out->n_graph_launches = ctx->graph_launches;
   return HYDRA_OK;
 }
 

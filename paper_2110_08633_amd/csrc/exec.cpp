@@ -137,15 +137,11 @@ GemmDesc attn_desc(const ModelShape &s, int dt) {
   return g;
 }
 
-hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, float *x_out,
-                         const LayerActs &A, float *Sbuf, hipStream_t st) {
-  const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
+// attention of one block as separate kernels (fp32 path, and head widths the fused kernels do not serve): scores
+// into Sbuf (fp32, [B,H,T,T], lower triangle), softmax into A.P, P V into A.o
+hipError_t attention_unfused_fwd(const ModelShape &s, int dt, const LayerActs &A, float *Sbuf, hipStream_t st) {
+  const int d = s.d, T = s.T, dh = s.dh;
   const int64_t TT = (int64_t)T * T;
-  CK(launch_layernorm_fwd(dt, x_in, W.ln1_g, W.ln1_b, A.a, A.mean1, A.rstd1, M, d, st));
-  CK(linear(dt, M, 3 * d, d, A.a, W.w_qkv, W.b_qkv, nullptr, nullptr, A.qkv, EPI_NONE, nullptr, st));
-  if (fused_attn(s, dt)) {
-    CK(launch_attention_fwd(A.qkv, A.o, A.lse, s.B, s.H, T, dh, st));
-  } else {
   {  // scores = q k^T / sqrt(dh), lower triangle
     GemmDesc g = attn_desc(s, dt);
     g.ta = 0; g.tb = 0; g.M = T; g.N = T; g.K = dh; g.alpha = 1.0f / sqrtf((float)dh);
@@ -165,7 +161,16 @@ hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const flo
     g.causal = CAUSAL_K_END;
     CK(launch_gemm(g, st));
   }
-  }
+  return hipSuccess;
+}
+
+hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, float *x_out,
+                         const LayerActs &A, float *Sbuf, hipStream_t st) {
+  const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
+  CK(launch_layernorm_fwd(dt, x_in, W.ln1_g, W.ln1_b, A.a, A.mean1, A.rstd1, M, d, st));
+  CK(linear(dt, M, 3 * d, d, A.a, W.w_qkv, W.b_qkv, nullptr, nullptr, A.qkv, EPI_NONE, nullptr, st));
+  if (fused_attn(s, dt)) CK(launch_attention_fwd(A.qkv, A.o, A.lse, s.B, s.H, T, dh, st));
+  else CK(attention_unfused_fwd(s, dt, A, Sbuf, st));
   CK(linear(dt, M, d, d, A.o, W.w_o, W.b_o, x_in, A.x1, nullptr, EPI_NONE, nullptr, st));
   CK(launch_layernorm_fwd(dt, A.x1, W.ln2_g, W.ln2_b, A.c, A.mean2, A.rstd2, M, d, st));
   CK(linear(dt, M, F, d, A.c, W.w_fc, W.b_fc, nullptr, nullptr, A.u, EPI_GELU, A.g, st));
@@ -196,36 +201,15 @@ hipError_t act_view(int dt, const float *src, void *scratch, int M, int d, const
   return launch_cast_act(dt, src, d, scratch, d, M, d, st);
 }
 
-hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, const LayerActs &A,
-                          const float *dx2, float *dx_out, const BwdScratch &Z, int acc, hipStream_t st) {
-  const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
+// backward of attention_unfused_fwd: d_o (Z.d_o) -> dq | dk | dv (Z.dqkv) through dP, the softmax backward and
+// three more batched products
+hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A, const BwdScratch &Z,
+                                 hipStream_t st) {
+  const int d = s.d, T = s.T, dh = s.dh;
   const int64_t TT = (int64_t)T * T;
-  const BlockOffsets &o = s.bo;
   const float scale = 1.0f / sqrtf((float)dh);
-  const void *dx2a;
-  CK(act_view(dt, dx2, Z.dact, M, d, &dx2a, st));
-  // MLP down projection
-  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, st));
-  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, st));
-  CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, Z.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
-  // MLP up projection
-  CK(launch_colsum(dt, Z.du, F, W.G + o.b_fc, Z.red, M, F, acc, st));
-  CK(linear_dw(dt, M, F, d, A.c, d, Z.du, F, W.G + o.w_fc, acc, st));
-  CK(linear_dx(dt, M, F, d, Z.du, W.w_fc, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // dc
-  CK(launch_layernorm_bwd_params(Z.dtmp, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, st));
-  CK(launch_layernorm_bwd_dx(Z.dtmp, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, Z.dx1, M, d, st));
-  // attention output projection
-  const void *dx1a;
-  CK(act_view(dt, Z.dx1, Z.dact, M, d, &dx1a, st));
-  CK(launch_colsum(DT_F32, Z.dx1, d, W.G + o.b_o, Z.red, M, d, acc, st));
-  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, st));
-  CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
-  // attention core
   const void *q = A.qkv, *k = off_act((const void *)A.qkv, d, dt), *v = off_act((const void *)A.qkv, 2 * d, dt);
   const int64_t sQ1 = (int64_t)T * 3 * d;
-  if (fused_attn(s, dt)) {
-    CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, Z.dqkv, s.B, s.H, T, dh, st));
-  } else {
   {  // dP = dO V^T
     GemmDesc g = attn_desc(s, dt);
     g.ta = 0; g.tb = 0; g.M = T; g.N = T; g.K = dh;
@@ -263,7 +247,34 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
     g.causal = CAUSAL_K_BEGIN;
     CK(launch_gemm(g, st));
   }
-  }
+  return hipSuccess;
+}
+
+hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, const LayerActs &A,
+                          const float *dx2, float *dx_out, const BwdScratch &Z, int acc, hipStream_t st) {
+  const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
+  const BlockOffsets &o = s.bo;
+  const void *dx2a;
+  CK(act_view(dt, dx2, Z.dact, M, d, &dx2a, st));
+  // MLP down projection
+  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, st));
+  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, st));
+  CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, Z.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
+  // MLP up projection
+  CK(launch_colsum(dt, Z.du, F, W.G + o.b_fc, Z.red, M, F, acc, st));
+  CK(linear_dw(dt, M, F, d, A.c, d, Z.du, F, W.G + o.w_fc, acc, st));
+  CK(linear_dx(dt, M, F, d, Z.du, W.w_fc, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // dc
+  CK(launch_layernorm_bwd_params(Z.dtmp, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, st));
+  CK(launch_layernorm_bwd_dx(Z.dtmp, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, Z.dx1, M, d, st));
+  // attention output projection
+  const void *dx1a;
+  CK(act_view(dt, Z.dx1, Z.dact, M, d, &dx1a, st));
+  CK(launch_colsum(DT_F32, Z.dx1, d, W.G + o.b_o, Z.red, M, d, acc, st));
+  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, st));
+  CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
+  // attention core
+  if (fused_attn(s, dt)) CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, Z.dqkv, s.B, s.H, T, dh, st));
+  else CK(attention_unfused_bwd(s, dt, A, Z, st));
   // QKV projection
   CK(launch_colsum(dt, Z.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, st));
   CK(linear_dw(dt, M, 3 * d, d, A.a, d, Z.dqkv, 3 * d, W.G + o.w_qkv, acc, st));
@@ -307,6 +318,52 @@ BwdScratch take_bwd(Bump &b, const ModelShape &s, int dt) {
 uint64_t head_bytes(const ModelShape &s, int dt) {
   const uint64_t e = dt_size(dt), M = s.M, d = s.d;
   return up256(M * s.Vpad * 4) + up256(M * d * e) + 2 * up256(M * 4) + up256(M * d * 4) + up256(red_elems(s) * 4);
+}
+
+// Runs the kernel sequence of a block-shard visit.  With HYDRA_FLAG_GRAPHS the second visit of a (model, shard,
+// phase, shard buffer) combination is captured from the stream as a HIP graph and every later one replays it: the
+// sequence is dozens of launches whose arguments depend on nothing else, and issuing them one by one costs the host
+// more time than the device needs to run them.  phase: 0 forward, 1 / 2 backward by boundary-gradient parity.
+template <typename F>
+hydra_status run_visit(hydra_ctx *ctx, Model *mm, Slot *sl, int shard, int phase, hipStream_t st, F &&enqueue) {
+  const bool use = (ctx->init.flags & HYDRA_FLAG_GRAPHS) && !(ctx->init.flags & HYDRA_FLAG_TIMING);
+  if (!use) {
+    HYDRA_HIP(ctx, enqueue());
+    return HYDRA_OK;
+  }
+  const uint64_t model_i = (uint64_t)(std::find(ctx->models.begin(), ctx->models.end(), mm) - ctx->models.begin());
+  const uint64_t slot_i = (uint64_t)(sl - ctx->slots.data());
+  const uint64_t key = (model_i << 40) | ((uint64_t)shard << 24) | ((uint64_t)phase << 16) | slot_i;
+  hydra_ctx::GraphEntry &e = ctx->graphs[key];
+  if (e.exec) {
+    HYDRA_HIP(ctx, hipGraphLaunch(e.exec, st));
+    ctx->graph_launches++;
+    return HYDRA_OK;
+  }
+  if (e.failed || e.seen == 0) {  // first visit: plain launches (one-time set-up of the kernels happens here)
+    e.seen++;
+    HYDRA_HIP(ctx, enqueue());
+    return HYDRA_OK;
+  }
+  hipGraph_t graph = nullptr;
+  hipError_t err = hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed);
+  if (err == hipSuccess) {
+    const hipError_t launch_err = enqueue();
+    err = hipStreamEndCapture(st, &graph);
+    if (err == hipSuccess) err = launch_err;
+  }
+  if (err == hipSuccess) err = hipGraphInstantiate(&e.exec, graph, nullptr, nullptr, 0);
+  if (graph) (void)hipGraphDestroy(graph);
+  if (err != hipSuccess) {  // capture is an optimisation: fall back to plain launches for this combination
+    (void)hipGetLastError();
+    e.exec = nullptr;
+    e.failed = true;
+    HYDRA_HIP(ctx, enqueue());
+    return HYDRA_OK;
+  }
+  HYDRA_HIP(ctx, hipGraphLaunch(e.exec, st));
+  ctx->graph_launches++;
+  return HYDRA_OK;
 }
 
 }  // namespace
@@ -356,15 +413,19 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     float *Sbuf = fused_attn(s, dt) ? nullptr : b.take<float>((uint64_t)s.B * s.H * s.T * s.T);
     float *pp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (forward)");
-    for (int u = 0; u < s.nm; ++u) {  // micro-batches share the workspace, one after the other
-      const float *x = mm->ckpt[shard - 1] + u * act;
-      for (int j = 0; j < s.k; ++j) {
-        float *y = (j == s.k - 1) ? mm->ckpt[shard] + u * act : pp[j & 1];
-        HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), x, y, A, Sbuf, st));
-        x = y;
+    // nothing but kernel launches with arguments that depend only on (model, shard, shard buffer): graphable
+    auto enqueue = [&]() -> hipError_t {
+      for (int u = 0; u < s.nm; ++u) {  // micro-batches share the workspace, one after the other
+        const float *x = mm->ckpt[shard - 1] + u * act;
+        for (int j = 0; j < s.k; ++j) {
+          float *y = (j == s.k - 1) ? mm->ckpt[shard] + u * act : pp[j & 1];
+          CK(block_forward(s, dt, block_ptrs(s, sl, dt, j), x, y, A, Sbuf, st));
+          x = y;
+        }
       }
-    }
-    return HYDRA_OK;
+      return hipSuccess;
+    };
+    return run_visit(ctx, mm, sl, shard, 0, st, enqueue);
   }
   // HEAD: final LayerNorm, logits, loss and d(loss)/d(logits)
   float *logits = b.take<float>((uint64_t)M * s.Vpad);
@@ -449,19 +510,24 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     BwdScratch Z = take_bwd(b, s, dt);
     float *gpp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (backward)");
-    for (int u = 0; u < s.nm; ++u) {  // recompute and back-propagate one micro-batch at a time
-      xs[0] = mm->ckpt[shard - 1] + u * act;
-      for (int j = 0; j < s.k; ++j)
-        HYDRA_HIP(ctx, block_forward(s, dt, block_ptrs(s, sl, dt, j), xs[j], xs[j + 1], acts[j], Z.dP, st));
-      const float *dx = mm->dbound[mm->dcur] + u * act;
-      for (int j = s.k - 1; j >= 0; --j) {
-        float *out = (j == 0) ? mm->dbound[mm->dcur ^ 1] + u * act : gpp[j & 1];
-        HYDRA_HIP(ctx, block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, out, Z, u > 0, st));
-        dx = out;
+    const int dcur = mm->dcur;
+    auto enqueue = [&]() -> hipError_t {
+      for (int u = 0; u < s.nm; ++u) {  // recompute and back-propagate one micro-batch at a time
+        xs[0] = mm->ckpt[shard - 1] + u * act;
+        for (int j = 0; j < s.k; ++j)
+          CK(block_forward(s, dt, block_ptrs(s, sl, dt, j), xs[j], xs[j + 1], acts[j], Z.dP, st));
+        const float *dx = mm->dbound[dcur] + u * act;
+        for (int j = s.k - 1; j >= 0; --j) {
+          float *out = (j == 0) ? mm->dbound[dcur ^ 1] + u * act : gpp[j & 1];
+          CK(block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, out, Z, u > 0, st));
+          dx = out;
+        }
       }
-    }
-    mm->dcur ^= 1;
-    return HYDRA_OK;
+      return hipSuccess;
+    };
+    const hydra_status rs = run_visit(ctx, mm, sl, shard, 1 + dcur, st, enqueue);
+    if (rs == HYDRA_OK) mm->dcur ^= 1;
+    return rs;
   }
   // EMBED
   if (s.tie)  // start from the LM head's part of the wte gradient

@@ -405,8 +405,6 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
                    ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
                    ((((uintptr_t)g.out_act | (uintptr_t)g.out_act2 | (uintptr_t)g.aux) & 7) == 0);
   constexpr int SP = WTN + 4;                 // patch pitch in floats
-  constexpr int LPR = WTN / 4;                // lanes per row when reading back
-  constexpr int RPI = 64 / LPR;               // rows per read instruction
   static_assert(4 * 32 * SP * 4 <= 2 * (BM + BN) * BK * 2, "staging patches must fit the operand buffers");
   float *const patch = (float *)lds_all + wave * 32 * SP;
   // every wavefront has passed the last barrier of the K loop, so nobody reads the operand buffers any more
@@ -680,8 +678,6 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
                    ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
                    ((((uintptr_t)g.out_act | (uintptr_t)g.out_act2 | (uintptr_t)g.aux) & 7) == 0);
   constexpr int SP = WTN + 4;
-  constexpr int LPR = WTN / 4;
-  constexpr int RPI = 64 / LPR;
   static_assert(4 * 32 * SP * 4 <= S * STAGE * 2, "staging patches must fit the stages");
   float *const patch = (float *)lds_dyn + wave * 32 * SP;
 #pragma unroll

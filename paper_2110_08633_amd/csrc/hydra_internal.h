@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <map>
 #include <string>
 #include <vector>
 
@@ -121,6 +122,14 @@ struct hydra_ctx {
   hydra_stats stats;
   uint64_t use_counter = 0;
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
+  // captured block-shard visits (HYDRA_FLAG_GRAPHS); key: model, shard, phase, shard buffer, boundary-gradient parity
+  struct GraphEntry {
+    int seen = 0;  // visits run so far without a graph
+    bool failed = false;
+    hipGraphExec_t exec = nullptr;
+  };
+  std::map<uint64_t, GraphEntry> graphs;
+  uint64_t graph_launches = 0;
   std::string err;
 };
 

@@ -21,7 +21,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 OK, E_INVAL, E_NOSLOT, E_STATE, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
-FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY = 1, 2, 4, 8, 16
+FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS = 1, 2, 4, 8, 16, 32
 LOAD_PARAMS, LOAD_OPT = 1, 2
 SPILL_WRITEBACK, SPILL_EVICT = 1, 2
 RD_LOGITS, RD_GRADS, RD_PARAMS, RD_ADAM_M, RD_ADAM_V, RD_CKPT, RD_DBOUND = range(7)
@@ -60,7 +60,7 @@ class Stats(C.Structure):
                 ("n_load_hits", C.c_uint64), ("n_evictions", C.c_uint64), ("n_writebacks", C.c_uint64),
                 ("n_tasks", C.c_uint64), ("n_slots", C.c_int32), ("reserved", C.c_int32),
                 ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("model_state_bytes", C.c_uint64),
-                ("reserved_ms", C.c_double * 3)]
+                ("n_graph_launches", C.c_uint64), ("reserved_ms", C.c_double * 2)]
 
 
 _P = C.POINTER

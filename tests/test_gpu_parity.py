@@ -420,3 +420,51 @@ def test_tied_lm_head(rt, dtype, mode):
             after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
             check_weights(after, refs[i]["after"], refs[0]["before"], ill, 1e-4, i + 1, dtype, f"step {i}: ")
     sess.close()
+
+
+@pytest.mark.parametrize("max_slots,lanes,nm", [(0, 2, 1), (3, 1, 1), (4, 2, 2)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_graph_replay_of_shard_visits(rt, dtype, max_slots, lanes, nm):
+    """HYDRA_FLAG_GRAPHS: the kernel sequence of a block-shard visit is captured on its second run with a given
+    shard buffer and replayed afterwards.  Five minibatches of two models, so every combination is run plainly,
+    captured and replayed several times with the uncaptured work (loads, Adam, write-backs, head, embedding) and
+    stream synchronisations in between; weights and loss against the oracle after the last one, and the result
+    must be bit-identical to the same run without graphs.  With few buffers the shards move between buffers, which
+    gives one graph per (shard, buffer) pair."""
+    H, R = rt
+    base = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=2, lrs=[1e-4, 3e-4])
+    cfg = dict(base, n_micro=nm)
+    big = dict(base, B=base["B"] * nm)
+    n, steps = 2, 5
+    Ws = [SI.make_weights(base, 80 + m) for m in range(n)]
+    batches = [[SI.make_batch(big, 500 + 10 * m + i) for i in range(steps)] for m in range(n)]
+    fc, bc = SI.task_costs(base)
+    results = []
+    for flags in (H.FLAG_GRAPHS, 0):
+        sess = R.Session(R.arena_bytes_for([cfg] * n, 12, lanes=lanes), max_slots=max_slots, lanes=lanes, flags=flags)
+        recs = [sess.add_model(cfg, Ws[m], base["lrs"][m]) for m in range(n)]
+        sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [steps] * n, [list(fc) + list(bc)] * n)
+        toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
+        tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
+        H.hydra_sched_run(sch, toks, tgts, sess.ctx)
+        sess.flush()
+        st = H.hydra_get_stats(sess.ctx)
+        if flags:
+            assert st["n_graph_launches"] > 0
+        else:
+            assert st["n_graph_launches"] == 0
+        results.append(([sess.unpack(recs[m], recs[m]["master"].copy()) for m in range(n)],
+                        [H.hydra_get_loss(sess.ctx, recs[m]["id"]) for m in range(n)]))
+        H.hydra_sched_destroy(sch)
+        sess.close()
+    (wg, lg), (we, le) = results
+    assert lg == le
+    for m in range(n):
+        for name in wg[m]:
+            assert (wg[m][name] == we[m][name]).all(), name       # graphs change nothing
+        refs, P, _, _ = oracle_steps(big, Ws[m], base["lrs"][m], batches[m])
+        ill = {}
+        for r in refs:
+            update_ill(ill, r["grads"], dtype)
+        assert abs(lg[m] - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
+        check_weights(wg[m], P, refs[0]["before"], ill, base["lrs"][m], steps, dtype, f"model {m} ")
