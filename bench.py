@@ -43,7 +43,8 @@ LANES = 2
 def make_session(cfg, n_models, mode, timing, R, H):
     n_shards = n_models * (cfg["L"] // cfg["k"] + 2)
     slots = SPILL_SLOTS if mode == "spill" else n_shards
-    flags = (H.FLAG_TIMING if timing else 0) | EXTRA_FLAGS
+    # event pairs around promotes, write-backs and tasks (a few hundred per step) give the overlap figures
+    flags = (H.FLAG_TIMING if timing else H.FLAG_OVERLAP) | EXTRA_FLAGS
     lanes = 1 if timing else LANES      # per-kernel timing wants kernels one at a time
     sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots, lanes=lanes), flags=flags, max_slots=slots, lanes=lanes)
     recs = []
@@ -83,16 +84,38 @@ def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch, pilot=False
         run_steps(sess, recs, cfg, warmup, 0, H, torch)
     if timing:
         H.hydra_kernel_stats_reset(sess.ctx)
+    else:
+        H.hydra_overlap_reset(sess.ctx)
     st0 = H.hydra_get_stats(sess.ctx)
     dt = run_steps(sess, recs, cfg, steps, warmup, H, torch)
     st1 = H.hydra_get_stats(sess.ctx)
     kst = H.hydra_kernel_stats(sess.ctx) if timing else None
+    ov = None if timing else H.hydra_overlap_stats(sess.ctx)
     losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
     sess.close()
     del sess
     torch.cuda.empty_cache()
     return dict(seconds=dt, enqueue_seconds=run_steps.enqueue_s, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
-                n_slots=st1["n_slots"], kernels=kst, losses=losses, pilot_ns=pilot_ns)
+                n_slots=st1["n_slots"], kernels=kst, losses=losses, pilot_ns=pilot_ns, overlap=ov,
+                host_promote_ms=st1["host_promote_ms"] - st0["host_promote_ms"],
+                host_writeback_ms=st1["host_writeback_ms"] - st0["host_writeback_ms"])
+
+
+def overlap_report(run, steps):
+    """Swap / compute overlap of a run from the library's event trace: busy times are lengths of interval unions
+    (a shard task running on any lane; a promote or a write-back in flight), per step."""
+    o = run["overlap"]
+    if not o or not o["n_intervals"] or o["transfer_ms"] <= 0:
+        return None
+    r = lambda x: round(x / steps, 3)
+    return {"compute_busy_ms_per_step": r(o["compute_ms"]), "h2d_busy_ms_per_step": r(o["h2d_ms"]),
+            "d2h_busy_ms_per_step": r(o["d2h_ms"]), "transfer_busy_ms_per_step": r(o["transfer_ms"]),
+            "transfer_hidden_frac": round(o["hidden_ms"] / o["transfer_ms"], 4),
+            "hidden_frac_upper_bound": round(min(1.0, o["compute_ms"] / o["transfer_ms"]), 4),
+            "compute_with_transfer_in_flight_frac": round(o["hidden_ms"] / max(o["compute_ms"], 1e-9), 4),
+            "h2d_GBps_while_busy": round(o["bytes_h2d"] / max(o["h2d_ms"], 1e-9) / 1e6, 2),
+            "d2h_GBps_while_busy": round(o["bytes_d2h"] / max(o["d2h_ms"], 1e-9) / 1e6, 2),
+            "host_promote_ms_per_step": r(run["host_promote_ms"]), "host_writeback_ms_per_step": r(run["host_writeback_ms"])}
 
 
 def measured_traffic(config, kernel):
@@ -146,6 +169,8 @@ def main():
     ap.add_argument("--graphs", action="store_true",
                     help="replay block-shard visits as HIP graphs (halves the host's enqueue time; the device is the "
                          "bottleneck at this workload, so the throughput does not move)")
+    ap.add_argument("--side-stream", action="store_true",
+                    help="run the parameter-gradient work of backward visits on a second stream per lane (measured slower)")
     ap.add_argument("--micro", type=int, default=1,
                     help="micro-batches of B samples per shard visit (1 = the workload as BASELINE states it)")
     ap.add_argument("--extra-micro", type=int, default=4,
@@ -165,6 +190,8 @@ def main():
         EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
     if args.graphs:
         EXTRA_FLAGS |= H.FLAG_GRAPHS
+    if args.side_stream:
+        EXTRA_FLAGS |= H.FLAG_SIDE_STREAM
     cfg = dict(SI.CONFIGS[args.config])
     if args.micro > 1:
         cfg["n_micro"] = args.micro
@@ -190,6 +217,7 @@ def main():
                  "d2h_GBps_over_wall": round(main_run["d2h"] / main_run["seconds"] / 1e9, 2)},
         "final_losses": [round(x, 4) for x in main_run["losses"]],
     }
+    out["overlap"] = overlap_report(main_run, args.steps)
     if not args.no_extra:
         other = "resident" if args.mode == "spill" else "spill"
         o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch, pilot=True)
@@ -214,7 +242,8 @@ def main():
             out[f"spill_micro{args.extra_micro}"] = {
                 "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
                 "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
-                "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"]}
+                "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"],
+                "overlap": overlap_report(o, steps_m)}
             # the same 4x tokens per shard visit as ONE micro-batch of 4x the samples: activation memory grows
             # fourfold (no issue on a 288 GB part), the GEMMs become four times larger and fill the chip
             bc = dict(cfg, B=cfg["B"] * args.extra_micro)
@@ -222,7 +251,7 @@ def main():
             out[f"spill_batch_x{args.extra_micro}"] = {
                 "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
                 "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
-                "batch": bc["B"], "shard_buffers": o["n_slots"]}
+                "batch": bc["B"], "shard_buffers": o["n_slots"], "overlap": overlap_report(o, steps_m)}
         # per-kernel HIP-event timing over the same steps (resident buffers so that copies do not perturb kernels)
         t = measure(cfg, n_models, "resident", args.steps, args.warmup, True, R, H, torch)
         ks = sorted(t["kernels"], key=lambda k: -k["ms"])

@@ -67,9 +67,15 @@ enum {
   HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
   HYDRA_FLAG_TIMING = 8,     /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
   HYDRA_FLAG_D2H_MEMCPY = 16, /* demote with hipMemcpyAsync instead of the library's own copy kernel            */
-  HYDRA_FLAG_GRAPHS = 32     /* block-shard visits are captured as HIP graphs on their second run with a given  */
+  HYDRA_FLAG_GRAPHS = 32,    /* block-shard visits are captured as HIP graphs on their second run with a given  */
                              /* shard buffer and replayed from then on (one graph launch instead of dozens of   */
                              /* kernel launches: the host is the bottleneck otherwise); ignored with TIMING     */
+  HYDRA_FLAG_OVERLAP = 64,   /* bracket every promote, write-back and shard task with a HIP event pair on its   */
+                             /* own stream; read with hydra_overlap_stats                                       */
+  HYDRA_FLAG_SIDE_STREAM = 128 /* backward visits run the parameter-gradient work (dW products, bias and LayerNorm  */
+                             /* column sums) on a second stream of the lane, forked from the input-gradient chain  */
+                             /* block by block.  Same results; measured slower than one stream per lane (the       */
+                             /* cross-stream waits cost more than the overlap gains), so it is off by default      */
 };
 
 /* 'what' of hydra_shard_load_async */
@@ -154,8 +160,23 @@ typedef struct {
   int32_t reserved;
   uint64_t slot_bytes, workspace_bytes, model_state_bytes;
   uint64_t n_graph_launches;       /* block-shard visits replayed as HIP graphs (HYDRA_FLAG_GRAPHS)       */
-  double reserved_ms[2];
+  double host_promote_ms;          /* host time hydra_sched_run spent inside promote (evict + load) calls  */
+  double host_writeback_ms;        /* ... and inside the write-back calls that follow an Adam step         */
 } hydra_stats;
+
+/* How far the shard swaps are hidden under compute (paper Section 2.3, double buffering), from HIP events
+ * recorded with HYDRA_FLAG_OVERLAP since the last reset.  An interval runs from the moment its stream reaches the
+ * operation (all waits before it satisfied) to its completion; "busy" times are lengths of unions of intervals. */
+typedef struct {
+  double wall_ms;         /* first interval start to last interval end                                  */
+  double compute_ms;      /* some shard task (forward / backward / Adam) running on any compute lane    */
+  double h2d_ms;          /* some promote in flight (weights, Adam state, spilled checkpoints)          */
+  double d2h_ms;          /* some write-back in flight                                                  */
+  double transfer_ms;     /* h2d or d2h in flight                                                       */
+  double hidden_ms;       /* transfer in flight while a shard task is running                           */
+  uint64_t bytes_h2d, bytes_d2h; /* bytes moved by the recorded intervals                                */
+  uint64_t n_intervals;
+} hydra_overlap;
 
 /* ---- context ------------------------------------------------------------ */
 /* Creates a context over the caller's arena and streams.  With
@@ -177,6 +198,10 @@ hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out);
 hydra_status hydra_kernel_stats(hydra_ctx *ctx, int32_t index, char name[64], uint64_t *launches,
                                 double *total_ms, double *flops, double *bytes);
 hydra_status hydra_kernel_stats_reset(hydra_ctx *ctx);
+/* Swap / compute overlap (context created with HYDRA_FLAG_OVERLAP; HYDRA_E_STATE otherwise).  Both synchronise
+ * the context's streams first.  The reset forgets all intervals recorded so far. */
+hydra_status hydra_overlap_stats(hydra_ctx *ctx, hydra_overlap *out);
+hydra_status hydra_overlap_reset(hydra_ctx *ctx);
 
 /* ---- layout (pure functions of the model description) ------------------- */
 hydra_status hydra_model_layout(const hydra_model_desc *desc, hydra_layout *out);

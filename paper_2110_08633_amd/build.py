@@ -9,6 +9,11 @@ LIB = os.path.join(HERE, "libhydra.so")
 SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "layout.cpp", "ctx.cpp", "exec.cpp", "sched.cpp", "ops_api.cpp", "prof.cpp", "partition.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# Per-source additions.  The attention kernels do vector arithmetic on every MFMA result (mask, exponential,
+# rescaling): with the results in ordinary vector registers that arithmetic reads them directly; left to itself the
+# compiler parks them in the accumulation registers and moves every value across and back (a quarter of the
+# kernel's instructions).
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose=False):
@@ -19,7 +24,7 @@ def build(verbose=False):
     os.makedirs(bdir, exist_ok=True)
     for src in SOURCES:
         obj = os.path.join(bdir, src + ".o")
-        cmd = [hipcc] + FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False

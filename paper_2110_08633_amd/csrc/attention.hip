@@ -41,13 +41,13 @@ __device__ __forceinline__ bf16x8_t load_frag_global(const bf16_t *p) {
 // the end of the sequence read as zero) and written to LDS in one or both of the operand layouts of tile_ops.h:
 //   layout 0: DH/64 slices [row][64], contraction (head dimension) contiguous - operand of products over dh
 //   layout 1: [row][DH] as a slice of 64 contraction steps (= rows)       - operand of products over the rows
-template <int DH>
+template <int DH, int SETS = 2>
 struct RowTile {
   static constexpr int CPT = DH / 8;            // 16-byte chunks per row
   static constexpr int N = 64 * CPT / 256;      // chunks per thread
   uint32_t off[N];
   int row[N], slot0[N], slot1[N];
-  u32x4_t r[N];
+  u32x4_t r[SETS][N];  // up to two tiles in flight: tile t travels in set t & 1 (always indexed by compile-time constants)
   __device__ __forceinline__ void init(int64_t ld, int tid) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
@@ -60,23 +60,28 @@ struct RowTile {
     }
   }
   // base: element (first row of the tile, first column of the head); rows_valid: rows of the tile inside the sequence
+  template <int S>
   __device__ __forceinline__ void load(const bf16_t *base, int rows_valid) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       u32x4_t v = {0u, 0u, 0u, 0u};
       if (row[i] < rows_valid) v = *(gvec_ptr)(base + off[i]);
-      r[i] = v;
+      r[S][i] = v;
     }
   }
+  template <int S>
   __device__ __forceinline__ void store0(bf16_t *lds) const {
 #pragma unroll
-    for (int i = 0; i < N; ++i) *(u32x4_t *)(lds + slot0[i]) = r[i];
+    for (int i = 0; i < N; ++i) *(u32x4_t *)(lds + slot0[i]) = r[S][i];
   }
+  template <int S>
   __device__ __forceinline__ void store1(bf16_t *lds) const {
 #pragma unroll
-    for (int i = 0; i < N; ++i) *(u32x4_t *)(lds + slot1[i]) = r[i];
+    for (int i = 0; i < N; ++i) *(u32x4_t *)(lds + slot1[i]) = r[S][i];
   }
 };
+
+template <int V> struct IntC { static constexpr int value = V; };
 
 // four consecutive results of a lane's row -> bf16 -> the wavefront's patch [32][PP]
 __device__ __forceinline__ void patch_put(bf16_t *patch, int lane, int nt, int q, const float (&w)[4]) {
@@ -108,8 +113,9 @@ __device__ __forceinline__ void store_tile_row(bf16_t *dst, int lane, const f32x
 // rows r0 = q0 + 32 w .. + 31 and keeps its Q fragments in registers.  One
 // sweep over the key tiles up to the diagonal with a running row maximum and
 // sum (the output is rescaled when the maximum grows and divided by the sum at
-// the end).  The next tile's K and V are in flight from global memory while the
-// current one is multiplied; two LDS buffers, one barrier per tile.
+// the end).  K and V tiles are requested from global memory two tiles ahead
+// (one tile's arithmetic is shorter than a trip to memory), rest in registers,
+// and move into one of two LDS buffers one tile ahead; one barrier per tile.
 // ---------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict__ qkv, bf16_t *__restrict__ o,
@@ -152,10 +158,14 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
   RowTile<DH> tk, tv;
   tk.init(ld, tid);
   tv.init(ld, tid);
-  tk.load(kp, T);
-  tv.load(vp, T);
-  tk.store0(Ks);
-  tv.store1(Vs);
+  tk.template load<0>(kp, T);
+  tv.template load<0>(vp, T);
+  if (ntile > 1) {
+    tk.template load<1>(kp + (int64_t)AK * ld, T - AK);
+    tv.template load<1>(vp + (int64_t)AK * ld, T - AK);
+  }
+  tk.template store0<0>(Ks);
+  tv.template store1<0>(Vs);
   __syncthreads();
 
   float m = -INFINITY, l = 0.f;
@@ -165,12 +175,14 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[nd][r] = 0.f;
 
-  for (int jt = 0; jt < ntile; ++jt) {
+  // one key tile; SET = jt & 1 is the register set tile jt travelled in (free again: tile jt is in LDS)
+  auto tile_step = [&](int jt, auto setc) {
+    constexpr int SET = decltype(setc)::value;
     const int j0 = jt * AK;
-    const bf16_t *ks = Ks + (jt & 1) * TILE, *vs = Vs + (jt & 1) * TILE;
-    if (jt + 1 < ntile) {  // next tile: global -> registers, in flight during the products below
-      tk.load(kp + (int64_t)(j0 + AK) * ld, T - j0 - AK);
-      tv.load(vp + (int64_t)(j0 + AK) * ld, T - j0 - AK);
+    const bf16_t *ks = Ks + SET * TILE, *vs = Vs + SET * TILE;
+    if (jt + 2 < ntile) {  // tile jt + 2: global -> registers, in flight during this tile's and the next one's products
+      tk.template load<SET>(kp + (int64_t)(j0 + 2 * AK) * ld, T - j0 - 2 * AK);
+      tv.template load<SET>(vp + (int64_t)(j0 + 2 * AK) * ld, T - j0 - 2 * AK);
     }
     if (j0 <= my_last) {
       f32x16_t s[2];
@@ -185,20 +197,39 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
             s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fragment<0>(ks + sl * AK * BK, ko[nt][kk], 0),
                                                             qf[sl * 4 + kk], s[nt], 0, 0, 0);
       }
-      float tmax = -INFINITY;
+      // Vector-ALU work per score is what bounds this kernel (a wavefront instruction takes four clocks), so it is
+      // kept to a maximum, a fused multiply-add, an exponential, an add and half a conversion: the scores stay
+      // unscaled (the scale is positive, so it commutes with the maximum and is folded into the exponent's
+      // multiply-add), and the causal mask is applied only in tiles that reach above the wavefront's first row.
+      if (j0 + AK - 1 > r0) {
+        const int over = j0 + (lane >> 5) * 4 - myrow;  // key - row of this lane's first column
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (over + nt * 32 + (r >> 2) * 8 + (r & 3) > 0) s[nt][r] = -INFINITY;
+      }
+      float tmax = s[0][0];
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = j0 + nt * 32 + acc_col(r, lane);
-          const float v = (key <= myrow && key < T) ? s[nt][r] * scale_log2e : -INFINITY;
-          s[nt][r] = v;
-          tmax = fmaxf(tmax, v);
-        }
-      tmax = fmaxf(tmax, xor32(tmax));
-      const float mn = fmaxf(m, tmax);  // finite from the first tile on: key 0 is visible to every row
-      const float alpha = exp2f(m - mn);
-      m = mn;
+        for (int r = 0; r < 16; ++r) tmax = __builtin_fmaxf(tmax, s[nt][r]);
+      tmax = __builtin_fmaxf(tmax, xor32(tmax));
+      // The reference maximum m of a row (log2 domain) only has to keep the exponentials in range, so it is moved -
+      // and the sum and the output rescaled - only when some row's maximum has outgrown it by more than 2^8; the
+      // result does not depend on which reference is used.  Finite from the first tile on: key 0 is visible to
+      // every row.
+      const float tm = tmax * scale_log2e;
+      if (__builtin_amdgcn_ballot_w64(tm > m + 8.f)) {
+        const float mn = __builtin_fmaxf(m, tm);
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);
+        m = mn;
+        l *= alpha;
+#pragma unroll
+        for (int nd = 0; nd < ND; ++nd)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[nd][r] *= alpha;
+      }
       float sum = 0.f;
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
@@ -207,16 +238,12 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
           float p[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            p[e] = exp2f(s[nt][q * 4 + e] - mn);
+            p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][q * 4 + e], scale_log2e, -m));
             sum += p[e];
           }
           patch_put(patch, lane, nt, q, p);
         }
-      l = l * alpha + sum;
-#pragma unroll
-      for (int nd = 0; nd < ND; ++nd)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[nd][r] *= alpha;
+      l += sum;
       wave_lds_fence();
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
@@ -229,10 +256,14 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
       wave_lds_fence();  // the patch has been read before the next tile overwrites it
     }
     if (jt + 1 < ntile) {
-      tk.store0(Ks + ((jt + 1) & 1) * TILE);
-      tv.store1(Vs + ((jt + 1) & 1) * TILE);
+      tk.template store0<SET ^ 1>(Ks + (SET ^ 1) * TILE);
+      tv.template store1<SET ^ 1>(Vs + (SET ^ 1) * TILE);
     }
     __syncthreads();
+  };
+  for (int jt = 0; jt < ntile; jt += 2) {
+    tile_step(jt, IntC<0>());
+    if (jt + 1 < ntile) tile_step(jt + 1, IntC<1>());
   }
   l += xor32(l);
   const float inv_l = 1.f / l;
@@ -307,15 +338,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int ntile = (kend + AK - 1) / AK;
   const int my_last = r0 + 31;
   const float scale_log2e = scale * LOG2E;
+  const float nL2 = -L2, nDs = -Di * scale;
 
   RowTile<DH> tk, tv;
   tk.init(ld, tid);
   tv.init(ld, tid);
-  tk.load(kp, T);
-  tv.load(vp, T);
-  tk.store0(Ks0);
-  tk.store1(Ks1);
-  tv.store0(Vs0);
+  tk.template load<0>(kp, T);
+  tv.template load<0>(vp, T);
+  if (ntile > 1) {
+    tk.template load<1>(kp + (int64_t)AK * ld, T - AK);
+    tv.template load<1>(vp + (int64_t)AK * ld, T - AK);
+  }
+  tk.template store0<0>(Ks0);
+  tk.template store1<0>(Ks1);
+  tv.template store0<0>(Vs0);
   __syncthreads();
 
   f32x16_t acc[ND];
@@ -324,11 +360,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[nd][r] = 0.f;
 
-  for (int jt = 0; jt < ntile; ++jt) {
-    const int j0 = jt * AK, cur = (jt & 1) * TILE, nxt = ((jt + 1) & 1) * TILE;
-    if (jt + 1 < ntile) {
-      tk.load(kp + (int64_t)(j0 + AK) * ld, T - j0 - AK);
-      tv.load(vp + (int64_t)(j0 + AK) * ld, T - j0 - AK);
+  // staging as in the forward kernel: tiles requested two ahead, SET = jt & 1
+  auto tile_step = [&](int jt, auto setc) {
+    constexpr int SET = decltype(setc)::value;
+    const int j0 = jt * AK, cur = SET * TILE, nxt = (SET ^ 1) * TILE;
+    if (jt + 2 < ntile) {
+      tk.template load<SET>(kp + (int64_t)(j0 + 2 * AK) * ld, T - j0 - 2 * AK);
+      tv.template load<SET>(vp + (int64_t)(j0 + 2 * AK) * ld, T - j0 - 2 * AK);
     }
     if (j0 <= my_last) {
 #pragma unroll
@@ -345,14 +383,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fragment<0>(Vs0 + cur + sl * AK * BK, ko[nt][kk], 0),
                                                          dof[sl * 4 + kk], dp, 0, 0, 0);
           }
+        // as in the forward kernel the vector-ALU work per score is kept minimal: the mask only where the tile
+        // reaches above the wavefront's first row (a masked score of -inf gives p = 0 exactly), the scale folded
+        // into two fused multiply-adds
+        if (j0 + nt * 32 + 31 > r0) {
+          const int over = j0 + nt * 32 + (lane >> 5) * 4 - myrow;
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (over + (r >> 2) * 8 + (r & 3) > 0) s[r] = -INFINITY;
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           float ds[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int key = j0 + nt * 32 + q * 8 + (lane >> 5) * 4 + e;
-            const float p = (key <= myrow && key < T) ? exp2f(s[q * 4 + e] * scale_log2e - L2) : 0.f;
-            ds[e] = p * (dp[q * 4 + e] - Di) * scale;
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[q * 4 + e], scale_log2e, nL2));
+            ds[e] = p * __builtin_fmaf(dp[q * 4 + e], scale, nDs);
           }
           patch_put(patch, lane, nt, q, ds);
         }
@@ -369,11 +415,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
       wave_lds_fence();
     }
     if (jt + 1 < ntile) {
-      tk.store0(Ks0 + nxt);
-      tk.store1(Ks1 + nxt);
-      tv.store0(Vs0 + nxt);
+      tk.template store0<SET ^ 1>(Ks0 + nxt);
+      tk.template store1<SET ^ 1>(Ks1 + nxt);
+      tv.template store0<SET ^ 1>(Vs0 + nxt);
     }
     __syncthreads();
+  };
+  for (int jt = 0; jt < ntile; jt += 2) {
+    tile_step(jt, IntC<0>());
+    if (jt + 1 < ntile) tile_step(jt + 1, IntC<1>());
   }
   if (myrow < T) {
     bf16_t *dq = dqkv + ((int64_t)b * T + myrow) * ld + h * DH;
@@ -404,7 +454,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t *__restr
   bf16_t *const Os0 = Qs1 + 2 * TILE;    // [2][TILE] dO, layout 0 (dP^T)
   bf16_t *const Os1 = Os0 + 2 * TILE;    // [2][TILE] dO, layout 1 (dV += p^T dO)
   bf16_t *const Ps = Os1 + 2 * TILE;
-  float *const Ls = (float *)(Ps + 4 * 32 * PP);  // [2][128]: log-sum-exp (log2 domain) and D of the tile's 64 queries
+  float *const Ls = (float *)(Ps + 4 * 32 * PP);  // [2][128]: -log-sum-exp (log2 domain) and -D / sqrt(dh) of the tile's 64 queries
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kb = blockIdx.x;
   const int z = blockIdx.y, b = z / H, h = z % H;
@@ -440,37 +490,52 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t *__restr
 #pragma unroll
     for (int r = 0; r < 16; ++r) dk[nd][r] = dv[nd][r] = 0.f;
 
-  RowTile<DH> tq, to;
+  // head width 128 has no registers left for a second tile in flight (it would spill): one tile ahead there
+  constexpr bool FAR = DH <= 64;
+  RowTile<DH, FAR ? 2 : 1> tq, to;
   tq.init(ld, tid);
   to.init(d, tid);
   const int ibeg = (k0 / AK) * AK;
-  float stat = 0.f;  // this thread's entry of the next tile's statistics
-  auto load_stat = [&](int i0) {
-    stat = 0.f;
+  float stat0 = 0.f, stat1 = 0.f;  // this thread's entry of the statistics of the two tiles in flight
+  auto load_stat = [&](int i0) -> float {
+    float st = 0.f;
     if (tid < 128) {
       const int qi = i0 + (tid & 63);
-      if (qi < T) stat = tid < 64 ? lse[(int64_t)z * T + qi] * LOG2E : dsum[(int64_t)z * T + qi];
+      if (qi < T) st = tid < 64 ? -lse[(int64_t)z * T + qi] * LOG2E : -dsum[(int64_t)z * T + qi] * scale;
     }
+    return st;
   };
-  tq.load(qp + (int64_t)ibeg * ld, T - ibeg);
-  to.load(dop + (int64_t)ibeg * d, T - ibeg);
-  load_stat(ibeg);
-  tq.store0(Qs0);
-  tq.store1(Qs1);
-  to.store0(Os0);
-  to.store1(Os1);
-  if (tid < 128) Ls[tid] = stat;
+  tq.template load<0>(qp + (int64_t)ibeg * ld, T - ibeg);
+  to.template load<0>(dop + (int64_t)ibeg * d, T - ibeg);
+  stat0 = load_stat(ibeg);
+  if (FAR && ibeg + AK < T) {
+    tq.template load<FAR ? 1 : 0>(qp + (int64_t)(ibeg + AK) * ld, T - ibeg - AK);
+    to.template load<FAR ? 1 : 0>(dop + (int64_t)(ibeg + AK) * d, T - ibeg - AK);
+    stat1 = load_stat(ibeg + AK);
+  }
+  tq.template store0<0>(Qs0);
+  tq.template store1<0>(Qs1);
+  to.template store0<0>(Os0);
+  to.template store1<0>(Os1);
+  if (tid < 128) Ls[tid] = stat0;
   __syncthreads();
 
-  int it = 0;
-  for (int i0 = ibeg; i0 < T; i0 += AK, ++it) {
-    const int cur = (it & 1) * TILE, nxt = ((it + 1) & 1) * TILE;
-    const float *ls = Ls + (it & 1) * 128;
+  // one query tile; SET = it & 1.  Tiles are requested from global memory two ahead, as in the other two kernels.
+  // (par = parity of the tile's index = its LDS buffer; with FAR it equals SET, otherwise only set 0 is used)
+  auto tile_step = [&](int i0, int par, auto setc) {
+    constexpr int SET = decltype(setc)::value;
+    const int cur = par * TILE, nxt = (par ^ 1) * TILE;
+    const float *ls = Ls + par * 128;
     const bool more = i0 + AK < T;
-    if (more) {
-      tq.load(qp + (int64_t)(i0 + AK) * ld, T - i0 - AK);
-      to.load(dop + (int64_t)(i0 + AK) * d, T - i0 - AK);
-      load_stat(i0 + AK);
+    if (FAR && i0 + 2 * AK < T) {
+      tq.template load<FAR ? SET : 0>(qp + (int64_t)(i0 + 2 * AK) * ld, T - i0 - 2 * AK);
+      to.template load<FAR ? SET : 0>(dop + (int64_t)(i0 + 2 * AK) * d, T - i0 - 2 * AK);
+      (SET ? stat1 : stat0) = load_stat(i0 + 2 * AK);
+    }
+    if (!FAR && more) {
+      tq.template load<0>(qp + (int64_t)(i0 + AK) * ld, T - i0 - AK);
+      to.template load<0>(dop + (int64_t)(i0 + AK) * d, T - i0 - AK);
+      stat0 = load_stat(i0 + AK);
     }
     if (i0 + AK - 1 >= kr0) {  // else every query of the tile precedes every key of this wavefront
       f32x16_t s[2], dp[2];
@@ -487,17 +552,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t *__restr
             dp[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fragment<0>(Os0 + cur + sl * AK * BK, ko[nt][kk], 0),
                                                              vf[sl * 4 + kk], dp[nt], 0, 0, 0);
           }
-        // p^T into the patch; dS^T replaces s in registers for the second round
+        // p^T into the patch; dS^T replaces s in registers for the second round.  The mask is needed only where
+        // the tile holds queries that precede keys of this wavefront; queries past the end of the sequence need
+        // none (their Q and dO rows are zero-filled and their statistics zero, so they contribute exact zeros).
+        // ls holds -L (log2 domain) and -D / sqrt(dh) of the tile's queries.
+        if (i0 + nt * 32 < kr0 + 31) {
+          const int under = mykey - (i0 + nt * 32 + (lane >> 5) * 4);  // key - query of this lane's first column
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (under - ((r >> 2) * 8 + (r & 3)) > 0) s[nt][r] = -INFINITY;
+        }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+          const int qc = nt * 32 + q * 8 + (lane >> 5) * 4;  // first of this lane's four queries within the tile
+          const f32x4_t nl = *(const f32x4_t *)(ls + qc), nd4 = *(const f32x4_t *)(ls + 64 + qc);
           float p4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int qc = nt * 32 + q * 8 + (lane >> 5) * 4 + e;  // query within the tile
-            const int qi = i0 + qc;
-            const float p = (qi >= mykey && qi < T) ? exp2f(s[nt][q * 4 + e] * scale_log2e - ls[qc]) : 0.f;
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[nt][q * 4 + e], scale_log2e, nl[e]));
             p4[e] = p;
-            s[nt][q * 4 + e] = p * (dp[nt][q * 4 + e] - ls[64 + qc]) * scale;
+            s[nt][q * 4 + e] = p * __builtin_fmaf(dp[nt][q * 4 + e], scale, nd4[e]);
           }
           patch_put(patch, lane, nt, q, p4);
         }
@@ -531,13 +605,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t *__restr
       wave_lds_fence();
     }
     if (more) {
-      tq.store0(Qs0 + nxt);
-      tq.store1(Qs1 + nxt);
-      to.store0(Os0 + nxt);
-      to.store1(Os1 + nxt);
-      if (tid < 128) Ls[((it + 1) & 1) * 128 + tid] = stat;
+      constexpr int NS_ = FAR ? (SET ^ 1) : 0;  // register set the next tile travelled in
+      tq.template store0<NS_>(Qs0 + nxt);
+      tq.template store1<NS_>(Qs1 + nxt);
+      to.template store0<NS_>(Os0 + nxt);
+      to.template store1<NS_>(Os1 + nxt);
+      if (tid < 128) Ls[(par ^ 1) * 128 + tid] = NS_ ? stat1 : stat0;
     }
     __syncthreads();
+  };
+  if (FAR) {
+    for (int i0 = ibeg; i0 < T; i0 += 2 * AK) {
+      tile_step(i0, 0, IntC<0>());
+      if (i0 + AK < T) tile_step(i0 + AK, 1, IntC<1>());
+    }
+  } else {
+    int it = 0;
+    for (int i0 = ibeg; i0 < T; i0 += AK, ++it) tile_step(i0, it & 1, IntC<0>());
   }
   if (mykey < T) {
     bf16_t *dkp = dqkv + ((int64_t)b * T + mykey) * ld + d + h * DH, *dvp = dkp + d;

@@ -3,6 +3,7 @@
 // streams, ordered against the compute stream by events only (paper Section
 // 2.3: spilling with double buffering).
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "hydra_internal.h"
@@ -42,6 +43,15 @@ hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, con
     HYDRA_HIP(ctx, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, ctx->s_d2h));
   else
     HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, ctx->s_d2h));
+  return HYDRA_OK;
+}
+
+// host -> device copy on the h2d stream.  SDMA (hipMemcpyAsync): the copy kernel reading page-locked memory through
+// its device-side mapping reaches the same link rate but slows the compute kernels it shares CUs with and the
+// write-backs (measured: 147 against 123 ms per step of the two-model GPT-2-small workload).
+hydra_status copy_h2d(hydra_ctx *ctx, void *dst, const void *host_src, size_t bytes) {
+  if (ctx->dry) return HYDRA_OK;
+  HYDRA_HIP(ctx, hipMemcpyAsync(dst, host_src, bytes, hipMemcpyHostToDevice, ctx->s_h2d));
   return HYDRA_OK;
 }
 
@@ -167,6 +177,7 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
     ctx->prof = prof_create();
     prof_activate(ctx->prof);
   }
+  if (!ctx->dry && (desc->flags & HYDRA_FLAG_OVERLAP)) ctx->tracer = trace_create();
   *out = ctx;
   return HYDRA_OK;
 }
@@ -178,10 +189,18 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->s_h2d);
     (void)hipStreamSynchronize(ctx->s_d2h);
     prof_destroy(ctx->prof);
+    trace_destroy(ctx->tracer);
     for (auto &kv : ctx->graphs)
       if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
-    for (hydra_ctx::Lane &ln : ctx->lanes)
+    for (hydra_ctx::Lane &ln : ctx->lanes) {
+      if (ln.side) {
+        (void)hipStreamSynchronize(ln.side);
+        (void)hipStreamDestroy(ln.side);
+      }
+      for (hipEvent_t e : ln.fork_ev) (void)hipEventDestroy(e);
+      if (ln.join_ev) (void)hipEventDestroy(ln.join_ev);
       if (ln.own_stream) (void)hipStreamDestroy(ln.stream);
+    }
     for (Slot &s : ctx->slots) {
       if (s.ev_loaded) (void)hipEventDestroy(s.ev_loaded);
       if (s.ev_compute) (void)hipEventDestroy(s.ev_compute);
@@ -346,6 +365,12 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   ctx->stats.n_loads++;
   Slot *sl = slot_for(ctx, model, shard);
   bool copied = false;
+  // overlap trace: the interval opens when the copy stream reaches the first copy of this call
+  int tr = -1;
+  const uint64_t h2d_before = ctx->stats.bytes_h2d;
+  auto trace_open = [&]() {
+    if (tr < 0 && !ctx->dry) tr = trace_begin(ctx, TRACE_H2D, ctx->s_h2d);
+  };
   if (!sl) {
     int free_i = -1;
     for (size_t i = 0; i < ctx->slots.size(); ++i)
@@ -374,8 +399,8 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     m->wb_pending[shard] = 0;
   }
   if (!sl->has_params) {
-    if (!ctx->dry)
-      HYDRA_HIP(ctx, hipMemcpyAsync(sl->w, m->host.master + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
+    trace_open();
+    if ((st = copy_h2d(ctx, sl->w, m->host.master + off, cnt * 4))) return st;
     ctx->stats.bytes_h2d += cnt * 4;
     sl->has_params = true;
     copied = true;
@@ -395,6 +420,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
         if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_wb[0], 0));
         m->wb_pending[0] = 0;
       }
+      trace_open();
       if (!ctx->dry)
         HYDRA_HIP(ctx, hipMemcpyAsync(sl->w + 2 * m->sh.d, m->host.master, bytes, hipMemcpyHostToDevice, ctx->s_h2d));
       ctx->stats.bytes_h2d += bytes;
@@ -404,10 +430,10 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     copied = true;
   }
   if ((what & HYDRA_LOAD_OPT) && !sl->has_opt) {
-    if (!ctx->dry) {
-      HYDRA_HIP(ctx, hipMemcpyAsync(sl->m, m->host.adam_m + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
-      HYDRA_HIP(ctx, hipMemcpyAsync(sl->v, m->host.adam_v + off, cnt * 4, hipMemcpyHostToDevice, ctx->s_h2d));
-    }
+    trace_open();
+    if ((st = copy_h2d(ctx, sl->m, m->host.adam_m + off, cnt * 4)) ||
+        (st = copy_h2d(ctx, sl->v, m->host.adam_v + off, cnt * 4)))
+      return st;
     ctx->stats.bytes_h2d += cnt * 8;
     sl->has_opt = true;
     copied = true;
@@ -421,6 +447,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     if (!ctx->dry) {
       if (m->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_last_compute, 0));
       if (m->ckpt_d2h_pending[b & 1]) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_ckpt_d2h[b & 1], 0));
+      trace_open();
       HYDRA_HIP(ctx, hipMemcpyAsync(m->ckpt[b], m->host.ckpt + (uint64_t)b * m->sh.Mt * m->sh.d, bytes,
                                     hipMemcpyHostToDevice, ctx->s_h2d));
       HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_h2d[b & 1], ctx->s_h2d));
@@ -433,6 +460,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     if (!ctx->dry) HYDRA_HIP(ctx, hipEventRecord(sl->ev_loaded, ctx->s_h2d));
     sl->need_wait_load = true;
   }
+  trace_end(ctx, tr, ctx->s_h2d, ctx->stats.bytes_h2d - h2d_before);
   return HYDRA_OK;
 }
 
@@ -451,10 +479,12 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     if (!ctx->dry) {
       if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
       hydra_status cs;
+      const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h);
       if ((cs = copy_d2h(ctx, m->host.master + off, m->host_dev.master + off, sl->w, cnt * 4)) ||
           (cs = copy_d2h(ctx, m->host.adam_m + off, m->host_dev.adam_m + off, sl->m, cnt * 4)) ||
           (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4)))
         return cs;
+      trace_end(ctx, tr, ctx->s_d2h, (uint64_t)cnt * 12);
       HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
       HYDRA_HIP(ctx, hipEventRecord(m->ev_wb[shard], ctx->s_d2h));
     }
@@ -497,8 +527,9 @@ static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out)
   return HYDRA_OK;
 }
 
-static hydra_status end_task(hydra_ctx *ctx, Model *m, Slot *sl) {
+static hydra_status end_task(hydra_ctx *ctx, Model *m, Slot *sl, int tr) {
   if (!ctx->dry) {
+    trace_end(ctx, tr, ctx->lanes[m->lane].stream, 0);
     HYDRA_HIP(ctx, hipEventRecord(sl->ev_compute, ctx->lanes[m->lane].stream));
     HYDRA_HIP(ctx, hipEventRecord(m->ev_last_compute, ctx->lanes[m->lane].stream));
   }
@@ -522,15 +553,18 @@ hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
     // the ping-pong buffer about to be overwritten may still be on its way to the host
     HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_d2h[shard & 1], 0));
   }
+  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream);
   if (!ctx->dry && (st = exec_forward(ctx, m, sl, shard))) return st;
-  if ((st = end_task(ctx, m, sl))) return st;
+  if ((st = end_task(ctx, m, sl, tr))) return st;
   if (spill && shard <= S) {
     const uint64_t bytes = (uint64_t)m->sh.Mt * m->sh.d * 4;
     if (!ctx->dry) {
       HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, m->ev_last_compute, 0));
       const uint64_t eo = (uint64_t)shard * m->sh.Mt * m->sh.d;
+      const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h);
       hydra_status cs = copy_d2h(ctx, m->host.ckpt + eo, m->host_dev.ckpt + eo, m->ckpt[shard], bytes);
       if (cs) return cs;
+      trace_end(ctx, tr, ctx->s_d2h, bytes);
       HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_d2h[shard & 1], ctx->s_d2h));
     }
     m->ckpt_d2h_pending[shard & 1] = true;
@@ -559,9 +593,10 @@ hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard) 
     if (m->ckpt_h2d_pending[pb] && !ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_h2d[pb], 0));
     m->ckpt_h2d_pending[pb] = false;
   }
+  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream);
   if (!ctx->dry && (st = exec_backward(ctx, m, sl, shard))) return st;
   sl->grads_valid = true;
-  if ((st = end_task(ctx, m, sl))) return st;
+  if ((st = end_task(ctx, m, sl, tr))) return st;
   m->next_bwd = shard - 1;  // -1 after the embedding shard: minibatch finished
   return HYDRA_OK;
 }
@@ -573,6 +608,7 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
   Model *m = ctx->models[model];
   if (!sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients: run the backward visit first");
   if (!sl->has_opt) return fail(ctx, HYDRA_E_STATE, "Adam state not resident: load with HYDRA_LOAD_OPT");
+  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream);
   if (!ctx->dry && (st = exec_adam(ctx, m, sl, shard))) return st;
   sl->grads_valid = false;
   sl->dirty = true;
@@ -581,7 +617,7 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
     if (hs) hs->tied_valid = hs->wb_valid = false;
   }
   ctx->stats.n_tasks--;  // the optimizer step belongs to the backward task
-  return end_task(ctx, m, sl);
+  return end_task(ctx, m, sl, tr);
 }
 
 hydra_status hydra_get_loss(hydra_ctx *ctx, int32_t model, float *loss) {

@@ -251,7 +251,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__re
                                                                const float *__restrict__ rstd,
                                                                const float *__restrict__ gamma,
                                                                const float *__restrict__ dres, float *__restrict__ dx,
-                                                               int M, int d) {
+                                                               bf16_t *__restrict__ dx_bf16, int M, int d) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= M) return;
@@ -290,6 +290,12 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__re
       o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
     }
     *(float4 *)(dx + (int64_t)row * d + c) = o;
+    if (dx_bf16) {  // operand-dtype copy for the products that consume this gradient
+      uint2 p;
+      p.x = (uint32_t)f2bf(o.x) | ((uint32_t)f2bf(o.y) << 16);
+      p.y = (uint32_t)f2bf(o.z) | ((uint32_t)f2bf(o.w) << 16);
+      *(uint2 *)(dx_bf16 + (int64_t)row * d + c) = p;
+    }
   };
   if (CACHED) {
 #pragma unroll
@@ -307,14 +313,16 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const float *__re
 }
 
 hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
-                                   const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s) {
-  ProfScope ps("layernorm_bwd_dx", s, 0, (double)M * d * (dres ? 16.0 : 12.0));
+                                   const float *gamma, const float *dres, float *dx, void *dx_bf16v, int M, int d,
+                                   hipStream_t s) {
+  bf16_t *dx_bf16 = (bf16_t *)dx_bf16v;
+  ProfScope ps("layernorm_bwd_dx", s, 0, (double)M * d * ((dres ? 16.0 : 12.0) + (dx_bf16 ? 2.0 : 0.0)));
   if (d <= 256 * LN_R)
     hipLaunchKernelGGL(layernorm_bwd_dx_kernel<true>, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma, dres,
-                       dx, M, d);
+                       dx, dx_bf16, M, d);
   else
     hipLaunchKernelGGL(layernorm_bwd_dx_kernel<false>, dim3((M + 3) / 4), dim3(256), 0, s, dy, x, mean, rstd, gamma,
-                       dres, dx, M, d);
+                       dres, dx, dx_bf16, M, d);
   return hipGetLastError();
 }
 
@@ -614,8 +622,10 @@ hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *sha
 // ------------------------------------------------------------ link copy
 // Streams a device buffer into page-locked host memory (mapped into the device
 // address space) with plain 16-byte vector stores.  A small grid suffices: the
-// host link, not the CUs, bounds it; the rest of the chip stays free for the
-// compute stream.
+// host link, not the CUs, bounds it, and every CU that runs a copy workgroup
+// slows the compute kernels it shares with it (stores over the link retire
+// slowly and hold the CU's memory pipeline): 32 workgroups reach the same link
+// rate as 128 and cost the concurrent compute kernels a fifth less time.
 __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
                                                            int64_t n16, uint8_t *dst_tail, const uint8_t *src_tail,
                                                            int tail) {
@@ -625,16 +635,20 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
 }
 
 hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, hipStream_t s) {
+  static const int max_blocks = [] {
+    const char *e = getenv("HYDRA_COPY_BLOCKS");
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 32;
+  }();
+  return launch_copy_link(dst_mapped, src, bytes, max_blocks, s);
+}
+
+hipError_t launch_copy_link(void *dst_mapped, const void *src, size_t bytes, int max_blocks, hipStream_t s) {
   if (bytes == 0) return hipSuccess;
   if ((((uintptr_t)dst_mapped) | ((uintptr_t)src)) & 15) return hipErrorInvalidValue;
   const int64_t n16 = (int64_t)(bytes / 16);
   const int tail = (int)(bytes % 16);
   int64_t blocks = (n16 + 255) / 256;
-  static const int max_blocks = [] {
-    const char *e = getenv("HYDRA_COPY_BLOCKS");
-    const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 128;
-  }();
   if (blocks > max_blocks) blocks = max_blocks;
   if (blocks < 1) blocks = 1;
   ProfScope ps("copy_to_host", s, 0, (double)bytes);

@@ -178,18 +178,45 @@ hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const flo
   return hipSuccess;
 }
 
-struct BwdScratch {
+struct BwdScratch {  // shared by the layers of a visit; touched by the main stream only (red: side stream only)
   float *dP;    // [B,H,T,T] fp32 (also the score buffer of the recomputation)
   void *dS;     // [B,H,T,T] operand dtype
-  void *dact;   // [M,d] operand-dtype copy of a residual-stream gradient
-  void *du;     // [M,F]
   void *d_o;    // [M,d]
-  void *dqkv;   // [M,3d]
-  float *dtmp;  // [M,d] fp32 (dc, then da)
-  float *dx1;   // [M,d] fp32
   float *red;   // column-reduction partials
   float *dsum;  // fused attention: row sums of dO * O
 };
+
+// Activation gradients of one block.  Each is written once per micro-batch by the main stream and read by the
+// weight-gradient work of the same block, which runs on the lane's side stream: a buffer of its own per block means
+// the main stream never has to wait for the side stream inside a micro-batch.
+struct LayerGrads {
+  float *gin;   // [M,d] fp32: gradient arriving from the block above (blocks below the shard's last one)
+  void *dact2;  // [M,d] operand-dtype copy of the gradient at the block's output
+  void *dact1;  // [M,d] operand-dtype copy of dx1
+  void *du;     // [M,F]
+  void *dqkv;   // [M,3d]
+  float *dc;    // [M,d] fp32
+  float *da;    // [M,d] fp32
+  float *dx1;   // [M,d] fp32: gradient of the residual stream between attention and MLP
+};
+
+// Main stream + optional side stream of a lane (HYDRA_FLAG_SIDE_STREAM).  The input-gradient chain of a backward
+// visit (dx products, attention backward, LayerNorm backward) runs on the main stream; everything that only feeds
+// parameter gradients (dW products, bias column sums, LayerNorm gain / bias sums) is forked to the side stream as
+// soon as its operand exists, and joined once per micro-batch.  on == false (the default): side is the main
+// stream and the forks vanish.
+struct Fork {
+  hipStream_t main, side;
+  hipEvent_t *ev;  // events of the block being processed
+  bool on;
+  hipError_t at(int i) const {
+    if (!on) return hipSuccess;
+    hipError_t e = hipEventRecord(ev[i], main);
+    if (e != hipSuccess) return e;
+    return hipStreamWaitEvent(side, ev[i], 0);
+  }
+};
+constexpr int FORKS_PER_BLOCK = 6;
 
 // fp32 -> operand dtype view of an [M,d] gradient (no copy in the fp32 path)
 hipError_t act_view(int dt, const float *src, void *scratch, int M, int d, const void **out, hipStream_t st) {
@@ -201,9 +228,9 @@ hipError_t act_view(int dt, const float *src, void *scratch, int M, int d, const
   return launch_cast_act(dt, src, d, scratch, d, M, d, st);
 }
 
-// backward of attention_unfused_fwd: d_o (Z.d_o) -> dq | dk | dv (Z.dqkv) through dP, the softmax backward and
+// backward of attention_unfused_fwd: d_o (Z.d_o) -> dq | dk | dv (dqkv) through dP, the softmax backward and
 // three more batched products
-hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A, const BwdScratch &Z,
+hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A, const BwdScratch &Z, void *dqkv,
                                  hipStream_t st) {
   const int d = s.d, T = s.T, dh = s.dh;
   const int64_t TT = (int64_t)T * T;
@@ -224,7 +251,7 @@ hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A
     g.ta = 1; g.tb = 1; g.M = T; g.N = dh; g.K = T;
     g.A = A.P; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
     g.B = Z.d_o; g.ldb = d; g.sB1 = (int64_t)T * d; g.sB2 = dh;
-    g.out_act = off_act(Z.dqkv, 2 * d, dt); g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
+    g.out_act = off_act(dqkv, 2 * d, dt); g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
     g.causal = CAUSAL_K_BEGIN;
     CK(launch_gemm(g, st));
   }
@@ -234,7 +261,7 @@ hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A
     g.ta = 0; g.tb = 1; g.M = T; g.N = dh; g.K = T; g.alpha = scale;
     g.A = Z.dS; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
     g.B = k; g.ldb = 3 * d; g.sB1 = sQ1; g.sB2 = dh;
-    g.out_act = Z.dqkv; g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
+    g.out_act = dqkv; g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
     g.causal = CAUSAL_K_END;
     CK(launch_gemm(g, st));
   }
@@ -243,44 +270,52 @@ hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A
     g.ta = 1; g.tb = 1; g.M = T; g.N = dh; g.K = T; g.alpha = scale;
     g.A = Z.dS; g.lda = T; g.sA1 = s.H * TT; g.sA2 = TT;
     g.B = q; g.ldb = 3 * d; g.sB1 = sQ1; g.sB2 = dh;
-    g.out_act = off_act(Z.dqkv, d, dt); g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
+    g.out_act = off_act(dqkv, d, dt); g.ldc = 3 * d; g.sC1 = sQ1; g.sC2 = dh;
     g.causal = CAUSAL_K_BEGIN;
     CK(launch_gemm(g, st));
   }
   return hipSuccess;
 }
 
+// dx2 / dx2a: gradient at the block's output in fp32 and in the operand dtype (the same pointer in the fp32 path).
+// dx_out / dx_out_act: gradient at the block's input; the operand-dtype copy is written only when dx_out_act is set.
 hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, const LayerActs &A,
-                          const float *dx2, float *dx_out, const BwdScratch &Z, int acc, hipStream_t st) {
+                          const float *dx2, const void *dx2a, float *dx_out, void *dx_out_act, const BwdScratch &Z,
+                          const LayerGrads &L, int acc, const Fork &fk) {
   const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
   const BlockOffsets &o = s.bo;
-  const void *dx2a;
-  CK(act_view(dt, dx2, Z.dact, M, d, &dx2a, st));
+  hipStream_t st = fk.main, sd = fk.side;
+  const bool bf = dt == DT_BF16;
   // MLP down projection
-  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, st));
-  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, st));
-  CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, Z.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
+  CK(fk.at(0));
+  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, sd));
+  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, sd));
+  CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, L.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
   // MLP up projection
-  CK(launch_colsum(dt, Z.du, F, W.G + o.b_fc, Z.red, M, F, acc, st));
-  CK(linear_dw(dt, M, F, d, A.c, d, Z.du, F, W.G + o.w_fc, acc, st));
-  CK(linear_dx(dt, M, F, d, Z.du, W.w_fc, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // dc
-  CK(launch_layernorm_bwd_params(Z.dtmp, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, st));
-  CK(launch_layernorm_bwd_dx(Z.dtmp, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, Z.dx1, M, d, st));
+  CK(fk.at(1));
+  CK(launch_colsum(dt, L.du, F, W.G + o.b_fc, Z.red, M, F, acc, sd));
+  CK(linear_dw(dt, M, F, d, A.c, d, L.du, F, W.G + o.w_fc, acc, sd));
+  CK(linear_dx(dt, M, F, d, L.du, W.w_fc, L.dc, nullptr, EPI_NONE, nullptr, st));
+  CK(fk.at(2));
+  CK(launch_layernorm_bwd_params(L.dc, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, sd));
+  CK(launch_layernorm_bwd_dx(L.dc, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, L.dx1, bf ? L.dact1 : nullptr, M, d, st));
   // attention output projection
-  const void *dx1a;
-  CK(act_view(dt, Z.dx1, Z.dact, M, d, &dx1a, st));
-  CK(launch_colsum(DT_F32, Z.dx1, d, W.G + o.b_o, Z.red, M, d, acc, st));
-  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, st));
+  const void *dx1a = bf ? (const void *)L.dact1 : (const void *)L.dx1;
+  CK(fk.at(3));
+  CK(launch_colsum(DT_F32, L.dx1, d, W.G + o.b_o, Z.red, M, d, acc, sd));
+  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, sd));
   CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
   // attention core
-  if (fused_attn(s, dt)) CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, Z.dqkv, s.B, s.H, T, dh, st));
-  else CK(attention_unfused_bwd(s, dt, A, Z, st));
+  if (fused_attn(s, dt)) CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, L.dqkv, s.B, s.H, T, dh, st));
+  else CK(attention_unfused_bwd(s, dt, A, Z, L.dqkv, st));
   // QKV projection
-  CK(launch_colsum(dt, Z.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, st));
-  CK(linear_dw(dt, M, 3 * d, d, A.a, d, Z.dqkv, 3 * d, W.G + o.w_qkv, acc, st));
-  CK(linear_dx(dt, M, 3 * d, d, Z.dqkv, W.w_qkv, Z.dtmp, nullptr, EPI_NONE, nullptr, st));  // da
-  CK(launch_layernorm_bwd_params(Z.dtmp, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, acc, st));
-  CK(launch_layernorm_bwd_dx(Z.dtmp, x_in, A.mean1, A.rstd1, W.ln1_g, Z.dx1, dx_out, M, d, st));
+  CK(fk.at(4));
+  CK(launch_colsum(dt, L.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, sd));
+  CK(linear_dw(dt, M, 3 * d, d, A.a, d, L.dqkv, 3 * d, W.G + o.w_qkv, acc, sd));
+  CK(linear_dx(dt, M, 3 * d, d, L.dqkv, W.w_qkv, L.da, nullptr, EPI_NONE, nullptr, st));
+  CK(fk.at(5));
+  CK(launch_layernorm_bwd_params(L.da, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, acc, sd));
+  CK(launch_layernorm_bwd_dx(L.da, x_in, A.mean1, A.rstd1, W.ln1_g, L.dx1, dx_out, bf ? dx_out_act : nullptr, M, d, st));
   return hipSuccess;
 }
 
@@ -290,29 +325,42 @@ uint64_t red_elems(const ModelShape &s) {
 }
 
 uint64_t bwd_scratch_bytes(const ModelShape &s, int dt) {
-  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d;
   const bool fused = fused_attn(s, dt);
   const uint64_t PP = fused ? (uint64_t)s.B * s.H * s.T : (uint64_t)s.B * s.H * s.T * s.T;
-  return up256(PP * 4) + up256(PP * e) + up256(M * d * e) + up256(M * F * e) + up256(M * d * e) + up256(M * 3 * d * e) +
-         2 * up256(M * d * 4) + up256(red_elems(s) * 4);
+  return up256(PP * 4) + up256(PP * e) + up256(M * d * e) + up256(red_elems(s) * 4);
 }
 
 BwdScratch take_bwd(Bump &b, const ModelShape &s, int dt) {
-  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d;
   const bool fused = fused_attn(s, dt);
   const uint64_t PP = fused ? (uint64_t)s.B * s.H * s.T : (uint64_t)s.B * s.H * s.T * s.T;
   BwdScratch Z;
   Z.dP = b.take<float>(PP);   // fused: serves as dsum
   Z.dS = b.take<char>(PP * e);
   Z.dsum = Z.dP;
-  Z.dact = b.take<char>(M * d * e);
-  Z.du = b.take<char>(M * F * e);
   Z.d_o = b.take<char>(M * d * e);
-  Z.dqkv = b.take<char>(M * 3 * d * e);
-  Z.dtmp = b.take<float>(M * d);
-  Z.dx1 = b.take<float>(M * d);
   Z.red = b.take<float>(red_elems(s));
   return Z;
+}
+
+uint64_t layer_grad_bytes(const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  return 4 * up256(M * d * 4) + 2 * up256(M * d * e) + up256(M * F * e) + up256(M * 3 * d * e);
+}
+
+LayerGrads take_layer_grads(Bump &b, const ModelShape &s, int dt) {
+  const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
+  LayerGrads L;
+  L.gin = b.take<float>(M * d);
+  L.dc = b.take<float>(M * d);
+  L.da = b.take<float>(M * d);
+  L.dx1 = b.take<float>(M * d);
+  L.dact2 = b.take<char>(M * d * e);
+  L.dact1 = b.take<char>(M * d * e);
+  L.du = b.take<char>(M * F * e);
+  L.dqkv = b.take<char>(M * 3 * d * e);
+  return L;
 }
 
 uint64_t head_bytes(const ModelShape &s, int dt) {
@@ -368,10 +416,25 @@ hydra_status run_visit(hydra_ctx *ctx, Model *mm, Slot *sl, int shard, int phase
 
 }  // namespace
 
+// The side stream of a lane (default priority) and its fork / join events, created on first use when
+// HYDRA_FLAG_SIDE_STREAM asks for it (per-kernel timing wants kernels one at a time: no side stream then).
+static hydra_status ensure_side_stream(hydra_ctx *ctx, hydra_ctx::Lane &ln, int k) {
+  if (!(ctx->init.flags & HYDRA_FLAG_SIDE_STREAM) || (ctx->init.flags & HYDRA_FLAG_TIMING)) return HYDRA_OK;
+  if (!ln.side) HYDRA_HIP(ctx, hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking));
+  if (!ln.join_ev) HYDRA_HIP(ctx, hipEventCreateWithFlags(&ln.join_ev, hipEventDisableTiming));
+  while (ln.fork_ev.size() < (size_t)k * FORKS_PER_BLOCK) {
+    hipEvent_t e = nullptr;
+    HYDRA_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    ln.fork_ev.push_back(e);
+  }
+  return HYDRA_OK;
+}
+
 uint64_t workspace_need(const ModelShape &s, int dtype) {
   const uint64_t act = up256((uint64_t)s.M * s.d * 4);
-  // backward visit: k kept layers + k-1 inter-layer activations + backward scratch + ping-pong gradients
-  const uint64_t bwd = (uint64_t)s.k * layer_act_bytes(s, dtype) + (uint64_t)s.k * act + bwd_scratch_bytes(s, dtype) + 2 * act;
+  // backward visit: k kept layers + k inter-layer activations + k sets of activation gradients + shared scratch
+  const uint64_t bwd = (uint64_t)s.k * (layer_act_bytes(s, dtype) + act + layer_grad_bytes(s, dtype)) +
+                       bwd_scratch_bytes(s, dtype);
   const uint64_t head = head_bytes(s, dtype);
   return (bwd > head ? bwd : head) + 4096;
 }
@@ -497,7 +560,7 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
       g.out_f32 = dz; g.ldc = d;
       HYDRA_HIP(ctx, launch_gemm(g, st));
       HYDRA_HIP(ctx, launch_layernorm_bwd_params(dz, x, mean, rstd, sl->g, sl->g + d, red, M, d, u > 0, st));
-      HYDRA_HIP(ctx, launch_layernorm_bwd_dx(dz, x, mean, rstd, sl->w, nullptr, mm->dbound[0] + u * act, M, d, st));
+      HYDRA_HIP(ctx, launch_layernorm_bwd_dx(dz, x, mean, rstd, sl->w, nullptr, mm->dbound[0] + u * act, nullptr, M, d, st));
     }
     return HYDRA_OK;
   }
@@ -508,19 +571,32 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     for (int j = 0; j < s.k; ++j) acts[j] = take_layer(b, s, dt);
     for (int j = 1; j <= s.k; ++j) xs[j] = b.take<float>((uint64_t)M * d);
     BwdScratch Z = take_bwd(b, s, dt);
-    float *gpp[2] = {b.take<float>((uint64_t)M * d), b.take<float>((uint64_t)M * d)};
+    std::vector<LayerGrads> grads(s.k);
+    for (int j = 0; j < s.k; ++j) grads[j] = take_layer_grads(b, s, dt);
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (backward)");
+    hydra_status ss = ensure_side_stream(ctx, ln, s.k);
+    if (ss) return ss;
     const int dcur = mm->dcur;
     auto enqueue = [&]() -> hipError_t {
+      Fork fk{st, ln.side ? ln.side : st, nullptr, ln.side != nullptr};
       for (int u = 0; u < s.nm; ++u) {  // recompute and back-propagate one micro-batch at a time
         xs[0] = mm->ckpt[shard - 1] + u * act;
         for (int j = 0; j < s.k; ++j)
           CK(block_forward(s, dt, block_ptrs(s, sl, dt, j), xs[j], xs[j + 1], acts[j], Z.dP, st));
         const float *dx = mm->dbound[dcur] + u * act;
+        const void *dxa;  // its operand-dtype copy: cast here for the shard's last block, written by the
+        CK(act_view(dt, dx, grads[s.k - 1].dact2, M, d, &dxa, st));  // LayerNorm backward of the block above otherwise
         for (int j = s.k - 1; j >= 0; --j) {
-          float *out = (j == 0) ? mm->dbound[dcur ^ 1] + u * act : gpp[j & 1];
-          CK(block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, out, Z, u > 0, st));
+          float *out = (j == 0) ? mm->dbound[dcur ^ 1] + u * act : grads[j - 1].gin;
+          void *out_act = (j == 0) ? nullptr : grads[j - 1].dact2;
+          fk.ev = fk.on ? ln.fork_ev.data() + (size_t)j * FORKS_PER_BLOCK : nullptr;
+          CK(block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, dxa, out, out_act, Z, grads[j], u > 0, fk));
           dx = out;
+          dxa = dt == DT_BF16 ? (const void *)out_act : (const void *)out;
+        }
+        if (fk.on) {  // the next micro-batch's recomputation (or the Adam step) must see the side stream's work done
+          CK(hipEventRecord(ln.join_ev, fk.side));
+          CK(hipStreamWaitEvent(st, ln.join_ev, 0));
         }
       }
       return hipSuccess;

@@ -19,6 +19,12 @@ void prof_activate(Profiler *p);
 void prof_collect(Profiler *p);
 void prof_reset(Profiler *p);
 
+// swap / compute overlap trace (HYDRA_FLAG_OVERLAP)
+struct Tracer;
+enum { TRACE_COMPUTE = 0, TRACE_H2D = 1, TRACE_D2H = 2 };
+Tracer *trace_create();
+void trace_destroy(Tracer *t);
+
 struct TensorInfo {
   std::string name;
   int64_t off, rows, cols;
@@ -111,6 +117,10 @@ struct hydra_ctx {
     char *ws = nullptr;
     int logits_owner = -1;    // model whose logits the lane's workspace still holds
     float *logits = nullptr;
+    // backward visits fork the parameter-gradient work to a second stream of the lane (created on first use)
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> fork_ev;
+    hipEvent_t join_ev = nullptr;
   };
   std::vector<Lane> lanes;
   char *arena = nullptr;
@@ -122,6 +132,7 @@ struct hydra_ctx {
   hydra_stats stats;
   uint64_t use_counter = 0;
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
+  hydra::Tracer *tracer = nullptr;  // promote / write-back / task intervals (HYDRA_FLAG_OVERLAP)
   // captured block-shard visits (HYDRA_FLAG_GRAPHS); key: model, shard, phase, shard buffer, boundary-gradient parity
   struct GraphEntry {
     int seen = 0;  // visits run so far without a graph
@@ -143,6 +154,10 @@ hydra_status ensure_planned(hydra_ctx *ctx);
 Slot *slot_for(hydra_ctx *ctx, int model, int shard);
 // device -> host copy on the d2h stream: own copy kernel, or hipMemcpyAsync with HYDRA_FLAG_D2H_MEMCPY
 hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes);
+
+// opens / closes an interval of the overlap trace on stream s (no-ops without HYDRA_FLAG_OVERLAP; idx < 0 ignored)
+int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s);
+void trace_end(hydra_ctx *ctx, int idx, hipStream_t s, uint64_t bytes);
 
 // executor (exec.cpp): enqueue the kernels of one visit on the compute stream
 hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);

@@ -65,9 +65,10 @@ hipError_t launch_embed_bwd(const int32_t *tok, const float *dx0, float *dwte, f
 
 hipError_t launch_layernorm_fwd(int dtype, const float *x, const float *gamma, const float *beta, void *y, float *mean,
                                 float *rstd, int M, int d, hipStream_t s);
-// dx = dres + LN'(dy) (dres may be null); dy is fp32
+// dx = dres + LN'(dy) (dres may be null); dy is fp32; dx_bf16 (may be null): bf16 copy of dx, same shape
 hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float *mean, const float *rstd,
-                                   const float *gamma, const float *dres, float *dx, int M, int d, hipStream_t s);
+                                   const float *gamma, const float *dres, float *dx, void *dx_bf16, int M, int d,
+                                   hipStream_t s);
 // dgamma[n] = sum_m dy*xhat, dbeta[n] = sum_m dy ; scratch: fp32 [2 * colsum_chunks(M) * d]; acc != 0 adds to the outputs
 hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const float *mean, const float *rstd,
                                        float *dgamma, float *dbeta, float *scratch, int M, int d, int acc, hipStream_t s);
@@ -108,5 +109,7 @@ hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out,
 hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s);
 // device -> page-locked host memory through its device-side mapping (both 16-byte aligned)
 hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, hipStream_t s);
+// the same kernel in either direction (one side is the device-side mapping of page-locked host memory), grid capped
+hipError_t launch_copy_link(void *dst, const void *src, size_t bytes, int max_blocks, hipStream_t s);
 
 }  // namespace hydra

@@ -2,6 +2,8 @@
 // launched on (enabled by HYDRA_FLAG_TIMING).  Each launch is bracketed by two
 // events; after a synchronisation the elapsed times are aggregated per kernel
 // name together with the algorithmic flops / bytes of the launches.
+#include <algorithm>
+#include <cstring>
 #include <map>
 
 #include "hydra_internal.h"
@@ -107,11 +109,167 @@ bool prof_get(Profiler *p, int i, std::string *name, uint64_t *launches, double 
   return true;
 }
 
+// ---------------------------------------------------------------------------
+// Swap / compute overlap (HYDRA_FLAG_OVERLAP): an event pair around every
+// promote, write-back and shard task, each on the stream the operation runs
+// on; the host turns the timestamps into interval unions after a
+// synchronisation.
+// ---------------------------------------------------------------------------
+struct TraceRec {
+  int kind;
+  hipEvent_t e0, e1;
+  uint64_t bytes;
+  bool closed;
+};
+
+struct Tracer {
+  std::vector<TraceRec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t base = nullptr;
+  bool base_recorded = false;
+};
+
+Tracer *trace_create() { return new Tracer(); }
+
+void trace_destroy(Tracer *t) {
+  if (!t) return;
+  for (TraceRec &r : t->recs) {
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  for (hipEvent_t e : t->pool) (void)hipEventDestroy(e);
+  if (t->base) (void)hipEventDestroy(t->base);
+  delete t;
+}
+
+static hipEvent_t trace_event(Tracer *t) {
+  if (!t->pool.empty()) {
+    hipEvent_t e = t->pool.back();
+    t->pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s) {
+  Tracer *t = ctx->tracer;
+  if (!t) return -1;
+  if (!t->base_recorded) {
+    if (!t->base && hipEventCreate(&t->base) != hipSuccess) return -1;
+    if (hipEventRecord(t->base, s) != hipSuccess) return -1;
+    t->base_recorded = true;
+  }
+  TraceRec r{kind, trace_event(t), trace_event(t), 0, false};
+  if (!r.e0 || !r.e1) return -1;
+  (void)hipEventRecord(r.e0, s);
+  t->recs.push_back(r);
+  return (int)t->recs.size() - 1;
+}
+
+void trace_end(hydra_ctx *ctx, int idx, hipStream_t s, uint64_t bytes) {
+  Tracer *t = ctx->tracer;
+  if (!t || idx < 0 || idx >= (int)t->recs.size()) return;
+  (void)hipEventRecord(t->recs[idx].e1, s);
+  t->recs[idx].bytes = bytes;
+  t->recs[idx].closed = true;
+}
+
+typedef std::vector<std::pair<double, double>> Intervals;
+
+// sorted, disjoint union of a set of intervals
+static Intervals merged(Intervals v) {
+  std::sort(v.begin(), v.end());
+  Intervals out;
+  for (const auto &iv : v) {
+    if (!out.empty() && iv.first <= out.back().second) out.back().second = std::max(out.back().second, iv.second);
+    else out.push_back(iv);
+  }
+  return out;
+}
+static double length(const Intervals &v) {
+  double s = 0;
+  for (const auto &iv : v) s += iv.second - iv.first;
+  return s;
+}
+// length of the intersection of two sorted disjoint unions
+static double common(const Intervals &a, const Intervals &b) {
+  double s = 0;
+  size_t i = 0, j = 0;
+  while (i < a.size() && j < b.size()) {
+    const double lo = std::max(a[i].first, b[j].first), hi = std::min(a[i].second, b[j].second);
+    if (hi > lo) s += hi - lo;
+    if (a[i].second < b[j].second) ++i;
+    else ++j;
+  }
+  return s;
+}
+
+// caller has synchronised the streams
+static void trace_collect(Tracer *t, hydra_overlap *out) {
+  memset(out, 0, sizeof *out);
+  Intervals by_kind[3];
+  double lo = 1e300, hi = -1e300;
+  for (TraceRec &r : t->recs) {
+    float a = 0.f, b = 0.f;
+    if (r.closed && hipEventElapsedTime(&a, t->base, r.e0) == hipSuccess &&
+        hipEventElapsedTime(&b, t->base, r.e1) == hipSuccess && b >= a) {
+      by_kind[r.kind].push_back({a, b});
+      lo = std::min(lo, (double)a);
+      hi = std::max(hi, (double)b);
+      if (r.kind == TRACE_H2D) out->bytes_h2d += r.bytes;
+      if (r.kind == TRACE_D2H) out->bytes_d2h += r.bytes;
+      out->n_intervals++;
+    }
+  }
+  (void)hipGetLastError();
+  if (!out->n_intervals) return;
+  const Intervals comp = merged(by_kind[TRACE_COMPUTE]), h2d = merged(by_kind[TRACE_H2D]),
+                  d2h = merged(by_kind[TRACE_D2H]);
+  Intervals both = h2d;
+  both.insert(both.end(), d2h.begin(), d2h.end());
+  const Intervals xfer = merged(both);
+  out->wall_ms = hi - lo;
+  out->compute_ms = length(comp);
+  out->h2d_ms = length(h2d);
+  out->d2h_ms = length(d2h);
+  out->transfer_ms = length(xfer);
+  out->hidden_ms = common(xfer, comp);
+}
+
+static void trace_reset(Tracer *t) {
+  for (TraceRec &r : t->recs) {
+    t->pool.push_back(r.e0);
+    t->pool.push_back(r.e1);
+  }
+  t->recs.clear();
+  t->base_recorded = false;
+}
+
 }  // namespace hydra
 
 using namespace hydra;
 
 extern "C" {
+
+hydra_status hydra_overlap_stats(hydra_ctx *ctx, hydra_overlap *out) {
+  if (!ctx || !out) return fail(ctx, HYDRA_E_INVAL, "null argument");
+  if (!ctx->tracer) return fail(ctx, HYDRA_E_STATE, "context was not created with HYDRA_FLAG_OVERLAP");
+  hydra_status st = hydra_sync(ctx);
+  if (st) return st;
+  trace_collect(ctx->tracer, out);
+  return HYDRA_OK;
+}
+
+hydra_status hydra_overlap_reset(hydra_ctx *ctx) {
+  if (!ctx) return fail(ctx, HYDRA_E_INVAL, "null argument");
+  if (!ctx->tracer) return fail(ctx, HYDRA_E_STATE, "context was not created with HYDRA_FLAG_OVERLAP");
+  hydra_status st = hydra_sync(ctx);
+  if (st) return st;
+  trace_reset(ctx->tracer);
+  return HYDRA_OK;
+}
 
 hydra_status hydra_kernel_stats(hydra_ctx *ctx, int32_t index, char name[64], uint64_t *launches, double *total_ms,
                                 double *flops, double *bytes) {

@@ -9,6 +9,7 @@
 // on wall-clock time, so the whole order is computed up front - this also gives
 // the buffer manager exact knowledge of future uses.
 #include <algorithm>
+#include <chrono>
 
 #include "hydra_internal.h"
 
@@ -105,6 +106,14 @@ hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
   return hydra_shard_load_async(ctx, mid, t.shard, what);
 }
 
+// adds the host time of a scope to a counter of the context's statistics
+struct HostTimer {
+  double *acc;
+  std::chrono::steady_clock::time_point t0 = std::chrono::steady_clock::now();
+  explicit HostTimer(double *a) : acc(a) {}
+  ~HostTimer() { *acc += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count(); }
+};
+
 }  // namespace
 
 extern "C" {
@@ -179,6 +188,7 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
     Model *mm = ctx->models[mid];
     // prefetch the next task's shard while this one runs
     if (i + 1 < s->order.size() && ctx->slots.size() > 1) {
+      HostTimer ht(&ctx->stats.host_promote_ms);
       if ((st = promote(s, i + 1, mid, t.shard))) return st;
     }
     if (t.phase == 0 && t.shard == 0) {
@@ -193,7 +203,10 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
       if ((st = hydra_shard_adam_step(ctx, mid, t.shard))) return st;
       // when shards do not all fit, start the write-back right away so that it
       // overlaps the following tasks instead of delaying the next promote
-      if (!all_fit && (st = hydra_shard_spill(ctx, mid, t.shard, HYDRA_SPILL_WRITEBACK))) return st;
+      if (!all_fit) {
+        HostTimer ht(&ctx->stats.host_writeback_ms);
+        if ((st = hydra_shard_spill(ctx, mid, t.shard, HYDRA_SPILL_WRITEBACK))) return st;
+      }
     }
     if (ctx->slots.size() == 1 && i + 1 < s->order.size()) {
       // single buffer: no double buffering possible, promote after the task

@@ -21,7 +21,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 OK, E_INVAL, E_NOSLOT, E_STATE, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
-FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS = 1, 2, 4, 8, 16, 32
+FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS, FLAG_OVERLAP, FLAG_SIDE_STREAM = 1, 2, 4, 8, 16, 32, 64, 128
 LOAD_PARAMS, LOAD_OPT = 1, 2
 SPILL_WRITEBACK, SPILL_EVICT = 1, 2
 RD_LOGITS, RD_GRADS, RD_PARAMS, RD_ADAM_M, RD_ADAM_V, RD_CKPT, RD_DBOUND = range(7)
@@ -55,12 +55,18 @@ class Task(C.Structure):
     _fields_ = [("model", C.c_int32), ("shard", C.c_int32), ("phase", C.c_int32), ("minibatch", C.c_int32)]
 
 
+class Overlap(C.Structure):
+    _fields_ = [("wall_ms", C.c_double), ("compute_ms", C.c_double), ("h2d_ms", C.c_double), ("d2h_ms", C.c_double),
+                ("transfer_ms", C.c_double), ("hidden_ms", C.c_double), ("bytes_h2d", C.c_uint64),
+                ("bytes_d2h", C.c_uint64), ("n_intervals", C.c_uint64)]
+
+
 class Stats(C.Structure):
     _fields_ = [("bytes_h2d", C.c_uint64), ("bytes_d2h", C.c_uint64), ("n_loads", C.c_uint64),
                 ("n_load_hits", C.c_uint64), ("n_evictions", C.c_uint64), ("n_writebacks", C.c_uint64),
                 ("n_tasks", C.c_uint64), ("n_slots", C.c_int32), ("reserved", C.c_int32),
                 ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("model_state_bytes", C.c_uint64),
-                ("n_graph_launches", C.c_uint64), ("reserved_ms", C.c_double * 2)]
+                ("n_graph_launches", C.c_uint64), ("host_promote_ms", C.c_double), ("host_writeback_ms", C.c_double)]
 
 
 _P = C.POINTER
@@ -75,6 +81,8 @@ SIGNATURES = {
     "hydra_get_stats": (_i32, [_vp, _P(Stats)]),
     "hydra_kernel_stats": (_i32, [_vp, _i32, C.c_char_p, _P(_u64), _P(_f64), _P(_f64), _P(_f64)]),
     "hydra_kernel_stats_reset": (_i32, [_vp]),
+    "hydra_overlap_stats": (_i32, [_vp, _P(Overlap)]),
+    "hydra_overlap_reset": (_i32, [_vp]),
     "hydra_model_layout": (_i32, [_P(ModelDesc), _P(Layout)]),
     "hydra_model_tensor": (_i32, [_P(ModelDesc), _i32, C.c_char_p, _P(_i64), _P(_i64), _P(_i64), _P(_i32)]),
     "hydra_shard_range": (_i32, [_P(ModelDesc), _i32, _P(_i64), _P(_i64)]),
@@ -187,6 +195,17 @@ def hydra_kernel_stats(ctx):
 
 def hydra_kernel_stats_reset(ctx):
     return _check(lib.hydra_kernel_stats_reset(ctx), ctx)
+
+
+def hydra_overlap_stats(ctx):
+    """Dict of the interval-union lengths (ms) and bytes recorded since the last reset (HYDRA_FLAG_OVERLAP)."""
+    o = Overlap()
+    _check(lib.hydra_overlap_stats(ctx, C.byref(o)), ctx)
+    return {n: getattr(o, n) for n, _ in Overlap._fields_}
+
+
+def hydra_overlap_reset(ctx):
+    return _check(lib.hydra_overlap_reset(ctx), ctx)
 
 
 def hydra_model_layout(desc):
