@@ -36,6 +36,7 @@ HBM_PEAK_GBPS = 8000.0
 
 
 SPILL_SLOTS = 4
+TRACE_OVERLAP = True
 EXTRA_FLAGS = 0
 LANES = 2
 
@@ -44,7 +45,7 @@ def make_session(cfg, n_models, mode, timing, R, H):
     n_shards = n_models * (cfg["L"] // cfg["k"] + 2)
     slots = SPILL_SLOTS if mode == "spill" else n_shards
     # event pairs around promotes, write-backs and tasks (a few hundred per step) give the overlap figures
-    flags = (H.FLAG_TIMING if timing else H.FLAG_OVERLAP) | EXTRA_FLAGS
+    flags = (H.FLAG_TIMING if timing else (H.FLAG_OVERLAP if TRACE_OVERLAP and mode == "spill" else 0)) | EXTRA_FLAGS
     lanes = 1 if timing else LANES      # per-kernel timing wants kernels one at a time
     sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots, lanes=lanes), flags=flags, max_slots=slots, lanes=lanes)
     recs = []
@@ -53,6 +54,10 @@ def make_session(cfg, n_models, mode, timing, R, H):
         recs.append(sess.add_model(cfg, W, cfg["lrs"][m]))
         del W
     return sess, recs
+
+
+def flags_have_overlap(sess, H):
+    return bool(sess.flags & H.FLAG_OVERLAP)
 
 
 def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
@@ -84,13 +89,13 @@ def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch, pilot=False
         run_steps(sess, recs, cfg, warmup, 0, H, torch)
     if timing:
         H.hydra_kernel_stats_reset(sess.ctx)
-    else:
+    elif flags_have_overlap(sess, H):
         H.hydra_overlap_reset(sess.ctx)
     st0 = H.hydra_get_stats(sess.ctx)
     dt = run_steps(sess, recs, cfg, steps, warmup, H, torch)
     st1 = H.hydra_get_stats(sess.ctx)
     kst = H.hydra_kernel_stats(sess.ctx) if timing else None
-    ov = None if timing else H.hydra_overlap_stats(sess.ctx)
+    ov = H.hydra_overlap_stats(sess.ctx) if flags_have_overlap(sess, H) else None
     losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
     sess.close()
     del sess
@@ -169,14 +174,15 @@ def main():
     ap.add_argument("--graphs", action="store_true",
                     help="replay block-shard visits as HIP graphs (halves the host's enqueue time; the device is the "
                          "bottleneck at this workload, so the throughput does not move)")
-    ap.add_argument("--side-stream", action="store_true",
-                    help="run the parameter-gradient work of backward visits on a second stream per lane (measured slower)")
+    ap.add_argument("--no-overlap-trace", action="store_true",
+                    help="spill mode: do not record the event pairs behind the 'overlap' figures")
     ap.add_argument("--micro", type=int, default=1,
                     help="micro-batches of B samples per shard visit (1 = the workload as BASELINE states it)")
     ap.add_argument("--extra-micro", type=int, default=4,
                     help="also report spill-mode throughput with this many micro-batches per visit (0 = skip)")
     args = ap.parse_args()
-    global SPILL_SLOTS, EXTRA_FLAGS, LANES
+    global SPILL_SLOTS, EXTRA_FLAGS, LANES, TRACE_OVERLAP
+    TRACE_OVERLAP = not args.no_overlap_trace
     SPILL_SLOTS = args.slots
     LANES = args.lanes
     if args.gpus != 1:
@@ -190,8 +196,6 @@ def main():
         EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
     if args.graphs:
         EXTRA_FLAGS |= H.FLAG_GRAPHS
-    if args.side_stream:
-        EXTRA_FLAGS |= H.FLAG_SIDE_STREAM
     cfg = dict(SI.CONFIGS[args.config])
     if args.micro > 1:
         cfg["n_micro"] = args.micro
@@ -217,7 +221,8 @@ def main():
                  "d2h_GBps_over_wall": round(main_run["d2h"] / main_run["seconds"] / 1e9, 2)},
         "final_losses": [round(x, 4) for x in main_run["losses"]],
     }
-    out["overlap"] = overlap_report(main_run, args.steps)
+    if main_run["overlap"]:
+        out["overlap"] = overlap_report(main_run, args.steps)
     if not args.no_extra:
         other = "resident" if args.mode == "spill" else "spill"
         o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch, pilot=True)

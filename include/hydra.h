@@ -70,12 +70,8 @@ enum {
   HYDRA_FLAG_GRAPHS = 32,    /* block-shard visits are captured as HIP graphs on their second run with a given  */
                              /* shard buffer and replayed from then on (one graph launch instead of dozens of   */
                              /* kernel launches: the host is the bottleneck otherwise); ignored with TIMING     */
-  HYDRA_FLAG_OVERLAP = 64,   /* bracket every promote, write-back and shard task with a HIP event pair on its   */
+  HYDRA_FLAG_OVERLAP = 64    /* bracket every promote, write-back and shard task with a HIP event pair on its   */
                              /* own stream; read with hydra_overlap_stats                                       */
-  HYDRA_FLAG_SIDE_STREAM = 128 /* backward visits run the parameter-gradient work (dW products, bias and LayerNorm  */
-                             /* column sums) on a second stream of the lane, forked from the input-gradient chain  */
-                             /* block by block.  Same results; measured slower than one stream per lane (the       */
-                             /* cross-stream waits cost more than the overlap gains), so it is off by default      */
 };
 
 /* 'what' of hydra_shard_load_async */

@@ -192,15 +192,8 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
     trace_destroy(ctx->tracer);
     for (auto &kv : ctx->graphs)
       if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
-    for (hydra_ctx::Lane &ln : ctx->lanes) {
-      if (ln.side) {
-        (void)hipStreamSynchronize(ln.side);
-        (void)hipStreamDestroy(ln.side);
-      }
-      for (hipEvent_t e : ln.fork_ev) (void)hipEventDestroy(e);
-      if (ln.join_ev) (void)hipEventDestroy(ln.join_ev);
+    for (hydra_ctx::Lane &ln : ctx->lanes)
       if (ln.own_stream) (void)hipStreamDestroy(ln.stream);
-    }
     for (Slot &s : ctx->slots) {
       if (s.ev_loaded) (void)hipEventDestroy(s.ev_loaded);
       if (s.ev_compute) (void)hipEventDestroy(s.ev_compute);

@@ -421,6 +421,280 @@ hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const fl
   return hipGetLastError();
 }
 
+// ------------------------------------------- fused backward of a LayerNorm
+// One pass over the rows gives everything a LayerNorm's backward produces: dx
+// (fp32, optionally a bf16 copy) and, per block of LNB_ROWS rows, the partial
+// column sums of dy * xhat (-> dgamma), of dy (-> dbeta) and of dx (-> the bias
+// gradient of the linear layer whose output gradient dx is).  A wavefront walks
+// LNB_ROWS / 4 rows with its column partials in registers; the four
+// wavefronts of a block are added in a fixed order through LDS.  The partials
+// [gridDim.x][3][d] are summed by colsum_finish_kernel.  NR = float4 per lane
+// that cover a row (d <= 256 * NR).
+constexpr int LNB_ROWS = 8;
+int layernorm_bwd_fused_blocks(int M) { return (M + LNB_ROWS - 1) / LNB_ROWS; }
+bool layernorm_bwd_fused_supported(int d) { return d % 4 == 0 && d <= 256 * LN_R; }
+
+template <int NR>
+__global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(const float *__restrict__ dy, const float *__restrict__ x,
+                                                                  const float *__restrict__ mean,
+                                                                  const float *__restrict__ rstd,
+                                                                  const float *__restrict__ gamma,
+                                                                  const float *__restrict__ dres, float *__restrict__ dx,
+                                                                  bf16_t *__restrict__ dx_bf16, float *__restrict__ part,
+                                                                  int M, int d) {
+  __shared__ float red[3][NR * 256];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float4 gm[NR], ag[NR], ab[NR], ax[NR];
+#pragma unroll
+  for (int i = 0; i < NR; ++i) {
+    const int c = lane * 4 + i * 256;
+    gm[i] = c < d ? *(const float4 *)(gamma + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    ag[i] = ab[i] = ax[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  constexpr int RPW = LNB_ROWS / 4;
+#pragma unroll 1
+  for (int rr = 0; rr < RPW; ++rr) {
+    const int row = blockIdx.x * LNB_ROWS + rr * 4 + wave;  // ascending rows within a wavefront
+    if (row >= M) break;
+    const float *xr = x + (int64_t)row * d, *dyr = dy + (int64_t)row * d;
+    const float mu = mean[row], rs = rstd[row];
+    float4 xh[NR], g[NR], h[NR];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const int c = lane * 4 + i * 256;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      g[i] = v;
+      if (c < d) {
+        v = *(const float4 *)(xr + c);
+        g[i] = *(const float4 *)(dyr + c);
+      }
+      xh[i] = c < d ? make_float4((v.x - mu) * rs, (v.y - mu) * rs, (v.z - mu) * rs, (v.w - mu) * rs) : v;
+      h[i] = make_float4(g[i].x * gm[i].x, g[i].y * gm[i].y, g[i].z * gm[i].z, g[i].w * gm[i].w);
+      s1 += (h[i].x + h[i].y) + (h[i].z + h[i].w);
+      s2 += (h[i].x * xh[i].x + h[i].y * xh[i].y) + (h[i].z * xh[i].z + h[i].w * xh[i].w);
+    }
+    const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const int c = lane * 4 + i * 256;
+      if (c < d) {
+        float4 o;
+        o.x = rs * (h[i].x - m1 - xh[i].x * m2);
+        o.y = rs * (h[i].y - m1 - xh[i].y * m2);
+        o.z = rs * (h[i].z - m1 - xh[i].z * m2);
+        o.w = rs * (h[i].w - m1 - xh[i].w * m2);
+        if (dres) {
+          const float4 r = *(const float4 *)(dres + (int64_t)row * d + c);
+          o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
+        }
+        *(float4 *)(dx + (int64_t)row * d + c) = o;
+        if (dx_bf16) {
+          uint2 p;
+          p.x = (uint32_t)f2bf(o.x) | ((uint32_t)f2bf(o.y) << 16);
+          p.y = (uint32_t)f2bf(o.z) | ((uint32_t)f2bf(o.w) << 16);
+          *(uint2 *)(dx_bf16 + (int64_t)row * d + c) = p;
+        }
+        ag[i].x += g[i].x * xh[i].x; ag[i].y += g[i].y * xh[i].y; ag[i].z += g[i].z * xh[i].z; ag[i].w += g[i].w * xh[i].w;
+        ab[i].x += g[i].x; ab[i].y += g[i].y; ab[i].z += g[i].z; ab[i].w += g[i].w;
+        ax[i].x += o.x; ax[i].y += o.y; ax[i].z += o.z; ax[i].w += o.w;
+      }
+    }
+  }
+  // wavefronts 1..3 add to what wavefront 0 holds, one after the other (fixed order)
+  float *out = part + (int64_t)blockIdx.x * 3 * d;
+  for (int w = 1; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < NR; ++i) {
+        *(float4 *)&red[0][lane * 4 + i * 256] = ag[i];
+        *(float4 *)&red[1][lane * 4 + i * 256] = ab[i];
+        *(float4 *)&red[2][lane * 4 + i * 256] = ax[i];
+      }
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int i = 0; i < NR; ++i) {
+        const float4 a = *(const float4 *)&red[0][lane * 4 + i * 256], b = *(const float4 *)&red[1][lane * 4 + i * 256],
+                     c4 = *(const float4 *)&red[2][lane * 4 + i * 256];
+        ag[i].x += a.x; ag[i].y += a.y; ag[i].z += a.z; ag[i].w += a.w;
+        ab[i].x += b.x; ab[i].y += b.y; ab[i].z += b.z; ab[i].w += b.w;
+        ax[i].x += c4.x; ax[i].y += c4.y; ax[i].z += c4.z; ax[i].w += c4.w;
+      }
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      const int c = lane * 4 + i * 256;
+      if (c < d) {
+        *(float4 *)(out + c) = ag[i];
+        *(float4 *)(out + d + c) = ab[i];
+        *(float4 *)(out + 2 * d + c) = ax[i];
+      }
+    }
+  }
+}
+
+hipError_t launch_layernorm_bwd_fused(const float *dy, const float *x, const float *mean, const float *rstd,
+                                      const float *gamma, const float *dres, float *dx, void *dx_bf16, float *part, int M,
+                                      int d, hipStream_t s) {
+  if (!layernorm_bwd_fused_supported(d)) return hipErrorInvalidValue;
+  const int nr = (d + 255) / 256;
+  dim3 grid(layernorm_bwd_fused_blocks(M)), block(256);
+  ProfScope ps("layernorm_bwd", s, 0, (double)M * d * ((dres ? 16.0 : 12.0) + (dx_bf16 ? 2.0 : 0.0)) + 12.0 * grid.x * d);
+#define HYDRA_LNB(NR_)                                                                                                  \
+  hipLaunchKernelGGL(layernorm_bwd_fused_kernel<NR_>, grid, block, 0, s, dy, x, mean, rstd, gamma, dres, dx,             \
+                     (bf16_t *)dx_bf16, part, M, d)
+  if (nr <= 1) HYDRA_LNB(1);
+  else if (nr <= 2) HYDRA_LNB(2);
+  else if (nr <= 3) HYDRA_LNB(3);
+  else if (nr <= 4) HYDRA_LNB(4);
+  else if (nr <= 6) HYDRA_LNB(6);
+  else HYDRA_LNB(8);
+#undef HYDRA_LNB
+  return hipGetLastError();
+}
+
+// The third part of layernorm_bwd_fused_kernel's partial sums (column sums of dx over blocks of LNB_ROWS rows) for
+// a gradient that was not produced by that kernel (the one a shard receives at its upper boundary), added in the
+// same order - rows w and w + 4 per wavefront w, then the wavefronts in ascending order - so that the sum does not
+// depend on where the shard boundaries lie.
+__global__ __launch_bounds__(256) void colsum_rows8_kernel(const float *__restrict__ in, float *__restrict__ part, int M,
+                                                           int d) {
+  static_assert(LNB_ROWS == 8, "summation order below is written out for 8 rows");
+  const int r0 = blockIdx.x * LNB_ROWS;
+  float *out = part + (int64_t)blockIdx.x * 3 * d + 2 * d;
+  for (int c = threadIdx.x * 4; c < d; c += 1024) {
+    float4 w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {  // wavefront k of the fused kernel: rows r0 + k, r0 + k + 4
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        const int row = r0 + rr * 4 + k;
+        if (row < M) {
+          const float4 v = *(const float4 *)(in + (int64_t)row * d + c);
+          a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        }
+      }
+      w[k] = a;
+    }
+    float4 t = w[0];
+#pragma unroll
+    for (int k = 1; k < 4; ++k) { t.x += w[k].x; t.y += w[k].y; t.z += w[k].z; t.w += w[k].w; }
+    *(float4 *)(out + c) = t;
+  }
+}
+
+hipError_t launch_colsum_rows8(const float *in, float *part, int M, int d, hipStream_t s) {
+  if (d % 4) return hipErrorInvalidValue;
+  ProfScope ps("colsum", s, 0, 4.0 * M * d);
+  hipLaunchKernelGGL(colsum_rows8_kernel, dim3(layernorm_bwd_fused_blocks(M)), dim3(256), 0, s, in, part, M, d);
+  return hipGetLastError();
+}
+
+// Column sums of two operands of one dtype in one launch (pass 1 of launch_colsum for each): the block's x index
+// runs over the 64-column groups of the first operand, then over those of the second.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum2_pass1_kernel(const T *__restrict__ in0, int N0, float *__restrict__ part0,
+                                                            const T *__restrict__ in1, int N1, float *__restrict__ part1,
+                                                            int M) {
+  __shared__ double sh[4][64];
+  const int nb0 = (N0 + 63) / 64;
+  const bool second = (int)blockIdx.x >= nb0;
+  const T *in = second ? in1 : in0;
+  const int N = second ? N1 : N0;
+  float *part = second ? part1 : part0;
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int col = ((int)blockIdx.x - (second ? nb0 : 0)) * 64 + cx;
+  const int r0 = blockIdx.y * CH, r1 = min(M, r0 + CH);
+  double a = 0.0;
+  if (col < N) {
+    constexpr int U = 8;
+    for (int rb = r0 + ry; rb < r1; rb += 4 * U) {
+      float v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = rb + 4 * u;
+        v[u] = r < r1 ? ldv<T>(in, (int64_t)r * N + col) : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) a += v[u];
+    }
+  }
+  sh[ry][cx] = a;
+  __syncthreads();
+  if (ry == 0 && col < N) part[(int64_t)blockIdx.y * N + col] = (float)((sh[0][cx] + sh[1][cx]) + (sh[2][cx] + sh[3][cx]));
+}
+
+hipError_t launch_colsum2_pass1(int dtype, const void *in0, int N0, float *part0, const void *in1, int N1, float *part1,
+                                int M, hipStream_t s) {
+  dim3 grid((N0 + 63) / 64 + (N1 + 63) / 64, colsum_chunks(M));
+  ProfScope ps("colsum", s, 0, (double)M * (N0 + N1) * dt_size(dtype));
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(colsum2_pass1_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)in0, N0, part0,
+                       (const bf16_t *)in1, N1, part1, M);
+  else
+    hipLaunchKernelGGL(colsum2_pass1_kernel<float>, grid, dim3(256), 0, s, (const float *)in0, N0, part0,
+                       (const float *)in1, N1, part1, M);
+  return hipGetLastError();
+}
+
+// Last pass of several column sums in one launch: segment i adds its nch partial rows (stride elements apart) into
+// out[0..N) (added to what out holds when acc is set).  A block takes 32 columns of one segment with 8 row lanes:
+// lane r adds rows r, r + 8, ... in ascending order in double (eight loads in flight at a time), the eight lanes
+// are combined in a fixed tree.
+constexpr int FIN_COLS = 32, FIN_LANES = 8;
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const ColsumFinish a) {
+  __shared__ double sh[FIN_LANES][FIN_COLS];
+  const int cx = threadIdx.x % FIN_COLS, ry = threadIdx.x / FIN_COLS;
+  const int col = blockIdx.x * FIN_COLS + cx;
+  int i = 0;
+#pragma unroll 1
+  while (i + 1 < a.nseg && (int)blockIdx.x * FIN_COLS >= a.seg[i + 1].col0) ++i;  // uniform over the block
+  const ColsumSeg &g = a.seg[i];
+  const int c = col - g.col0;
+  double v = 0.0;
+  if (c < g.N) {
+    constexpr int U = 8;
+    for (int k0 = ry; k0 < g.nch; k0 += FIN_LANES * U) {
+      float w[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = k0 + u * FIN_LANES;
+        w[u] = k < g.nch ? g.part[(int64_t)k * g.stride + c] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) v += (double)w[u];
+    }
+  }
+  sh[ry][cx] = v;
+  __syncthreads();
+  if (ry == 0 && c < g.N) {
+    const double t = ((sh[0][cx] + sh[1][cx]) + (sh[2][cx] + sh[3][cx])) + ((sh[4][cx] + sh[5][cx]) + (sh[6][cx] + sh[7][cx]));
+    g.out[c] = (float)(a.acc ? (double)g.out[c] + t : t);
+  }
+}
+
+hipError_t launch_colsum_finish(ColsumFinish &a, hipStream_t s) {
+  if (a.nseg <= 0) return hipSuccess;
+  if (a.nseg > COLSUM_MAX_SEGS) return hipErrorInvalidValue;
+  // segments start at multiples of the block's column count so that a block never straddles two of them
+  int col = 0;
+  double bytes = 0;
+  for (int i = 0; i < a.nseg; ++i) {
+    a.seg[i].col0 = col;
+    col += (a.seg[i].N + FIN_COLS - 1) / FIN_COLS * FIN_COLS;
+    bytes += 4.0 * a.seg[i].N * a.seg[i].nch;
+  }
+  ProfScope ps("colsum_finish", s, 0, bytes);
+  hipLaunchKernelGGL(colsum_finish_kernel, dim3(col / FIN_COLS), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ softmax
 // One wavefront per row i of one [T,T] score matrix; only j <= i is read.
 // Entries i < j < min(T, roundup(i+1, 256)) are written as exact zeros so that

@@ -39,6 +39,14 @@ struct LayerActs {  // what the backward visit keeps of one block's forward
 // the softmax as separate kernels with the T x T matrices in the workspace
 inline bool fused_attn(const ModelShape &s, int dt) { return attention_fused_supported(dt, s.dh); }
 
+hipError_t launch_colsum_finish_one(const float *part, int64_t stride, int nch, int N, float *out, int acc,
+                                    hipStream_t st) {
+  ColsumFinish f;
+  f.acc = acc;
+  f.add(part, stride, nch, N, out);
+  return launch_colsum_finish(f, st);
+}
+
 struct BlockW {  // pointers into a shard buffer for one block
   const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc, *b_proj;
   const void *w_qkv, *w_o, *w_fc, *w_proj;  // operand dtype (bf16 working copy, or the fp32 master itself)
@@ -178,7 +186,7 @@ hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const flo
   return hipSuccess;
 }
 
-struct BwdScratch {  // shared by the layers of a visit; touched by the main stream only (red: side stream only)
+struct BwdScratch {  // shared by the layers of a visit
   float *dP;    // [B,H,T,T] fp32 (also the score buffer of the recomputation)
   void *dS;     // [B,H,T,T] operand dtype
   void *d_o;    // [M,d]
@@ -186,37 +194,23 @@ struct BwdScratch {  // shared by the layers of a visit; touched by the main str
   float *dsum;  // fused attention: row sums of dO * O
 };
 
-// Activation gradients of one block.  Each is written once per micro-batch by the main stream and read by the
-// weight-gradient work of the same block, which runs on the lane's side stream: a buffer of its own per block means
-// the main stream never has to wait for the side stream inside a micro-batch.
+// Activation gradients of one block, each written once per micro-batch, and the partial column sums behind the
+// block's bias and LayerNorm gradients.  A set per block: the weight-gradient work of a block may then be placed
+// anywhere after its operands exist (the sums of a block are finished by one launch at its end).
 struct LayerGrads {
-  float *gin;   // [M,d] fp32: gradient arriving from the block above (blocks below the shard's last one)
-  void *dact2;  // [M,d] operand-dtype copy of the gradient at the block's output
-  void *dact1;  // [M,d] operand-dtype copy of dx1
-  void *du;     // [M,F]
-  void *dqkv;   // [M,3d]
-  float *dc;    // [M,d] fp32
-  float *da;    // [M,d] fp32
-  float *dx1;   // [M,d] fp32: gradient of the residual stream between attention and MLP
+  float *gin;    // [M,d] fp32: gradient arriving from the block above (blocks below the shard's last one)
+  void *dact2;   // [M,d] operand-dtype copy of the gradient at the block's output
+  void *dact1;   // [M,d] operand-dtype copy of dx1
+  void *du;      // [M,F]
+  void *dqkv;    // [M,3d]
+  float *dc;     // [M,d] fp32
+  float *da;     // [M,d] fp32
+  float *dx1;    // [M,d] fp32: gradient of the residual stream between attention and MLP
+  float *part1;  // [blocks][3][d]: partial sums of the first LayerNorm's backward (dgamma, dbeta, sum of dx)
+  float *part2;  // the same for the second LayerNorm
+  float *pdu;    // [chunks][F] partial column sums of du
+  float *pdqkv;  // [chunks][3d] partial column sums of dqkv
 };
-
-// Main stream + optional side stream of a lane (HYDRA_FLAG_SIDE_STREAM).  The input-gradient chain of a backward
-// visit (dx products, attention backward, LayerNorm backward) runs on the main stream; everything that only feeds
-// parameter gradients (dW products, bias column sums, LayerNorm gain / bias sums) is forked to the side stream as
-// soon as its operand exists, and joined once per micro-batch.  on == false (the default): side is the main
-// stream and the forks vanish.
-struct Fork {
-  hipStream_t main, side;
-  hipEvent_t *ev;  // events of the block being processed
-  bool on;
-  hipError_t at(int i) const {
-    if (!on) return hipSuccess;
-    hipError_t e = hipEventRecord(ev[i], main);
-    if (e != hipSuccess) return e;
-    return hipStreamWaitEvent(side, ev[i], 0);
-  }
-};
-constexpr int FORKS_PER_BLOCK = 6;
 
 // fp32 -> operand dtype view of an [M,d] gradient (no copy in the fp32 path)
 hipError_t act_view(int dt, const float *src, void *scratch, int M, int d, const void **out, hipStream_t st) {
@@ -278,44 +272,73 @@ hipError_t attention_unfused_bwd(const ModelShape &s, int dt, const LayerActs &A
 }
 
 // dx2 / dx2a: gradient at the block's output in fp32 and in the operand dtype (the same pointer in the fp32 path).
+// dx2_part: partial sums [blocks][3][d] of the LayerNorm backward that produced dx2 (its third part sums dx2 over
+// the rows = the gradient of b_proj), or null when dx2 came from elsewhere.
 // dx_out / dx_out_act: gradient at the block's input; the operand-dtype copy is written only when dx_out_act is set.
+// The gradients of the biases and of the LayerNorm parameters are column sums over the tokens; where the row fits
+// the fused LayerNorm backward, its partial sums and those of one two-operand pass over du and dqkv are finished
+// by a single launch at the end of the block (2 launches instead of 12).
 hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const float *x_in, const LayerActs &A,
-                          const float *dx2, const void *dx2a, float *dx_out, void *dx_out_act, const BwdScratch &Z,
-                          const LayerGrads &L, int acc, const Fork &fk) {
+                          const float *dx2, const void *dx2a, const float *dx2_part, float *dx_out, void *dx_out_act,
+                          const BwdScratch &Z, const LayerGrads &L, int acc, hipStream_t st) {
   const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
   const BlockOffsets &o = s.bo;
-  hipStream_t st = fk.main, sd = fk.side;
   const bool bf = dt == DT_BF16;
+  const bool fl = layernorm_bwd_fused_supported(d);
+  const int nb = layernorm_bwd_fused_blocks(M), nch = colsum_chunks(M);
+  ColsumFinish fin;
+  fin.acc = acc;
   // MLP down projection
-  CK(fk.at(0));
-  CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, sd));
-  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, sd));
+  if (fl) {
+    if (!dx2_part) {  // the gradient came in over the shard boundary: sum it the way the LayerNorm backward would have
+      CK(launch_colsum_rows8(dx2, L.part2, M, d, st));  // (part2 is rewritten by this block's second LayerNorm later)
+      CK(launch_colsum_finish_one(L.part2 + 2 * d, 3 * (int64_t)d, nb, d, W.G + o.b_proj, acc, st));
+    } else {
+      fin.add(dx2_part + 2 * d, 3 * (int64_t)d, nb, d, W.G + o.b_proj);
+    }
+  } else {
+    CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, st));
+  }
+  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, st));
   CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, L.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
   // MLP up projection
-  CK(fk.at(1));
-  CK(launch_colsum(dt, L.du, F, W.G + o.b_fc, Z.red, M, F, acc, sd));
-  CK(linear_dw(dt, M, F, d, A.c, d, L.du, F, W.G + o.w_fc, acc, sd));
+  CK(linear_dw(dt, M, F, d, A.c, d, L.du, F, W.G + o.w_fc, acc, st));
   CK(linear_dx(dt, M, F, d, L.du, W.w_fc, L.dc, nullptr, EPI_NONE, nullptr, st));
-  CK(fk.at(2));
-  CK(launch_layernorm_bwd_params(L.dc, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, sd));
-  CK(launch_layernorm_bwd_dx(L.dc, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, L.dx1, bf ? L.dact1 : nullptr, M, d, st));
+  if (fl) {
+    CK(launch_layernorm_bwd_fused(L.dc, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, L.dx1, bf ? L.dact1 : nullptr, L.part2, M, d, st));
+    fin.add(L.part2, 3 * (int64_t)d, nb, d, W.G + o.ln2_g);
+    fin.add(L.part2 + d, 3 * (int64_t)d, nb, d, W.G + o.ln2_b);
+    fin.add(L.part2 + 2 * d, 3 * (int64_t)d, nb, d, W.G + o.b_o);
+  } else {
+    CK(launch_layernorm_bwd_params(L.dc, A.x1, A.mean2, A.rstd2, W.G + o.ln2_g, W.G + o.ln2_b, Z.red, M, d, acc, st));
+    CK(launch_layernorm_bwd_dx(L.dc, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, L.dx1, bf ? L.dact1 : nullptr, M, d, st));
+    CK(launch_colsum(DT_F32, L.dx1, d, W.G + o.b_o, Z.red, M, d, acc, st));
+  }
   // attention output projection
   const void *dx1a = bf ? (const void *)L.dact1 : (const void *)L.dx1;
-  CK(fk.at(3));
-  CK(launch_colsum(DT_F32, L.dx1, d, W.G + o.b_o, Z.red, M, d, acc, sd));
-  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, sd));
+  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, st));
   CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
   // attention core
   if (fused_attn(s, dt)) CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, L.dqkv, s.B, s.H, T, dh, st));
   else CK(attention_unfused_bwd(s, dt, A, Z, L.dqkv, st));
   // QKV projection
-  CK(fk.at(4));
-  CK(launch_colsum(dt, L.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, sd));
-  CK(linear_dw(dt, M, 3 * d, d, A.a, d, L.dqkv, 3 * d, W.G + o.w_qkv, acc, sd));
+  CK(linear_dw(dt, M, 3 * d, d, A.a, d, L.dqkv, 3 * d, W.G + o.w_qkv, acc, st));
   CK(linear_dx(dt, M, 3 * d, d, L.dqkv, W.w_qkv, L.da, nullptr, EPI_NONE, nullptr, st));
-  CK(fk.at(5));
-  CK(launch_layernorm_bwd_params(L.da, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, acc, sd));
-  CK(launch_layernorm_bwd_dx(L.da, x_in, A.mean1, A.rstd1, W.ln1_g, L.dx1, dx_out, bf ? dx_out_act : nullptr, M, d, st));
+  if (fl) {
+    CK(launch_layernorm_bwd_fused(L.da, x_in, A.mean1, A.rstd1, W.ln1_g, L.dx1, dx_out, bf ? dx_out_act : nullptr, L.part1, M, d, st));
+    fin.add(L.part1, 3 * (int64_t)d, nb, d, W.G + o.ln1_g);
+    fin.add(L.part1 + d, 3 * (int64_t)d, nb, d, W.G + o.ln1_b);
+    // bias gradients of the two wide linears: one pass over du and dqkv, then every sum of the block in one launch
+    CK(launch_colsum2_pass1(dt, L.du, F, L.pdu, L.dqkv, 3 * d, L.pdqkv, M, st));
+    fin.add(L.pdu, F, nch, F, W.G + o.b_fc);
+    fin.add(L.pdqkv, 3 * (int64_t)d, nch, 3 * d, W.G + o.b_qkv);
+    CK(launch_colsum_finish(fin, st));
+  } else {
+    CK(launch_layernorm_bwd_params(L.da, x_in, A.mean1, A.rstd1, W.G + o.ln1_g, W.G + o.ln1_b, Z.red, M, d, acc, st));
+    CK(launch_layernorm_bwd_dx(L.da, x_in, A.mean1, A.rstd1, W.ln1_g, L.dx1, dx_out, bf ? dx_out_act : nullptr, M, d, st));
+    CK(launch_colsum(dt, L.du, F, W.G + o.b_fc, Z.red, M, F, acc, st));
+    CK(launch_colsum(dt, L.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, st));
+  }
   return hipSuccess;
 }
 
@@ -346,7 +369,9 @@ BwdScratch take_bwd(Bump &b, const ModelShape &s, int dt) {
 
 uint64_t layer_grad_bytes(const ModelShape &s, int dt) {
   const uint64_t e = dt_size(dt), M = s.M, d = s.d, F = s.F;
-  return 4 * up256(M * d * 4) + 2 * up256(M * d * e) + up256(M * F * e) + up256(M * 3 * d * e);
+  const uint64_t nb = layernorm_bwd_fused_blocks((int)s.M), nch = colsum_chunks((int)s.M);
+  return 4 * up256(M * d * 4) + 2 * up256(M * d * e) + up256(M * F * e) + up256(M * 3 * d * e) +
+         2 * up256(nb * 3 * d * 4) + up256(nch * F * 4) + up256(nch * 3 * d * 4);
 }
 
 LayerGrads take_layer_grads(Bump &b, const ModelShape &s, int dt) {
@@ -360,6 +385,11 @@ LayerGrads take_layer_grads(Bump &b, const ModelShape &s, int dt) {
   L.dact1 = b.take<char>(M * d * e);
   L.du = b.take<char>(M * F * e);
   L.dqkv = b.take<char>(M * 3 * d * e);
+  const uint64_t nb = layernorm_bwd_fused_blocks((int)s.M), nch = colsum_chunks((int)s.M);
+  L.part1 = b.take<float>(nb * 3 * d);
+  L.part2 = b.take<float>(nb * 3 * d);
+  L.pdu = b.take<float>(nch * F);
+  L.pdqkv = b.take<float>(nch * 3 * d);
   return L;
 }
 
@@ -415,20 +445,6 @@ hydra_status run_visit(hydra_ctx *ctx, Model *mm, Slot *sl, int shard, int phase
 }
 
 }  // namespace
-
-// The side stream of a lane (default priority) and its fork / join events, created on first use when
-// HYDRA_FLAG_SIDE_STREAM asks for it (per-kernel timing wants kernels one at a time: no side stream then).
-static hydra_status ensure_side_stream(hydra_ctx *ctx, hydra_ctx::Lane &ln, int k) {
-  if (!(ctx->init.flags & HYDRA_FLAG_SIDE_STREAM) || (ctx->init.flags & HYDRA_FLAG_TIMING)) return HYDRA_OK;
-  if (!ln.side) HYDRA_HIP(ctx, hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking));
-  if (!ln.join_ev) HYDRA_HIP(ctx, hipEventCreateWithFlags(&ln.join_ev, hipEventDisableTiming));
-  while (ln.fork_ev.size() < (size_t)k * FORKS_PER_BLOCK) {
-    hipEvent_t e = nullptr;
-    HYDRA_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    ln.fork_ev.push_back(e);
-  }
-  return HYDRA_OK;
-}
 
 uint64_t workspace_need(const ModelShape &s, int dtype) {
   const uint64_t act = up256((uint64_t)s.M * s.d * 4);
@@ -574,11 +590,8 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
     std::vector<LayerGrads> grads(s.k);
     for (int j = 0; j < s.k; ++j) grads[j] = take_layer_grads(b, s, dt);
     if (!b.ok) return fail(ctx, HYDRA_E_NOMEM, "workspace too small (backward)");
-    hydra_status ss = ensure_side_stream(ctx, ln, s.k);
-    if (ss) return ss;
     const int dcur = mm->dcur;
     auto enqueue = [&]() -> hipError_t {
-      Fork fk{st, ln.side ? ln.side : st, nullptr, ln.side != nullptr};
       for (int u = 0; u < s.nm; ++u) {  // recompute and back-propagate one micro-batch at a time
         xs[0] = mm->ckpt[shard - 1] + u * act;
         for (int j = 0; j < s.k; ++j)
@@ -586,17 +599,15 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
         const float *dx = mm->dbound[dcur] + u * act;
         const void *dxa;  // its operand-dtype copy: cast here for the shard's last block, written by the
         CK(act_view(dt, dx, grads[s.k - 1].dact2, M, d, &dxa, st));  // LayerNorm backward of the block above otherwise
+        const float *dx_part = nullptr;
         for (int j = s.k - 1; j >= 0; --j) {
           float *out = (j == 0) ? mm->dbound[dcur ^ 1] + u * act : grads[j - 1].gin;
           void *out_act = (j == 0) ? nullptr : grads[j - 1].dact2;
-          fk.ev = fk.on ? ln.fork_ev.data() + (size_t)j * FORKS_PER_BLOCK : nullptr;
-          CK(block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, dxa, out, out_act, Z, grads[j], u > 0, fk));
+          CK(block_backward(s, dt, block_ptrs(s, sl, dt, j), xs[j], acts[j], dx, dxa, dx_part, out, out_act, Z, grads[j],
+                            u > 0, st));
           dx = out;
           dxa = dt == DT_BF16 ? (const void *)out_act : (const void *)out;
-        }
-        if (fk.on) {  // the next micro-batch's recomputation (or the Adam step) must see the side stream's work done
-          CK(hipEventRecord(ln.join_ev, fk.side));
-          CK(hipStreamWaitEvent(st, ln.join_ev, 0));
+          dx_part = grads[j].part1;
         }
       }
       return hipSuccess;

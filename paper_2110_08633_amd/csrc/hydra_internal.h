@@ -117,10 +117,6 @@ struct hydra_ctx {
     char *ws = nullptr;
     int logits_owner = -1;    // model whose logits the lane's workspace still holds
     float *logits = nullptr;
-    // backward visits fork the parameter-gradient work to a second stream of the lane (created on first use)
-    hipStream_t side = nullptr;
-    std::vector<hipEvent_t> fork_ev;
-    hipEvent_t join_ev = nullptr;
   };
   std::vector<Lane> lanes;
   char *arena = nullptr;

@@ -73,6 +73,38 @@ hipError_t launch_layernorm_bwd_dx(const float *dy, const float *x, const float 
 hipError_t launch_layernorm_bwd_params(const float *dy, const float *x, const float *mean, const float *rstd,
                                        float *dgamma, float *dbeta, float *scratch, int M, int d, int acc, hipStream_t s);
 int colsum_chunks(int M);
+// Backward of a LayerNorm in one pass: dx = dres + LN'(dy) (dres may be null), its bf16 copy (dx_bf16 may be null)
+// and per-block partial column sums part[blocks][3][d] of dy*xhat, dy and dx, blocks = layernorm_bwd_fused_blocks(M);
+// the sums are finished by launch_colsum_finish.  Rows of up to 2048 elements (layernorm_bwd_fused_supported).
+bool layernorm_bwd_fused_supported(int d);
+int layernorm_bwd_fused_blocks(int M);
+hipError_t launch_layernorm_bwd_fused(const float *dy, const float *x, const float *mean, const float *rstd,
+                                      const float *gamma, const float *dres, float *dx, void *dx_bf16, float *part, int M,
+                                      int d, hipStream_t s);
+// part[blocks][3][d]: third part = column sums of in [M,d] over the same row blocks, added in the same order as
+// launch_layernorm_bwd_fused adds its dx (bit-identical to it for the same values)
+hipError_t launch_colsum_rows8(const float *in, float *part, int M, int d, hipStream_t s);
+// pass 1 of the column sums of two [M,N0] / [M,N1] operands of one dtype (leading dimension = N): partials
+// part0 [colsum_chunks(M)][N0], part1 [colsum_chunks(M)][N1]
+hipError_t launch_colsum2_pass1(int dtype, const void *in0, int N0, float *part0, const void *in1, int N1, float *part1,
+                                int M, hipStream_t s);
+// Several column sums finished by one launch: out[c] (+)= sum over k < nch of part[k * stride + c], c < N.
+constexpr int COLSUM_MAX_SEGS = 10;
+struct ColsumSeg {
+  const float *part;
+  float *out;
+  int64_t stride;
+  int nch, N, col0;  // col0 is filled in by the launcher
+};
+struct ColsumFinish {
+  ColsumSeg seg[COLSUM_MAX_SEGS];
+  int nseg = 0, acc = 0;
+  void add(const float *part, int64_t stride, int nch, int N, float *out) {
+    if (nseg < COLSUM_MAX_SEGS) seg[nseg] = ColsumSeg{part, out, stride, nch, N, 0};
+    ++nseg;
+  }
+};
+hipError_t launch_colsum_finish(ColsumFinish &a, hipStream_t s);
 // out[n] (+)= sum_m in[m,n]; in has operand dtype (or fp32 when in_dtype == DT_F32); scratch fp32 [colsum_chunks(M)*N]
 hipError_t launch_colsum(int in_dtype, const void *in, int64_t ld, float *out, float *scratch, int M, int N, int acc,
                          hipStream_t s);

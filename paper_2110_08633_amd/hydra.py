@@ -21,7 +21,7 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 OK, E_INVAL, E_NOSLOT, E_STATE, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
-FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS, FLAG_OVERLAP, FLAG_SIDE_STREAM = 1, 2, 4, 8, 16, 32, 64, 128
+FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS, FLAG_OVERLAP = 1, 2, 4, 8, 16, 32, 64
 LOAD_PARAMS, LOAD_OPT = 1, 2
 SPILL_WRITEBACK, SPILL_EVICT = 1, 2
 RD_LOGITS, RD_GRADS, RD_PARAMS, RD_ADAM_M, RD_ADAM_V, RD_CKPT, RD_DBOUND = range(7)

@@ -143,7 +143,9 @@ def arena_bytes_for(cfgs, n_slots, ckpt_spill=False, lanes=1):
             total += V * d * 4 + 256
         layer = 5 * act + 3 * M * d * 4 + M * 3 * d * 4 + B * c["H"] * T * T * 4 + 2 * M * F * 4
         scratch = 2 * B * c["H"] * T * T * 4 + 4 * act + M * F * 4 + M * 3 * d * 4 + 4 * act
-        grads = 6 * act + M * F * 4 + M * 3 * d * 4     # activation gradients kept per block of a backward visit
+        # activation gradients kept per block of a backward visit, and the partial column sums behind its
+        # bias / LayerNorm gradients
+        grads = 6 * act + M * F * 4 + M * 3 * d * 4 + (M // 8 + 1) * 6 * d * 4 + (M // 128 + 1) * (F + 3 * d) * 4 + 4096
         ws = max(ws, k * (layer + act + grads) + scratch + 2 * act + (1 << 20), M * vpad * 4 + 4 * act + (1 << 20))
         blk = 12 * d * d + 13 * d if F == 4 * d else 4 * d * d + 2 * d * F + 9 * d + F
         max_shard = max(max_shard, V * d + T * d, k * blk, 2 * d + d * V)

@@ -468,40 +468,3 @@ def test_graph_replay_of_shard_visits(rt, dtype, max_slots, lanes, nm):
             update_ill(ill, r["grads"], dtype)
         assert abs(lg[m] - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
         check_weights(wg[m], P, refs[0]["before"], ill, base["lrs"][m], steps, dtype, f"model {m} ")
-
-
-@pytest.mark.parametrize("max_slots,lanes,nm,k", [(0, 2, 1, 2), (3, 1, 2, 2), (4, 2, 2, 1), (0, 1, 1, 4)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_side_stream_changes_nothing(rt, dtype, max_slots, lanes, nm, k):
-    """With HYDRA_FLAG_SIDE_STREAM backward visits run the parameter-gradient work (dW products, bias and LayerNorm
-    column sums) on a second stream of the lane, forked from the input-gradient chain block by block and joined
-    once per micro-batch.  The same kernels produce every tensor in the same order, so three minibatches of two
-    models must end in weights, Adam state and losses that are bit-identical to a run without the flag - a missing
-    fork or join shows as a difference (or as NaN patterns with poisoned buffers)."""
-    H, R = rt
-    base = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=k, dtype=dtype, n_models=2, lrs=[1e-4, 3e-4])
-    cfg = dict(base, n_micro=nm)
-    big = dict(base, B=base["B"] * nm)
-    n, steps = 2, 3
-    Ws = [SI.make_weights(base, 90 + m) for m in range(n)]
-    batches = [[SI.make_batch(big, 700 + 10 * m + i) for i in range(steps)] for m in range(n)]
-    fc, bc = SI.task_costs(base)
-    results = []
-    for flags in (H.FLAG_POISON | H.FLAG_SIDE_STREAM, H.FLAG_POISON):
-        sess = R.Session(R.arena_bytes_for([cfg] * n, 12, lanes=lanes), max_slots=max_slots, lanes=lanes, flags=flags)
-        recs = [sess.add_model(cfg, Ws[m], base["lrs"][m]) for m in range(n)]
-        sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [steps] * n, [list(fc) + list(bc)] * n)
-        toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
-        tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
-        H.hydra_sched_run(sch, toks, tgts, sess.ctx)
-        sess.flush()
-        results.append(([(recs[m]["master"].copy(), recs[m]["m"].copy(), recs[m]["v"].copy()) for m in range(n)],
-                        [H.hydra_get_loss(sess.ctx, recs[m]["id"]) for m in range(n)]))
-        H.hydra_sched_destroy(sch)
-        sess.close()
-    (ws, ls), (wn, lnn) = results
-    assert ls == lnn
-    for m in range(n):
-        for a, b in zip(ws[m], wn[m]):
-            assert np.isfinite(a).all()
-            assert (a == b).all()
