@@ -323,6 +323,18 @@ hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *s
 /* Row LayerNorm: y (dtype) [M,d], mean/rstd fp32 [M]. */
 hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *gamma, const float *beta,
                                     void *y, float *mean, float *rstd, int32_t M, int32_t d, void *stream);
+/* Backward of the row LayerNorm y = xhat * gamma + beta (the textbook formulas; the paper only names the
+ * architecture, Section 3) in one pass over the rows: dx = dres + rstd * (dxhat - mean(dxhat) - xhat *
+ * mean(dxhat * xhat)) with dxhat = dy * gamma, optionally its bf16 copy, and the column sums dgamma = sum_rows
+ * dy * xhat, dbeta = sum_rows dy, dx_colsum = sum_rows dx (the bias gradient of a linear layer whose output
+ * gradient dx is).  All pointers device; dy, x, dx fp32 [M,d]; mean, rstd fp32 [M] as written by
+ * hydra_op_layernorm_fwd; gamma, dgamma, dbeta, dx_colsum fp32 [d]; dres (fp32 [M,d]), dx_bf16 and dx_colsum
+ * may be NULL; scratch: fp32 [3 * d * ceil(M / 8)], overwritten.  d must be a multiple of 4 and at most 2048
+ * (HYDRA_E_INVAL otherwise). */
+hydra_status hydra_op_layernorm_bwd(const float *dy, const float *x, const float *mean, const float *rstd,
+                                    const float *gamma, const float *dres, float *dx, void *dx_bf16,
+                                    float *dgamma, float *dbeta, float *dx_colsum, float *scratch, int32_t M,
+                                    int32_t d, void *stream);
 /* Causal softmax over rows of S fp32 [n_mat, T, T] -> P (dtype); entries j>i are 0. */
 hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T,
                                      void *stream);

@@ -36,6 +36,24 @@ hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *
   return ret(launch_layernorm_fwd(dtype, x, gamma, beta, y, mean, rstd, M, d, (hipStream_t)stream), "layernorm");
 }
 
+hydra_status hydra_op_layernorm_bwd(const float *dy, const float *x, const float *mean, const float *rstd,
+                                    const float *gamma, const float *dres, float *dx, void *dx_bf16, float *dgamma,
+                                    float *dbeta, float *dx_colsum, float *scratch, int32_t M, int32_t d, void *stream) {
+  if (!dy || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || !scratch || M < 0 || d <= 0 ||
+      !layernorm_bwd_fused_supported(d))
+    return fail(nullptr, HYDRA_E_INVAL, "bad LayerNorm backward argument (d % 4 == 0, d <= 2048)");
+  if (M == 0) return HYDRA_OK;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_layernorm_bwd_fused(dy, x, mean, rstd, gamma, dres, dx, dx_bf16, scratch, M, d, st);
+  if (e != hipSuccess) return ret(e, "layernorm_bwd");
+  ColsumFinish fin;
+  const int nb = layernorm_bwd_fused_blocks(M);
+  fin.add(scratch, 3 * (int64_t)d, nb, d, dgamma);
+  fin.add(scratch + d, 3 * (int64_t)d, nb, d, dbeta);
+  if (dx_colsum) fin.add(scratch + 2 * d, 3 * (int64_t)d, nb, d, dx_colsum);
+  return ret(launch_colsum_finish(fin, st), "layernorm_bwd (column sums)");
+}
+
 hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T, void *stream) {
   if (!S || !P || n_mat < 0 || T <= 0) return fail(nullptr, HYDRA_E_INVAL, "bad softmax argument");
   return ret(launch_softmax_causal_fwd(dtype, S, P, n_mat, T, (hipStream_t)stream), "softmax");

@@ -108,6 +108,7 @@ SIGNATURES = {
                              _i64, _vp]),
     "hydra_op_adam": (_i32, [_vp, _vp, _vp, _vp, _vp, _i64, _f64, _f64, _f64, _f64, _i64, _vp]),
     "hydra_op_layernorm_fwd": (_i32, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
+    "hydra_op_layernorm_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_softmax_causal": (_i32, [_i32, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_cross_entropy": (_i32, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _f32, _vp]),
 }
@@ -341,6 +342,13 @@ def hydra_op_adam(w, m, v, g, shadow, n, lr, beta1, beta2, eps, t, stream=None):
 def hydra_op_layernorm_fwd(dtype, x, gamma, beta, y, mean, rstd, M, d, stream=None):
     return _check(lib.hydra_op_layernorm_fwd(dtype, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(mean),
                                              _ptr(rstd), M, d, _stream(stream)))
+
+
+def hydra_op_layernorm_bwd(dy, x, mean, rstd, gamma, dres, dx, dx_bf16, dgamma, dbeta, dx_colsum, scratch, M, d,
+                           stream=None):
+    return _check(lib.hydra_op_layernorm_bwd(_ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(dres),
+                                             _ptr(dx), _ptr(dx_bf16), _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum),
+                                             _ptr(scratch), M, d, _stream(stream)))
 
 
 def hydra_op_softmax_causal(dtype, S, P, n_mat, T, stream=None):

@@ -113,6 +113,39 @@ def test_layernorm_fwd(H, dtype, M, d):
     assert_close(mean.cpu().numpy(), x.astype(np.float64).mean(-1), 1e-5, "mean")
 
 
+@pytest.mark.parametrize("with_res", [False, True])
+@pytest.mark.parametrize("M,d", [(5, 8), (37, 200), (130, 768), (64, 1024), (19, 1600), (9, 2048)])
+def test_layernorm_bwd_one_pass(H, M, d, with_res):
+    """Backward of a LayerNorm in one pass: dx (with and without a residual gradient added), its bf16 copy, and the
+    three column sums (dgamma, dbeta, sum of dx) against the oracle's formulas in float64; row counts that are not
+    multiples of the kernel's row block, widths that fill 1 to 8 register chunks per lane."""
+    rng = np.random.default_rng(1000 * M + d)
+    x = (rng.standard_normal((M, d)) * 2 + 0.5).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+    b = (0.1 * rng.standard_normal(d)).astype(np.float32)
+    dy = rng.standard_normal((M, d)).astype(np.float32)
+    res = rng.standard_normal((M, d)).astype(np.float32) if with_res else None
+    y = torch.zeros((M, d), device="cuda")
+    mean, rstd = torch.zeros(M, device="cuda"), torch.zeros(M, device="cuda")
+    H.hydra_op_layernorm_fwd(0, dev(x), dev(g), dev(b), y, mean, rstd, M, d)
+    dx = torch.full((M, d), float("nan"), device="cuda")
+    dxh = torch.zeros((M, d), device="cuda", dtype=torch.bfloat16)
+    dg, db, dc = (torch.full((d,), float("nan"), device="cuda") for _ in range(3))
+    scratch = torch.empty(3 * d * ((M + 7) // 8), device="cuda")
+    H.hydra_op_layernorm_bwd(dev(dy), dev(x), mean, rstd, dev(g), dev(res) if with_res else None, dx, dxh, dg, db, dc,
+                             scratch, M, d)
+    torch.cuda.synchronize()
+    _, cache = D.layernorm_fwd(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64))
+    rdx, rdg, rdb = D.layernorm_bwd(dy.astype(np.float64), g.astype(np.float64), cache)
+    if with_res:
+        rdx = rdx + res.astype(np.float64)
+    assert_close(dx.cpu().numpy(), rdx, 2e-5, "dx")
+    assert_close(dxh.float().cpu().numpy(), rdx, 8e-3, "dx bf16")
+    assert_close(dg.cpu().numpy(), rdg, 2e-5, "dgamma")
+    assert_close(db.cpu().numpy(), rdb, 2e-5, "dbeta")
+    assert_close(dc.cpu().numpy(), rdx.sum(axis=0), 2e-5, "column sum of dx")
+
+
 @pytest.mark.parametrize("dtype", [0, 1])
 @pytest.mark.parametrize("n_mat,T", [(3, 8), (2, 72), (2, 264), (1, 520)])
 def test_softmax_causal(H, dtype, n_mat, T):

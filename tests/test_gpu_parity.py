@@ -468,3 +468,47 @@ def test_graph_replay_of_shard_visits(rt, dtype, max_slots, lanes, nm):
             update_ill(ill, r["grads"], dtype)
         assert abs(lg[m] - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
         check_weights(wg[m], P, refs[0]["before"], ill, base["lrs"][m], steps, dtype, f"model {m} ")
+
+
+def test_overlap_trace_of_a_spilled_run(rt):
+    """HYDRA_FLAG_OVERLAP: the event pairs around promotes, write-backs and shard tasks of a spilled two-model run
+    give interval unions that are consistent with each other and with the byte counters; without the flag the call
+    reports a state error.  The traced run's weights equal those of an untraced run bit for bit."""
+    H, R = rt
+    cfg = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=1, dtype="bf16", n_models=2, lrs=[1e-4, 3e-4])
+    n, steps = 2, 3
+    Ws = [SI.make_weights(cfg, 60 + m) for m in range(n)]
+    batches = [[SI.make_batch(cfg, 900 + 10 * m + i) for i in range(steps)] for m in range(n)]
+    fc, bc = SI.task_costs(cfg)
+    finals = []
+    for flags in (H.FLAG_OVERLAP, 0):
+        sess = R.Session(R.arena_bytes_for([cfg] * n, 3, lanes=2), max_slots=3, lanes=2, flags=flags)
+        recs = [sess.add_model(cfg, Ws[m], cfg["lrs"][m]) for m in range(n)]
+        sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [steps] * n, [list(fc) + list(bc)] * n)
+        toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
+        tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
+        st0 = H.hydra_get_stats(sess.ctx)
+        H.hydra_sched_run(sch, toks, tgts, sess.ctx)
+        if flags:
+            o = H.hydra_overlap_stats(sess.ctx)
+            st1 = H.hydra_get_stats(sess.ctx)
+            assert o["n_intervals"] > 0 and o["wall_ms"] > 0
+            assert o["bytes_h2d"] == st1["bytes_h2d"] - st0["bytes_h2d"]
+            assert o["bytes_d2h"] == st1["bytes_d2h"] - st0["bytes_d2h"]
+            eps = 1e-6
+            assert 0 < o["compute_ms"] <= o["wall_ms"] + eps
+            assert max(o["h2d_ms"], o["d2h_ms"]) <= o["transfer_ms"] + eps <= o["h2d_ms"] + o["d2h_ms"] + 2 * eps
+            assert 0 <= o["hidden_ms"] <= min(o["transfer_ms"], o["compute_ms"]) + eps
+            assert o["transfer_ms"] <= o["wall_ms"] + eps
+            H.hydra_overlap_reset(sess.ctx)
+            assert H.hydra_overlap_stats(sess.ctx)["n_intervals"] == 0
+        else:
+            with pytest.raises(H.HydraError) as ei:
+                H.hydra_overlap_stats(sess.ctx)
+            assert ei.value.code == H.E_STATE
+        sess.flush()
+        finals.append([recs[m]["master"].copy() for m in range(n)])
+        H.hydra_sched_destroy(sch)
+        sess.close()
+    for a, b in zip(*finals):
+        assert np.isfinite(a).all() and (a == b).all()
