@@ -103,7 +103,9 @@ def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch, pilot=False
     return dict(seconds=dt, enqueue_seconds=run_steps.enqueue_s, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
                 n_slots=st1["n_slots"], kernels=kst, losses=losses, pilot_ns=pilot_ns, overlap=ov,
                 host_promote_ms=st1["host_promote_ms"] - st0["host_promote_ms"],
-                host_writeback_ms=st1["host_writeback_ms"] - st0["host_writeback_ms"])
+                host_writeback_ms=st1["host_writeback_ms"] - st0["host_writeback_ms"],
+                host_task_ms=st1["host_task_ms"] - st0["host_task_ms"],
+                host_batch_ms=st1["host_batch_ms"] - st0["host_batch_ms"])
 
 
 def overlap_report(run, steps):
@@ -120,7 +122,8 @@ def overlap_report(run, steps):
             "compute_with_transfer_in_flight_frac": round(o["hidden_ms"] / max(o["compute_ms"], 1e-9), 4),
             "h2d_GBps_while_busy": round(o["bytes_h2d"] / max(o["h2d_ms"], 1e-9) / 1e6, 2),
             "d2h_GBps_while_busy": round(o["bytes_d2h"] / max(o["d2h_ms"], 1e-9) / 1e6, 2),
-            "host_promote_ms_per_step": r(run["host_promote_ms"]), "host_writeback_ms_per_step": r(run["host_writeback_ms"])}
+            "host_promote_ms_per_step": r(run["host_promote_ms"]), "host_writeback_ms_per_step": r(run["host_writeback_ms"]),
+            "host_task_enqueue_ms_per_step": r(run["host_task_ms"]), "host_set_batch_ms_per_step": r(run["host_batch_ms"])}
 
 
 def measured_traffic(config, kernel):

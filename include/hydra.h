@@ -157,7 +157,10 @@ typedef struct {
   uint64_t slot_bytes, workspace_bytes, model_state_bytes;
   uint64_t n_graph_launches;       /* block-shard visits replayed as HIP graphs (HYDRA_FLAG_GRAPHS)       */
   double host_promote_ms;          /* host time hydra_sched_run spent inside promote (evict + load) calls  */
-  double host_writeback_ms;        /* ... and inside the write-back calls that follow an Adam step         */
+  double host_writeback_ms;        /* ... inside the write-back calls that follow an Adam step             */
+  double host_task_ms;             /* ... and inside the forward / backward / Adam calls (kernel launches) */
+  double host_batch_ms;            /* ... and inside hydra_set_batch: token staging is two minibatches deep, so this is */
+                                   /* where a host that runs more than two minibatches ahead waits for the device       */
 } hydra_stats;
 
 /* How far the shard swaps are hidden under compute (paper Section 2.3, double buffering), from HIP events

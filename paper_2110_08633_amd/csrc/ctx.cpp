@@ -362,7 +362,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   int tr = -1;
   const uint64_t h2d_before = ctx->stats.bytes_h2d;
   auto trace_open = [&]() {
-    if (tr < 0 && !ctx->dry) tr = trace_begin(ctx, TRACE_H2D, ctx->s_h2d);
+    if (tr < 0 && !ctx->dry) tr = trace_begin(ctx, TRACE_H2D, ctx->s_h2d, model << 16 | shard);
   };
   if (!sl) {
     int free_i = -1;
@@ -375,6 +375,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     sl = &ctx->slots[free_i];
     sl->model = model; sl->shard = shard;
     sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->dirty = sl->tied_valid = false;
+    sl->wb_seq = 0;
     m->slot_of[shard] = free_i;
     // the buffer's previous occupant must be done with it
     if (!ctx->dry) {
@@ -472,7 +473,7 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     if (!ctx->dry) {
       if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
       hydra_status cs;
-      const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h);
+      const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h, model << 16 | shard);
       if ((cs = copy_d2h(ctx, m->host.master + off, m->host_dev.master + off, sl->w, cnt * 4)) ||
           (cs = copy_d2h(ctx, m->host.adam_m + off, m->host_dev.adam_m + off, sl->m, cnt * 4)) ||
           (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4)))
@@ -483,6 +484,7 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     }
     m->wb_pending[shard] = 1;
     sl->spill_pending = true;
+    sl->wb_seq = ++ctx->wb_counter;
     sl->dirty = false;
     ctx->stats.bytes_d2h += cnt * 12;
     ctx->stats.n_writebacks++;
@@ -546,7 +548,7 @@ hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
     // the ping-pong buffer about to be overwritten may still be on its way to the host
     HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_d2h[shard & 1], 0));
   }
-  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream);
+  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream, model << 16 | shard);
   if (!ctx->dry && (st = exec_forward(ctx, m, sl, shard))) return st;
   if ((st = end_task(ctx, m, sl, tr))) return st;
   if (spill && shard <= S) {
@@ -586,7 +588,7 @@ hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard) 
     if (m->ckpt_h2d_pending[pb] && !ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_h2d[pb], 0));
     m->ckpt_h2d_pending[pb] = false;
   }
-  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream);
+  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream, model << 16 | shard);
   if (!ctx->dry && (st = exec_backward(ctx, m, sl, shard))) return st;
   sl->grads_valid = true;
   if ((st = end_task(ctx, m, sl, tr))) return st;
@@ -601,7 +603,7 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
   Model *m = ctx->models[model];
   if (!sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients: run the backward visit first");
   if (!sl->has_opt) return fail(ctx, HYDRA_E_STATE, "Adam state not resident: load with HYDRA_LOAD_OPT");
-  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream);
+  const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream, model << 16 | shard);
   if (!ctx->dry && (st = exec_adam(ctx, m, sl, shard))) return st;
   sl->grads_valid = false;
   sl->dirty = true;

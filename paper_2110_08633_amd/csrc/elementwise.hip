@@ -931,6 +931,14 @@ hipError_t launch_copy_link(void *dst_mapped, const void *src, size_t bytes, int
   return hipGetLastError();
 }
 
+// An empty kernel: a point in a stream that is certainly ordered after every wait enqueued before it (used by the
+// overlap trace, whose interval must not start while its stream still waits for another stream's event).
+__global__ void stream_marker_kernel() {}
+hipError_t launch_stream_marker(hipStream_t s) {
+  hipLaunchKernelGGL(stream_marker_kernel, dim3(1), dim3(64), 0, s);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ casts
 __global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out,
                                                         int64_t n) {

@@ -63,6 +63,8 @@ struct Slot {
   bool compute_pending = false, spill_pending = false;
   bool tied_valid = false;  // HEAD shard of a tied model: the buffer's copy of wte is current
   uint64_t last_use = 0;  // value of the context's task counter when a task last ran on this buffer
+  uint64_t wb_seq = 0;    // position of the buffer's last write-back in the order write-backs were enqueued (0: none
+                          // since it was filled); the d2h stream works in that order, so a smaller value is free earlier
 };
 
 struct Model {
@@ -127,6 +129,7 @@ struct hydra_ctx {
   uint64_t ws_bytes = 0;  // workspace per lane (one task at a time runs on a lane)
   hydra_stats stats;
   uint64_t use_counter = 0;
+  uint64_t wb_counter = 0;  // write-backs enqueued so far
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
   hydra::Tracer *tracer = nullptr;  // promote / write-back / task intervals (HYDRA_FLAG_OVERLAP)
   // captured block-shard visits (HYDRA_FLAG_GRAPHS); key: model, shard, phase, shard buffer, boundary-gradient parity
@@ -152,7 +155,7 @@ Slot *slot_for(hydra_ctx *ctx, int model, int shard);
 hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes);
 
 // opens / closes an interval of the overlap trace on stream s (no-ops without HYDRA_FLAG_OVERLAP; idx < 0 ignored)
-int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s);
+int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s, int tag = 0);  // tag: model << 16 | shard
 void trace_end(hydra_ctx *ctx, int idx, hipStream_t s, uint64_t bytes);
 
 // executor (exec.cpp): enqueue the kernels of one visit on the compute stream

@@ -138,6 +138,7 @@ hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C
 // fp32 [R,C] (ld_in) -> operand dtype [R,C] (ld_out)
 hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C,
                            hipStream_t s);
+hipError_t launch_stream_marker(hipStream_t s);  // empty kernel
 hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s);
 // device -> page-locked host memory through its device-side mapping (both 16-byte aligned)
 hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, hipStream_t s);

@@ -3,6 +3,8 @@
 // events; after a synchronisation the elapsed times are aggregated per kernel
 // name together with the algorithmic flops / bytes of the launches.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 
@@ -116,7 +118,7 @@ bool prof_get(Profiler *p, int i, std::string *name, uint64_t *launches, double 
 // synchronisation.
 // ---------------------------------------------------------------------------
 struct TraceRec {
-  int kind;
+  int kind, tag;
   hipEvent_t e0, e1;
   uint64_t bytes;
   bool closed;
@@ -153,7 +155,7 @@ static hipEvent_t trace_event(Tracer *t) {
   return e;
 }
 
-int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s) {
+int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s, int tag) {
   Tracer *t = ctx->tracer;
   if (!t) return -1;
   if (!t->base_recorded) {
@@ -161,8 +163,12 @@ int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s) {
     if (hipEventRecord(t->base, s) != hipSuccess) return -1;
     t->base_recorded = true;
   }
-  TraceRec r{kind, trace_event(t), trace_event(t), 0, false};
+  TraceRec r{kind, tag, trace_event(t), trace_event(t), 0, false};
   if (!r.e0 || !r.e1) return -1;
+  // The start event follows an empty kernel: a kernel is held back by the waits enqueued before it, so the interval
+  // opens when the stream has actually reached the operation (an event recorded directly after a wait for another
+  // stream's event was seen to carry a time stamp from before that wait was satisfied).
+  (void)launch_stream_marker(s);
   (void)hipEventRecord(r.e0, s);
   t->recs.push_back(r);
   return (int)t->recs.size() - 1;
@@ -211,10 +217,16 @@ static void trace_collect(Tracer *t, hydra_overlap *out) {
   memset(out, 0, sizeof *out);
   Intervals by_kind[3];
   double lo = 1e300, hi = -1e300;
+  // HYDRA_TRACE_DUMP=<file>: one line per interval (kind, model, shard, start ms, end ms, bytes) for timeline studies
+  const char *dump_path = getenv("HYDRA_TRACE_DUMP");
+  FILE *dump = dump_path ? fopen(dump_path, "w") : nullptr;
   for (TraceRec &r : t->recs) {
     float a = 0.f, b = 0.f;
     if (r.closed && hipEventElapsedTime(&a, t->base, r.e0) == hipSuccess &&
         hipEventElapsedTime(&b, t->base, r.e1) == hipSuccess && b >= a) {
+      if (dump)
+        fprintf(dump, "%s %d %d %.4f %.4f %llu\n", r.kind == TRACE_COMPUTE ? "compute" : r.kind == TRACE_H2D ? "h2d" : "d2h",
+                r.tag >> 16, r.tag & 0xffff, a, b, (unsigned long long)r.bytes);
       by_kind[r.kind].push_back({a, b});
       lo = std::min(lo, (double)a);
       hi = std::max(hi, (double)b);
@@ -223,6 +235,7 @@ static void trace_collect(Tracer *t, hydra_overlap *out) {
       out->n_intervals++;
     }
   }
+  if (dump) fclose(dump);
   (void)hipGetLastError();
   if (!out->n_intervals) return;
   const Intervals comp = merged(by_kind[TRACE_COMPUTE]), h2d = merged(by_kind[TRACE_H2D]),

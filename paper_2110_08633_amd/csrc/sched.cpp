@@ -79,12 +79,15 @@ hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
     bool has_free = false;
     for (const Slot &sl : ctx->slots) has_free |= sl.model < 0;
     if (!has_free) {
-      // Candidates are the buffers not needed again soon; among them the one idle longest goes first, because its
-      // write-back has had the most time to finish (the promote waits for it).  If every buffer is needed soon, the
-      // one whose next use is furthest away is taken.
+      // Candidates are the buffers not needed again soon.  Among them the one that is free first goes: a buffer
+      // whose shard was never written back since it was filled (a forward visit changes nothing) is free at once,
+      // otherwise write-backs finish in the order they were enqueued; ties go to the buffer idle longest.  (Taking
+      // the buffer idle longest regardless evicted the embedding shard at every step boundary and stalled the
+      // promote for the 7 ms its 470 MB write-back still needed.)  If every buffer is needed soon, the one whose
+      // next use is furthest away is taken.
       int victim = -1, oldest = -1;
       size_t far = 0;
-      uint64_t oldest_use = ~0ull;
+      uint64_t oldest_use = ~0ull, oldest_wb = ~0ull;
       const size_t soon = 2 * ctx->slots.size();
       for (size_t j = 0; j < ctx->slots.size(); ++j) {
         const Slot &sl = ctx->slots[j];
@@ -94,7 +97,12 @@ hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
           if (s->model_id[m] == sl.model) local = m;
         const size_t nu = local < 0 ? (size_t)-1 : next_use(s, i, local, sl.shard);
         if (victim < 0 || nu > far) { victim = (int)j; far = nu; }
-        if ((nu == (size_t)-1 || nu - i > soon) && sl.last_use < oldest_use) { oldest = (int)j; oldest_use = sl.last_use; }
+        const uint64_t wb = sl.dirty ? ~0ull - 1 : sl.wb_seq;  // a write-back not even enqueued yet comes last
+        if ((nu == (size_t)-1 || nu - i > soon) && (wb < oldest_wb || (wb == oldest_wb && sl.last_use < oldest_use))) {
+          oldest = (int)j;
+          oldest_use = sl.last_use;
+          oldest_wb = wb;
+        }
       }
       if (oldest >= 0) victim = oldest;
       if (victim < 0) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the prefetch");
@@ -192,15 +200,20 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
       if ((st = promote(s, i + 1, mid, t.shard))) return st;
     }
     if (t.phase == 0 && t.shard == 0) {
+      HostTimer ht(&ctx->stats.host_batch_ms);
       const int64_t per = mm->sh.Mt;
       if ((st = hydra_set_batch(ctx, mid, tokens[t.model] + t.minibatch * per, targets[t.model] + t.minibatch * per)))
         return st;
     }
     if (t.phase == 0) {
+      HostTimer ht(&ctx->stats.host_task_ms);
       if ((st = hydra_shard_forward(ctx, mid, t.shard))) return st;
     } else {
-      if ((st = hydra_shard_backward(ctx, mid, t.shard))) return st;
-      if ((st = hydra_shard_adam_step(ctx, mid, t.shard))) return st;
+      {
+        HostTimer ht(&ctx->stats.host_task_ms);
+        if ((st = hydra_shard_backward(ctx, mid, t.shard))) return st;
+        if ((st = hydra_shard_adam_step(ctx, mid, t.shard))) return st;
+      }
       // when shards do not all fit, start the write-back right away so that it
       // overlaps the following tasks instead of delaying the next promote
       if (!all_fit) {

@@ -66,7 +66,8 @@ class Stats(C.Structure):
                 ("n_load_hits", C.c_uint64), ("n_evictions", C.c_uint64), ("n_writebacks", C.c_uint64),
                 ("n_tasks", C.c_uint64), ("n_slots", C.c_int32), ("reserved", C.c_int32),
                 ("slot_bytes", C.c_uint64), ("workspace_bytes", C.c_uint64), ("model_state_bytes", C.c_uint64),
-                ("n_graph_launches", C.c_uint64), ("host_promote_ms", C.c_double), ("host_writeback_ms", C.c_double)]
+                ("n_graph_launches", C.c_uint64), ("host_promote_ms", C.c_double), ("host_writeback_ms", C.c_double),
+                ("host_task_ms", C.c_double), ("host_batch_ms", C.c_double)]
 
 
 _P = C.POINTER
