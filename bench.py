@@ -177,6 +177,9 @@ def main():
     ap.add_argument("--graphs", action="store_true",
                     help="replay block-shard visits as HIP graphs (halves the host's enqueue time; the device is the "
                          "bottleneck at this workload, so the throughput does not move)")
+    ap.add_argument("--layers", type=int, default=0, help="cut the model depth (other configs than the default: a "
+                    "depth-reduced copy with full widths; reported in config)")
+    ap.add_argument("--models", type=int, default=0, help="number of models (default: the config's)")
     ap.add_argument("--no-overlap-trace", action="store_true",
                     help="spill mode: do not record the event pairs behind the 'overlap' figures")
     ap.add_argument("--micro", type=int, default=1,
@@ -202,6 +205,11 @@ def main():
     cfg = dict(SI.CONFIGS[args.config])
     if args.micro > 1:
         cfg["n_micro"] = args.micro
+    if args.layers:
+        cfg["L"] = args.layers
+    if args.models:
+        cfg["n_models"] = args.models
+        cfg["lrs"] = (cfg["lrs"] * args.models)[:args.models]
     n_models = cfg["n_models"]
     tokens_per_step = n_models * args.micro * cfg["B"] * cfg["T"]
 
@@ -213,9 +221,10 @@ def main():
         "ms_per_step": round(1e3 * main_run["seconds"] / args.steps, 3),
         "host_enqueue_ms_per_step": round(1e3 * main_run["enqueue_seconds"] / args.steps, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: {n_models} GPT-2-small-shaped models (12L d768 H12 F3072 V50257), "
-                               f"B{cfg['B']} T{cfg['T']}, 2-layer shards alternated by Sharded-LRTF, bf16 MFMA + fp32 "
-                               "master/Adam, seeded N(0,0.02) weights, uniform tokens",
+        "config": {"workload": f"{args.config}: {n_models} GPT-2-shaped models ({cfg['L']}L d{cfg['d']} H{cfg['H']} "
+                               f"F{cfg['F']} V{cfg['V']}), B{cfg['B']} T{cfg['T']}, {cfg['k']}-layer shards alternated by "
+                               "Sharded-LRTF, bf16 MFMA + fp32 master/Adam, seeded N(0,0.02) weights, uniform tokens"
+                               + (" [depth / model count reduced on the command line]" if args.layers or args.models else ""),
                    "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes, "hip_graphs": args.graphs,
                    "micro_batches_per_visit": args.micro, "tokens_per_step": tokens_per_step},
         "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),

@@ -93,9 +93,9 @@ hydra_status ensure_planned(hydra_ctx *ctx) {
     ln.ws = arena_take(ctx, ctx->ws_bytes);
     if (!ln.ws) return fail(ctx, HYDRA_E_NOMEM, "device arena too small for the workspace");
   }
-  // a slot: fp32 master, m, v, grad and a bf16 working copy of the largest shard
+  // a slot: fp32 master, m, v, grad and two bf16 working copies (as stored / matrices transposed) of the largest shard
   ctx->slot_elems = align_up(max_shard, 64);
-  ctx->slot_bytes = align_up(ctx->slot_elems * 18, 256);
+  ctx->slot_bytes = align_up(ctx->slot_elems * 20, 256);
   const uint64_t base = align_up(ctx->arena_used, 256);
   uint64_t room = ctx->arena_bytes > base ? ctx->arena_bytes - base : 0;
   if (ctx->init.shard_buffer_cap_bytes && ctx->init.shard_buffer_cap_bytes < room)
@@ -114,6 +114,7 @@ hydra_status ensure_planned(hydra_ctx *ctx) {
     s.v = s.m + ctx->slot_elems;
     s.g = s.v + ctx->slot_elems;
     s.wb = (bf16_t *)(s.g + ctx->slot_elems);
+    s.wbt = s.wb + ctx->slot_elems;
     hydra_status st;
     if ((st = make_event(ctx, &s.ev_loaded)) || (st = make_event(ctx, &s.ev_compute)) ||
         (st = make_event(ctx, &s.ev_spilled)))
@@ -374,7 +375,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     }
     sl = &ctx->slots[free_i];
     sl->model = model; sl->shard = shard;
-    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->dirty = sl->tied_valid = false;
+    sl->has_params = sl->has_opt = sl->wb_valid = sl->wbt_valid = sl->grads_valid = sl->dirty = sl->tied_valid = false;
     sl->wb_seq = 0;
     m->slot_of[shard] = free_i;
     // the buffer's previous occupant must be done with it
@@ -499,7 +500,7 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     }
     m->slot_of[shard] = -1;
     sl->model = sl->shard = -1;
-    sl->has_params = sl->has_opt = sl->wb_valid = sl->grads_valid = sl->tied_valid = false;
+    sl->has_params = sl->has_opt = sl->wb_valid = sl->wbt_valid = sl->grads_valid = sl->tied_valid = false;
     ctx->stats.n_evictions++;
   }
   return HYDRA_OK;

@@ -985,6 +985,45 @@ hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C
   return hipGetLastError();
 }
 
+template <typename SrcT>
+__global__ __launch_bounds__(256) void transpose_group_kernel(const SrcT *__restrict__ src, bf16_t *__restrict__ dst,
+                                                              const TransposeGroup g) {
+  __shared__ float t[64][65];
+  int i = 0;
+#pragma unroll 1
+  while (i + 1 < g.n && (int)blockIdx.x >= g.tile0[i + 1]) ++i;  // uniform over the block
+  const int R = g.R[i], C = g.C[i];
+  const int tile = blockIdx.x - g.tile0[i], tc = (C + 63) / 64;
+  const int c0 = (tile % tc) * 64, r0 = (tile / tc) * 64;
+  const SrcT *in = src + g.off[i];
+  bf16_t *out = dst + g.off[i];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4)
+    t[r][tx] = (r0 + r < R && c0 + tx < C) ? ldv<SrcT>(in, (int64_t)(r0 + r) * C + c0 + tx) : 0.f;
+  __syncthreads();
+  for (int c = ty; c < 64; c += 4)
+    if (c0 + c < C && r0 + tx < R) out[(int64_t)(c0 + c) * R + r0 + tx] = f2bf(t[tx][c]);
+}
+
+hipError_t launch_transpose_group(int src_dtype, const void *src, bf16_t *dst, TransposeGroup &g, hipStream_t s) {
+  if (g.n <= 0) return hipSuccess;
+  if (g.n > TRANSPOSE_MAX) return hipErrorInvalidValue;
+  int tiles = 0;
+  double elems = 0;
+  for (int i = 0; i < g.n; ++i) {
+    g.tile0[i] = tiles;
+    tiles += ((g.R[i] + 63) / 64) * ((g.C[i] + 63) / 64);
+    elems += (double)g.R[i] * g.C[i];
+  }
+  g.tile0[g.n] = tiles;
+  ProfScope ps("transpose_weights", s, 0, elems * (dt_size(src_dtype) + 2.0));
+  if (src_dtype == DT_BF16)
+    hipLaunchKernelGGL(transpose_group_kernel<bf16_t>, dim3(tiles), dim3(256), 0, s, (const bf16_t *)src, dst, g);
+  else
+    hipLaunchKernelGGL(transpose_group_kernel<float>, dim3(tiles), dim3(256), 0, s, (const float *)src, dst, g);
+  return hipGetLastError();
+}
+
 template <typename OutT>
 __global__ void cast_act_kernel(const float *__restrict__ in, int64_t ld_in, OutT *__restrict__ out, int64_t ld_out, int R,
                                 int C) {

@@ -49,7 +49,8 @@ hipError_t launch_colsum_finish_one(const float *part, int64_t stride, int nch, 
 
 struct BlockW {  // pointers into a shard buffer for one block
   const float *ln1_g, *ln1_b, *b_qkv, *b_o, *ln2_g, *ln2_b, *b_fc, *b_proj;
-  const void *w_qkv, *w_o, *w_fc, *w_proj;  // operand dtype (bf16 working copy, or the fp32 master itself)
+  const void *w_qkv, *w_o, *w_fc, *w_proj;  // operand dtype (bf16 working copy, or the fp32 master itself), [in, out]
+  const void *t_qkv, *t_o, *t_fc, *t_proj;  // bf16 path: the same matrices transposed, [out, in]; null in the fp32 path
   float *G;                                  // gradient base of the block
 };
 
@@ -90,10 +91,12 @@ BlockW block_ptrs(const ModelShape &s, const Slot *sl, int dt, int j) {
   B.ln1_g = w + o.ln1_g; B.ln1_b = w + o.ln1_b; B.b_qkv = w + o.b_qkv; B.b_o = w + o.b_o;
   B.ln2_g = w + o.ln2_g; B.ln2_b = w + o.ln2_b; B.b_fc = w + o.b_fc; B.b_proj = w + o.b_proj;
   if (dt == DT_BF16) {
-    const bf16_t *h = sl->wb + base;
+    const bf16_t *h = sl->wb + base, *t = sl->wbt + base;
     B.w_qkv = h + o.w_qkv; B.w_o = h + o.w_o; B.w_fc = h + o.w_fc; B.w_proj = h + o.w_proj;
+    B.t_qkv = t + o.w_qkv; B.t_o = t + o.w_o; B.t_fc = t + o.w_fc; B.t_proj = t + o.w_proj;
   } else {
     B.w_qkv = w + o.w_qkv; B.w_o = w + o.w_o; B.w_fc = w + o.w_fc; B.w_proj = w + o.w_proj;
+    B.t_qkv = B.t_o = B.t_fc = B.t_proj = nullptr;
   }
   B.G = sl->g + base;
   return B;
@@ -102,12 +105,15 @@ BlockW block_ptrs(const ModelShape &s, const Slot *sl, int dt, int j) {
 inline const void *off_act(const void *p, int64_t elems, int dt) { return (const char *)p + elems * (int64_t)dt_size(dt); }
 inline void *off_act(void *p, int64_t elems, int dt) { return (char *)p + elems * (int64_t)dt_size(dt); }
 
-// y = x*W + b : X [M,K] operand dtype, W [K,N]
-hipError_t linear(int dt, int M, int N, int K, const void *X, const void *W, const float *bias, const float *resid,
-                  float *out_f32, void *out_act, int epi, void *out_act2, hipStream_t st) {
+// y = x*W + b : X [M,K] operand dtype, W [K,N]; Wt (may be null) is the same matrix stored [N,K]: both operands then
+// have the contraction index contiguous, which is the layout the direct-to-LDS kernel with its large tiles serves
+hipError_t linear(int dt, int M, int N, int K, const void *X, const void *W, const void *Wt, const float *bias,
+                  const float *resid, float *out_f32, void *out_act, int epi, void *out_act2, hipStream_t st) {
   GemmDesc g;
-  g.dtype = dt; g.ta = 0; g.tb = 1; g.M = M; g.N = N; g.K = K;
-  g.A = X; g.lda = K; g.B = W; g.ldb = N; g.ldc = N;
+  g.dtype = dt; g.ta = 0; g.M = M; g.N = N; g.K = K;
+  g.A = X; g.lda = K; g.ldc = N;
+  if (Wt) { g.tb = 0; g.B = Wt; g.ldb = K; }
+  else { g.tb = 1; g.B = W; g.ldb = N; }
   g.bias = bias; g.resid = resid; g.out_f32 = out_f32; g.out_act = out_act; g.epi = epi; g.out_act2 = out_act2;
   return launch_gemm(g, st);
 }
@@ -176,13 +182,13 @@ hipError_t block_forward(const ModelShape &s, int dt, const BlockW &W, const flo
                          const LayerActs &A, float *Sbuf, hipStream_t st) {
   const int M = (int)s.M, d = s.d, F = s.F, T = s.T, dh = s.dh;
   CK(launch_layernorm_fwd(dt, x_in, W.ln1_g, W.ln1_b, A.a, A.mean1, A.rstd1, M, d, st));
-  CK(linear(dt, M, 3 * d, d, A.a, W.w_qkv, W.b_qkv, nullptr, nullptr, A.qkv, EPI_NONE, nullptr, st));
+  CK(linear(dt, M, 3 * d, d, A.a, W.w_qkv, W.t_qkv, W.b_qkv, nullptr, nullptr, A.qkv, EPI_NONE, nullptr, st));
   if (fused_attn(s, dt)) CK(launch_attention_fwd(A.qkv, A.o, A.lse, s.B, s.H, T, dh, st));
   else CK(attention_unfused_fwd(s, dt, A, Sbuf, st));
-  CK(linear(dt, M, d, d, A.o, W.w_o, W.b_o, x_in, A.x1, nullptr, EPI_NONE, nullptr, st));
+  CK(linear(dt, M, d, d, A.o, W.w_o, W.t_o, W.b_o, x_in, A.x1, nullptr, EPI_NONE, nullptr, st));
   CK(launch_layernorm_fwd(dt, A.x1, W.ln2_g, W.ln2_b, A.c, A.mean2, A.rstd2, M, d, st));
-  CK(linear(dt, M, F, d, A.c, W.w_fc, W.b_fc, nullptr, nullptr, A.u, EPI_GELU, A.g, st));
-  CK(linear(dt, M, d, F, A.g, W.w_proj, W.b_proj, A.x1, x_out, nullptr, EPI_NONE, nullptr, st));
+  CK(linear(dt, M, F, d, A.c, W.w_fc, W.t_fc, W.b_fc, nullptr, nullptr, A.u, EPI_GELU, A.g, st));
+  CK(linear(dt, M, d, F, A.g, W.w_proj, W.t_proj, W.b_proj, A.x1, x_out, nullptr, EPI_NONE, nullptr, st));
   return hipSuccess;
 }
 
@@ -455,20 +461,44 @@ uint64_t workspace_need(const ModelShape &s, int dtype) {
   return (bwd > head ? bwd : head) + 4096;
 }
 
-// make the operand-dtype copy of a shard's matrices current
-static hipError_t ensure_working_copy(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
-  if (mm->dtype != DT_BF16 || sl->wb_valid) return hipSuccess;
+// Make the bf16 working copies of a shard current.  Block shards keep two: the shard as stored (wb: operand of the
+// dx products, dy W^T) and every matrix transposed (wbt: operand of the forward products, so that they too have both
+// operands contraction-contiguous).  A forward visit needs only wbt, taken straight from the fp32 master; a backward
+// visit needs both (wbt for the recomputation) and transposes the bf16 copy, which Adam keeps current while the
+// shard stays resident.
+static hipError_t ensure_working_copy(hydra_ctx *ctx, Model *mm, Slot *sl, int shard, bool backward) {
+  if (mm->dtype != DT_BF16) return hipSuccess;
   const ModelShape &s = mm->sh;
   hipStream_t st = ctx->lanes[mm->lane].stream;
   if (shard >= 1 && shard <= s.S) {
-    CK(launch_cast_bf16(sl->w, sl->wb, s.shard_off[shard + 1] - s.shard_off[shard], st));
-  } else if (shard == s.S + 1) {
+    if (backward && !sl->wb_valid) {
+      CK(launch_cast_bf16(sl->w, sl->wb, s.shard_off[shard + 1] - s.shard_off[shard], st));
+      sl->wb_valid = true;
+    }
+    if (!sl->wbt_valid) {
+      const BlockOffsets &o = s.bo;
+      const bool from_bf16 = sl->wb_valid;
+      TransposeGroup g;
+      for (int j = 0; j < s.k; ++j) {
+        const int64_t base = (int64_t)j * o.size;
+        const bool ok = g.add(base + o.w_qkv, s.d, 3 * s.d) && g.add(base + o.w_o, s.d, s.d) &&
+                        g.add(base + o.w_fc, s.d, s.F) && g.add(base + o.w_proj, s.F, s.d);
+        if (!ok || g.n + 4 > TRANSPOSE_MAX || j == s.k - 1) {
+          if (!ok) return hipErrorInvalidValue;
+          CK(launch_transpose_group(from_bf16 ? DT_BF16 : DT_F32, from_bf16 ? (const void *)sl->wb : (const void *)sl->w,
+                                    sl->wbt, g, st));
+          g = TransposeGroup();
+        }
+      }
+      sl->wbt_valid = true;
+    }
+  } else if (shard == s.S + 1 && !sl->wb_valid) {
     // LM head kept transposed [V,d] so that the odd vocabulary size never is a leading dimension; a tied head's
     // copy of wte already is [V,d]
     if (s.tie) CK(launch_cast_bf16(sl->w + 2 * s.d, sl->wb + 2 * s.d, (int64_t)s.V * s.d, st));
     else CK(launch_cast_transpose_bf16(sl->w + 2 * s.d, sl->wb + 2 * s.d, s.d, s.V, st));
+    sl->wb_valid = true;
   }
-  sl->wb_valid = true;
   return hipSuccess;
 }
 
@@ -478,7 +508,7 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   hipStream_t st = ctx->lanes[mm->lane].stream;
   const int M = (int)s.M, d = s.d;
   const int64_t act = (int64_t)M * d;  // elements of one micro-batch's boundary activation
-  HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
+  HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard, false));
   hydra_ctx::Lane &ln = ctx->lanes[mm->lane];
   Bump b{ln.ws, ctx->ws_bytes};
   if (shard == 0) {
@@ -538,7 +568,7 @@ hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   hipStream_t st = ctx->lanes[mm->lane].stream;
   const int M = (int)s.M, d = s.d;
   const int64_t act = (int64_t)M * d;
-  HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard));
+  HYDRA_HIP(ctx, ensure_working_copy(ctx, mm, sl, shard, true));
   hydra_ctx::Lane &ln = ctx->lanes[mm->lane];
   Bump b{ln.ws, ctx->ws_bytes};
   if (shard == s.S + 1) {
@@ -634,6 +664,7 @@ hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard) {
   HYDRA_HIP(ctx, launch_adam(sl->w, sl->m, sl->v, sl->g, shadow, n, h.lr, h.beta1, h.beta2, h.eps, mm->t,
                              ctx->lanes[mm->lane].stream));
   sl->wb_valid = shadow != nullptr;
+  sl->wbt_valid = false;  // re-made from the bf16 copy at the shard's next visit
   return HYDRA_OK;
 }
 

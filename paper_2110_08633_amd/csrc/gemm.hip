@@ -26,8 +26,25 @@ struct GemmArgs {
   int epi, causal;
   int tiles_m, tiles_n;
   float alpha;  // kept among the 32-bit fields: next to a pointer the compiler fused both into one 16-byte load and
-  int pad_;     // parked it in scratch memory, and a kernel that uses scratch pays microseconds per launch
+  int grp;      // parked it in scratch memory, and a kernel that uses scratch pays microseconds per launch
+                // grp: tile rows per group of the tile numbering (see xcd_group_rows)
 };
+
+// Tiles are numbered so that the run of tiles an XCD works on (consecutive workgroup ids go round-robin to the 8
+// XCDs, each with its own L2) is a block of grp tile rows by a few tile columns: every XCD then fetches grp row
+// panels of A and those few column panels of B once.  grp minimises the operand rows + columns such a block
+// spans; a fixed 8 made the XCDs of an N = 768 product fetch 60 MB for 17 MB of operands, 4 rows give 44 MB.
+static int xcd_group_rows(int tiles_m, int tiles_n, int bm, int bn) {
+  const long per = ((long)tiles_m * tiles_n + 7) / 8;  // tiles per XCD
+  int best = 1;
+  long best_cost = -1;
+  for (int g = 1; g <= 16 && g <= tiles_m; ++g) {
+    const long cols = (per + g - 1) / g;
+    const long cost = (long)g * bm + (cols < tiles_n ? cols : tiles_n) * bn;
+    if (best_cost < 0 || cost <= best_cost) { best = g; best_cost = cost; }
+  }
+  return best;
+}
 
 template <typename T> __device__ __forceinline__ float ld_act(const void *p, int64_t i);
 template <> __device__ __forceinline__ float ld_act<float>(const void *p, int64_t i) { return ((const float *)p)[i]; }
@@ -286,12 +303,12 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   const int nt = gridDim.x, bid = blockIdx.x;
   const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
   const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
-  // ... and within the run, groups of up to 8 tile rows are walked column by column: the tiles an XCD works on at
-  // any time then share a few row panels of A and a few column panels of B instead of one A panel and all of B
-  const int gsz = 8 * g.tiles_n;
+  // ... and within the run, groups of up to g.grp tile rows are walked column by column: the tiles an XCD works on
+  // at any time then share a few row panels of A and a few column panels of B instead of one A panel and all of B
+  const int gsz = g.grp * g.tiles_n;
   const int grp = tile / gsz, in_grp = tile - grp * gsz;
-  const int rows_in_grp = min(8, g.tiles_m - grp * 8);
-  const int tm = grp * 8 + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
+  const int rows_in_grp = min(g.grp, g.tiles_m - grp * g.grp);
+  const int tm = grp * g.grp + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
   const int m0 = tm * BM, n0 = tn * BN;
   if (g.causal == CAUSAL_SKIP_UPPER && n0 > m0 + BM - 1) return;
   const int z = blockIdx.y, z1 = z / g.nb2, z2 = z % g.nb2;
@@ -560,11 +577,11 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
   const int nt = gridDim.x, bid = blockIdx.x;
   const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
   const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
-  // groups of up to 8 tile rows, walked column by column
-  const int gsz = 8 * g.tiles_n;
+  // groups of up to g.grp tile rows, walked column by column
+  const int gsz = g.grp * g.tiles_n;
   const int grp = tile / gsz, in_grp = tile - grp * gsz;
-  const int rows_in_grp = min(8, g.tiles_m - grp * 8);
-  const int tm = grp * 8 + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
+  const int rows_in_grp = min(g.grp, g.tiles_m - grp * g.grp);
+  const int tm = grp * g.grp + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
   const int m0 = tm * BM, n0 = tn * BN;
   const int nk = g.K / BKT;
 
@@ -835,6 +852,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   a.alpha = d.alpha; a.bias = d.bias; a.resid = d.resid;
   a.out_f32 = d.out_f32; a.out_act = d.out_act; a.out_act2 = d.out_act2; a.aux = d.aux;
   a.epi = d.epi; a.causal = d.causal;
+  a.grp = 8;
   const int nbatch = d.nb1 * d.nb2;
   if (d.dtype == DT_F32) {
     a.tiles_m = (d.M + FBM - 1) / FBM;
@@ -869,6 +887,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   do {                                                                                                    \
     a.tiles_m = (d.M + BM_ - 1) / BM_;                                                                    \
     a.tiles_n = (d.N + BN_ - 1) / BN_;                                                                    \
+    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_);                                               \
     ProfScope ps(gemm_name(DT_BF16, BN_, d.ta, d.tb), s, gemm_flops(d), 0);                              \
     return launch_bf16_cfg<BM_, BN_, 2, 2, DD_>(a, d.ta, d.tb, dim3(a.tiles_m * a.tiles_n, nbatch), s); \
   } while (0)
@@ -877,6 +896,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   do {                                                                                          \
     a.tiles_m = (d.M + BM_ - 1) / BM_;                                                          \
     a.tiles_n = (d.N + BN_ - 1) / BN_;                                                          \
+    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_);                                     \
     static const char *names[4] = {NAME_ "_nt", NAME_ "_nn", NAME_ "_tt", NAME_ "_tn"};         \
     ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
     return launch_bf16_big<BM_, BN_, BK_, S_, OCC_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s);   \

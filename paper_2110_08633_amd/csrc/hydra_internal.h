@@ -55,9 +55,12 @@ void list_tensors(const ModelShape &s, std::vector<TensorInfo> *out);
 struct Slot {
   char *base = nullptr;
   float *w = nullptr, *m = nullptr, *v = nullptr, *g = nullptr;
-  bf16_t *wb = nullptr;
+  bf16_t *wb = nullptr;   // bf16 working copy of the shard, same layout as the master (dx products; the LM head's
+                          // copy is kept transposed here)
+  bf16_t *wbt = nullptr;  // block shards: every weight matrix transposed ([out, in]) at the matrix's own offset, so
+                          // that forward products have both operands contraction-contiguous
   int model = -1, shard = -1;
-  bool has_params = false, has_opt = false, wb_valid = false, grads_valid = false, dirty = false;
+  bool has_params = false, has_opt = false, wb_valid = false, wbt_valid = false, grads_valid = false, dirty = false;
   bool need_wait_load = false;  // a copy into this slot was enqueued since the compute stream last waited
   hipEvent_t ev_loaded = nullptr, ev_compute = nullptr, ev_spilled = nullptr;
   bool compute_pending = false, spill_pending = false;

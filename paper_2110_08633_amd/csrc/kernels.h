@@ -135,6 +135,22 @@ hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *sha
 hipError_t launch_cast_bf16(const float *in, bf16_t *out, int64_t n, hipStream_t s);
 // out[c, r] = bf16(in[r, c]) ; in is [R, C] row-major, out is [C, R]
 hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C, hipStream_t s);
+// Several matrices of one flat array transposed by one launch: matrix i is [R[i], C[i]] row-major at element offset
+// off[i] of src (fp32 or bf16) and is written as bf16 [C[i], R[i]] at the same offset of dst.
+constexpr int TRANSPOSE_MAX = 64;
+struct TransposeGroup {
+  int n = 0;
+  int64_t off[TRANSPOSE_MAX];
+  int R[TRANSPOSE_MAX], C[TRANSPOSE_MAX];
+  int tile0[TRANSPOSE_MAX + 1];  // filled in by the launcher: first 64x64 tile of every matrix
+  bool add(int64_t o, int r, int c) {
+    if (n >= TRANSPOSE_MAX) return false;
+    off[n] = o; R[n] = r; C[n] = c;
+    ++n;
+    return true;
+  }
+};
+hipError_t launch_transpose_group(int src_dtype, const void *src, bf16_t *dst, TransposeGroup &g, hipStream_t s);
 // fp32 [R,C] (ld_in) -> operand dtype [R,C] (ld_out)
 hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out, int64_t ld_out, int R, int C,
                            hipStream_t s);

@@ -20,8 +20,8 @@ namespace {
 uint64_t up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 // bytes a visit of a shard of `elems` parameters needs in a shard buffer: fp32 weights, Adam m and v, gradients,
-// and the bf16 working copy (same formula as the buffer planner of the context)
-uint64_t buffer_bytes(uint64_t elems) { return up(up(elems, 64) * 18, 256); }
+// and the two bf16 working copies (same formula as the buffer planner of the context)
+uint64_t buffer_bytes(uint64_t elems) { return up(up(elems, 64) * 20, 256); }
 
 }  // namespace
 

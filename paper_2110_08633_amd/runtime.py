@@ -149,4 +149,4 @@ def arena_bytes_for(cfgs, n_slots, ckpt_spill=False, lanes=1):
         ws = max(ws, k * (layer + act + grads) + scratch + 2 * act + (1 << 20), M * vpad * 4 + 4 * act + (1 << 20))
         blk = 12 * d * d + 13 * d if F == 4 * d else 4 * d * d + 2 * d * F + 9 * d + F
         max_shard = max(max_shard, V * d + T * d, k * blk, 2 * d + d * V)
-    return int(total + lanes * ws + n_slots * (max_shard * 18 + 4096) + (64 << 20))
+    return int(total + lanes * ws + n_slots * (max_shard * 20 + 4096) + (64 << 20))
