@@ -985,7 +985,18 @@ hipError_t launch_cast_transpose_bf16(const float *in, bf16_t *out, int R, int C
   return hipGetLastError();
 }
 
-template <typename SrcT>
+// four consecutive elements as floats
+__device__ __forceinline__ float4 ld4(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ float4 ld4(const bf16_t *p) {
+  const uint2 u = *(const uint2 *)p;
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                     __uint_as_float(u.y & 0xffff0000u));
+}
+
+// 64x64 tiles through LDS; 16 lanes cover a row of the tile with four elements each, on the way in (along the
+// source's columns) and on the way out (along its rows).  VEC: every matrix has R, C multiples of 4 and an offset
+// that keeps the vector accesses aligned; otherwise element by element.
+template <typename SrcT, bool VEC>
 __global__ __launch_bounds__(256) void transpose_group_kernel(const SrcT *__restrict__ src, bf16_t *__restrict__ dst,
                                                               const TransposeGroup g) {
   __shared__ float t[64][65];
@@ -997,6 +1008,28 @@ __global__ __launch_bounds__(256) void transpose_group_kernel(const SrcT *__rest
   const int c0 = (tile % tc) * 64, r0 = (tile / tc) * 64;
   const SrcT *in = src + g.off[i];
   bf16_t *out = dst + g.off[i];
+  if (VEC) {
+    const int q = (threadIdx.x & 15) * 4, p = threadIdx.x >> 4;  // 4 elements at q of line p, p + 16, ...
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int r = p + 16 * k;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (r0 + r < R && c0 + q < C) v = ld4(in + (int64_t)(r0 + r) * C + c0 + q);
+      t[r][q] = v.x; t[r][q + 1] = v.y; t[r][q + 2] = v.z; t[r][q + 3] = v.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int c = p + 16 * k;
+      if (c0 + c < C && r0 + q < R) {
+        uint2 o;
+        o.x = (uint32_t)f2bf(t[q][c]) | ((uint32_t)f2bf(t[q + 1][c]) << 16);
+        o.y = (uint32_t)f2bf(t[q + 2][c]) | ((uint32_t)f2bf(t[q + 3][c]) << 16);
+        *(uint2 *)(out + (int64_t)(c0 + c) * R + r0 + q) = o;
+      }
+    }
+    return;
+  }
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int r = ty; r < 64; r += 4)
     t[r][tx] = (r0 + r < R && c0 + tx < C) ? ldv<SrcT>(in, (int64_t)(r0 + r) * C + c0 + tx) : 0.f;
@@ -1016,11 +1049,16 @@ hipError_t launch_transpose_group(int src_dtype, const void *src, bf16_t *dst, T
     elems += (double)g.R[i] * g.C[i];
   }
   g.tile0[g.n] = tiles;
+  bool vec = ((((uintptr_t)src) & 15) == 0) && ((((uintptr_t)dst) & 7) == 0);
+  for (int i = 0; i < g.n; ++i) vec = vec && g.R[i] % 4 == 0 && g.C[i] % 4 == 0 && g.off[i] % 4 == 0;
   ProfScope ps("transpose_weights", s, 0, elems * (dt_size(src_dtype) + 2.0));
-  if (src_dtype == DT_BF16)
-    hipLaunchKernelGGL(transpose_group_kernel<bf16_t>, dim3(tiles), dim3(256), 0, s, (const bf16_t *)src, dst, g);
-  else
-    hipLaunchKernelGGL(transpose_group_kernel<float>, dim3(tiles), dim3(256), 0, s, (const float *)src, dst, g);
+  if (src_dtype == DT_BF16) {
+    if (vec) hipLaunchKernelGGL((transpose_group_kernel<bf16_t, true>), dim3(tiles), dim3(256), 0, s, (const bf16_t *)src, dst, g);
+    else hipLaunchKernelGGL((transpose_group_kernel<bf16_t, false>), dim3(tiles), dim3(256), 0, s, (const bf16_t *)src, dst, g);
+  } else {
+    if (vec) hipLaunchKernelGGL((transpose_group_kernel<float, true>), dim3(tiles), dim3(256), 0, s, (const float *)src, dst, g);
+    else hipLaunchKernelGGL((transpose_group_kernel<float, false>), dim3(tiles), dim3(256), 0, s, (const float *)src, dst, g);
+  }
   return hipGetLastError();
 }
 
