@@ -127,14 +127,18 @@ hipError_t linear_dx(int dt, int M, int N, int K, const void *dY, const void *W,
   return launch_gemm(g, st);
 }
 // dW (+)= x^T*dy : X [M,K] (ldx), dY [M,N] (ldy) -> fp32 [K,N]; acc adds to what dW holds
-hipError_t linear_dw(int dt, int M, int N, int K, const void *X, int64_t ldx, const void *dY, int64_t ldy, float *dW,
-                     int acc, hipStream_t st) {
+GemmDesc dw_desc(int dt, int M, int N, int K, const void *X, int64_t ldx, const void *dY, int64_t ldy, float *dW,
+                 int acc) {
   GemmDesc g;
   g.dtype = dt; g.ta = 1; g.tb = 1; g.M = K; g.N = N; g.K = M;
   g.A = X; g.lda = ldx; g.B = dY; g.ldb = ldy; g.ldc = N;
   g.out_f32 = dW;
   if (acc) g.resid = dW;  // every element is read and then written by the same thread
-  return launch_gemm(g, st);
+  return g;
+}
+hipError_t linear_dw(int dt, int M, int N, int K, const void *X, int64_t ldx, const void *dY, int64_t ldy, float *dW,
+                     int acc, hipStream_t st) {
+  return launch_gemm(dw_desc(dt, M, N, K, X, ldx, dY, ldy, dW, acc), st);
 }
 
 #define CK(call)                                \
@@ -305,10 +309,8 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
   } else {
     CK(launch_colsum(DT_F32, dx2, d, W.G + o.b_proj, Z.red, M, d, acc, st));
   }
-  CK(linear_dw(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc, st));
   CK(linear_dx(dt, M, d, F, dx2a, W.w_proj, nullptr, L.du, EPI_DGELU, A.u, st));  // du = (dx2 Wp^T) * gelu'(u)
   // MLP up projection
-  CK(linear_dw(dt, M, F, d, A.c, d, L.du, F, W.G + o.w_fc, acc, st));
   CK(linear_dx(dt, M, F, d, L.du, W.w_fc, L.dc, nullptr, EPI_NONE, nullptr, st));
   if (fl) {
     CK(launch_layernorm_bwd_fused(L.dc, A.x1, A.mean2, A.rstd2, W.ln2_g, dx2, L.dx1, bf ? L.dact1 : nullptr, L.part2, M, d, st));
@@ -322,13 +324,11 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
   }
   // attention output projection
   const void *dx1a = bf ? (const void *)L.dact1 : (const void *)L.dx1;
-  CK(linear_dw(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc, st));
   CK(linear_dx(dt, M, d, d, dx1a, W.w_o, nullptr, Z.d_o, EPI_NONE, nullptr, st));
   // attention core
   if (fused_attn(s, dt)) CK(launch_attention_bwd(A.qkv, A.o, Z.d_o, A.lse, Z.dsum, L.dqkv, s.B, s.H, T, dh, st));
   else CK(attention_unfused_bwd(s, dt, A, Z, L.dqkv, st));
   // QKV projection
-  CK(linear_dw(dt, M, 3 * d, d, A.a, d, L.dqkv, 3 * d, W.G + o.w_qkv, acc, st));
   CK(linear_dx(dt, M, 3 * d, d, L.dqkv, W.w_qkv, L.da, nullptr, EPI_NONE, nullptr, st));
   if (fl) {
     CK(launch_layernorm_bwd_fused(L.da, x_in, A.mean1, A.rstd1, W.ln1_g, L.dx1, dx_out, bf ? dx_out_act : nullptr, L.part1, M, d, st));
@@ -345,6 +345,13 @@ hipError_t block_backward(const ModelShape &s, int dt, const BlockW &W, const fl
     CK(launch_colsum(dt, L.du, F, W.G + o.b_fc, Z.red, M, F, acc, st));
     CK(launch_colsum(dt, L.dqkv, 3 * d, W.G + o.b_qkv, Z.red, M, 3 * d, acc, st));
   }
+  // The four weight-gradient products of the block, in one launch where the kernel allows it: each alone leaves
+  // most of the chip idle (72-288 tiles, a contraction over all tokens), and nothing waits for them before Adam.
+  const GemmDesc dw[4] = {dw_desc(dt, M, d, F, A.g, F, dx2a, d, W.G + o.w_proj, acc),
+                          dw_desc(dt, M, F, d, A.c, d, L.du, F, W.G + o.w_fc, acc),
+                          dw_desc(dt, M, d, d, A.o, d, dx1a, d, W.G + o.w_o, acc),
+                          dw_desc(dt, M, 3 * d, d, A.a, d, L.dqkv, 3 * d, W.G + o.w_qkv, acc)};
+  CK(launch_gemm_group(dw, 4, st));
   return hipSuccess;
 }
 

@@ -282,8 +282,10 @@ __device__ unsigned long long g_gemm_trace[8192];
 #define TRACE_STAMP(slot)
 #endif
 
+// One tile of one product: g describes the product, bid is the workgroup's index among the nt workgroups that
+// work on it, z its batch index.
 template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
+__device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, const int bid, const int nt, const int z) {
 #ifdef HYDRA_GEMM_TRACE
   int trace_n = 0;
 #endif
@@ -300,7 +302,6 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   const int wm = wave / WN, wn = wave % WN;
   // consecutive workgroup ids are dealt round-robin to the 8 XCDs; renumber so that each XCD (own L2)
   // works on a contiguous run of tiles, which share operand rows
-  const int nt = gridDim.x, bid = blockIdx.x;
   const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
   const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
   // ... and within the run, groups of up to g.grp tile rows are walked column by column: the tiles an XCD works on
@@ -311,7 +312,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   const int tm = grp * g.grp + in_grp % rows_in_grp, tn = in_grp / rows_in_grp;
   const int m0 = tm * BM, n0 = tn * BN;
   if (g.causal == CAUSAL_SKIP_UPPER && n0 > m0 + BM - 1) return;
-  const int z = blockIdx.y, z1 = z / g.nb2, z2 = z % g.nb2;
+  const int z1 = z / g.nb2, z2 = z % g.nb2;
   const bf16_t *A = (const bf16_t *)g.A + z1 * g.sA1 + z2 * g.sA2;
   const bf16_t *B = (const bf16_t *)g.B + z1 * g.sB1 + z2 * g.sB2;
   const int64_t coff = z1 * g.sC1 + z2 * g.sC2;
@@ -444,6 +445,29 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
 #ifdef HYDRA_GEMM_TRACE
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_gemm_trace[8191] = trace_n;
 #endif
+}
+
+template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
+  gemm_bf16_tile<BM, BN, WM, WN, TA, TB, D>(g, blockIdx.x, gridDim.x, blockIdx.y);
+}
+
+// Several products of one layout in one launch (the weight-gradient products of a block: each alone has 72-288
+// tiles for the 512 tile slots of the chip and a long contraction, together they fill it): workgroups
+// tile0[i] .. tile0[i+1]-1 work on product i.
+constexpr int GEMM_GROUP_MAX = 4;
+struct GemmGroup {
+  GemmArgs p[GEMM_GROUP_MAX];
+  int tile0[GEMM_GROUP_MAX + 1];
+  int n;
+};
+
+template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_group_kernel(const GemmGroup gg) {
+  int i = 0;
+#pragma unroll 1
+  while (i + 1 < gg.n && (int)blockIdx.x >= gg.tile0[i + 1]) ++i;  // uniform over the workgroup
+  gemm_bf16_tile<BM, BN, WM, WN, TA, TB, D>(gg.p[i], blockIdx.x - gg.tile0[i], gg.tile0[i + 1] - gg.tile0[i], 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -921,6 +945,53 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   if (D == 4) HYDRA_LAUNCH(128, 64, 4);
   HYDRA_LAUNCH(128, 64, 2);
 #undef HYDRA_LAUNCH
+}
+
+static void fill_args(GemmArgs &a, const GemmDesc &d) {
+  a.A = d.A; a.B = d.B; a.M = d.M; a.N = d.N; a.K = d.K;
+  a.lda = d.lda; a.ldb = d.ldb; a.ldc = d.ldc;
+  a.nb2 = d.nb2;
+  a.sA1 = d.sA1; a.sA2 = d.sA2; a.sB1 = d.sB1; a.sB2 = d.sB2; a.sC1 = d.sC1; a.sC2 = d.sC2;
+  a.alpha = d.alpha; a.bias = d.bias; a.resid = d.resid;
+  a.out_f32 = d.out_f32; a.out_act = d.out_act; a.out_act2 = d.out_act2; a.aux = d.aux;
+  a.epi = d.epi; a.causal = d.causal;
+  a.grp = 8;
+}
+
+hipError_t launch_gemm_group(const GemmDesc *d, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  bool groupable = n <= GEMM_GROUP_MAX && d[0].dtype == DT_BF16;
+  for (int i = 0; i < n && groupable; ++i) {
+    const GemmDesc &x = d[i];
+    groupable = x.dtype == DT_BF16 && x.ta == 1 && x.tb == 1 && x.causal == CAUSAL_NONE && x.nb1 * x.nb2 == 1 &&
+                x.M > 0 && x.N > 0 && x.K >= 24 * BK && !(x.lda & 7) && !(x.ldb & 7) && !(((uintptr_t)x.A) & 15) &&
+                !(((uintptr_t)x.B) & 15);
+  }
+  if (!groupable) {  // other layouts, dtypes or short contractions: one launch each
+    for (int i = 0; i < n; ++i) {
+      hipError_t e = launch_gemm(d[i], s);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  GemmGroup gg;
+  gg.n = n;
+  int tiles = 0;
+  double flops = 0;
+  for (int i = 0; i < n; ++i) {
+    GemmArgs &a = gg.p[i];
+    fill_args(a, d[i]);
+    a.tiles_m = (d[i].M + 127) / 128;
+    a.tiles_n = (d[i].N + 63) / 64;
+    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, 128, 64);
+    gg.tile0[i] = tiles;
+    tiles += a.tiles_m * a.tiles_n;
+    flops += gemm_flops(d[i]);
+  }
+  for (int i = n; i <= GEMM_GROUP_MAX; ++i) gg.tile0[i] = tiles;
+  ProfScope ps("gemm_bf16_x64_tn_group", s, flops, 0);
+  hipLaunchKernelGGL((gemm_bf16_group_kernel<128, 64, 2, 2, 1, 1, 4>), dim3(tiles), dim3(256), 0, s, gg);
+  return hipGetLastError();
 }
 
 }  // namespace hydra

@@ -52,6 +52,9 @@ struct GemmDesc {
 };
 
 hipError_t launch_gemm(const GemmDesc &g, hipStream_t s);
+// n products in one launch where they allow it (bf16, both operands stored with the contraction index strided, no
+// batching, contraction of at least 1536): the weight-gradient products of a block; otherwise one launch each
+hipError_t launch_gemm_group(const GemmDesc *g, int n, hipStream_t s);
 
 // x0[m,:] = wte[tok[m],:] + wpe[m % T,:]
 hipError_t launch_embed_fwd(const int32_t *tok, const float *wte, const float *wpe, float *x0, int M, int T, int d,
