@@ -900,7 +900,11 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   // plain products whose operands both have the contraction index contiguous go to the direct-to-LDS kernel:
   // 256x256 tiles once they fill three quarters of the CUs, else 128x64 tiles.  Operands stored the other way
   // round need two half-rate transposing LDS reads per fragment, which takes the advantage away (measured).
-  if (d.ta == 0 && d.tb == 0) tile = t256 >= 192 ? 4 : 10;
+  // (128x64 tiles: three LDS stages and two blocks per CU; with more than 512 tiles, two stages and three blocks per
+  // CU, which takes such a product through in one round of tiles - measured 15.3 against 16.5 us at 2048x2304x768 -
+  // while with fewer tiles the shallower pipeline only costs: 30.6 against 18.9 us at 2048x768x3072)
+  if (d.ta == 0 && d.tb == 0)
+    tile = t256 >= 192 ? 4 : ((long)((d.M + 127) / 128) * ((d.N + 63) / 64) > 512 ? 12 : 10);
   // too few 128x64 tiles to occupy half the CUs (the d x d weight gradient): 64x64 tiles measured a third faster
   else if (tile == 2 && (long)((d.M + 127) / 128) * ((d.N + 63) / 64) * nbatch < 128 && d.M > 64) tile = 3;
   if (force_tile) tile = force_tile;
@@ -933,6 +937,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   if (plain && tile == 9) HYDRA_LAUNCH_BIG(128, 64, 32, 4, 2, "gemm_bf16_d128x64");
   if (plain && tile == 10) HYDRA_LAUNCH_BIG(128, 64, 64, 3, 2, "gemm_bf16_d128x64k64");
   if (plain && tile == 11) HYDRA_LAUNCH_BIG(128, 128, 64, 3, 1, "gemm_bf16_d128x128k64");
+  if (plain && tile == 12) HYDRA_LAUNCH_BIG(128, 64, 64, 2, 3, "gemm_bf16_d128x64k64s2");
 #undef HYDRA_LAUNCH_BIG
   if (tile >= 4) tile = 2;
   if (tile == 1) {
