@@ -968,9 +968,10 @@ hipError_t launch_gemm_group(const GemmDesc *d, int n, hipStream_t s) {
   bool groupable = n <= GEMM_GROUP_MAX && d[0].dtype == DT_BF16;
   for (int i = 0; i < n && groupable; ++i) {
     const GemmDesc &x = d[i];
+    // (a product with more than a round of 128x64 tiles fills the chip by itself and may want another tile)
     groupable = x.dtype == DT_BF16 && x.ta == 1 && x.tb == 1 && x.causal == CAUSAL_NONE && x.nb1 * x.nb2 == 1 &&
                 x.M > 0 && x.N > 0 && x.K >= 24 * BK && !(x.lda & 7) && !(x.ldb & 7) && !(((uintptr_t)x.A) & 15) &&
-                !(((uintptr_t)x.B) & 15);
+                !(((uintptr_t)x.B) & 15) && (long)((x.M + 127) / 128) * ((x.N + 63) / 64) <= 512;
   }
   if (!groupable) {  // other layouts, dtypes or short contractions: one launch each
     for (int i = 0; i < n; ++i) {
