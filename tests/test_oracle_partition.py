@@ -85,7 +85,7 @@ def test_library_partitioner_equals_oracle_on_the_library_footprint(name):
 
 
 def test_footprint_grows_with_the_parts_it_names():
-    """18 bytes per parameter of shard buffer (fp32 w, m, v, g + bf16 copy) is a lower bound; micro-batches do
+    """18 bytes per parameter of shard buffer (fp32 w, m, v, g + one bf16 copy; the library keeps two) is a lower bound; micro-batches do
     not change it (activation memory is that of one micro-batch)."""
     cfg = SI.CONFIGS["gpt2s"]
     desc = H.model_desc(cfg, 1e-4)
