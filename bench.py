@@ -177,6 +177,8 @@ def main():
     ap.add_argument("--graphs", action="store_true",
                     help="replay block-shard visits as HIP graphs (halves the host's enqueue time; the device is the "
                          "bottleneck at this workload, so the throughput does not move)")
+    ap.add_argument("--ckpt-spill", action="store_true",
+                    help="boundary activations travel through host DRAM between visits (HYDRA_FLAG_CKPT_SPILL)")
     ap.add_argument("--layers", type=int, default=0, help="cut the model depth (other configs than the default: a "
                     "depth-reduced copy with full widths; reported in config)")
     ap.add_argument("--models", type=int, default=0, help="number of models (default: the config's)")
@@ -202,6 +204,8 @@ def main():
         EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
     if args.graphs:
         EXTRA_FLAGS |= H.FLAG_GRAPHS
+    if args.ckpt_spill:
+        EXTRA_FLAGS |= H.FLAG_CKPT_SPILL
     cfg = dict(SI.CONFIGS[args.config])
     if args.micro > 1:
         cfg["n_micro"] = args.micro
@@ -225,7 +229,7 @@ def main():
                                f"F{cfg['F']} V{cfg['V']}), B{cfg['B']} T{cfg['T']}, {cfg['k']}-layer shards alternated by "
                                "Sharded-LRTF, bf16 MFMA + fp32 master/Adam, seeded N(0,0.02) weights, uniform tokens"
                                + (" [depth / model count reduced on the command line]" if args.layers or args.models else ""),
-                   "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes, "hip_graphs": args.graphs,
+                   "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes, "hip_graphs": args.graphs, "checkpoints_through_host": args.ckpt_spill,
                    "micro_batches_per_visit": args.micro, "tokens_per_step": tokens_per_step},
         "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),
                  "d2h_GB_per_step": round(main_run["d2h"] / args.steps / 1e9, 3),
