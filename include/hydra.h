@@ -198,7 +198,13 @@ hydra_status hydra_kernel_stats(hydra_ctx *ctx, int32_t index, char name[64], ui
                                 double *total_ms, double *flops, double *bytes);
 hydra_status hydra_kernel_stats_reset(hydra_ctx *ctx);
 /* Swap / compute overlap (context created with HYDRA_FLAG_OVERLAP; HYDRA_E_STATE otherwise).  Both synchronise
- * the context's streams first.  The reset forgets all intervals recorded so far. */
+ * the context's streams first.  The reset forgets all intervals recorded so far.  With the environment variable
+ * HYDRA_TRACE_DUMP=<file>, hydra_overlap_stats also writes one line per interval to that file (kind, model,
+ * shard, start ms, end ms, bytes) for timeline studies.
+ *
+ * Other environment variables read by the library (experiments; the defaults are the measured best):
+ * HYDRA_COPY_BLOCKS (workgroups of the write-back copy kernel, default 32), HYDRA_GEMM_TILE and HYDRA_GEMM_D
+ * (force a tile configuration / the number of contraction slices in flight of the bf16 products). */
 hydra_status hydra_overlap_stats(hydra_ctx *ctx, hydra_overlap *out);
 hydra_status hydra_overlap_reset(hydra_ctx *ctx);
 
