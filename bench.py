@@ -257,14 +257,15 @@ def main():
         if args.extra_micro > 1 and args.micro == 1:
             # same models, shards and buffers, but every shard visit runs several micro-batches while the shard is
             # resident: the state traffic per step is unchanged and serves that many times the tokens
-            mc = dict(cfg, n_micro=args.extra_micro)
-            o = measure(mc, n_models, "spill", max(2, args.steps // 2), 1, False, R, H, torch)
             steps_m = max(2, args.steps // 2)
-            out[f"spill_micro{args.extra_micro}"] = {
-                "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
-                "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
-                "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"],
-                "overlap": overlap_report(o, steps_m)}
+            for nm in (args.extra_micro, 2 * args.extra_micro):
+                mc = dict(cfg, n_micro=nm)
+                o = measure(mc, n_models, "spill", steps_m, 1, False, R, H, torch)
+                out[f"spill_micro{nm}"] = {
+                    "value": round(tokens_per_step * nm * steps_m / o["seconds"], 1), "unit": "tokens/s",
+                    "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * nm,
+                    "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"],
+                    "overlap": overlap_report(o, steps_m)}
             # the same 4x tokens per shard visit as ONE micro-batch of 4x the samples: activation memory grows
             # fourfold (no issue on a 288 GB part), the GEMMs become four times larger and fill the chip
             bc = dict(cfg, B=cfg["B"] * args.extra_micro)
