@@ -502,10 +502,11 @@ template <int BKT> __device__ __forceinline__ int kc_swz_t(int row) {
   return BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <int R, int RCL, int BKT>
+template <int R, int RCL, int BKT, int NW>
 struct DirectMover {
   static constexpr int CPRT = BKT / 8;             // 16-byte chunks per row of a contraction-contiguous tile
-  static constexpr int N = R * CPRT / 256;         // chunks per thread and slice
+  static constexpr int N = R * CPRT / (64 * NW);   // chunks per thread and slice (NW wavefronts share the work)
+  static_assert(N * 64 * NW == R * CPRT, "the slice divides evenly over the wavefronts");
   static constexpr int CPK = R / 8;
   const bf16_t *base;
   int64_t kstep;
@@ -521,7 +522,7 @@ struct DirectMover {
     }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int p = (i * 4 + wave) * 64 + lane;  // LDS chunk this lane fills
+      const int p = (i * NW + wave) * 64 + lane;  // LDS chunk this lane fills
       if (!RCL) {
         int row = p / CPRT;
         const int kc = (p % CPRT) ^ kc_swz_t<BKT>(row);
@@ -538,23 +539,24 @@ struct DirectMover {
   // chunk i of slice t into the operand's tile at lds
   __device__ __forceinline__ void issue(int i, int t, bf16_t *lds, int wave) const {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + t * kstep + off[i]),
-                                     (__attribute__((address_space(3))) void *)(lds + (i * 4 + wave) * 64 * 8), 16, 0, 0);
+                                     (__attribute__((address_space(3))) void *)(lds + (i * NW + wave) * 64 * 8), 16, 0, 0);
   }
 };
 
-// LDS addresses of a wavefront's operand fragments: NF groups of 32 rows from row rb0 on.  Only NF or BKT/16
-// per-lane offsets are kept; the other index enters as a compile-time constant.
-template <int R, int RCL, int NF, int BKT>
+// LDS addresses of a wavefront's operand fragments: NF groups of 32 rows from row rb0 on, contraction steps
+// kbase .. kbase + KSW - 1 of a slice.  Only NF or KSW per-lane offsets are kept; the other index enters as a
+// compile-time constant.
+template <int R, int RCL, int NF, int BKT, int KSW>
 struct FragAddr {
   static constexpr int CPRT = BKT / 8;
   static constexpr int CPK = R / 8;
-  static constexpr int NO = RCL ? NF : BKT / 16;
+  static constexpr int NO = RCL ? NF : KSW;
   int o[NO];
-  __device__ __forceinline__ void init(int rb0, int lane) {
+  __device__ __forceinline__ void init(int rb0, int lane, int kbase) {
     if (!RCL) {
       const int row = rb0 + (lane & 31), s = kc_swz_t<BKT>(row), hi = lane >> 5;
 #pragma unroll
-      for (int kk = 0; kk < BKT / 16; ++kk) o[kk] = (row * CPRT + ((kk * 2 + hi) ^ s)) * 8;
+      for (int kk = 0; kk < KSW; ++kk) o[kk] = (row * CPRT + (((kbase + kk) * 2 + hi) ^ s)) * 8;
     } else {
       const int G = lane >> 4, sl = lane & 15;
       const int k0 = (G >> 1) * 8 + (sl >> 2);
@@ -562,7 +564,7 @@ struct FragAddr {
 #pragma unroll
       for (int f = 0; f < NF; ++f) {
         const int m = m0 + f * 32;
-        o[f] = (k0 * CPK + ((m >> 3) ^ rc_swz<R>(k0))) * 8 + ((m >> 2) & 1) * 4;
+        o[f] = (k0 * CPK + ((m >> 3) ^ rc_swz<R>(k0))) * 8 + ((m >> 2) & 1) * 4 + kbase * 16 * CPK * 8;
       }
     }
   }
@@ -580,24 +582,28 @@ template <int n> __device__ __forceinline__ void wait_loads_le() {
   __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | 0x0070);
 }
 
-template <int BM, int BN, int TA, int TB, int BKT, int S, int OCC>
-__global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs g) {
-  constexpr int WTM = BM / 2, WTN = BN / 2;
+template <int BM, int BN, int TA, int TB, int BKT, int S, int OCC, int KW, int WGN>
+__global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_big_kernel(const GemmArgs g) {
+  constexpr int WTM = BM / 2, WTN = BN / WGN;
   constexpr int MI = WTM / 32, NJ = WTN / 32;
-  constexpr int KS = BKT / 16;                   // contraction steps of one MFMA per slice
+  constexpr int WPG = 2 * WGN;                   // wavefronts of a group: 2 x WGN over the tile
+  constexpr int NW = WPG * KW;                   // KW groups; group kg takes steps kg*KS.. of a slice
+  constexpr int KS = BKT / 16 / KW;              // contraction steps of one MFMA per slice and wavefront
   constexpr int STAGE = (BM + BN) * BKT;         // elements per stage
-  constexpr int NLA = DirectMover<BM, TA, BKT>::N, NLB = DirectMover<BN, TB, BKT>::N, NL = NLA + NLB;
+  constexpr int NLA = DirectMover<BM, TA, BKT, NW>::N, NLB = DirectMover<BN, TB, BKT, NW>::N, NL = NLA + NLB;
   constexpr int G = KS * MI;                     // groups of NJ MFMAs per slice
   constexpr int QB = (KS - 1) * MI;              // the barrier sits before this group
-  static_assert(KS % 2 == 0 && NL <= G && S >= 2, "pipeline shape");
+  static_assert(KS % 2 == 0 && KS * KW * 16 == BKT && NL <= G && S >= 2, "pipeline shape");
+  static_assert(KW == 1 || MI % KW == 0, "the groups share the write-out by rows of fragments");
   extern __shared__ __attribute__((aligned(16))) bf16_t lds_dyn[];
 #ifdef HYDRA_GEMM_TRACE
   int trace_n = 0;
 #endif
 
+  TRACE_STAMP(0);
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int kg = wave / WPG, wig = wave % WPG, wm = wig / WGN, wn = wig % WGN;
   const int nt = gridDim.x, bid = blockIdx.x;
   const int xcd = bid & 7, per = nt >> 3, rem = nt & 7;
   const int tile = xcd * per + min(xcd, rem) + (bid >> 3);
@@ -609,14 +615,14 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
   const int m0 = tm * BM, n0 = tn * BN;
   const int nk = g.K / BKT;
 
-  DirectMover<BM, TA, BKT> ma;
-  DirectMover<BN, TB, BKT> mb;
+  DirectMover<BM, TA, BKT, NW> ma;
+  DirectMover<BN, TB, BKT, NW> mb;
   ma.init((const bf16_t *)g.A, g.lda, m0, g.M, tid);
   mb.init((const bf16_t *)g.B, g.ldb, n0, g.N, tid);
-  FragAddr<BM, TA, MI, BKT> fa;
-  FragAddr<BN, TB, NJ, BKT> fb;
-  fa.init(wm * WTM, lane);
-  fb.init(wn * WTN, lane);
+  FragAddr<BM, TA, MI, BKT, KS> fa;
+  FragAddr<BN, TB, NJ, BKT, KS> fb;
+  fa.init(wm * WTM, lane, kg * KS);
+  fb.init(wn * WTN, lane, kg * KS);
 
   // load l (0..NL-1: first A's chunks, then B's) of slice sl into stage sg
   auto issue = [&](int l, int sl, int sg) {
@@ -648,6 +654,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
   if (nk >= S) wait_loads_le<(S - 2) * NL + HEAD>();
   else wait_loads_le<0>();
   __builtin_amdgcn_s_barrier();
+  TRACE_STAMP(4);
   bf16x8_t af[2][MI], bfr[2][NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i) af[0][i] = fa.get(lds_dyn, i, 0);
@@ -663,12 +670,13 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
     const int st_next = (st + 1 == S) ? 0 : st + 1;   // stage of slice t + 1
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      if (kk + 1 < KS) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) af[(kk + 1) & 1][i] = fa.get(as, i, kk + 1);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) bfr[(kk + 1) & 1][j] = fb.get(bs, j, kk + 1);
-      } else if (!GUARD || t + 1 < nk) {
+      // fragments of the next step: step kk + 1 of this slice, or step 0 of slice t + 1 once everybody is through
+      // with slice t.  Their MI + NJ reads go out one by one between this step's MI * NJ MFMAs, in the order the
+      // next step needs them (a wavefront that issues them in a burst stands still until LDS has taken them all,
+      // and with one wavefront per SIMD the matrix pipe stands still with it).
+      const bool more = (kk + 1 < KS) || !GUARD || (t + 1 < nk);
+      const bf16_t *na = as, *nb = bs;
+      if (kk + 1 == KS && more) {
         TRACE_STAMP(1);
         // slice t + 1 must have landed (S - 2 younger slices may stay in flight) and this wavefront's reads of
         // slice t must be complete before anybody overwrites its stage
@@ -677,18 +685,29 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
         TRACE_STAMP(2);
         __builtin_amdgcn_s_barrier();
         TRACE_STAMP(3);
-        const bf16_t *an = lds_dyn + st_next * STAGE, *bn = an + BM * BKT;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) af[0][i] = fa.get(an, i, 0);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) bfr[0][j] = fb.get(bn, j, 0);
+        na = lds_dyn + st_next * STAGE;
+        nb = na + BM * BKT;
       }
+      constexpr int NR = MI + NJ, NS = MI * NJ;
+      const int nkk = (kk + 1 < KS) ? kk + 1 : 0, nbuf = (kk + 1) & 1;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+        for (int j = 0; j < NJ; ++j) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+          if (more) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+              if (r * NS / NR == i * NJ + j) {  // read r: a0, b0 .. b(NJ-1), a1 .. a(MI-1)
+                if (r == 0) af[nbuf][0] = fa.get(na, 0, nkk);
+                else if (r <= NJ) bfr[nbuf][r - 1] = fb.get(nb, r - 1, nkk);
+                else af[nbuf][r - NJ] = fa.get(na, r - NJ, nkk);
+              }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
         __builtin_amdgcn_sched_barrier(0);
         const int q = kk * MI + i;
         if (q >= QB) {  // after the barrier: the head of slice t + S goes into the stage slice t just left
@@ -719,10 +738,47 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
                    ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
                    ((((uintptr_t)g.out_act | (uintptr_t)g.out_act2 | (uintptr_t)g.aux) & 7) == 0);
   constexpr int SP = WTN + 4;
-  static_assert(4 * 32 * SP * 4 <= S * STAGE * 2, "staging patches must fit the stages");
+  static_assert(NW * 32 * SP * 4 <= S * STAGE * 2, "staging patches must fit the stages");
+  if constexpr (KW > 1) {
+    // Each group holds a partial sum of the whole tile.  Group kg writes out the fragment rows i with i % KW == kg:
+    // it hands its other rows to their owner through LDS (lane-contiguous 16-byte pieces, one area per position in
+    // the 2 x 2 arrangement and owner) and adds what it receives (two terms: the order cannot matter).
+    static_assert(KW <= 2, "one partner per fragment row");
+    constexpr int XA = (MI / KW) * NJ * 4 * 64;  // 16-byte pieces per area
+    static_assert(WPG * KW * XA * 16 <= S * STAGE * 2, "exchange areas must fit the stages");
+    f32x4_t *const xch = (f32x4_t *)lds_dyn + wig * KW * XA + lane;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+      if (i % KW != kg) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f32x4_t v = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+            xch[(i % KW) * XA + (((i / KW) * NJ + j) * 4 + q) * 64] = v;
+          }
+      }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+      if (i % KW == kg) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4_t v = xch[(i % KW) * XA + (((i / KW) * NJ + j) * 4 + q) * 64];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][q * 4 + r] += v[r];
+          }
+      }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();  // the staging patches overlap the exchange area
+  }
   float *const patch = (float *)lds_dyn + wave * 32 * SP;
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
+    if (KW > 1 && i % KW != kg) continue;
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -743,17 +799,17 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_big_kernel(const GemmArgs 
 #endif
 }
 
-template <int BM, int BN, int BKT, int S, int OCC>
+template <int BM, int BN, int BKT, int S, int OCC, int KW = 1, int WGN = 2>
 static hipError_t launch_bf16_big(const GemmArgs &a, int ta, int tb, int ntiles, hipStream_t s) {
   constexpr size_t lds = (size_t)S * (BM + BN) * BKT * 2;
   static_assert(lds <= 160 * 1024, "LDS per CU");
 #define HYDRA_BIG(TA_, TB_)                                                                                   \
   do {                                                                                                         \
-    auto kern = gemm_bf16_big_kernel<BM, BN, TA_, TB_, BKT, S, OCC>;                                           \
+    auto kern = gemm_bf16_big_kernel<BM, BN, TA_, TB_, BKT, S, OCC, KW, WGN>;                                          \
     static hipError_t attr = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                  (int)lds);                                                    \
     if (attr != hipSuccess) return attr;                                                                       \
-    hipLaunchKernelGGL(kern, dim3(ntiles), dim3(256), lds, s, a);                                              \
+    hipLaunchKernelGGL(kern, dim3(ntiles), dim3(128 * WGN * KW), lds, s, a);                                         \
   } while (0)
   if (ta == 0 && tb == 0) HYDRA_BIG(0, 0);
   else if (ta == 0 && tb == 1) HYDRA_BIG(0, 1);
@@ -903,8 +959,17 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   // (128x64 tiles: three LDS stages and two blocks per CU; with more than 512 tiles, two stages and three blocks per
   // CU, which takes such a product through in one round of tiles - measured 15.3 against 16.5 us at 2048x2304x768 -
   // while with fewer tiles the shallower pipeline only costs: 30.6 against 18.9 us at 2048x768x3072)
-  if (d.ta == 0 && d.tb == 0)
-    tile = t256 >= 192 ? 4 : ((long)((d.M + 127) / 128) * ((d.N + 63) / 64) > 512 ? 12 : 10);
+  // Between the two: a round of 256x128 tiles worked on by eight wavefronts (two groups that split every slice's
+  // contraction steps) once there are 200 of them (measured 22.8 against 26.1 us at 2048x4096x1024, 26.5 against
+  // 33.5 us at 1024x6400x1600), and one round of 128x128 tiles for long contractions (39.9 against 44.3 us at
+  // 1024x4096x4096, 131 against 156 us at 1024x4096x16384).
+  if (d.ta == 0 && d.tb == 0) {
+    const long t256x128 = (long)((d.M + 255) / 256) * ((d.N + 127) / 128);
+    if (t256 >= 192) tile = 4;
+    else if (t256x128 >= 200) tile = 16;
+    else if (t128 >= 192 && t128 <= 256 && d.K >= 2048) tile = 11;
+    else tile = (long)((d.M + 127) / 128) * ((d.N + 63) / 64) > 512 ? 12 : 10;
+  }
   // too few 128x64 tiles to occupy half the CUs (the d x d weight gradient): 64x64 tiles measured a third faster
   else if (tile == 2 && (long)((d.M + 127) / 128) * ((d.N + 63) / 64) * nbatch < 128 && d.M > 64) tile = 3;
   if (force_tile) tile = force_tile;
@@ -929,6 +994,16 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
     ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
     return launch_bf16_big<BM_, BN_, BK_, S_, OCC_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s);   \
   } while (0)
+#define HYDRA_LAUNCH_BIG2(BM_, BN_, BK_, S_, OCC_, NAME_) HYDRA_LAUNCH_BIGW(BM_, BN_, BK_, S_, OCC_, 2, 2, NAME_)
+#define HYDRA_LAUNCH_BIGW(BM_, BN_, BK_, S_, OCC_, KW_, WGN_, NAME_)                                      \
+  do {                                                                                          \
+    a.tiles_m = (d.M + BM_ - 1) / BM_;                                                          \
+    a.tiles_n = (d.N + BN_ - 1) / BN_;                                                          \
+    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_);                                     \
+    static const char *names[4] = {NAME_ "_nt", NAME_ "_nn", NAME_ "_tt", NAME_ "_tn"};         \
+    ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
+    return launch_bf16_big<BM_, BN_, BK_, S_, OCC_, KW_, WGN_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s); \
+  } while (0)
   if (plain && tile == 4) HYDRA_LAUNCH_BIG(256, 256, 32, 4, 1, "gemm_bf16_256x256");
   if (plain && tile == 5) HYDRA_LAUNCH_BIG(256, 128, 32, 5, 1, "gemm_bf16_256x128");
   if (plain && tile == 6) HYDRA_LAUNCH_BIG(128, 128, 32, 4, 2, "gemm_bf16_d128x128");
@@ -938,7 +1013,17 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   if (plain && tile == 10) HYDRA_LAUNCH_BIG(128, 64, 64, 3, 2, "gemm_bf16_d128x64k64");
   if (plain && tile == 11) HYDRA_LAUNCH_BIG(128, 128, 64, 3, 1, "gemm_bf16_d128x128k64");
   if (plain && tile == 12) HYDRA_LAUNCH_BIG(128, 64, 64, 2, 3, "gemm_bf16_d128x64k64s2");
+  if (plain && tile == 13) HYDRA_LAUNCH_BIG2(128, 64, 64, 3, 2, "gemm_bf16_w8_128x64k64");
+  if (plain && tile == 14) HYDRA_LAUNCH_BIG2(128, 64, 64, 2, 3, "gemm_bf16_w8_128x64k64s2");
+  if (plain && tile == 15) HYDRA_LAUNCH_BIG2(128, 128, 64, 3, 1, "gemm_bf16_w8_128x128k64");
+  if (plain && tile == 16) HYDRA_LAUNCH_BIG2(256, 128, 64, 3, 1, "gemm_bf16_w8_256x128k64");
+  if (plain && tile == 17) HYDRA_LAUNCH_BIGW(256, 256, 32, 4, 1, 1, 4, "gemm_bf16_w8_256x256");
+  if (plain && tile == 18) HYDRA_LAUNCH_BIGW(256, 256, 64, 2, 1, 1, 4, "gemm_bf16_w8_256x256k64");
+  if (plain && tile == 19) HYDRA_LAUNCH_BIGW(256, 256, 32, 5, 1, 1, 4, "gemm_bf16_w8_256x256s5");
+  if (plain && tile == 20) HYDRA_LAUNCH_BIGW(256, 128, 32, 5, 1, 1, 4, "gemm_bf16_w8s_256x128");
 #undef HYDRA_LAUNCH_BIG
+#undef HYDRA_LAUNCH_BIG2
+#undef HYDRA_LAUNCH_BIGW
   if (tile >= 4) tile = 2;
   if (tile == 1) {
     HYDRA_LAUNCH(128, 128, 2);

@@ -219,6 +219,40 @@ def test_single_slice_gemm_under_concurrency(H):
         assert_close(o.cpu().numpy(), ref, 1e-5, "single-slice gemm")
 
 
+# products large enough for each tile shape the launcher picks for contraction-contiguous operands (256x256,
+# 256x128 with eight wavefronts, 128x128, 128x64 in both pipeline depths), with and without ragged edges
+LARGE_NT = [(1024, 12288, 1024), (1000, 12200, 512), (2048, 4096, 1024), (2000, 4100, 1024), (1024, 4096, 4096),
+            (1000, 4000, 2048), (2048, 2304, 768), (2048, 768, 2304), (1100, 3000, 192)]
+
+
+@pytest.mark.parametrize("M,N,K", LARGE_NT)
+def test_gemm_large_tiles_on_sampled_rows(H, M, N, K):
+    """Full-size products against the oracle on sampled rows of C (all columns): the rows at tile boundaries and
+    a random set; the fp32 and the bf16 output, bias and residual included."""
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    Bt = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
+    bias = rng.standard_normal(N).astype(np.float32)
+    resid = rng.standard_normal((M, N)).astype(np.float32)
+    out = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    out_act = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    H.hydra_op_gemm(1, 0, 0, M, N, K, 0.25, dev(A, torch.bfloat16), K, dev(Bt, torch.bfloat16), K, dev(bias),
+                    dev(resid), out, out_act, N)
+    torch.cuda.synchronize()
+    rows = {0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 257, M // 2, M - 129, M - 33, M - 2, M - 1}
+    rows |= set(int(r) for r in rng.integers(0, M, 48))
+    rows = np.array(sorted(r for r in rows if 0 <= r < M))
+    ref = 0.25 * D.linear_fwd(A[rows].astype(np.float64), Bt.T.astype(np.float64)) + bias + resid[rows]
+    assert_close(out[rows].cpu().numpy(), ref, 1e-5, "large gemm f32 out")
+    assert_close(out_act[rows].float().cpu().numpy(), ref, 8e-3, "large gemm bf16 out")
+    # every element was written exactly once with a finite value: compare the checksum of all rows in fp64
+    full = out.double().sum(dim=1).cpu().numpy()
+    ref_sum = 0.25 * (A.astype(np.float64) @ Bt.astype(np.float64).sum(axis=0)) + bias.astype(np.float64).sum() \
+        + resid.astype(np.float64).sum(axis=1)
+    scale = np.sqrt(N) * np.abs(ref).max()
+    assert np.abs(full - ref_sum).max() <= 1e-4 * scale, "row checksums"
+
+
 @pytest.mark.parametrize("B,Hh,T,dh", [(2, 3, 72, 64), (1, 2, 264, 64), (2, 1, 136, 128), (1, 4, 512, 64), (1, 1, 8, 64)])
 def test_fused_attention_forward_and_backward(H, B, Hh, T, dh):
     """Fused causal attention (scores, mask, softmax, PV in one kernel; backward without a stored probability
