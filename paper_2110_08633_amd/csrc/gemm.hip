@@ -475,13 +475,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_group_kernel(const GemmGroup
 // multiple of the slice width) with large tiles.
 //
 // Two per-CU rates bound a bf16 GEMM on this chip besides the MFMA rate (about
-// 4096 flop per clock and CU): the vector-memory path delivers 64 bytes per
-// clock, so a tile needs 2*BM*BN/(BM+BN) >= 64 flop per operand byte just to
-// keep up (128x128 tiles sit exactly on that line, 256x256 tiles need half of
-// it), and LDS serves every byte once on its way in and once per wavefront that
-// multiplies it.  Hence
-//   - a wavefront owns (BM/2) x (BN/2) results (up to 128x128, accumulators in
-//     up to 256 registers), one block per CU;
+// 4096 flop per clock and CU): the vector-memory path delivers about 60 bytes
+// per clock (measured; 43 for rows of only 64 bytes), so a tile needs
+// 2*BM*BN/(BM+BN) >= 64 flop per operand byte just to keep up (128x128 tiles
+// sit exactly on that line, 256x256 tiles need half of it), and LDS serves
+// every byte once on its way in and once per wavefront that multiplies it.
+// Hence
+//   - a group of 2 x WGN wavefronts covers the tile, a wavefront owns
+//     (BM/2) x (BN/WGN) results (up to 128x128, accumulators in up to 256
+//     registers); KW such groups may share a tile, group kg multiplying
+//     contraction steps kg*KS .. kg*KS+KS-1 of every slice into accumulators
+//     of its own, which are summed through LDS before the write-out: more
+//     wavefronts to hide latency behind, at unchanged LDS traffic;
 //   - operand slices go from global memory straight into LDS (16 bytes per
 //     lane; lane l of a wavefront fills LDS base + 16*l), so nothing is staged
 //     in registers and no LDS store is issued; the XOR swizzle of the tiles is
@@ -493,8 +498,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_group_kernel(const GemmGroup
 //     then every wavefront has read that slice completely, so its stage is
 //     handed to the loads of slice t + S, and the first fragments of slice
 //     t + 1 are read while the last MFMAs of slice t run;
-//   - fragments for step kk + 1 are read while the MFMAs of step kk run (one
-//     wavefront per SIMD: the overlap has to come from inside it).
+//   - fragments for step kk + 1 are read one by one between the MFMAs of step
+//     kk (one wavefront per SIMD: the overlap has to come from inside it).
 // Tiles of C are numbered so that each XCD (own L2) works through groups of up
 // to 8 tile rows column by column: the operand panels of a group stay in L2.
 // ---------------------------------------------------------------------------
@@ -672,8 +677,9 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
     for (int kk = 0; kk < KS; ++kk) {
       // fragments of the next step: step kk + 1 of this slice, or step 0 of slice t + 1 once everybody is through
       // with slice t.  Their MI + NJ reads go out one by one between this step's MI * NJ MFMAs, in the order the
-      // next step needs them (a wavefront that issues them in a burst stands still until LDS has taken them all,
-      // and with one wavefront per SIMD the matrix pipe stands still with it).
+      // next step needs them and from the first MFMA on, so that the last has returned when the step ends (a
+      // wavefront that issues them in a burst stands still until LDS has taken them all, and with one wavefront
+      // per SIMD the matrix pipe stands still with it).
       const bool more = (kk + 1 < KS) || !GUARD || (t + 1 < nk);
       const bf16_t *na = as, *nb = bs;
       if (kk + 1 == KS && more) {
@@ -700,22 +706,24 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = 0; r < NR; ++r)
-              if (r * NS / NR == i * NJ + j) {  // read r: a0, b0 .. b(NJ-1), a1 .. a(MI-1)
+              if ((NS >= NR ? r : r * NS / NR) == i * NJ + j) {  // read r: a0, b0 .. b(NJ-1), a1 .. a(MI-1)
                 if (r == 0) af[nbuf][0] = fa.get(na, 0, nkk);
                 else if (r <= NJ) bfr[nbuf][r - 1] = fb.get(nb, r - 1, nkk);
                 else af[nbuf][r - NJ] = fa.get(na, r - NJ, nkk);
               }
             __builtin_amdgcn_sched_barrier(0);
           }
+          if (j == NJ - 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            const int q = kk * MI + i;
+            if (q >= QB) {  // after the barrier: the head of slice t + S goes into the stage slice t just left
+              if (q - QB < NL && (!GUARD || t + S < nk)) issue(q - QB, t + S, st);
+            } else {        // before it: the rest of slice t + S - 1
+              if (q + (G - QB) < NL && (!GUARD || t + S - 1 < nk)) issue(q + (G - QB), t + S - 1, st_prev);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
-        __builtin_amdgcn_sched_barrier(0);
-        const int q = kk * MI + i;
-        if (q >= QB) {  // after the barrier: the head of slice t + S goes into the stage slice t just left
-          if (q - QB < NL && (!GUARD || t + S < nk)) issue(q - QB, t + S, st);
-        } else {        // before it: the rest of slice t + S - 1
-          if (q + (G - QB) < NL && (!GUARD || t + S - 1 < nk)) issue(q + (G - QB), t + S - 1, st_prev);
-        }
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
@@ -994,7 +1002,6 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
     ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
     return launch_bf16_big<BM_, BN_, BK_, S_, OCC_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s);   \
   } while (0)
-#define HYDRA_LAUNCH_BIG2(BM_, BN_, BK_, S_, OCC_, NAME_) HYDRA_LAUNCH_BIGW(BM_, BN_, BK_, S_, OCC_, 2, 2, NAME_)
 #define HYDRA_LAUNCH_BIGW(BM_, BN_, BK_, S_, OCC_, KW_, WGN_, NAME_)                                      \
   do {                                                                                          \
     a.tiles_m = (d.M + BM_ - 1) / BM_;                                                          \
@@ -1005,24 +1012,11 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
     return launch_bf16_big<BM_, BN_, BK_, S_, OCC_, KW_, WGN_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s); \
   } while (0)
   if (plain && tile == 4) HYDRA_LAUNCH_BIG(256, 256, 32, 4, 1, "gemm_bf16_256x256");
-  if (plain && tile == 5) HYDRA_LAUNCH_BIG(256, 128, 32, 5, 1, "gemm_bf16_256x128");
-  if (plain && tile == 6) HYDRA_LAUNCH_BIG(128, 128, 32, 4, 2, "gemm_bf16_d128x128");
-  if (plain && tile == 7) HYDRA_LAUNCH_BIG(256, 256, 32, 5, 1, "gemm_bf16_256x256s5");
-  if (plain && tile == 8) HYDRA_LAUNCH_BIG(256, 256, 64, 2, 1, "gemm_bf16_256x256k64");
-  if (plain && tile == 9) HYDRA_LAUNCH_BIG(128, 64, 32, 4, 2, "gemm_bf16_d128x64");
   if (plain && tile == 10) HYDRA_LAUNCH_BIG(128, 64, 64, 3, 2, "gemm_bf16_d128x64k64");
   if (plain && tile == 11) HYDRA_LAUNCH_BIG(128, 128, 64, 3, 1, "gemm_bf16_d128x128k64");
   if (plain && tile == 12) HYDRA_LAUNCH_BIG(128, 64, 64, 2, 3, "gemm_bf16_d128x64k64s2");
-  if (plain && tile == 13) HYDRA_LAUNCH_BIG2(128, 64, 64, 3, 2, "gemm_bf16_w8_128x64k64");
-  if (plain && tile == 14) HYDRA_LAUNCH_BIG2(128, 64, 64, 2, 3, "gemm_bf16_w8_128x64k64s2");
-  if (plain && tile == 15) HYDRA_LAUNCH_BIG2(128, 128, 64, 3, 1, "gemm_bf16_w8_128x128k64");
-  if (plain && tile == 16) HYDRA_LAUNCH_BIG2(256, 128, 64, 3, 1, "gemm_bf16_w8_256x128k64");
-  if (plain && tile == 17) HYDRA_LAUNCH_BIGW(256, 256, 32, 4, 1, 1, 4, "gemm_bf16_w8_256x256");
-  if (plain && tile == 18) HYDRA_LAUNCH_BIGW(256, 256, 64, 2, 1, 1, 4, "gemm_bf16_w8_256x256k64");
-  if (plain && tile == 19) HYDRA_LAUNCH_BIGW(256, 256, 32, 5, 1, 1, 4, "gemm_bf16_w8_256x256s5");
-  if (plain && tile == 20) HYDRA_LAUNCH_BIGW(256, 128, 32, 5, 1, 1, 4, "gemm_bf16_w8s_256x128");
+  if (plain && tile == 16) HYDRA_LAUNCH_BIGW(256, 128, 64, 3, 1, 2, 2, "gemm_bf16_w8_256x128k64");
 #undef HYDRA_LAUNCH_BIG
-#undef HYDRA_LAUNCH_BIG2
 #undef HYDRA_LAUNCH_BIGW
   if (tile >= 4) tile = 2;
   if (tile == 1) {
