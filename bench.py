@@ -162,6 +162,32 @@ def cpu_baseline(cfg):
                        f"float32 numpy oracle, unsharded steps, {dt:.1f} s; loss {out['loss']:.4f}")
 
 
+def block_gemm_large_shapes(H, torch, iters=20):
+    """Context beside the workload's own figures: the library's GEMM entry point on the block products of the
+    largest configuration (28 layers, d 4096, F 16384, 1024 tokens per visit), where a product fills the chip:
+    HIP events over back-to-back launches, bf16 operands, bf16 result, flops = 2 M N K."""
+    res = {}
+    for name, (M, N, K) in {"qkv": (1024, 12288, 4096), "mlp_up": (1024, 16384, 4096), "mlp_down": (1024, 4096, 16384)}.items():
+        A = torch.randn((M, K), device="cuda").to(torch.bfloat16)
+        B = torch.randn((N, K), device="cuda").to(torch.bfloat16)
+        C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+        call = lambda: H.hydra_op_gemm(1, 0, 0, M, N, K, 1.0, A, K, B, K, None, None, None, C, N)
+        for _ in range(3):
+            call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        tf = 2.0 * M * N * K / us / 1e6
+        res[name] = {"MxNxK": f"{M}x{N}x{K}", "us": round(us, 1), "TFLOPs": round(tf, 1),
+                     "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -302,6 +328,7 @@ def main():
         out["gemm_aggregate"] = {"TFLOPs": round(sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12, 1),
                                  "frac_of_mfma_peak": round(sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                                  "kernel_ms_per_step": round(total_ms / args.steps, 3)}
+        out["block_gemm_large_shapes"] = block_gemm_large_shapes(H, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
