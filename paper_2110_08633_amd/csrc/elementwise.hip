@@ -113,8 +113,9 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
 hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   ProfScope ps("fill_u32", s, 0, 4.0 * n);
+  // one workgroup per 1024 elements, however many that makes: on arrays far larger than the caches a capped grid that
+  // strides through them streamed a fifth slower (measured on the Adam update: 4.6 against 5.5 TB/s at 4e8 elements)
   int64_t blocks = (n / 4 + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, value, n);
   return hipGetLastError();
@@ -985,8 +986,7 @@ hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *sha
   if (n <= 0) return hipSuccess;
   const float corr1 = (float)(1.0 - pow(beta1, (double)t)), corr2 = (float)(1.0 - pow(beta2, (double)t));
   ProfScope ps("adam", s, 0, (double)n * (shadow ? 30.0 : 28.0));
-  int64_t blocks = (n / 4 + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
+  int64_t blocks = (n / 4 + 255) / 256;  // uncapped, see launch_fill_u32
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(adam_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, m, v, g, shadow, n, (float)lr, (float)beta1,
                      (float)beta2, (float)(1.0 - beta1), (float)(1.0 - beta2), (float)eps, corr1, corr2);
@@ -1059,8 +1059,7 @@ __global__ __launch_bounds__(256) void cast_bf16_kernel(const float *__restrict_
 hipError_t launch_cast_bf16(const float *in, bf16_t *out, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   ProfScope ps("cast_bf16", s, 0, 6.0 * n);
-  int64_t blocks = (n / 4 + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
+  int64_t blocks = (n / 4 + 255) / 256;  // uncapped, see launch_fill_u32
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, in, out, n);
   return hipGetLastError();
