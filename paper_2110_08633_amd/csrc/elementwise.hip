@@ -631,10 +631,83 @@ __global__ __launch_bounds__(256) void colsum2_pass1_kernel(const T *__restrict_
   if (ry == 0 && col < N) part[(int64_t)blockIdx.y * N + col] = (float)((sh[0][cx] + sh[1][cx]) + (sh[2][cx] + sh[3][cx]));
 }
 
+// The same with four columns per thread (one 8- or 16-byte load per row) and 16 row lanes: a chunk of CH rows is one
+// batch of eight loads per thread.  Needs N0 and N1 multiples of 4 and 16-byte aligned operands; lane r adds rows
+// r, r + 16, ... in ascending order, the sixteen lanes are combined in a fixed tree.
+template <typename T> struct Vec4Ld;
+template <> struct Vec4Ld<float> {
+  static __device__ __forceinline__ void ld(const float *p, float (&o)[4]) {
+    const float4 v = *(const float4 *)p;
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  }
+};
+template <> struct Vec4Ld<bf16_t> {
+  static __device__ __forceinline__ void ld(const bf16_t *p, float (&o)[4]) {
+    const uint2 v = *(const uint2 *)p;
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+  }
+};
+template <typename T>
+__global__ __launch_bounds__(256) void colsum2_pass1_vec_kernel(const T *__restrict__ in0, int N0, float *__restrict__ part0,
+                                                                const T *__restrict__ in1, int N1, float *__restrict__ part1,
+                                                                int M) {
+  __shared__ double sh[16][65];
+  const int nb0 = (N0 + 63) / 64;
+  const bool second = (int)blockIdx.x >= nb0;
+  const T *in = second ? in1 : in0;
+  const int N = second ? N1 : N0;
+  float *part = second ? part1 : part0;
+  const int cx = threadIdx.x & 15, ry = threadIdx.x >> 4;
+  const int cb = ((int)blockIdx.x - (second ? nb0 : 0)) * 64;
+  const int col = cb + cx * 4;
+  const int r0 = blockIdx.y * CH, r1 = min(M, r0 + CH);
+  double a[4] = {0.0, 0.0, 0.0, 0.0};
+  if (col < N) {
+    constexpr int U = 8;
+    for (int rb = r0 + ry; rb < r1; rb += 16 * U) {
+      float v[U][4];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int r = rb + 16 * u;
+        if (r < r1) Vec4Ld<T>::ld(in + (int64_t)r * N + col, v[u]);
+        else v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] += v[u][j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) sh[ry][cx * 4 + j] = a[j];
+  __syncthreads();
+  const int c = threadIdx.x;
+  if (c < 64 && cb + c < N) {
+    double t[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t[k] = sh[k][c];
+#pragma unroll
+    for (int w = 1; w < 16; w *= 2)
+#pragma unroll
+      for (int k = 0; k < 16; k += 2 * w) t[k] += t[k + w];
+    part[(int64_t)blockIdx.y * N + cb + c] = (float)t[0];
+  }
+}
+
 hipError_t launch_colsum2_pass1(int dtype, const void *in0, int N0, float *part0, const void *in1, int N1, float *part1,
                                 int M, hipStream_t s) {
   dim3 grid((N0 + 63) / 64 + (N1 + 63) / 64, colsum_chunks(M));
   ProfScope ps("colsum", s, 0, (double)M * (N0 + N1) * dt_size(dtype));
+  if (N0 % 4 == 0 && N1 % 4 == 0 && ((((uintptr_t)in0) | ((uintptr_t)in1)) & 15) == 0) {
+    if (dtype == DT_BF16)
+      hipLaunchKernelGGL(colsum2_pass1_vec_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)in0, N0, part0,
+                         (const bf16_t *)in1, N1, part1, M);
+    else
+      hipLaunchKernelGGL(colsum2_pass1_vec_kernel<float>, grid, dim3(256), 0, s, (const float *)in0, N0, part0,
+                         (const float *)in1, N1, part1, M);
+    return hipGetLastError();
+  }
   if (dtype == DT_BF16)
     hipLaunchKernelGGL(colsum2_pass1_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)in0, N0, part0,
                        (const bf16_t *)in1, N1, part1, M);
@@ -645,38 +718,59 @@ hipError_t launch_colsum2_pass1(int dtype, const void *in0, int N0, float *part0
 }
 
 // Last pass of several column sums in one launch: segment i adds its nch partial rows (stride elements apart) into
-// out[0..N) (added to what out holds when acc is set).  A block takes 32 columns of one segment with 8 row lanes:
-// lane r adds rows r, r + 8, ... in ascending order in double (eight loads in flight at a time), the eight lanes
-// are combined in a fixed tree.
-constexpr int FIN_COLS = 32, FIN_LANES = 8;
+// out[0..N) (added to what out holds when acc is set).  A block takes 32 columns of one segment with 32 row lanes of
+// 8 threads, four columns each (one 16-byte load per row where the segment allows it, else four 4-byte loads): lane r
+// adds rows r, r + 32, ... in ascending order in double, eight loads in flight at a time (256 partial rows, the
+// usual count, are one batch); the 32 lanes are combined in a fixed tree.
+constexpr int FIN_COLS = 32, FIN_LANES = 32;
 __global__ __launch_bounds__(256) void colsum_finish_kernel(const ColsumFinish a) {
-  __shared__ double sh[FIN_LANES][FIN_COLS];
-  const int cx = threadIdx.x % FIN_COLS, ry = threadIdx.x / FIN_COLS;
-  const int col = blockIdx.x * FIN_COLS + cx;
+  __shared__ double sh[FIN_LANES][FIN_COLS + 1];
+  const int cx = threadIdx.x & 7, ry = threadIdx.x >> 3;
   int i = 0;
 #pragma unroll 1
   while (i + 1 < a.nseg && (int)blockIdx.x * FIN_COLS >= a.seg[i + 1].col0) ++i;  // uniform over the block
   const ColsumSeg &g = a.seg[i];
-  const int c = col - g.col0;
-  double v = 0.0;
+  const int cb = blockIdx.x * FIN_COLS - g.col0;  // first column of the block within its segment
+  const int c = cb + cx * 4;
+  const bool vec = (g.N % 4 == 0) && (g.stride % 4 == 0) && ((((uintptr_t)g.part) & 15) == 0);
+  double v[4] = {0.0, 0.0, 0.0, 0.0};
   if (c < g.N) {
     constexpr int U = 8;
     for (int k0 = ry; k0 < g.nch; k0 += FIN_LANES * U) {
-      float w[U];
+      float w[U][4];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int k = k0 + u * FIN_LANES;
-        w[u] = k < g.nch ? g.part[(int64_t)k * g.stride + c] : 0.f;
+        const float *p = g.part + (int64_t)k * g.stride + c;
+        if (k >= g.nch) {
+          w[u][0] = w[u][1] = w[u][2] = w[u][3] = 0.f;
+        } else if (vec) {
+          const float4 q = *(const float4 *)p;
+          w[u][0] = q.x; w[u][1] = q.y; w[u][2] = q.z; w[u][3] = q.w;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) w[u][j] = c + j < g.N ? p[j] : 0.f;
+        }
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u) v += (double)w[u];
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] += (double)w[u][j];
     }
   }
-  sh[ry][cx] = v;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) sh[ry][cx * 4 + j] = v[j];
   __syncthreads();
-  if (ry == 0 && c < g.N) {
-    const double t = ((sh[0][cx] + sh[1][cx]) + (sh[2][cx] + sh[3][cx])) + ((sh[4][cx] + sh[5][cx]) + (sh[6][cx] + sh[7][cx]));
-    g.out[c] = (float)(a.acc ? (double)g.out[c] + t : t);
+  const int cc = threadIdx.x;
+  if (cc < FIN_COLS && cb + cc < g.N) {
+    double t[FIN_LANES];
+#pragma unroll
+    for (int k = 0; k < FIN_LANES; ++k) t[k] = sh[k][cc];
+#pragma unroll
+    for (int w = 1; w < FIN_LANES; w *= 2)
+#pragma unroll
+      for (int k = 0; k < FIN_LANES; k += 2 * w) t[k] += t[k + w];
+    g.out[cb + cc] = (float)(a.acc ? (double)g.out[cb + cc] + t[0] : t[0]);
   }
 }
 
