@@ -8,7 +8,7 @@ Sharded-LRTF scheduler.  One step = one minibatch of every model through the
 whole path: promote shard, forward visit, checkpoint, backward visit with
 recomputation, Adam, demote.
 
-Default mode "spill": four shard buffers (one computing, one filling, two draining), so every shard's state streams in
+Default mode "spill": six shard buffers (per compute lane one computing, one filling, one draining), so every shard's state streams in
 from pinned host DRAM before each visit and the updated state streams back.
 Mode "resident": as many buffers as shards (state crosses the link once).
 
@@ -197,7 +197,7 @@ def main():
     ap.add_argument("--config", default="gpt2s")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the second mode and the timing pass")
-    ap.add_argument("--slots", type=int, default=4, help="shard buffers in spill mode")
+    ap.add_argument("--slots", type=int, default=6, help="shard buffers in spill mode (three per compute lane)")
     ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
     ap.add_argument("--lanes", type=int, default=2, help="compute lanes (streams); models are spread over them")
     ap.add_argument("--graphs", action="store_true",
