@@ -37,12 +37,13 @@ Slot *slot_for(hydra_ctx *ctx, int model, int shard) {
   return i < 0 ? nullptr : &ctx->slots[i];
 }
 
-hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes) {
+hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes,
+                      int64_t tokens_per_visit) {
   if (ctx->dry) return HYDRA_OK;
   if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)
     HYDRA_HIP(ctx, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, ctx->s_d2h));
   else
-    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, ctx->s_d2h));
+    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, tokens_per_visit, ctx->s_d2h));
   return HYDRA_OK;
 }
 
@@ -475,9 +476,9 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
       if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
       hydra_status cs;
       const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h, model << 16 | shard);
-      if ((cs = copy_d2h(ctx, m->host.master + off, m->host_dev.master + off, sl->w, cnt * 4)) ||
-          (cs = copy_d2h(ctx, m->host.adam_m + off, m->host_dev.adam_m + off, sl->m, cnt * 4)) ||
-          (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4)))
+      if ((cs = copy_d2h(ctx, m->host.master + off, m->host_dev.master + off, sl->w, cnt * 4, m->sh.Mt)) ||
+          (cs = copy_d2h(ctx, m->host.adam_m + off, m->host_dev.adam_m + off, sl->m, cnt * 4, m->sh.Mt)) ||
+          (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4, m->sh.Mt)))
         return cs;
       trace_end(ctx, tr, ctx->s_d2h, (uint64_t)cnt * 12);
       HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
@@ -558,7 +559,7 @@ hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
       HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, m->ev_last_compute, 0));
       const uint64_t eo = (uint64_t)shard * m->sh.Mt * m->sh.d;
       const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h);
-      hydra_status cs = copy_d2h(ctx, m->host.ckpt + eo, m->host_dev.ckpt + eo, m->ckpt[shard], bytes);
+      hydra_status cs = copy_d2h(ctx, m->host.ckpt + eo, m->host_dev.ckpt + eo, m->ckpt[shard], bytes, m->sh.Mt);
       if (cs) return cs;
       trace_end(ctx, tr, ctx->s_d2h, bytes);
       HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_d2h[shard & 1], ctx->s_d2h));

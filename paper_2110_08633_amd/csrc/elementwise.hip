@@ -1090,10 +1090,9 @@ hipError_t launch_adam(float *w, float *m, float *v, const float *g, bf16_t *sha
 // ------------------------------------------------------------ link copy
 // Streams a device buffer into page-locked host memory (mapped into the device
 // address space) with plain 16-byte vector stores.  A small grid suffices: the
-// host link, not the CUs, bounds it, and every CU that runs a copy workgroup
-// slows the compute kernels it shares with it (stores over the link retire
-// slowly and hold the CU's memory pipeline): 32 workgroups reach the same link
-// rate as 128 and cost the concurrent compute kernels a fifth less time.
+// host link, not the CUs, bounds it (16 workgroups already reach its rate), and
+// the more workgroups copy the slower all compute kernels run meanwhile; how
+// many a write-back gets is decided in copy_to_host_blocks.
 __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
                                                            int64_t n16, uint8_t *dst_tail, const uint8_t *src_tail,
                                                            int tail) {
@@ -1102,13 +1101,28 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
   if (blockIdx.x == 0 && threadIdx.x < tail) dst_tail[threadIdx.x] = src_tail[threadIdx.x];
 }
 
-hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, hipStream_t s) {
-  static const int max_blocks = [] {
+// Workgroups of a write-back copy.  Stores to host memory sit in the L2 channels' queues until the link has taken
+// them, in front of everybody else's requests: the more workgroups copy, the slower every compute kernel on the
+// device runs (the same write-back through SDMA slows nothing, but reaches only 15-30 GB/s next to the promotes).
+// Where a step is bound by the link (few tokens per shard visit) the buffer has to be free again as early as
+// possible and 32 workgroups are best; the more tokens a visit works on, the more the compute kernels matter and the
+// fewer workgroups a write-back gets (measured on the two-model GPT-2-small workload, tokens per visit 2048 x
+// 1 / 4 / 6 / 8 / 12: best at 32 / 16 / 12 / 8 / 8 workgroups, up to a fifth faster than with 32).
+int copy_to_host_blocks(int64_t tokens_per_visit) {
+  static const int forced = [] {
     const char *e = getenv("HYDRA_COPY_BLOCKS");
     const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 32;
+    return v > 0 ? v : 0;
   }();
-  return launch_copy_link(dst_mapped, src, bytes, max_blocks, s);
+  if (forced) return forced;
+  if (tokens_per_visit < 6144) return 32;
+  if (tokens_per_visit < 12288) return 16;
+  if (tokens_per_visit < 16384) return 12;
+  return 8;
+}
+
+hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, int64_t tokens_per_visit, hipStream_t s) {
+  return launch_copy_link(dst_mapped, src, bytes, copy_to_host_blocks(tokens_per_visit), s);
 }
 
 hipError_t launch_copy_link(void *dst_mapped, const void *src, size_t bytes, int max_blocks, hipStream_t s) {

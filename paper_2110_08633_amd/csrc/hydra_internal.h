@@ -155,7 +155,8 @@ const char *global_error();
 hydra_status ensure_planned(hydra_ctx *ctx);
 Slot *slot_for(hydra_ctx *ctx, int model, int shard);
 // device -> host copy on the d2h stream: own copy kernel, or hipMemcpyAsync with HYDRA_FLAG_D2H_MEMCPY
-hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes);
+hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, const void *src, size_t bytes,
+                      int64_t tokens_per_visit);
 
 // opens / closes an interval of the overlap trace on stream s (no-ops without HYDRA_FLAG_OVERLAP; idx < 0 ignored)
 int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s, int tag = 0);  // tag: model << 16 | shard
