@@ -1101,9 +1101,10 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
   if (blockIdx.x == 0 && threadIdx.x < tail) dst_tail[threadIdx.x] = src_tail[threadIdx.x];
 }
 
-// Workgroups of a write-back copy.  Stores to host memory sit in the L2 channels' queues until the link has taken
-// them, in front of everybody else's requests: the more workgroups copy, the slower every compute kernel on the
-// device runs (the same write-back through SDMA slows nothing, but reaches only 15-30 GB/s next to the promotes).
+// Workgroups of a write-back copy.  The more workgroups copy, the slower every compute kernel on the device runs
+// meanwhile, wherever it runs (measured; presumably stores to host memory wait in the L2 channels' queues, in front
+// of everybody else's requests, until the link has taken them; the same write-back through SDMA slows nothing, but
+// reaches only 15-30 GB/s next to the promotes).
 // Where a step is bound by the link (few tokens per shard visit) the buffer has to be free again as early as
 // possible and 32 workgroups are best; the more tokens a visit works on, the more the compute kernels matter and the
 // fewer workgroups a write-back gets (measured on the two-model GPT-2-small workload, tokens per visit 2048 x
