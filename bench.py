@@ -197,6 +197,8 @@ def main():
     ap.add_argument("--config", default="gpt2s")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the second mode and the timing pass")
+    ap.add_argument("--large-gemm-only", action="store_true",
+                    help="only time the block products of the largest configuration (for counter runs) and print them")
     ap.add_argument("--slots", type=int, default=6, help="shard buffers in spill mode (three per compute lane)")
     ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
     ap.add_argument("--lanes", type=int, default=2, help="compute lanes (streams); models are spread over them")
@@ -226,6 +228,9 @@ def main():
     import torch
     from paper_2110_08633_amd import hydra as H, runtime as R
     assert torch.cuda.is_available(), "no GPU visible"
+    if args.large_gemm_only:
+        print(json.dumps({"block_gemm_large_shapes": block_gemm_large_shapes(H, torch)}))
+        return
     if args.d2h_memcpy:
         EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
     if args.graphs:
