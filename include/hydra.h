@@ -203,7 +203,7 @@ hydra_status hydra_kernel_stats_reset(hydra_ctx *ctx);
  * shard, start ms, end ms, bytes) for timeline studies.
  *
  * Other environment variables read by the library (experiments; the defaults are the measured best):
- * HYDRA_COPY_BLOCKS (workgroups of the write-back copy kernel; default 32 to 8, fewer the more tokens a shard visit works on), HYDRA_GEMM_TILE and HYDRA_GEMM_D
+ * HYDRA_COPY_BLOCKS (workgroups of the write-back copy kernel; default 48 to 8, fewer the more tokens a shard visit works on), HYDRA_GEMM_TILE and HYDRA_GEMM_D
  * (force a tile configuration / the number of contraction slices in flight of the bf16 products). */
 hydra_status hydra_overlap_stats(hydra_ctx *ctx, hydra_overlap *out);
 hydra_status hydra_overlap_reset(hydra_ctx *ctx);

@@ -1106,9 +1106,9 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
 // of everybody else's requests, until the link has taken them; the same write-back through SDMA slows nothing, but
 // reaches only 15-30 GB/s next to the promotes).
 // Where a step is bound by the link (few tokens per shard visit) the buffer has to be free again as early as
-// possible and 32 workgroups are best; the more tokens a visit works on, the more the compute kernels matter and the
-// fewer workgroups a write-back gets (measured on the two-model GPT-2-small workload, tokens per visit 2048 x
-// 1 / 4 / 6 / 8 / 12: best at 32 / 16 / 12 / 8 / 8 workgroups, up to a fifth faster than with 32).
+// possible and 48 to 64 workgroups are best; the more tokens a visit works on, the more the compute kernels matter
+// and the fewer workgroups a write-back gets (measured on the two-model GPT-2-small workload, tokens per visit 2048 x
+// 1 / 4 / 6 / 8 / 12: best at 48 / 16 / 12 / 8 / 8 workgroups, up to a fifth faster than with 32 throughout).
 int copy_to_host_blocks(int64_t tokens_per_visit) {
   static const int forced = [] {
     const char *e = getenv("HYDRA_COPY_BLOCKS");
@@ -1116,7 +1116,7 @@ int copy_to_host_blocks(int64_t tokens_per_visit) {
     return v > 0 ? v : 0;
   }();
   if (forced) return forced;
-  if (tokens_per_visit < 6144) return 32;
+  if (tokens_per_visit < 6144) return 48;
   if (tokens_per_visit < 12288) return 16;
   if (tokens_per_visit < 16384) return 12;
   return 8;
