@@ -253,6 +253,30 @@ def test_gemm_large_tiles_on_sampled_rows(H, M, N, K):
     assert np.abs(full - ref_sum).max() <= 1e-4 * scale, "row checksums"
 
 
+@pytest.mark.parametrize("M,N,K", [(2048, 4096, 1024), (1024, 4096, 4096), (2048, 2304, 768)])
+def test_large_tile_gemms_repeat_bitwise_under_concurrency(H, M, N, K):
+    """The tiles whose wavefront groups exchange partial sums through LDS (and the other direct-to-LDS tiles) while a
+    second stream keeps the device busy: every repetition must give the same bits, and sampled rows the oracle's."""
+    rng = np.random.default_rng(M + N + K)
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    Bt = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
+    dA, dB = dev(A, torch.bfloat16), dev(Bt, torch.bfloat16)
+    big = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+    bigC = torch.empty((4096, 4096), device="cuda", dtype=torch.float32)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [torch.zeros((M, N), device="cuda", dtype=torch.float32) for _ in range(12)]
+    torch.cuda.synchronize()
+    for o in outs:
+        H.hydra_op_gemm(1, 0, 0, 4096, 4096, 4096, 1.0, big, 4096, big, 4096, None, None, bigC, None, 4096, s2)
+        H.hydra_op_gemm(1, 0, 0, M, N, K, 1.0, dA, K, dB, K, None, None, o, None, N, s1)
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    rows = np.array([0, 127, 128, 255, 256, M // 2 + 1, M - 1])
+    ref = D.linear_fwd(A[rows].astype(np.float64), Bt.T.astype(np.float64))
+    assert_close(outs[0][rows].cpu().numpy(), ref, 1e-5, "large gemm under concurrency")
+
+
 @pytest.mark.parametrize("B,Hh,T,dh", [(2, 3, 72, 64), (1, 2, 264, 64), (2, 1, 136, 128), (1, 4, 512, 64), (1, 1, 8, 64)])
 def test_fused_attention_forward_and_backward(H, B, Hh, T, dh):
     """Fused causal attention (scores, mask, softmax, PV in one kernel; backward without a stored probability
