@@ -222,7 +222,9 @@ def test_single_slice_gemm_under_concurrency(H):
 # products large enough for each tile shape the launcher picks for contraction-contiguous operands (256x256,
 # 256x128 with eight wavefronts, 128x128, 128x64 in both pipeline depths), with and without ragged edges
 LARGE_NT = [(1024, 12288, 1024), (1000, 12200, 512), (2048, 4096, 1024), (2000, 4100, 1024), (1024, 4096, 4096),
-            (1000, 4000, 2048), (2048, 2304, 768), (2048, 768, 2304), (1100, 3000, 192)]
+            (1000, 4000, 2048), (2048, 2304, 768), (2048, 768, 2304), (1100, 3000, 192),
+            # a single, partly empty row of tiles: 256x128 (40 rows), 128x128 (100 rows), 256x256 (200 rows)
+            (40, 26000, 128), (100, 30000, 2048), (200, 50000, 256)]
 
 
 @pytest.mark.parametrize("M,N,K", LARGE_NT)
