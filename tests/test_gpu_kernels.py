@@ -224,7 +224,9 @@ def test_single_slice_gemm_under_concurrency(H):
 LARGE_NT = [(1024, 12288, 1024), (1000, 12200, 512), (2048, 4096, 1024), (2000, 4100, 1024), (1024, 4096, 4096),
             (1000, 4000, 2048), (2048, 2304, 768), (2048, 768, 2304), (1100, 3000, 192),
             # a single, partly empty row of tiles: 256x128 (40 rows), 128x128 (100 rows), 256x256 (200 rows)
-            (40, 26000, 128), (100, 30000, 2048), (200, 50000, 256)]
+            (40, 26000, 128), (100, 30000, 2048), (200, 50000, 256),
+            # and a single, partly empty column of tiles
+            (52000, 120, 128), (30000, 100, 2048), (50000, 200, 256)]
 
 
 @pytest.mark.parametrize("M,N,K", LARGE_NT)
