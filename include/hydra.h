@@ -15,11 +15,18 @@
  * Conventions
  *  - All functions return hydra_status (0 = ok, <0 = error).  Nothing aborts
  *    and no exception crosses the boundary; hydra_last_error() gives text.
- *  - The CALLER owns all memory: one device arena (sub-allocated by the
- *    library, never freed by it) and the pinned host arrays of every model.
- *    The library allocates no device memory.
- *  - Every hydra_shard_* call only enqueues work on the three streams given to
+ *  - The CALLER owns all memory and all streams: one device arena
+ *    (sub-allocated by the library, never freed by it), the page-locked host
+ *    arrays of every model including the staging area of its token batches,
+ *    and the compute / copy streams.  The library allocates neither device nor
+ *    page-locked memory and creates no stream; what it creates are HIP events
+ *    (and HIP graphs with HYDRA_FLAG_GRAPHS), destroyed by hydra_destroy.
+ *  - Every hydra_shard_* call only enqueues work on the streams given to
  *    hydra_init; ordering between streams is by events on the device.
+ *  - The library reads no environment variable.
+ *  - Each declaration below names the passage of the paper it follows; calls
+ *    marked "plumbing" exist for the caller's convenience (set-up, inspection,
+ *    measurement) and follow no passage.
  *  - Shards of a model: 0 = EMBED (wte, wpe); 1..S = runs of layers_per_shard
  *    blocks; S+1 = HEAD (final LayerNorm, LM head, loss).
  *  - Canonical flat parameter layout (fp32, row-major, matrices are [in,out]
@@ -63,7 +70,8 @@ enum {
 /* hydra_init_desc.flags */
 enum {
   HYDRA_FLAG_DRY_RUN = 1,    /* no HIP call is made: state machine, slot table and traces only (host tests) */
-  HYDRA_FLAG_CKPT_SPILL = 2, /* boundary activations travel through host DRAM between visits                */
+  HYDRA_FLAG_CKPT_SPILL = 2, /* boundary activations travel through host DRAM between visits (Section 2.3:   */
+                             /* "intermediate data" is demoted too); the device keeps a ping-pong pair       */
   HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
   HYDRA_FLAG_TIMING = 8,     /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
   HYDRA_FLAG_D2H_MEMCPY = 16, /* demote with hipMemcpyAsync instead of the library's own copy kernel            */
@@ -95,6 +103,8 @@ enum {
   HYDRA_RD_DBOUND = 6  /* fp32 [n_micro*B*T, d]: gradient w.r.t. the input of the last backward visit */
 };
 
+#define HYDRA_MAX_LANES 8
+
 typedef struct {
   void *dev_arena;                 /* device pointer; one buffer the library carves up        */
   uint64_t dev_arena_bytes;
@@ -104,9 +114,15 @@ typedef struct {
   void *compute_stream;            /* hipStream_t handles; NULL = the null stream             */
   void *h2d_stream;
   void *d2h_stream;
-  int32_t compute_lanes;           /* 0 or 1: every task on compute_stream.  n > 1: model i runs on lane i % n;   */
-  int32_t reserved;                /* lanes 1.. use streams (default priority) and workspaces of the library's    */
-                                   /* own, so that tasks of different models overlap on the device               */
+  int32_t compute_lanes;           /* 0 or 1: every task on compute_stream.  n > 1: model i runs on lane i % n, so  */
+                                   /* that tasks of different models overlap on the device; lane 0 is compute_stream */
+  int32_t copy_blocks;             /* workgroups of the write-back copy kernel; 0 = chosen from the tokens a shard  */
+                                   /* visit works on (48 down to 8: fewer the more compute there is to disturb)     */
+  void *lane_streams[HYDRA_MAX_LANES - 1]; /* caller's streams (default priority) of lanes 1 .. compute_lanes - 1;  */
+                                   /* distinct non-null handles (ignored with HYDRA_FLAG_DRY_RUN)                   */
+  int32_t prefetch_depth;          /* how many tasks ahead hydra_sched_run promotes shards for; 0 = as far as free   */
+                                   /* shard buffers allow (at least one: the paper's double buffering, Section 2.3)  */
+  int32_t reserved;
 } hydra_init_desc;
 
 typedef struct {
@@ -130,6 +146,8 @@ typedef struct {
   float *adam_m;  /* [n_params]                               */
   float *adam_v;  /* [n_params]                               */
   float *ckpt;    /* [(S+1) * n_micro*B*T * d] fp32; only read/written with HYDRA_FLAG_CKPT_SPILL, else may be NULL */
+  int32_t *batch_stage; /* [4 * n_micro*B*T] int32: staging of two minibatches' token ids and targets on their   */
+                        /* way to the device; contents belong to the library while the model is registered        */
 } hydra_host_state;
 
 typedef struct {
@@ -168,28 +186,33 @@ typedef struct {
  * operation (all waits before it satisfied) to its completion; "busy" times are lengths of unions of intervals. */
 typedef struct {
   double wall_ms;         /* first interval start to last interval end                                  */
-  double compute_ms;      /* some shard task (forward / backward / Adam) running on any compute lane    */
+  double compute_ms;      /* some shard task (forward / backward / Adam) in flight on any compute lane: */
+                          /* from its first kernel's start to its last kernel's end, gaps included      */
   double h2d_ms;          /* some promote in flight (weights, Adam state, spilled checkpoints)          */
   double d2h_ms;          /* some write-back in flight                                                  */
   double transfer_ms;     /* h2d or d2h in flight                                                       */
-  double hidden_ms;       /* transfer in flight while a shard task is running                           */
+  double hidden_ms;       /* transfer in flight while a shard task is in flight                         */
   uint64_t bytes_h2d, bytes_d2h; /* bytes moved by the recorded intervals                                */
   uint64_t n_intervals;
+  double kernel_ms;       /* with HYDRA_FLAG_TIMING as well: some kernel of a shard task executing      */
+  double hidden_kernel_ms;/* ... and transfer in flight while one executes (0 without HYDRA_FLAG_TIMING) */
 } hydra_overlap;
 
-/* ---- context ------------------------------------------------------------ */
+/* ---- context (plumbing) -------------------------------------------------- */
 /* Creates a context over the caller's arena and streams.  With
  * HYDRA_FLAG_DRY_RUN the arena pointer may be any non-null value. */
 hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out);
+/* Waits for all streams, destroys the library's events and graphs.  Caller memory and streams are left alone. */
 hydra_status hydra_destroy(hydra_ctx *ctx);
-/* Blocks until all three streams are idle. */
+/* Blocks until all streams of the context are idle. */
 hydra_status hydra_sync(hydra_ctx *ctx);
 /* Text of the last error seen on this context (ctx may be NULL for errors of
  * functions that take no context). Never NULL. */
 const char *hydra_last_error(const hydra_ctx *ctx);
+/* Byte, task and buffer counters since hydra_init (plumbing; the swap traffic of Section 2.3 in numbers). */
 hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out);
 
-/* Per-kernel timing (context created with HYDRA_FLAG_TIMING): entry 'index' of
+/* Per-kernel timing (plumbing; context created with HYDRA_FLAG_TIMING): entry 'index' of
  * the table of kernels launched since the last reset - name, number of
  * launches, summed HIP-event time on the launching stream, and the summed
  * algorithmic flops and bytes of those launches.  Synchronises.  Returns 1 when
@@ -197,18 +220,17 @@ hydra_status hydra_get_stats(hydra_ctx *ctx, hydra_stats *out);
 hydra_status hydra_kernel_stats(hydra_ctx *ctx, int32_t index, char name[64], uint64_t *launches,
                                 double *total_ms, double *flops, double *bytes);
 hydra_status hydra_kernel_stats_reset(hydra_ctx *ctx);
-/* Swap / compute overlap (context created with HYDRA_FLAG_OVERLAP; HYDRA_E_STATE otherwise).  Both synchronise
- * the context's streams first.  The reset forgets all intervals recorded so far.  With the environment variable
- * HYDRA_TRACE_DUMP=<file>, hydra_overlap_stats also writes one line per interval to that file (kind, model,
- * shard, start ms, end ms, bytes) for timeline studies.
- *
- * Other environment variables read by the library (experiments; the defaults are the measured best):
- * HYDRA_COPY_BLOCKS (workgroups of the write-back copy kernel; default 48 to 8, fewer the more tokens a shard visit works on), HYDRA_GEMM_TILE and HYDRA_GEMM_D
- * (force a tile configuration / the number of contraction slices in flight of the bf16 products). */
+/* Swap / compute overlap (measures what Section 2.3's double buffering hides; context created with
+ * HYDRA_FLAG_OVERLAP, HYDRA_E_STATE otherwise).  All three synchronise the context's streams first.  The reset
+ * forgets all intervals recorded so far.  hydra_overlap_dump writes one line per interval to a text file (kind,
+ * model, shard, start ms, end ms, bytes; kind "kernel" lines with HYDRA_FLAG_TIMING) for timeline studies. */
 hydra_status hydra_overlap_stats(hydra_ctx *ctx, hydra_overlap *out);
 hydra_status hydra_overlap_reset(hydra_ctx *ctx);
+hydra_status hydra_overlap_dump(hydra_ctx *ctx, const char *path);
 
-/* ---- layout (pure functions of the model description) ------------------- */
+/* ---- layout (pure functions of the model description) -------------------
+ * A shard is a contiguous run of layers (Section 2.2: a model is rewritten into shards); these calls give the
+ * element ranges that promotes and demotes move. */
 hydra_status hydra_model_layout(const hydra_model_desc *desc, hydra_layout *out);
 /* Tensor 'index' (0..n_tensors-1) in canonical order: name ("wte", "h3.w_qkv",
  * "lnf_g", ...; at most 31 chars + NUL), element offset into the flat arrays,
@@ -231,7 +253,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc,
 hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *tokens, const int32_t *targets);
 
 /* ---- shard tasks (paper Section 2.3) ------------------------------------- */
-/* Promote: start copying the shard's state from the host arrays into a free
+/* Promote (Section 2.3): start copying the shard's state from the host arrays into a free
  * shard buffer on the h2d stream; returns at once.  Already resident: only
  * missing parts are fetched.  No free buffer: HYDRA_E_NOSLOT. */
 hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what);
@@ -248,9 +270,9 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
 /* Demote: write back changed state on the d2h stream and/or release the buffer. */
 hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what);
 
-/* Loss of the model's last HEAD forward (synchronises the compute stream). */
+/* Loss of the model's last HEAD forward (plumbing; synchronises the model's compute stream). */
 hydra_status hydra_get_loss(hydra_ctx *ctx, int32_t model, float *loss);
-/* Copies device data to host memory for inspection (synchronous). */
+/* Copies device data to host memory for inspection (plumbing; synchronous). */
 hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t which,
                                void *host_dst, uint64_t bytes);
 
@@ -268,8 +290,10 @@ hydra_status hydra_sched_create(hydra_ctx *ctx, int32_t n_models, const int32_t 
 hydra_status hydra_sched_destroy(hydra_sched *s);
 /* Next decision; returns 1 (not an error) when all tasks have been handed out. */
 hydra_status hydra_sched_next(hydra_sched *s, hydra_task *out);
-/* Runs every remaining task: prefetch of task n+1 is issued before task n is
- * enqueued, dirty shards are written back when their buffer is needed.
+/* Runs every remaining task: the shards of the following tasks are promoted
+ * before task n is enqueued - as many tasks ahead as buffers can be freed without
+ * touching a shard an earlier task needs, at most hydra_init_desc.prefetch_depth -
+ * and a shard's updated state is written back right after its Adam step.
  * tokens[m] / targets[m]: host int32 [n_minibatches[m], n_micro*B, T].  trace (may be
  * NULL) receives the executed order. Returns after everything is enqueued
  * (call hydra_sync to wait). */
@@ -313,6 +337,10 @@ hydra_status hydra_pilot_costs(hydra_ctx *ctx, int32_t model, const int32_t *tok
                                int64_t *costs_ns);
 
 /* ---- single kernels, exposed for parity tests and roofline measurement ----
+ * Plumbing: the paper names the architecture (GPT-2, Section 3) and none of its
+ * operators; each call below is one operator of that decoder with the textbook
+ * definition stated.  No call allocates; bad sizes, leading dimensions or dtypes
+ * return HYDRA_E_INVAL before anything is launched.
  * All pointers are DEVICE pointers, 'stream' a hipStream_t (NULL = null
  * stream).  dtype: 0 = fp32 operands, 1 = bf16 operands (fp32 accumulate). */
 

@@ -43,7 +43,7 @@ hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, con
   if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)
     HYDRA_HIP(ctx, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, ctx->s_d2h));
   else
-    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, tokens_per_visit, ctx->s_d2h));
+    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, tokens_per_visit, ctx->init.copy_blocks, ctx->s_d2h));
   return HYDRA_OK;
 }
 
@@ -59,7 +59,8 @@ hydra_status copy_h2d(hydra_ctx *ctx, void *dst, const void *host_src, size_t by
 // device-side address of caller memory that must be page-locked and mapped
 static hydra_status mapped_pointer(hydra_ctx *ctx, const void *host, const char *what, float **out) {
   *out = (float *)host;
-  if (ctx->dry || !host) return HYDRA_OK;
+  // the device-side mapping is what the library's copy kernel stores through; hipMemcpyAsync takes the host address
+  if (ctx->dry || !host || (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)) return HYDRA_OK;
   hipPointerAttribute_t at;
   hipError_t e = hipPointerGetAttributes(&at, host);
   if (e != hipSuccess || at.type != hipMemoryTypeHost || !at.devicePointer) {
@@ -128,6 +129,17 @@ hydra_status ensure_planned(hydra_ctx *ctx) {
   return HYDRA_OK;
 }
 
+static void destroy_model_events(Model *m) {
+  for (int i = 0; i < 2; ++i) {
+    if (m->ev_stage[i]) (void)hipEventDestroy(m->ev_stage[i]);
+    if (m->ev_ckpt_d2h[i]) (void)hipEventDestroy(m->ev_ckpt_d2h[i]);
+    if (m->ev_ckpt_h2d[i]) (void)hipEventDestroy(m->ev_ckpt_h2d[i]);
+  }
+  if (m->ev_last_compute) (void)hipEventDestroy(m->ev_last_compute);
+  for (hipEvent_t e : m->ev_wb)
+    if (e) (void)hipEventDestroy(e);
+}
+
 static hydra_status check_model(hydra_ctx *ctx, int model, int shard) {
   if (!ctx) return fail(nullptr, HYDRA_E_INVAL, "null context");
   if (model < 0 || model >= (int)ctx->models.size()) return fail(ctx, HYDRA_E_INVAL, "model index out of range");
@@ -149,9 +161,9 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
   ctx->init = *desc;
   ctx->dry = (desc->flags & HYDRA_FLAG_DRY_RUN) != 0;
   const int n_lanes = desc->compute_lanes > 0 ? desc->compute_lanes : 1;
-  if (n_lanes > 8) {
+  if (n_lanes > HYDRA_MAX_LANES) {
     delete ctx;
-    return fail(nullptr, HYDRA_E_INVAL, "at most 8 compute lanes");
+    return fail(nullptr, HYDRA_E_INVAL, "at most HYDRA_MAX_LANES compute lanes");
   }
   ctx->lanes.resize(n_lanes);
   ctx->lanes[0].stream = (hipStream_t)desc->compute_stream;
@@ -169,11 +181,18 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
     }
   }
   for (int i = 1; i < n_lanes && !ctx->dry; ++i) {
-    if (hipStreamCreateWithFlags(&ctx->lanes[i].stream, hipStreamNonBlocking) != hipSuccess) {
+    hipStream_t ls = (hipStream_t)desc->lane_streams[i - 1];
+    bool distinct = ls != nullptr && ls != ctx->lanes[0].stream && ls != ctx->s_h2d && ls != ctx->s_d2h;
+    for (int j = 1; j < i; ++j) distinct &= ls != ctx->lanes[j].stream;
+    if (!distinct) {
       delete ctx;
-      return fail(nullptr, HYDRA_E_HIP, "cannot create a compute lane stream");
+      return fail(nullptr, HYDRA_E_INVAL, "lane_streams must hold a distinct non-null stream for every lane above 0");
     }
-    ctx->lanes[i].own_stream = true;
+    ctx->lanes[i].stream = ls;
+  }
+  if (desc->copy_blocks < 0 || desc->copy_blocks > 1024 || desc->prefetch_depth < 0) {
+    delete ctx;
+    return fail(nullptr, HYDRA_E_INVAL, "copy_blocks must be 0..1024 and prefetch_depth >= 0");
   }
   if (!ctx->dry && (desc->flags & HYDRA_FLAG_TIMING)) {
     ctx->prof = prof_create();
@@ -194,8 +213,6 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
     trace_destroy(ctx->tracer);
     for (auto &kv : ctx->graphs)
       if (kv.second.exec) (void)hipGraphExecDestroy(kv.second.exec);
-    for (hydra_ctx::Lane &ln : ctx->lanes)
-      if (ln.own_stream) (void)hipStreamDestroy(ln.stream);
     for (Slot &s : ctx->slots) {
       if (s.ev_loaded) (void)hipEventDestroy(s.ev_loaded);
       if (s.ev_compute) (void)hipEventDestroy(s.ev_compute);
@@ -203,19 +220,7 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
     }
   }
   for (Model *m : ctx->models) {
-    if (!ctx->dry) {
-      for (int i = 0; i < 2; ++i) {
-        if (m->ev_stage[i]) (void)hipEventDestroy(m->ev_stage[i]);
-        if (m->ev_ckpt_d2h[i]) (void)hipEventDestroy(m->ev_ckpt_d2h[i]);
-        if (m->ev_ckpt_h2d[i]) (void)hipEventDestroy(m->ev_ckpt_h2d[i]);
-      }
-      if (m->ev_last_compute) (void)hipEventDestroy(m->ev_last_compute);
-      for (hipEvent_t e : m->ev_wb)
-        if (e) (void)hipEventDestroy(e);
-      if (m->stage) (void)hipHostFree(m->stage);
-    } else {
-      delete[] m->stage;
-    }
+    if (!ctx->dry) destroy_model_events(m);
     delete m;
   }
   delete ctx;
@@ -245,6 +250,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   if (!ctx || !desc || !host || !model_id) return fail(ctx, HYDRA_E_INVAL, "null argument");
   if (ctx->planned) return fail(ctx, HYDRA_E_STATE, "models must be registered before the first shard call");
   if (!host->master || !host->adam_m || !host->adam_v) return fail(ctx, HYDRA_E_INVAL, "null host state array");
+  if (!host->batch_stage) return fail(ctx, HYDRA_E_INVAL, "null batch staging array");
   if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && !host->ckpt)
     return fail(ctx, HYDRA_E_INVAL, "checkpoint spilling needs a host checkpoint array");
   Model *m = new Model();
@@ -293,23 +299,27 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   m->slot_of.assign(s.S + 2, -1);
   m->wb_pending.assign(s.S + 2, 0);
   m->lane = (int)(ctx->models.size() % ctx->lanes.size());
+  m->stage = host->batch_stage;
   if (!ctx->dry) {
-    hipError_t e = hipHostMalloc((void **)&m->stage, (size_t)s.Mt * 4 * 4, hipHostMallocDefault);
-    if (e != hipSuccess) {
+    hipPointerAttribute_t at;
+    if (hipPointerGetAttributes(&at, m->stage) != hipSuccess || at.type != hipMemoryTypeHost) {
+      (void)hipGetLastError();
       delete m;
-      return hipfail(ctx, e, "hipHostMalloc(token staging)");
+      return fail(ctx, HYDRA_E_INVAL, "batch_stage is not page-locked host memory");
     }
-    for (int i = 0; i < 2; ++i) {
-      if ((st = make_event(ctx, &m->ev_stage[i])) || (st = make_event(ctx, &m->ev_ckpt_d2h[i])) ||
-          (st = make_event(ctx, &m->ev_ckpt_h2d[i])))
-        return st;
-    }
-    if ((st = make_event(ctx, &m->ev_last_compute))) return st;
     m->ev_wb.assign(s.S + 2, nullptr);
+    st = HYDRA_OK;
+    for (int i = 0; i < 2 && !st; ++i)
+      (void)((st = make_event(ctx, &m->ev_stage[i])) || (st = make_event(ctx, &m->ev_ckpt_d2h[i])) ||
+             (st = make_event(ctx, &m->ev_ckpt_h2d[i])));
+    if (!st) st = make_event(ctx, &m->ev_last_compute);
     for (hipEvent_t &e : m->ev_wb)
-      if ((st = make_event(ctx, &e))) return st;
-  } else {
-    m->stage = new int32_t[(size_t)s.Mt * 4];
+      if (!st) st = make_event(ctx, &e);
+    if (st) {  // release what was created: the model is not registered
+      destroy_model_events(m);
+      delete m;
+      return st;
+    }
   }
   *model_id = (int32_t)ctx->models.size();
   ctx->models.push_back(m);
@@ -434,24 +444,6 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     sl->has_opt = true;
     copied = true;
   }
-  // a backward visit of shard s >= 1 reads the checkpoint at its input; when
-  // checkpoints live in host DRAM it is promoted together with the shard
-  if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && (what & HYDRA_LOAD_OPT) && shard >= 1 &&
-      m->ckpt_in_buf[(shard - 1) & 1] != shard - 1 && m->next_bwd >= 0) {
-    const int b = shard - 1;
-    const uint64_t bytes = (uint64_t)m->sh.Mt * m->sh.d * 4;
-    if (!ctx->dry) {
-      if (m->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_last_compute, 0));
-      if (m->ckpt_d2h_pending[b & 1]) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_ckpt_d2h[b & 1], 0));
-      trace_open();
-      HYDRA_HIP(ctx, hipMemcpyAsync(m->ckpt[b], m->host.ckpt + (uint64_t)b * m->sh.Mt * m->sh.d, bytes,
-                                    hipMemcpyHostToDevice, ctx->s_h2d));
-      HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_h2d[b & 1], ctx->s_h2d));
-    }
-    m->ckpt_h2d_pending[b & 1] = true;
-    m->ckpt_in_buf[b & 1] = b;
-    ctx->stats.bytes_h2d += bytes;
-  }
   if (copied) {
     if (!ctx->dry) HYDRA_HIP(ctx, hipEventRecord(sl->ev_loaded, ctx->s_h2d));
     sl->need_wait_load = true;
@@ -504,6 +496,28 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     sl->has_params = sl->has_opt = sl->wb_valid = sl->wbt_valid = sl->grads_valid = sl->tied_valid = false;
     ctx->stats.n_evictions++;
   }
+  return HYDRA_OK;
+}
+
+// Checkpoints through host DRAM (HYDRA_FLAG_CKPT_SPILL): the device holds a ping-pong pair of boundary buffers, and
+// boundary b lives in buffer b & 1 while it is needed.  The backward visit of shard sh reads boundary sh - 1.  The
+// last two boundaries are still on the device when the backward pass starts; every other one is fetched from the
+// host right after the backward visit that last needed the buffer it goes into has been enqueued (shard sh + 1).
+static hydra_status promote_checkpoint(hydra_ctx *ctx, Model *m, int b) {
+  if (b < 0 || m->ckpt_in_buf[b & 1] == b) return HYDRA_OK;
+  const uint64_t bytes = (uint64_t)m->sh.Mt * m->sh.d * 4;
+  if (!ctx->dry) {
+    if (m->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_last_compute, 0));
+    if (m->ckpt_d2h_pending[b & 1]) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_ckpt_d2h[b & 1], 0));
+    const int tr = trace_begin(ctx, TRACE_H2D, ctx->s_h2d);
+    HYDRA_HIP(ctx, hipMemcpyAsync(m->ckpt[b], m->host.ckpt + (uint64_t)b * m->sh.Mt * m->sh.d, bytes,
+                                  hipMemcpyHostToDevice, ctx->s_h2d));
+    trace_end(ctx, tr, ctx->s_h2d, bytes);
+    HYDRA_HIP(ctx, hipEventRecord(m->ev_ckpt_h2d[b & 1], ctx->s_h2d));
+  }
+  m->ckpt_h2d_pending[b & 1] = true;
+  m->ckpt_in_buf[b & 1] = b;
+  ctx->stats.bytes_h2d += bytes;
   return HYDRA_OK;
 }
 
@@ -583,10 +597,10 @@ hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard) 
   Model *m = ctx->models[model];
   if (m->next_bwd < 0) return fail(ctx, HYDRA_E_STATE, "backward before the forward pass has finished");
   if (shard != m->next_bwd) return fail(ctx, HYDRA_E_STATE, "backward visits must follow reverse shard order");
-  if ((ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) && shard >= 1) {
+  const bool ckpt_spill = (ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) != 0;
+  if (ckpt_spill && shard >= 1) {
     const int pb = (shard - 1) & 1;
-    if (m->ckpt_in_buf[pb] != shard - 1)
-      return fail(ctx, HYDRA_E_STATE, "input checkpoint not promoted: load the shard with HYDRA_LOAD_OPT first");
+    if ((st = promote_checkpoint(ctx, m, shard - 1))) return st;  // a no-op unless the caller skipped a visit's prefetch
     if (m->ckpt_h2d_pending[pb] && !ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, m->ev_ckpt_h2d[pb], 0));
     m->ckpt_h2d_pending[pb] = false;
   }
@@ -595,6 +609,8 @@ hydra_status hydra_shard_backward(hydra_ctx *ctx, int32_t model, int32_t shard) 
   sl->grads_valid = true;
   if ((st = end_task(ctx, m, sl, tr))) return st;
   m->next_bwd = shard - 1;  // -1 after the embedding shard: minibatch finished
+  // the boundary the next backward visit (shard - 1) reads goes into the buffer this visit's predecessor used
+  if (ckpt_spill && shard - 1 >= 1 && (st = promote_checkpoint(ctx, m, shard - 2))) return st;
   return HYDRA_OK;
 }
 
@@ -605,6 +621,10 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
   Model *m = ctx->models[model];
   if (!sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients: run the backward visit first");
   if (!sl->has_opt) return fail(ctx, HYDRA_E_STATE, "Adam state not resident: load with HYDRA_LOAD_OPT");
+  if (sl->spill_pending && !ctx->dry) {
+    // a write-back of this buffer (the shard stayed resident after it) may still be reading w, m and v
+    HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, sl->ev_spilled, 0));
+  }
   const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream, model << 16 | shard);
   if (!ctx->dry && (st = exec_adam(ctx, m, sl, shard))) return st;
   sl->grads_valid = false;

@@ -873,7 +873,7 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float *__restr
   const float *lr = logits + (int64_t)row * ld;
   OutT *dr = dlogits + (int64_t)row * ld;
   const int tgt = targets[row];
-  if (tgt < 0) {
+  if (tgt < 0 || tgt >= V) {  // ignored position (an id outside the vocabulary is treated the same way)
     for (int c = tid; c < ld; c += 256) stv<OutT>(dr, c, 0.f);
     if (tid == 0) row_loss[row] = 0.f;
     return;
@@ -915,7 +915,7 @@ __global__ __launch_bounds__(1024) void cross_entropy_row_kernel(const float *__
   OutT *dr = dlogits + (int64_t)row * ld;
   const int tgt = targets[row];
   const int n4 = (int)(ld / 4);
-  if (tgt < 0) {
+  if (tgt < 0 || tgt >= V) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int q = i * 1024 + tid;
@@ -1110,20 +1110,15 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
 // and the fewer workgroups a write-back gets (measured on the two-model GPT-2-small workload, tokens per visit 2048 x
 // 1 / 4 / 6 / 8 / 12: best at 48 / 16 / 12 / 8 / 8 workgroups, up to a fifth faster than with 32 throughout).
 int copy_to_host_blocks(int64_t tokens_per_visit) {
-  static const int forced = [] {
-    const char *e = getenv("HYDRA_COPY_BLOCKS");
-    const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 0;
-  }();
-  if (forced) return forced;
   if (tokens_per_visit < 6144) return 48;
   if (tokens_per_visit < 12288) return 16;
   if (tokens_per_visit < 16384) return 12;
   return 8;
 }
 
-hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, int64_t tokens_per_visit, hipStream_t s) {
-  return launch_copy_link(dst_mapped, src, bytes, copy_to_host_blocks(tokens_per_visit), s);
+hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, int64_t tokens_per_visit, int blocks,
+                               hipStream_t s) {
+  return launch_copy_link(dst_mapped, src, bytes, blocks > 0 ? blocks : copy_to_host_blocks(tokens_per_visit), s);
 }
 
 hipError_t launch_copy_link(void *dst_mapped, const void *src, size_t bytes, int max_blocks, hipStream_t s) {

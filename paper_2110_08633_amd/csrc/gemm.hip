@@ -269,26 +269,11 @@ __device__ __forceinline__ void store_patch(const GemmArgs &g, int64_t coff, con
   }
 }
 
-#ifdef HYDRA_GEMM_TRACE
-__device__ unsigned long long g_gemm_trace[8192];
-#define TRACE_STAMP(slot)                                                                     \
-  do {                                                                                        \
-    __builtin_amdgcn_sched_barrier(0);                                                        \
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && trace_n < 8190)             \
-      g_gemm_trace[trace_n++] = ((unsigned long long)(slot) << 56) | (__builtin_amdgcn_s_memtime() & 0xffffffffffffffull); \
-    __builtin_amdgcn_sched_barrier(0);                                                        \
-  } while (0)
-#else
-#define TRACE_STAMP(slot)
-#endif
 
 // One tile of one product: g describes the product, bid is the workgroup's index among the nt workgroups that
 // work on it, z its batch index.
 template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, const int bid, const int nt, const int z) {
-#ifdef HYDRA_GEMM_TRACE
-  int trace_n = 0;
-#endif
   static_assert(D >= 2 && D % 2 == 0, "slices in flight");
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int MI = WTM / 32, NJ = WTN / 32;
@@ -389,17 +374,12 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, const int bid,
   for (; t + 2 * D + 1 <= nk; t += D) {
 #pragma unroll
     for (int j = 0; j < D; ++j) {
-      TRACE_STAMP(1);
       ma.load_full(ra[j], t + j + D);
       mb.load_full(rb[j], t + j + D);
-      TRACE_STAMP(2);
       ma.store(ra[(j + 1) % D], As[(j + 1) & 1]);
       mb.store(rb[(j + 1) % D], Bs[(j + 1) & 1]);
-      TRACE_STAMP(3);
       compute(As[j & 1], Bs[j & 1]);
-      TRACE_STAMP(4);
       __syncthreads();
-      TRACE_STAMP(5);
     }
   }
   for (; t < nk; t += D) {
@@ -413,8 +393,6 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, const int bid,
       __syncthreads();
     }
   }
-
-  TRACE_STAMP(6);
   // Epilogue through LDS.  Lane L of a 32x32 result (B fragment first) holds row L%32 and columns
   // (r/4)*8 + (L/32)*4 + r%4: storing that directly would touch 32 different rows per instruction.  Each
   // wavefront instead parks 32 rows of its sub-tile in a private LDS patch [32][WTN + 4] (fp32) and reads it
@@ -441,10 +419,6 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, const int bid,
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_wave_barrier();
   }
-  TRACE_STAMP(7);
-#ifdef HYDRA_GEMM_TRACE
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_gemm_trace[8191] = trace_n;
-#endif
 }
 
 template <int BM, int BN, int WM, int WN, int TA, int TB, int D>
@@ -601,11 +575,6 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
   static_assert(KS % 2 == 0 && KS * KW * 16 == BKT && NL <= G && S >= 2, "pipeline shape");
   static_assert(KW == 1 || MI % KW == 0, "the groups share the write-out by rows of fragments");
   extern __shared__ __attribute__((aligned(16))) bf16_t lds_dyn[];
-#ifdef HYDRA_GEMM_TRACE
-  int trace_n = 0;
-#endif
-
-  TRACE_STAMP(0);
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = wave / WPG, wig = wave % WPG, wm = wig / WGN, wn = wig % WGN;
@@ -659,7 +628,6 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
   if (nk >= S) wait_loads_le<(S - 2) * NL + HEAD>();
   else wait_loads_le<0>();
   __builtin_amdgcn_s_barrier();
-  TRACE_STAMP(4);
   bf16x8_t af[2][MI], bfr[2][NJ];
 #pragma unroll
   for (int i = 0; i < MI; ++i) af[0][i] = fa.get(lds_dyn, i, 0);
@@ -683,14 +651,11 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
       const bool more = (kk + 1 < KS) || !GUARD || (t + 1 < nk);
       const bf16_t *na = as, *nb = bs;
       if (kk + 1 == KS && more) {
-        TRACE_STAMP(1);
         // slice t + 1 must have landed (S - 2 younger slices may stay in flight) and this wavefront's reads of
         // slice t must be complete before anybody overwrites its stage
         if (!GUARD) wait_loads_le<(S - 2) * NL>();
         else wait_loads_le<0>();
-        TRACE_STAMP(2);
         __builtin_amdgcn_s_barrier();
-        TRACE_STAMP(3);
         na = lds_dyn + st_next * STAGE;
         nb = na + BM * BKT;
       }
@@ -737,10 +702,8 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
     slice(t, st, std::true_type{});
     if (++st == S) st = 0;
   }
-  TRACE_STAMP(5);
   wait_loads_le<0>();
   __builtin_amdgcn_s_barrier();  // the epilogue reuses the stages
-  TRACE_STAMP(6);
 
   const bool vec = ((g.ldc & 3) == 0) &&
                    ((((uintptr_t)g.out_f32 | (uintptr_t)g.resid | (uintptr_t)g.bias) & 15) == 0) &&
@@ -797,14 +760,9 @@ __global__ __launch_bounds__(128 * WGN * KW, OCC * KW * WGN / 2) void gemm_bf16_
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_wave_barrier();
     store_patch<WTN>(g, 0, patch, m0 + wm * WTM + i * 32, n0 + wn * WTN, lane, vec);
-    TRACE_STAMP(9);
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_wave_barrier();
   }
-  TRACE_STAMP(7);
-#ifdef HYDRA_GEMM_TRACE
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) g_gemm_trace[8191] = trace_n;
-#endif
 }
 
 template <int BM, int BN, int BKT, int S, int OCC, int KW = 1, int WGN = 2>
@@ -899,11 +857,6 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g, int ta,
     }
 }
 
-#ifdef HYDRA_GEMM_TRACE
-extern "C" int hydra_debug_gemm_trace(unsigned long long *host_out) {
-  return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gemm_trace), sizeof(unsigned long long) * 8192);
-}
-#endif
 
 template <int BM, int BN, int WM, int WN, int D>
 static hipError_t launch_bf16_cfg(const GemmArgs &a, int ta, int tb, dim3 grid, hipStream_t s) {
@@ -953,9 +906,6 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   // operand alignment the vector loads rely on
   if ((d.lda & 7) || (d.ldb & 7) || (((uintptr_t)d.A) & 15) || (((uintptr_t)d.B) & 15)) return hipErrorInvalidValue;
   if ((d.sA1 & 7) || (d.sA2 & 7) || (d.sB1 & 7) || (d.sB2 & 7)) return hipErrorInvalidValue;
-  // experimental overrides (tile / slices in flight)
-  static const int force_tile = getenv("HYDRA_GEMM_TILE") ? atoi(getenv("HYDRA_GEMM_TILE")) : 0;
-  static const int force_d = getenv("HYDRA_GEMM_D") ? atoi(getenv("HYDRA_GEMM_D")) : 0;
   // tile choice: 128x128 only for problems of many waves of tiles (the LM head); at a few thousand tokens per
   // visit the block GEMMs have 100-400 tiles and the narrower tile measured faster on every one of them
   const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128) * nbatch;
@@ -980,10 +930,8 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   }
   // too few 128x64 tiles to occupy half the CUs (the d x d weight gradient): 64x64 tiles measured a third faster
   else if (tile == 2 && (long)((d.M + 127) / 128) * ((d.N + 63) / 64) * nbatch < 128 && d.M > 64) tile = 3;
-  if (force_tile) tile = force_tile;
   // slices in flight: a deeper pipeline pays once the contraction is long enough to amortise filling it
   int D = (d.causal == CAUSAL_NONE && d.K >= 24 * BK) ? 4 : 2;
-  if (force_d && d.K > 4 * BK) D = force_d;
 #define HYDRA_LAUNCH(BM_, BN_, DD_)                                                                      \
   do {                                                                                                    \
     a.tiles_m = (d.M + BM_ - 1) / BM_;                                                                    \

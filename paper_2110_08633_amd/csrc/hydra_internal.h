@@ -16,7 +16,7 @@ struct Profiler;
 Profiler *prof_create();
 void prof_destroy(Profiler *p);
 void prof_activate(Profiler *p);
-void prof_collect(Profiler *p);
+void prof_collect(Profiler *p, hipEvent_t base);
 void prof_reset(Profiler *p);
 
 // swap / compute overlap trace (HYDRA_FLAG_OVERLAP)
@@ -117,8 +117,7 @@ struct hydra_ctx {
   // Compute lanes: each has its own stream and workspace; a model always runs on lane (model id % lanes), so
   // tasks of different models may overlap on the device while every model's own tasks stay in order.
   struct Lane {
-    hipStream_t stream = nullptr;
-    bool own_stream = false;
+    hipStream_t stream = nullptr;  // the caller's
     char *ws = nullptr;
     int logits_owner = -1;    // model whose logits the lane's workspace still holds
     float *logits = nullptr;

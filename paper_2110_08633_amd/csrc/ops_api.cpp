@@ -16,6 +16,9 @@ hydra_status hydra_op_gemm(int32_t dtype, int32_t ta, int32_t tb, int32_t M, int
                            const float *resid, float *out_f32, void *out_act, int64_t ldc, void *stream) {
   if ((dtype != 0 && dtype != 1) || M < 0 || N < 0 || K < 0 || !A || !B || (!out_f32 && !out_act))
     return fail(nullptr, HYDRA_E_INVAL, "bad GEMM argument");
+  // a leading dimension shorter than a stored row would make the kernel read or write outside the operands
+  if (lda < (ta ? M : K) || ldb < (tb ? N : K) || ldc < N)
+    return fail(nullptr, HYDRA_E_INVAL, "GEMM leading dimension shorter than a stored row");
   GemmDesc g;
   g.dtype = dtype; g.ta = ta != 0; g.tb = tb != 0; g.M = M; g.N = N; g.K = K; g.alpha = alpha;
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.ldc = ldc;
@@ -31,7 +34,7 @@ hydra_status hydra_op_adam(float *w, float *m, float *v, const float *g, void *s
 
 hydra_status hydra_op_layernorm_fwd(int32_t dtype, const float *x, const float *gamma, const float *beta, void *y,
                                     float *mean, float *rstd, int32_t M, int32_t d, void *stream) {
-  if (!x || !gamma || !beta || !y || !mean || !rstd || M < 0 || d <= 0 || (d & 7))
+  if ((dtype != 0 && dtype != 1) || !x || !gamma || !beta || !y || !mean || !rstd || M < 0 || d <= 0 || (d & 7))
     return fail(nullptr, HYDRA_E_INVAL, "bad LayerNorm argument");
   return ret(launch_layernorm_fwd(dtype, x, gamma, beta, y, mean, rstd, M, d, (hipStream_t)stream), "layernorm");
 }
@@ -55,13 +58,13 @@ hydra_status hydra_op_layernorm_bwd(const float *dy, const float *x, const float
 }
 
 hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T, void *stream) {
-  if (!S || !P || n_mat < 0 || T <= 0) return fail(nullptr, HYDRA_E_INVAL, "bad softmax argument");
+  if ((dtype != 0 && dtype != 1) || !S || !P || n_mat < 0 || T <= 0) return fail(nullptr, HYDRA_E_INVAL, "bad softmax argument");
   return ret(launch_softmax_causal_fwd(dtype, S, P, n_mat, T, (hipStream_t)stream), "softmax");
 }
 
 hydra_status hydra_op_cross_entropy(int32_t dtype, const float *logits, const int32_t *targets, float *row_loss,
                                     void *dlogits, int32_t M, int32_t V, int64_t ld, float inv_n, void *stream) {
-  if (!logits || !targets || !row_loss || !dlogits || M < 0 || V <= 0 || ld < V)
+  if ((dtype != 0 && dtype != 1) || !logits || !targets || !row_loss || !dlogits || M < 0 || V <= 0 || ld < V)
     return fail(nullptr, HYDRA_E_INVAL, "bad cross-entropy argument");
   return ret(launch_cross_entropy(dtype, logits, targets, row_loss, dlogits, M, V, ld, inv_n, (hipStream_t)stream),
              "cross_entropy");

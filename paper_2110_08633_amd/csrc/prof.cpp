@@ -25,6 +25,7 @@ struct ProfAgg {
 
 struct Profiler {
   std::vector<ProfRec> recs;
+  std::vector<std::pair<double, double>> ivals;  // launch intervals (ms after the overlap trace's base event)
   std::vector<hipEvent_t> pool;
   std::map<std::string, ProfAgg> agg;
   std::vector<std::string> order;
@@ -72,11 +73,14 @@ ProfScope::~ProfScope() {
   (void)hipEventRecord(p->recs[idx_].e1, stream_);
 }
 
-// caller has synchronised the streams
-void prof_collect(Profiler *p) {
+// caller has synchronised the streams.  base (may be null): an event recorded before all of these launches; the
+// launches' intervals relative to it are kept for the overlap trace.
+void prof_collect(Profiler *p, hipEvent_t base) {
   for (ProfRec &r : p->recs) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+      float a = 0.f;
+      if (base && hipEventElapsedTime(&a, base, r.e0) == hipSuccess && a >= 0.f) p->ivals.push_back({a, a + ms});
       auto it = p->agg.find(r.name);
       if (it == p->agg.end()) {
         p->order.push_back(r.name);
@@ -94,7 +98,8 @@ void prof_collect(Profiler *p) {
 }
 
 void prof_reset(Profiler *p) {
-  prof_collect(p);
+  prof_collect(p, nullptr);
+  p->ivals.clear();
   p->agg.clear();
   p->order.clear();
 }
@@ -212,14 +217,13 @@ static double common(const Intervals &a, const Intervals &b) {
   return s;
 }
 
-// caller has synchronised the streams
-static void trace_collect(Tracer *t, hydra_overlap *out) {
+// caller has synchronised the streams.  dump (may be null): one line per interval (kind, model, shard, start ms, end
+// ms, bytes).  prof (may be null): per-kernel timing of the same context, whose launch intervals give the
+// kernel-level figures.
+static void trace_collect(Tracer *t, Profiler *prof, hydra_overlap *out, FILE *dump) {
   memset(out, 0, sizeof *out);
   Intervals by_kind[3];
   double lo = 1e300, hi = -1e300;
-  // HYDRA_TRACE_DUMP=<file>: one line per interval (kind, model, shard, start ms, end ms, bytes) for timeline studies
-  const char *dump_path = getenv("HYDRA_TRACE_DUMP");
-  FILE *dump = dump_path ? fopen(dump_path, "w") : nullptr;
   for (TraceRec &r : t->recs) {
     float a = 0.f, b = 0.f;
     if (r.closed && hipEventElapsedTime(&a, t->base, r.e0) == hipSuccess &&
@@ -235,7 +239,6 @@ static void trace_collect(Tracer *t, hydra_overlap *out) {
       out->n_intervals++;
     }
   }
-  if (dump) fclose(dump);
   (void)hipGetLastError();
   if (!out->n_intervals) return;
   const Intervals comp = merged(by_kind[TRACE_COMPUTE]), h2d = merged(by_kind[TRACE_H2D]),
@@ -249,9 +252,19 @@ static void trace_collect(Tracer *t, hydra_overlap *out) {
   out->d2h_ms = length(d2h);
   out->transfer_ms = length(xfer);
   out->hidden_ms = common(xfer, comp);
+  if (prof) {
+    prof_collect(prof, t->base_recorded ? t->base : nullptr);
+    (void)hipGetLastError();
+    const Intervals kern = merged(prof->ivals);
+    out->kernel_ms = length(kern);
+    out->hidden_kernel_ms = common(xfer, kern);
+    if (dump)
+      for (const auto &iv : prof->ivals) fprintf(dump, "kernel -1 -1 %.4f %.4f 0\n", iv.first, iv.second);
+  }
 }
 
-static void trace_reset(Tracer *t) {
+static void trace_reset(Tracer *t, Profiler *prof) {
+  if (prof) prof->ivals.clear();
   for (TraceRec &r : t->recs) {
     t->pool.push_back(r.e0);
     t->pool.push_back(r.e1);
@@ -271,7 +284,20 @@ hydra_status hydra_overlap_stats(hydra_ctx *ctx, hydra_overlap *out) {
   if (!ctx->tracer) return fail(ctx, HYDRA_E_STATE, "context was not created with HYDRA_FLAG_OVERLAP");
   hydra_status st = hydra_sync(ctx);
   if (st) return st;
-  trace_collect(ctx->tracer, out);
+  trace_collect(ctx->tracer, ctx->prof, out, nullptr);
+  return HYDRA_OK;
+}
+
+hydra_status hydra_overlap_dump(hydra_ctx *ctx, const char *path) {
+  if (!ctx || !path) return fail(ctx, HYDRA_E_INVAL, "null argument");
+  if (!ctx->tracer) return fail(ctx, HYDRA_E_STATE, "context was not created with HYDRA_FLAG_OVERLAP");
+  hydra_status st = hydra_sync(ctx);
+  if (st) return st;
+  FILE *f = fopen(path, "w");
+  if (!f) return fail(ctx, HYDRA_E_INVAL, std::string("cannot open ") + path);
+  hydra_overlap o;
+  trace_collect(ctx->tracer, ctx->prof, &o, f);
+  fclose(f);
   return HYDRA_OK;
 }
 
@@ -280,7 +306,7 @@ hydra_status hydra_overlap_reset(hydra_ctx *ctx) {
   if (!ctx->tracer) return fail(ctx, HYDRA_E_STATE, "context was not created with HYDRA_FLAG_OVERLAP");
   hydra_status st = hydra_sync(ctx);
   if (st) return st;
-  trace_reset(ctx->tracer);
+  trace_reset(ctx->tracer, ctx->prof);
   return HYDRA_OK;
 }
 
@@ -290,7 +316,7 @@ hydra_status hydra_kernel_stats(hydra_ctx *ctx, int32_t index, char name[64], ui
   if (!ctx->prof) return fail(ctx, HYDRA_E_STATE, "context was not created with HYDRA_FLAG_TIMING");
   hydra_status st = hydra_sync(ctx);
   if (st) return st;
-  prof_collect(ctx->prof);
+  prof_collect(ctx->prof, ctx->tracer && ctx->tracer->base_recorded ? ctx->tracer->base : nullptr);
   std::string n;
   if (!prof_get(ctx->prof, index, &n, launches, total_ms, flops, bytes)) return 1;
   snprintf(name, 64, "%s", n.c_str());

@@ -19,6 +19,7 @@ struct hydra_sched {
   std::vector<int> model_id, S, n_mb;
   std::vector<hydra_task> order;  // complete decision sequence; model = index into model_id
   size_t cursor = 0;
+  size_t promoted = 0;  // tasks [0, promoted) of the order have had their shard promoted
 };
 
 using namespace hydra;
@@ -66,11 +67,11 @@ size_t next_use(const hydra_sched *s, size_t from, int model, int shard) {
   return (size_t)-1;
 }
 
-// Promote the shard of task i.  When no buffer is free, the resident shard
-// whose next use lies furthest in the future is demoted first.
-hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
+// Promote the shard of task j while tasks i .. j-1 have not been enqueued yet.  When no buffer is free, a resident
+// shard that none of the tasks i .. j needs is demoted first; returns 1 (not an error) when there is none.
+hydra_status promote(hydra_sched *s, size_t j, size_t i) {
   hydra_ctx *ctx = s->ctx;
-  const hydra_task &t = s->order[i];
+  const hydra_task &t = s->order[j];
   const int mid = s->model_id[t.model];
   const int what = t.phase == 1 ? (HYDRA_LOAD_PARAMS | HYDRA_LOAD_OPT) : HYDRA_LOAD_PARAMS;
   hydra_status st = ensure_planned(ctx);
@@ -89,23 +90,23 @@ hydra_status promote(hydra_sched *s, size_t i, int keep_model, int keep_shard) {
       size_t far = 0;
       uint64_t oldest_use = ~0ull, oldest_wb = ~0ull;
       const size_t soon = 2 * ctx->slots.size();
-      for (size_t j = 0; j < ctx->slots.size(); ++j) {
-        const Slot &sl = ctx->slots[j];
-        if (sl.model == keep_model && sl.shard == keep_shard) continue;  // in use by the running task
+      for (size_t q = 0; q < ctx->slots.size(); ++q) {
+        const Slot &sl = ctx->slots[q];
         int local = -1;
         for (int m = 0; m < s->n_models; ++m)
           if (s->model_id[m] == sl.model) local = m;
         const size_t nu = local < 0 ? (size_t)-1 : next_use(s, i, local, sl.shard);
-        if (victim < 0 || nu > far) { victim = (int)j; far = nu; }
+        if (nu <= j) continue;  // a task that runs before the prefetched one (or that one itself) works on it
+        if (victim < 0 || nu > far) { victim = (int)q; far = nu; }
         const uint64_t wb = sl.dirty ? ~0ull - 1 : sl.wb_seq;  // a write-back not even enqueued yet comes last
         if ((nu == (size_t)-1 || nu - i > soon) && (wb < oldest_wb || (wb == oldest_wb && sl.last_use < oldest_use))) {
-          oldest = (int)j;
+          oldest = (int)q;
           oldest_use = sl.last_use;
           oldest_wb = wb;
         }
       }
       if (oldest >= 0) victim = oldest;
-      if (victim < 0) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the prefetch");
+      if (victim < 0) return 1;
       const Slot &v = ctx->slots[victim];
       st = hydra_shard_spill(ctx, v.model, v.shard, HYDRA_SPILL_WRITEBACK | HYDRA_SPILL_EVICT);
       if (st) return st;
@@ -188,16 +189,26 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
   for (Model *m : ctx->models) total_shards += m->sh.S + 2;
   const bool all_fit = ctx->slots.size() >= total_shards;
   int64_t done = 0;
-  if (s->cursor < s->order.size() && (st = promote(s, s->cursor, -1, -1))) return st;
+  // how many tasks ahead shards are promoted for: as far as buffers can be found (each prefetched shard holds one),
+  // or the caller's limit
+  const size_t depth = ctx->init.prefetch_depth > 0 ? (size_t)ctx->init.prefetch_depth : ctx->slots.size();
+  if (s->promoted < s->cursor) s->promoted = s->cursor;
   while (s->cursor < s->order.size()) {
     const size_t i = s->cursor;
     const hydra_task t = s->order[i];
     const int mid = s->model_id[t.model];
     Model *mm = ctx->models[mid];
-    // prefetch the next task's shard while this one runs
-    if (i + 1 < s->order.size() && ctx->slots.size() > 1) {
+    // promote this task's shard if that has not happened yet, and prefetch the shards of the tasks after it while
+    // this one runs (double buffering, paper Section 2.3; deeper where more buffers are free)
+    {
       HostTimer ht(&ctx->stats.host_promote_ms);
-      if ((st = promote(s, i + 1, mid, t.shard))) return st;
+      while (s->promoted < s->order.size() && s->promoted <= i + depth) {
+        st = promote(s, s->promoted, i);
+        if (st == 1) break;  // every buffer holds a shard that a task before that one needs
+        if (st) return st;
+        s->promoted++;
+      }
+      if (s->promoted <= i) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the next task");
     }
     if (t.phase == 0 && t.shard == 0) {
       HostTimer ht(&ctx->stats.host_batch_ms);
@@ -220,10 +231,6 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
         HostTimer ht(&ctx->stats.host_writeback_ms);
         if ((st = hydra_shard_spill(ctx, mid, t.shard, HYDRA_SPILL_WRITEBACK))) return st;
       }
-    }
-    if (ctx->slots.size() == 1 && i + 1 < s->order.size()) {
-      // single buffer: no double buffering possible, promote after the task
-      if ((st = promote(s, i + 1, -1, -1))) return st;
     }
     if (trace && done < trace_cap) {
       trace[done] = t;

@@ -24,6 +24,7 @@ OK, E_INVAL, E_NOSLOT, E_STATE, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
 FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS, FLAG_OVERLAP = 1, 2, 4, 8, 16, 32, 64
 LOAD_PARAMS, LOAD_OPT = 1, 2
 SPILL_WRITEBACK, SPILL_EVICT = 1, 2
+MAX_LANES = 8
 RD_LOGITS, RD_GRADS, RD_PARAMS, RD_ADAM_M, RD_ADAM_V, RD_CKPT, RD_DBOUND = range(7)
 
 
@@ -31,7 +32,8 @@ class InitDesc(C.Structure):
     _fields_ = [("dev_arena", C.c_void_p), ("dev_arena_bytes", C.c_uint64),
                 ("shard_buffer_cap_bytes", C.c_uint64), ("max_slots", C.c_int32), ("flags", C.c_int32),
                 ("compute_stream", C.c_void_p), ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
-                ("compute_lanes", C.c_int32), ("reserved", C.c_int32)]
+                ("compute_lanes", C.c_int32), ("copy_blocks", C.c_int32),
+                ("lane_streams", C.c_void_p * (MAX_LANES - 1)), ("prefetch_depth", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ModelDesc(C.Structure):
@@ -43,7 +45,8 @@ class ModelDesc(C.Structure):
 
 
 class HostState(C.Structure):
-    _fields_ = [("master", C.c_void_p), ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("ckpt", C.c_void_p)]
+    _fields_ = [("master", C.c_void_p), ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("ckpt", C.c_void_p),
+                ("batch_stage", C.c_void_p)]
 
 
 class Layout(C.Structure):
@@ -58,7 +61,8 @@ class Task(C.Structure):
 class Overlap(C.Structure):
     _fields_ = [("wall_ms", C.c_double), ("compute_ms", C.c_double), ("h2d_ms", C.c_double), ("d2h_ms", C.c_double),
                 ("transfer_ms", C.c_double), ("hidden_ms", C.c_double), ("bytes_h2d", C.c_uint64),
-                ("bytes_d2h", C.c_uint64), ("n_intervals", C.c_uint64)]
+                ("bytes_d2h", C.c_uint64), ("n_intervals", C.c_uint64), ("kernel_ms", C.c_double),
+                ("hidden_kernel_ms", C.c_double)]
 
 
 class Stats(C.Structure):
@@ -84,6 +88,7 @@ SIGNATURES = {
     "hydra_kernel_stats_reset": (_i32, [_vp]),
     "hydra_overlap_stats": (_i32, [_vp, _P(Overlap)]),
     "hydra_overlap_reset": (_i32, [_vp]),
+    "hydra_overlap_dump": (_i32, [_vp, C.c_char_p]),
     "hydra_model_layout": (_i32, [_P(ModelDesc), _P(Layout)]),
     "hydra_model_tensor": (_i32, [_P(ModelDesc), _i32, C.c_char_p, _P(_i64), _P(_i64), _P(_i64), _P(_i32)]),
     "hydra_shard_range": (_i32, [_P(ModelDesc), _i32, _P(_i64), _P(_i64)]),
@@ -156,9 +161,12 @@ def model_desc(cfg, lr, dtype=None, beta1=0.9, beta2=0.999, eps=1e-8):
 # ---- thin wrappers, same names as the C functions --------------------------
 
 def hydra_init(arena, arena_bytes, compute_stream=None, h2d_stream=None, d2h_stream=None, flags=0,
-               shard_buffer_cap_bytes=0, max_slots=0, compute_lanes=1):
+               shard_buffer_cap_bytes=0, max_slots=0, compute_lanes=1, lane_streams=(), copy_blocks=0,
+               prefetch_depth=0):
+    lanes = (C.c_void_p * (MAX_LANES - 1))(*[_stream(x) for x in lane_streams])
     d = InitDesc(arena if isinstance(arena, int) else _ptr(arena), arena_bytes, shard_buffer_cap_bytes, max_slots,
-                 flags, _stream(compute_stream), _stream(h2d_stream), _stream(d2h_stream), compute_lanes, 0)
+                 flags, _stream(compute_stream), _stream(h2d_stream), _stream(d2h_stream), compute_lanes, copy_blocks,
+                 lanes, prefetch_depth, 0)
     out = _vp()
     _check(lib.hydra_init(C.byref(d), C.byref(out)))
     return out
@@ -210,6 +218,10 @@ def hydra_overlap_reset(ctx):
     return _check(lib.hydra_overlap_reset(ctx), ctx)
 
 
+def hydra_overlap_dump(ctx, path):
+    return _check(lib.hydra_overlap_dump(ctx, os.fsencode(path)), ctx)
+
+
 def hydra_model_layout(desc):
     lay = Layout()
     _check(lib.hydra_model_layout(C.byref(desc), C.byref(lay)))
@@ -230,8 +242,8 @@ def hydra_shard_range(desc, shard):
     return off.value, cnt.value
 
 
-def hydra_register_model(ctx, desc, master, adam_m, adam_v, ckpt=None):
-    hs = HostState(_ptr(master), _ptr(adam_m), _ptr(adam_v), _ptr(ckpt))
+def hydra_register_model(ctx, desc, master, adam_m, adam_v, ckpt, batch_stage):
+    hs = HostState(_ptr(master), _ptr(adam_m), _ptr(adam_v), _ptr(ckpt), _ptr(batch_stage))
     mid = _i32()
     _check(lib.hydra_register_model(ctx, C.byref(desc), C.byref(hs), C.byref(mid)), ctx)
     return mid.value

@@ -6,21 +6,70 @@ state machine tests).
 """
 from __future__ import annotations
 
+import ctypes as C
+
 import numpy as np
 
 from . import hydra as H
+
+_hip = None
+
+
+def _hip_runtime():
+    """The HIP runtime already loaded into this process (torch's), so that host memory page-locked here is known to
+    the runtime the library and torch use."""
+    global _hip
+    if _hip is None:
+        path = None
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    path = line.split()[-1]
+                    break
+        if path is None:
+            raise RuntimeError("no HIP runtime is loaded in this process")
+        _hip = C.CDLL(path)
+        _hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+        _hip.hipHostFree.argtypes = [C.c_void_p]
+    return _hip
+
+
+class PinnedArray:
+    """Page-locked host memory from hipHostMalloc, viewed as a numpy array; released by free() (torch's pinned
+    allocator rounds sizes up to powers of two and keeps what it is given back, which does not suit arrays of tens
+    of gigabytes).  Fresh pages read as zero; zero=True clears them regardless."""
+
+    def __init__(self, n, dtype=np.float32, zero=True):
+        self.nbytes = max(int(n) * np.dtype(dtype).itemsize, 16)
+        p = C.c_void_p()
+        e = _hip_runtime().hipHostMalloc(C.byref(p), self.nbytes, 0)
+        if e != 0 or not p.value:
+            raise MemoryError(f"hipHostMalloc of {self.nbytes} bytes failed (HIP error {e})")
+        self.ptr = p.value
+        if zero:
+            C.memset(self.ptr, 0, self.nbytes)
+        self.array = np.frombuffer((C.c_char * self.nbytes).from_address(self.ptr), dtype=dtype, count=int(n))
+
+    def free(self):
+        if self.ptr:
+            self.array = None
+            _hip_runtime().hipHostFree(self.ptr)
+            self.ptr = None
 
 
 class Session:
     """One hydra context with its arena, three streams and registered models."""
 
-    def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False, lanes=1):
+    def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False, lanes=1,
+                 copy_blocks=0, prefetch_depth=0):
         self.dry = dry_run
         self.models = []      # dicts: desc, cfg, master, m, v, ckpt, id, names
+        self._pinned = []
         if dry_run:
             flags |= H.FLAG_DRY_RUN
             self.arena = None
             self.streams = (None, None, None)
+            self.lane_streams = []
             arena_ptr = 256
         else:
             import torch
@@ -28,17 +77,19 @@ class Session:
             self.arena = torch.empty(arena_bytes + 256, dtype=torch.uint8, device="cuda:0")
             arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
             self.streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+            self.lane_streams = [torch.cuda.Stream() for _ in range(lanes - 1)]     # default priority
         self.ctx = H.hydra_init(arena_ptr, arena_bytes, *self.streams, flags=flags,
                                 shard_buffer_cap_bytes=shard_buffer_cap_bytes, max_slots=max_slots,
-                                compute_lanes=lanes)
+                                compute_lanes=lanes, lane_streams=self.lane_streams, copy_blocks=copy_blocks,
+                                prefetch_depth=prefetch_depth)
         self.flags = flags
 
     def _host(self, n, dtype=np.float32):
         if self.dry:
             return np.zeros(n, dtype)
-        t = self.torch.zeros(n, dtype=self.torch.float32, pin_memory=True)
-        self._keep = getattr(self, "_keep", []) + [t]
-        return t.numpy()
+        buf = PinnedArray(n, dtype)
+        self._pinned.append(buf)
+        return buf.array
 
     def add_model(self, cfg, weights, lr, dtype=None):
         """weights: dict name -> float32 array (names as given by hydra_model_tensor)."""
@@ -54,8 +105,9 @@ class Session:
         ckpt = None
         if self.flags & H.FLAG_CKPT_SPILL:
             ckpt = self._host((lay.n_block_shards + 1) * cfg.get("n_micro", 1) * cfg["B"] * cfg["T"] * cfg["d"])
-        mid = H.hydra_register_model(self.ctx, desc, master, m, v, ckpt)
-        rec = dict(id=mid, desc=desc, cfg=cfg, layout=lay, master=master, m=m, v=v, ckpt=ckpt, tensors=tensors,
+        stage = self._host(4 * cfg.get("n_micro", 1) * cfg["B"] * cfg["T"], np.int32)
+        mid = H.hydra_register_model(self.ctx, desc, master, m, v, ckpt, stage)
+        rec = dict(id=mid, desc=desc, cfg=cfg, layout=lay, master=master, m=m, v=v, ckpt=ckpt, stage=stage, tensors=tensors,
                    S=lay.n_block_shards)
         self.models.append(rec)
         return rec
@@ -124,9 +176,16 @@ class Session:
         H.hydra_sync(self.ctx)
 
     def close(self):
+        """Destroys the context and releases the page-locked arrays: views of them (rec["master"] ...) die here."""
         if self.ctx is not None:
             H.hydra_destroy(self.ctx)
             self.ctx = None
+        for rec in self.models:
+            for k in ("master", "m", "v", "ckpt", "stage"):
+                rec[k] = None
+        for buf in self._pinned:
+            buf.free()
+        self._pinned = []
 
 
 def arena_bytes_for(cfgs, n_slots, ckpt_spill=False, lanes=1):

@@ -23,50 +23,90 @@ def rt():
     return hydra, runtime
 
 
-def oracle_steps(cfg, W, lr, batches, dtype=np.float64):
-    P = D.cast_params(W, dtype)
-    Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
-    outs = []
-    for t, (tok, tgt) in enumerate(batches, 1):
-        before = {k: v.copy() for k, v in P.items()}
-        o = D.train_step(P, Mo, Vo, tok, tgt, cfg, lr, t)
-        o["before"] = before
-        o["after"] = {k: v.copy() for k, v in P.items()}
-        outs.append(o)
-    return outs, P, Mo, Vo
+# ---------------------------------------------------------------------------------------------------------------
+# Updated weights and optimizer state.  Adam's first steps move a weight by about lr * m_hat / sqrt(v_hat), a
+# quantity that depends on the gradient history only through ratios: where a gradient element is at the noise
+# level of the arithmetic (the key bias, whose exact gradient is zero) its sign - and with it the whole step - is
+# decided by rounding on either side, while 2e-2 of max|w| is many Adam steps wide.  So "updated weights match"
+# is split into checks that each bite:
+#   (1) replay: the oracle's Adam, fed the gradients the GPU itself produced (read back before each step), must
+#       reproduce the GPU's w, m and v element by element to fp32 rounding.  This pins step counter, learning rate,
+#       state plumbing and write-back for EVERY element, whatever its gradient;
+#   (2) m (linear in the gradients) and v (quadratic) against the oracle's at tol and (1+tol)^2-1, every element;
+#   (3) w against the oracle's, every element: within tol * max|w| (the stated criterion) plus what the gradient
+#       error can move Adam by - lr per step times min(2 * rel, 2.5), rel being the element's relative gradient
+#       error (below); an element whose gradient is pure rounding noise may thus differ by whole Adam steps, and
+#       (1) still pins its update exactly;
+#   (4) the weight delta against the oracle's element by element wherever the element is well-conditioned:
+#       rel = max over steps of |g_gpu - g_oracle| / |g_oracle| <= WELL.  The update ratio m_hat/sqrt(v_hat) is
+#       homogeneous of degree 0 in the gradient history and its logarithmic derivatives sum to at most about 1 in
+#       magnitude per step, so a relative perturbation rel of the gradients moves each step by at most
+#       about 2 * lr * rel.  The share of well-conditioned elements per tensor is reported and must
+#       stay above MIN_WELL (the key third of b_qkv is left out of that share: softmax is invariant to a shift
+#       along the key axis, its exact gradient is zero).
+WELL = 0.2
+MIN_WELL = {"f32": 0.99, "bf16": 0.85}     # measured: at most 0.10 excused (small bias vectors), 0.06 on the large workloads
+EXCLUDED_SHARE = {}          # test id -> tensor -> share of elements not well-conditioned (printed with -s)
 
 
-# Adam's first steps move a weight by about lr * g / |g|: where the gradient of an element is at the noise level of
-# the arithmetic (e.g. the key bias, whose exact gradient is zero), the step is decided by rounding noise on either
-# side.  The gradient check admits an absolute error of tol * max|g| per element, so elements whose oracle gradient is
-# below FLOOR = 5 * tol times max|g| of their tensor at any step so far are called ill-conditioned: they may differ by
-# a full Adam step; all other elements must meet the tolerance.
-FLOOR = {"f32": 5e-4, "bf16": 1e-1}
-DELTA_TOL = {"f32": 2e-3, "bf16": 5e-2}
+def _key_bias_mask(name, n):
+    keep = np.ones(n, bool)
+    if name.endswith("b_qkv"):
+        keep[n // 3: 2 * n // 3] = False
+    return keep
 
 
-def update_ill(ill, grads, dtype):
-    for name, g in grads.items():
-        a = np.abs(g)
-        bad = a < FLOOR[dtype] * a.max()
-        ill[name] = bad if name not in ill else (ill[name] | bad)
-    return ill
+class UpdateCheck:
+    def __init__(self, W0, lr, dtype, what=""):
+        self.lr, self.dtype, self.what, self.t = lr, dtype, what, 0
+        self.w0 = {k: np.asarray(v, np.float64).copy() for k, v in W0.items()}
+        self.rw = {k: v.copy() for k, v in self.w0.items()}
+        self.rm = {k: np.zeros_like(v) for k, v in self.w0.items()}
+        self.rv = {k: np.zeros_like(v) for k, v in self.w0.items()}
+        self.rel = {k: np.zeros_like(v) for k, v in self.w0.items()}
+        self.share = {}
 
+    def step(self, gpu_grads, ref_grads, gpu_w, gpu_m, gpu_v, ref_w, ref_m, ref_v):
+        self.t += 1
+        t, lr, tol = self.t, self.lr, TOL[self.dtype]
+        for name in ref_w:
+            tag = f"{self.what}step {t} {name}"
+            g = np.asarray(gpu_grads[name], np.float64)
+            w, m, v = (np.asarray(a[name], np.float64) for a in (gpu_w, gpu_m, gpu_v))
+            assert np.isfinite(w).all() and np.isfinite(m).all() and np.isfinite(v).all(), tag
+            # (1) replay of the GPU's own gradients through the oracle's Adam
+            self.rw[name], self.rm[name], self.rv[name] = D.adam_update(self.rw[name], self.rm[name], self.rv[name], g, t, lr)
+            rw, rm, rv = self.rw[name], self.rm[name], self.rv[name]
+            ex = np.abs(w - rw) - (1e-3 * lr * t + 1.5e-7 * t * np.abs(rw))
+            assert (ex <= 0).all(), f"{tag}: update is not Adam of the gradients held (excess {ex.max():.3e})"
+            assert (np.abs(m - rm) <= 1e-5 * np.abs(rm).max() + 1e-30).all(), f"{tag}: m is not Adam's"
+            assert (np.abs(v - rv) <= 1e-5 * np.abs(rv).max() + 1e-30).all(), f"{tag}: v is not Adam's"
+            # (2) optimizer state against the oracle
+            assert_close(m, ref_m[name], tol, tag + " adam m")
+            assert_close(v, ref_v[name], (1 + tol) ** 2 - 1, tag + " adam v")
+            go = np.abs(np.asarray(ref_grads[name], np.float64))
+            err = np.abs(g - ref_grads[name])
+            self.rel[name] = np.maximum(self.rel[name], err / np.maximum(go, 1e-300))
+            # (3) weights against the oracle, every element
+            ex = np.abs(w - ref_w[name]) - (tol * np.abs(ref_w[name]).max() + lr * t * np.minimum(2 * self.rel[name], 2.5))
+            assert (ex <= 0).all(), f"{tag}: weight differs from the oracle's (excess {ex.max():.3e})"
+            # (4) weight delta, element by element where the gradient history is well-conditioned
+            well = self.rel[name] <= WELL
+            keep = _key_bias_mask(name, well.size).reshape(well.shape)
+            self.share[name] = 1.0 - float(well[keep].mean())
+            dref, dgot = ref_w[name] - self.w0[name], w - self.w0[name]
+            allowed = 2 * lr * t * self.rel[name] + 1e-3 * lr * t + 1.5e-7 * t * np.abs(ref_w[name])
+            bad = well & (np.abs(dgot - dref) > allowed)
+            assert not bad.any(), f"{tag}: delta differs on {bad.sum()} well-conditioned elements"
+            # (a share over a few dozen elements is too coarse to bound)
+            assert keep.sum() < 256 or 1.0 - self.share[name] >= MIN_WELL[self.dtype], \
+                f"{tag}: only {1 - self.share[name]:.3f} of the elements are well-conditioned"
 
-def check_weights(after_gpu, ref_after, ref_before_first, ill, lr, steps, dtype, what=""):
-    tol = TOL[dtype]
-    for name, ref in ref_after.items():
-        got = after_gpu[name].astype(np.float64)
-        assert np.isfinite(got).all(), f"{what}weight {name}: non-finite"
-        err = np.abs(got - ref)
-        allowed = tol * np.abs(ref).max() + np.where(ill[name], 2.5 * lr * steps, 0.0)
-        assert (err <= allowed).all(), f"{what}weight {name}: max excess {(err - allowed).max():.3e}"
-        well = ~ill[name]
-        if well.any():
-            dref = (ref - ref_before_first[name])[well]
-            dgot = (got - ref_before_first[name])[well]
-            em, e2 = rel_errs(dgot, dref)
-            assert e2 <= DELTA_TOL[dtype], f"{what}delta {name}: l2-rel {e2:.3e} (max-rel {em:.3e})"
+    def report(self, test_id):
+        EXCLUDED_SHARE[test_id] = dict(self.share)
+        worst = sorted(self.share.items(), key=lambda kv: -kv[1])[:4]
+        print(f"[{test_id}] share of elements excused from the delta check, worst tensors: "
+              + ", ".join(f"{k} {v:.3f}" for k, v in worst))
 
 
 def check_step(cfg, got, ref, tol):
@@ -76,35 +116,65 @@ def check_step(cfg, got, ref, tol):
         assert_close(got["grads"][name], g, tol, f"grad {name}")
 
 
-def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False):
+def host_state(sess, rec):
+    """Copies of the model's host arrays (master, m, v) as dicts of named tensors."""
+    return tuple({k: a.copy() for k, a in sess.unpack(rec, rec[key]).items()} for key in ("master", "m", "v"))
+
+
+def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False, W=None, lr=None, batches=None, oracle_cfg=None,
+               test_id=None, cap=0, oracle=True):
+    """n_steps minibatches of one model through the shard calls one by one (every shard spilled between visits),
+    everything compared with the oracle after every step: logits, loss, every gradient tensor, updated weights,
+    weight deltas, Adam state.  Returns the per-step oracle losses, the final host state (w, m, v), the last loss
+    and the oracle's final (P, m, v).  oracle=False only runs the GPU side (for bit-for-bit comparisons)."""
     H, R = rt
-    W = SI.make_weights(cfg, SI.model_seed(cfg, 0))
-    lr = cfg["lrs"][0]
-    batches = [SI.make_batch(cfg, SI.batch_seed(cfg, 0, i), zipf=zipf) for i in range(n_steps)]
-    refs, P, Mo, Vo = oracle_steps(cfg, W, lr, batches)
-    sess = R.Session(R.arena_bytes_for([cfg], 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags, max_slots=max_slots or 4)
+    W = SI.make_weights(cfg, SI.model_seed(cfg, 0)) if W is None else W
+    lr = cfg["lrs"][0] if lr is None else lr
+    ocfg = oracle_cfg or cfg
+    if batches is None:
+        batches = [SI.make_batch(ocfg, SI.batch_seed(cfg, 0, i), zipf=zipf) for i in range(n_steps)]
+    sess = R.Session(R.arena_bytes_for([cfg], max_slots or 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags,
+                     max_slots=max_slots or 4, shard_buffer_cap_bytes=cap)
     rec = sess.add_model(cfg, W, lr)
-    bf16 = cfg["dtype"] == "bf16"
-    ill = {}
+    if oracle:
+        P = D.cast_params(W, np.float64)
+        Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
+        chk = UpdateCheck(W, lr, cfg["dtype"])
+    refs, loss = [], None
+    M = cfg["B"] * cfg["T"]
+    tol = TOL[cfg["dtype"]]
     for i, (tok, tgt) in enumerate(batches):
-        got = sess.train_step_manual(rec, tok, tgt)
+        got = sess.train_step_manual(rec, tok, tgt, collect=oracle)
         H.hydra_sync(sess.ctx)
-        after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
-        check_step(cfg, got, refs[i], TOL[cfg["dtype"]])
-        update_ill(ill, refs[i]["grads"], cfg["dtype"])
-        check_weights(after, refs[i]["after"], refs[0]["before"], ill, lr, i + 1, cfg["dtype"], f"step {i}: ")
-    if not bf16:
-        for name, a in sess.unpack(rec, rec["m"]).items():
-            assert_close(a, Mo[name], 1e-4, f"adam m {name}")
-        for name, a in sess.unpack(rec, rec["v"]).items():
-            assert_close(a, Vo[name], 2e-4, f"adam v {name}")
+        loss = got["loss"]
+        if not oracle:
+            continue
+        ref = D.train_step(P, Mo, Vo, tok, tgt, ocfg, lr, i + 1)
+        assert_close(got["logits"], ref["logits"][-M:], tol, "logits (of the last micro-batch)")
+        assert abs(got["loss"] - ref["loss"]) <= tol * abs(ref["loss"]), ("loss", got["loss"], ref["loss"])
+        for name, g in ref["grads"].items():
+            assert_close(got["grads"][name], g, tol, f"step {i} grad {name}")
+        w, m, v = host_state(sess, rec)
+        chk.step(got["grads"], ref["grads"], w, m, v, P, Mo, Vo)
+        refs.append(dict(loss=ref["loss"]))
+        del ref, got, w, m, v
+    if oracle:
+        chk.report(test_id or f"manual {cfg['dtype']} L{cfg['L']} d{cfg['d']} T{cfg['T']}")
+    final = host_state(sess, rec)
     sess.close()
-    return refs
+    return refs, final, loss, ((P, Mo, Vo) if oracle else None)
+
+
+def assert_same_state(got, want, what=""):
+    """Bit-for-bit: interleaving, prefetching, lanes, buffers and graphs must not change a model's result."""
+    for a, b, kind in zip(got, want, ("weight", "adam m", "adam v")):
+        for name in b:
+            assert (a[name] == b[name]).all(), f"{what}{kind} {name} differs from the model run alone"
 
 
 def test_tiny_config_fp32_three_steps(rt):
     """BASELINE config 1: 2 layers, d 128, 4 heads, MLP 512, vocab 512, seq 64, batch 2, 1 layer per shard."""
-    refs = run_manual(rt, SI.CONFIGS["tiny"], 3)
+    refs, _, _, _ = run_manual(rt, SI.CONFIGS["tiny"], 3, test_id="tiny f32")
     assert abs(refs[0]["loss"] - np.log(512)) < 5e-2
 
 
@@ -154,7 +224,72 @@ def test_embedding_forward_is_bit_exact_and_absent_rows_untouched(rt):
     sess.close()
 
 
-@pytest.mark.parametrize("max_slots,lanes", [(2, 1), (3, 1), (0, 1), (3, 2), (0, 3)])
+def scheduled_run(rt, cfgs, Ws, lrs, batches, nmb, tables, max_slots=0, lanes=1, flags=0, cap=0, slots_for_arena=12):
+    """All models through hydra_sched_run; returns (trace, per-model host state, per-model last loss, stats)."""
+    H, R = rt
+    n = len(cfgs)
+    sess = R.Session(R.arena_bytes_for(cfgs, slots_for_arena, bool(flags & H.FLAG_CKPT_SPILL), lanes=lanes),
+                     max_slots=max_slots, lanes=lanes, flags=flags, shard_buffer_cap_bytes=cap)
+    recs = [sess.add_model(cfgs[m], Ws[m], lrs[m]) for m in range(n)]
+    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, tables)
+    toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
+    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
+    trace, done = H.hydra_sched_run(sch, toks, tgts, sess.ctx, trace_cap=8192)
+    sess.flush()
+    st = H.hydra_get_stats(sess.ctx)
+    states = [host_state(sess, r) for r in recs]
+    losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
+    assert done == len(trace) == st["n_tasks"]
+    H.hydra_sched_destroy(sch)
+    sess.close()
+    return trace, states, losses, st
+
+
+def oracle_order(cfgs, nmb, tables):
+    """Task order of the oracle's Sharded-LRTF on the same cost tables, as (model, shard, phase, minibatch)."""
+    chains = [SP.model_task_chain(cfgs[m], nmb[m]) for m in range(len(cfgs))]
+    costs = []
+    for m, ch in enumerate(chains):
+        ns = cfgs[m]["L"] // cfgs[m]["k"] + 2
+        costs.append([tables[m][s if ph == SP.FWD else ns + s] for s, ph in ch])
+    order = SP.sharded_lrtf(chains, costs)
+    out = []
+    for m, i in order:
+        per = 2 * (cfgs[m]["L"] // cfgs[m]["k"] + 2)
+        out.append((m, chains[m][i][0], chains[m][i][1], i // per))
+    return out, order, chains
+
+
+def costs_of(cfg):
+    fc, bc = SI.task_costs(cfg)
+    return list(fc) + list(bc)
+
+
+def check_against_models_alone(rt, cfgs, bigs, Ws, lrs, batches, states, losses, dtype, flags=0, what="",
+                               oracle_models=None):
+    """Every model of a scheduled run, run alone through the shard calls with every step compared against the
+    oracle (run_manual); the scheduled run must have left exactly the same weights, Adam state and last loss.
+    oracle_models (default: all): the models whose run alone is compared with the oracle; the others are only run
+    alone on the GPU for the bit-for-bit comparison (large models, where the oracle takes minutes)."""
+    out = []
+    for m in range(len(cfgs)):
+        with_oracle = oracle_models is None or m in oracle_models
+        refs, final, loss, oracle = run_manual(rt, cfgs[m], len(batches[m]), W=Ws[m], lr=lrs[m], batches=batches[m],
+                                              oracle_cfg=bigs[m], flags=flags, test_id=f"{what}model {m} {dtype}",
+                                              oracle=with_oracle)
+        assert_same_state(states[m], final, f"{what}model {m}: ")
+        assert losses[m] == loss, (what, m, losses[m], loss)
+        tol = TOL[dtype]
+        if with_oracle:   # (the weights equal the run alone bit for bit, and that run was compared step by step)
+            for got, ref, kind, tl in zip(states[m][1:], oracle[1:], ("adam m", "adam v"), (tol, (1 + tol) ** 2 - 1)):
+                for name in ref:
+                    assert_close(got[name], ref[name], tl, f"{what}model {m} {kind} {name}")
+        out.append(oracle)
+        del final
+    return out
+
+
+@pytest.mark.parametrize("max_slots,lanes", [(2, 1), (3, 1), (0, 1), (2, 2), (3, 2), (0, 3)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_scheduled_multi_model_run_matches_oracle(rt, max_slots, lanes, dtype):
     """Three models with different learning rates and weights, interleaved by the library's scheduler with
@@ -165,40 +300,18 @@ def test_scheduled_multi_model_run_matches_oracle(rt, max_slots, lanes, dtype):
     n, nmb = 3, [2, 1, 2]
     Ws = [SI.make_weights(cfg, 40 + m) for m in range(n)]
     batches = [[SI.make_batch(cfg, 700 + 10 * m + i) for i in range(nmb[m])] for m in range(n)]
-    fc, bc = SI.task_costs(cfg)
-    chains = [SP.model_task_chain(cfg, nmb[m]) for m in range(n)]
-    costs = [[(fc if ph == SP.FWD else bc)[s] for s, ph in ch] for ch in chains]
-    order = SP.sharded_lrtf(chains, costs)
+    tables = [costs_of(cfg)] * n
+    want, order, chains = oracle_order([cfg] * n, nmb, tables)
     oracle = [SP.SpilledModel(cfg, Ws[m], cfg["lrs"][m], np.float64) for m in range(n)]
     SP.run_interleaved(oracle, batches, order, chains)
-
-    sess = R.Session(R.arena_bytes_for([cfg] * n, 12, lanes=lanes), max_slots=max_slots, lanes=lanes,
-                     flags=H.FLAG_POISON if lanes > 1 else 0)
-    recs = [sess.add_model(cfg, Ws[m], cfg["lrs"][m]) for m in range(n)]
-    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, [list(fc) + list(bc)] * n)
-    toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
-    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
-    trace, done = H.hydra_sched_run(sch, toks, tgts, sess.ctx, trace_cap=4096)
-    sess.flush()
-    S = cfg["L"] // cfg["k"]
-    per = 2 * (S + 2)
-    assert trace == [(m, chains[m][i][0], chains[m][i][1], i // per) for m, i in order]      # exact
-    tol = TOL[dtype]
+    trace, states, losses, st = scheduled_run(rt, [cfg] * n, Ws, cfg["lrs"], batches, nmb, tables, max_slots=max_slots,
+                                              lanes=lanes, flags=H.FLAG_POISON if lanes > 1 else 0)
+    assert trace == want                                                        # exact
+    plain = check_against_models_alone(rt, [cfg] * n, [cfg] * n, Ws, cfg["lrs"], batches, states, losses, dtype)
     for m in range(n):
-        assert abs(H.hydra_get_loss(sess.ctx, recs[m]["id"]) - oracle[m].loss) <= tol * oracle[m].loss
-        after = sess.unpack(recs[m], recs[m]["master"])
-        # gradients of every step from the plain (unsharded) oracle, to mark ill-conditioned elements
-        refs, P, _, _ = oracle_steps(cfg, Ws[m], cfg["lrs"][m], batches[m])
-        ill = {}
-        for r in refs:
-            update_ill(ill, r["grads"], dtype)
-        for name in P:
-            assert (P[name] == oracle[m].P[name]).all()       # interleaved spilled oracle == plain oracle
-        check_weights(after, oracle[m].P, refs[0]["before"], ill, cfg["lrs"][m], nmb[m], dtype, f"model {m} ")
-    st = H.hydra_get_stats(sess.ctx)
-    assert st["n_tasks"] == done == len(order)
-    H.hydra_sched_destroy(sch)
-    sess.close()
+        assert abs(losses[m] - oracle[m].loss) <= TOL[dtype] * oracle[m].loss
+        for name in plain[m][0]:
+            assert (plain[m][0][name] == oracle[m].P[name]).all()       # interleaved spilled oracle == plain oracle
 
 
 def test_sharding_does_not_change_gpu_results(rt):
@@ -226,9 +339,9 @@ def test_sharding_does_not_change_gpu_results(rt):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_micro_batches_equal_one_large_minibatch(rt, nm, flags, dtype):
     """A minibatch run as nm micro-batches per shard visit (gradients summed while the shard is resident) equals
-    the oracle's single step on all nm*B samples: loss over all valid targets, every gradient, weights after
-    two steps.  Micro-batches carry different numbers of valid targets, so averaging per micro-batch would fail."""
-    H, R = rt
+    the oracle's single step on all nm*B samples: loss over all valid targets, every gradient, weights and Adam
+    state after two steps.  Micro-batches carry different numbers of valid targets, so averaging per micro-batch
+    would fail."""
     base = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=72, B=2, k=2, dtype=dtype, lrs=[1e-4])
     big = dict(base, B=base["B"] * nm)
     cfg = dict(base, n_micro=nm)
@@ -238,21 +351,7 @@ def test_micro_batches_equal_one_large_minibatch(rt, nm, flags, dtype):
         tok, tgt = SI.make_batch(big, 900 + i, zipf=(i == 1))
         tgt[: base["B"], 5:] = -1          # the first micro-batch has few valid targets
         batches.append((tok, tgt))
-    refs, P, Mo, Vo = oracle_steps(big, W, 1e-4, batches)
-    sess = R.Session(R.arena_bytes_for([cfg], 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags, max_slots=3)
-    rec = sess.add_model(cfg, W, 1e-4)
-    ill, tol, M = {}, TOL[dtype], base["B"] * base["T"]
-    for i, (tok, tgt) in enumerate(batches):
-        got = sess.train_step_manual(rec, tok, tgt)
-        H.hydra_sync(sess.ctx)
-        assert_close(got["logits"], refs[i]["logits"][-M:], tol, "logits of the last micro-batch")
-        assert abs(got["loss"] - refs[i]["loss"]) <= tol * abs(refs[i]["loss"])
-        for name, g in refs[i]["grads"].items():
-            assert_close(got["grads"][name], g, tol, f"grad {name}")
-        update_ill(ill, refs[i]["grads"], dtype)
-        after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
-        check_weights(after, refs[i]["after"], refs[0]["before"], ill, 1e-4, i + 1, dtype, f"step {i}: ")
-    sess.close()
+    run_manual(rt, cfg, 2, flags=flags, max_slots=3, W=W, lr=1e-4, batches=batches, oracle_cfg=big)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -266,24 +365,53 @@ def test_scheduled_run_with_micro_batches(rt, dtype):
     bigs = [dict(base, B=base["B"] * nm) for nm in nms]
     Ws = [SI.make_weights(base, 50 + m) for m in range(2)]
     batches = [[SI.make_batch(bigs[m], 800 + 10 * m + i) for i in range(2)] for m in range(2)]
-    fc, bc = SI.task_costs(base)
-    sess = R.Session(R.arena_bytes_for(cfgs, 3, lanes=2), max_slots=3, lanes=2, flags=H.FLAG_POISON)
-    recs = [sess.add_model(cfgs[m], Ws[m], base["lrs"][m]) for m in range(2)]
-    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [2, 2], [list(fc) + list(bc)] * 2)
-    toks = [np.stack([b[0] for b in batches[m]]) for m in range(2)]
-    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(2)]
-    H.hydra_sched_run(sch, toks, tgts, sess.ctx)
-    sess.flush()
-    for m in range(2):
-        refs, P, _, _ = oracle_steps(bigs[m], Ws[m], base["lrs"][m], batches[m])
-        ill = {}
-        for r in refs:
-            update_ill(ill, r["grads"], dtype)
-        assert abs(H.hydra_get_loss(sess.ctx, recs[m]["id"]) - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
-        check_weights(sess.unpack(recs[m], recs[m]["master"]), P, refs[0]["before"], ill, base["lrs"][m], 2, dtype,
-                      f"model {m} ")
-    H.hydra_sched_destroy(sch)
-    sess.close()
+    trace, states, losses, st = scheduled_run(rt, cfgs, Ws, base["lrs"], batches, [2, 2], [costs_of(base)] * 2,
+                                              max_slots=3, lanes=2, flags=H.FLAG_POISON, slots_for_arena=3)
+    check_against_models_alone(rt, cfgs, bigs, Ws, base["lrs"], batches, states, losses, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_scheduled_run_with_checkpoints_through_host_on_two_lanes(rt, dtype):
+    """Boundary activations spilled to host DRAM (paper Section 2.3) in a scheduled run: two models of three block
+    shards each on two lanes with three buffers, so checkpoint promotes, shard prefetches and write-backs of two
+    models interleave on the copy streams."""
+    H, R = rt
+    cfg = SI.small_cfg(L=6, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=2, lrs=[1e-4, 3e-4])
+    Ws = [SI.make_weights(cfg, 90 + m) for m in range(2)]
+    nmb = [2, 2]
+    batches = [[SI.make_batch(cfg, 810 + 10 * m + i) for i in range(nmb[m])] for m in range(2)]
+    tables = [costs_of(cfg)] * 2
+    want, _, _ = oracle_order([cfg] * 2, nmb, tables)
+    trace, states, losses, st = scheduled_run(rt, [cfg] * 2, Ws, cfg["lrs"], batches, nmb, tables, max_slots=3, lanes=2,
+                                              flags=H.FLAG_CKPT_SPILL | H.FLAG_POISON)
+    assert trace == want
+    act = cfg["B"] * cfg["T"] * cfg["d"] * 4
+    n_par = SI.n_params(cfg)
+    # every boundary (S + 1 per minibatch) goes to the host; S - 1 come back (the last two are still on the device)
+    assert st["bytes_d2h"] == sum(nmb) * (12 * n_par + 4 * act)
+    check_against_models_alone(rt, [cfg] * 2, [cfg] * 2, Ws, cfg["lrs"], batches, states, losses, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_four_models_under_a_byte_cap(rt, dtype):
+    """hydra_init_desc.shard_buffer_cap_bytes (BASELINE config 4 caps the shard buffers by bytes): four models, cap
+    worth three buffers, two lanes; the cap decides the number of buffers and the run still equals each model alone."""
+    H, R = rt
+    cfg = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=4,
+                       lrs=[3e-4, 1e-4, 5e-5, 1e-5])
+    n, nmb = 4, [2, 2, 1, 2]
+    Ws = [SI.make_weights(cfg, 20 + m) for m in range(n)]
+    batches = [[SI.make_batch(cfg, 300 + 10 * m + i) for i in range(nmb[m])] for m in range(n)]
+    tables = [costs_of(cfg)] * n
+    want, _, _ = oracle_order([cfg] * n, nmb, tables)
+    # a shard buffer holds 20 bytes per parameter of the largest shard (rounded up to 64 elements / 256 bytes)
+    largest = max(H.hydra_shard_range(H.model_desc(cfg, 1e-4), s)[1] for s in range(4))
+    slot = ((largest + 63) // 64 * 64 * 20 + 255) // 256 * 256
+    trace, states, losses, st = scheduled_run(rt, [cfg] * n, Ws, cfg["lrs"], batches, nmb, tables, lanes=2,
+                                              cap=3 * slot + slot // 2, flags=H.FLAG_POISON)
+    assert st["slot_bytes"] == slot and st["n_slots"] == 3
+    assert trace == want
+    check_against_models_alone(rt, [cfg] * n, [cfg] * n, Ws, cfg["lrs"], batches, states, losses, dtype)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -293,7 +421,7 @@ def test_pilot_pass_measures_costs_and_leaves_the_model_untouched(rt, dtype):
     runs two models on the measured tables and its order equals the oracle's Sharded-LRTF on the same numbers."""
     H, R = rt
     cfg = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=2, lrs=[1e-3, 3e-4])
-    S, n = 2, 4
+    n = 4
     Ws = [SI.make_weights(cfg, 60 + m) for m in range(2)]
     sess = R.Session(R.arena_bytes_for([cfg] * 2, 3), max_slots=3)
     recs = [sess.add_model(cfg, Ws[m], cfg["lrs"][m]) for m in range(2)]
@@ -311,26 +439,19 @@ def test_pilot_pass_measures_costs_and_leaves_the_model_untouched(rt, dtype):
         tables.append(costs)
     # scheduler on the measured tables: same decisions as the oracle
     nmb = [2, 1]
-    chains = [SP.model_task_chain(cfg, nmb[m]) for m in range(2)]
-    costs = [[tables[m][s if ph == SP.FWD else n + s] for s, ph in chains[m]] for m in range(2)]
-    order = SP.sharded_lrtf(chains, costs)
+    want, _, _ = oracle_order([cfg] * 2, nmb, tables)
     batches = [[SI.make_batch(cfg, 700 + 10 * m + i) for i in range(nmb[m])] for m in range(2)]
     sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, tables)
     toks = [np.stack([b[0] for b in batches[m]]) for m in range(2)]
     tgts = [np.stack([b[1] for b in batches[m]]) for m in range(2)]
     trace, done = H.hydra_sched_run(sch, toks, tgts, sess.ctx, trace_cap=256)
     sess.flush()
-    per = 2 * n
-    assert trace == [(m, chains[m][i][0], chains[m][i][1], i // per) for m, i in order]
-    for m in range(2):
-        refs, P, _, _ = oracle_steps(cfg, Ws[m], cfg["lrs"][m], batches[m])   # Adam step counter starts at 1
-        ill = {}
-        for r in refs:
-            update_ill(ill, r["grads"], dtype)
-        check_weights(sess.unpack(recs[m], recs[m]["master"]), P, refs[0]["before"], ill, cfg["lrs"][m], nmb[m], dtype,
-                      f"model {m} ")
+    assert trace == want
+    states = [host_state(sess, r) for r in recs]
+    losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
     H.hydra_sched_destroy(sch)
     sess.close()
+    check_against_models_alone(rt, [cfg] * 2, [cfg] * 2, Ws, cfg["lrs"], batches, states, losses, dtype)   # Adam's t starts at 1
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -345,35 +466,16 @@ def test_heterogeneous_models_in_one_job(rt, dtype):
     bigs = [dict(c, B=c["B"] * c.get("n_micro", 1)) for c in cfgs]
     nmb = [1, 2, 2]
     n = len(cfgs)
+    lrs = [c["lrs"][0] for c in cfgs]
     Ws = [SI.make_weights(cfgs[m], 70 + m) for m in range(n)]
     batches = [[SI.make_batch(bigs[m], 600 + 10 * m + i) for i in range(nmb[m])] for m in range(n)]
-    tabs = [SI.task_costs(c) for c in cfgs]
-    chains = [SP.model_task_chain(cfgs[m], nmb[m]) for m in range(n)]
-    costs = [[(tabs[m][0] if ph == SP.FWD else tabs[m][1])[s] for s, ph in chains[m]] for m in range(n)]
-    order = SP.sharded_lrtf(chains, costs)
-    sess = R.Session(R.arena_bytes_for(cfgs, 4, lanes=2), max_slots=4, lanes=2, flags=H.FLAG_POISON)
-    recs = [sess.add_model(cfgs[m], Ws[m], cfgs[m]["lrs"][0]) for m in range(n)]
-    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, [list(t[0]) + list(t[1]) for t in tabs])
-    toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
-    tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
-    trace, done = H.hydra_sched_run(sch, toks, tgts, sess.ctx, trace_cap=4096)
-    sess.flush()
-    want = []
-    for m, i in order:
-        per = 2 * (cfgs[m]["L"] // cfgs[m]["k"] + 2)
-        want.append((m, chains[m][i][0], chains[m][i][1], i // per))
+    tables = [costs_of(c) for c in cfgs]
+    want, _, _ = oracle_order(cfgs, nmb, tables)
+    trace, states, losses, st = scheduled_run(rt, cfgs, Ws, lrs, batches, nmb, tables, max_slots=4, lanes=2,
+                                              flags=H.FLAG_POISON, slots_for_arena=4)
     assert trace == want
     assert [t[0] for t in trace[:n]] != list(range(n))            # not a round-robin start
-    for m in range(n):
-        refs, P, _, _ = oracle_steps(bigs[m], Ws[m], cfgs[m]["lrs"][0], batches[m])
-        ill = {}
-        for r in refs:
-            update_ill(ill, r["grads"], dtype)
-        assert abs(H.hydra_get_loss(sess.ctx, recs[m]["id"]) - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
-        check_weights(sess.unpack(recs[m], recs[m]["master"]), P, refs[0]["before"], ill, cfgs[m]["lrs"][0], nmb[m],
-                      dtype, f"model {m} ")
-    H.hydra_sched_destroy(sch)
-    sess.close()
+    check_against_models_alone(rt, cfgs, bigs, Ws, lrs, batches, states, losses, dtype)
 
 
 @pytest.mark.parametrize("mode", ["manual_spill", "resident", "scheduled_micro"])
@@ -392,35 +494,26 @@ def test_tied_lm_head(rt, dtype, mode):
     W = SI.make_weights(base, 31)
     assert "w_lm" not in W
     batches = [SI.make_batch(big, 400 + i, zipf=(i == 1)) for i in range(3)]
-    refs, P, Mo, Vo = oracle_steps(big, W, 1e-4, batches)
-    sess = R.Session(R.arena_bytes_for([cfg], 4), max_slots=2 if mode == "manual_spill" else 4,
-                     flags=H.FLAG_POISON if mode == "manual_spill" else 0)
+    # every shard spilled between visits, each step checked against the oracle
+    refs, final, loss, oracle = run_manual(rt, cfg, 3, flags=H.FLAG_POISON, max_slots=2, W=W, lr=1e-4, batches=batches,
+                                           oracle_cfg=big, test_id=f"tied {dtype}")
+    if mode == "manual_spill":
+        return
+    if mode == "scheduled_micro":
+        trace, states, losses, st = scheduled_run(rt, [cfg], [W], [1e-4], [batches], [3], [costs_of(base)], max_slots=4,
+                                                  slots_for_arena=4)
+        assert_same_state(states[0], final, "scheduled: ")
+        assert losses[0] == loss
+        return
+    # all shards resident: the updates exist only on the device until the flush
+    sess = R.Session(R.arena_bytes_for([cfg], 4), max_slots=4)
     rec = sess.add_model(cfg, W, 1e-4)
     assert rec["layout"].n_params == SI.n_params(base)
-    ill, tol, M = {}, TOL[dtype], base["B"] * base["T"]
-    if mode == "scheduled_micro":
-        fc, bc = SI.task_costs(base)
-        sch = H.hydra_sched_create(sess.ctx, [rec["id"]], [3], [list(fc) + list(bc)])
-        H.hydra_sched_run(sch, [np.stack([b[0] for b in batches])], [np.stack([b[1] for b in batches])], sess.ctx)
-        sess.flush()
-        H.hydra_sched_destroy(sch)
-        for r in refs:
-            update_ill(ill, r["grads"], dtype)
-        assert abs(H.hydra_get_loss(sess.ctx, rec["id"]) - refs[-1]["loss"]) <= tol * refs[-1]["loss"]
-        check_weights(sess.unpack(rec, rec["master"]), P, refs[0]["before"], ill, 1e-4, 3, dtype)
-    else:
-        for i, (tok, tgt) in enumerate(batches):
-            got = sess.train_step_manual(rec, tok, tgt, spill=(mode == "manual_spill"))
-            H.hydra_sync(sess.ctx)
-            assert_close(got["logits"], refs[i]["logits"][-M:], tol, "logits")
-            assert abs(got["loss"] - refs[i]["loss"]) <= tol * abs(refs[i]["loss"])
-            for name, g in refs[i]["grads"].items():
-                assert_close(got["grads"][name], g, tol, f"grad {name}")
-            update_ill(ill, refs[i]["grads"], dtype)
-            if mode == "resident":
-                sess.flush()
-            after = {k: v.copy() for k, v in sess.unpack(rec, rec["master"]).items()}
-            check_weights(after, refs[i]["after"], refs[0]["before"], ill, 1e-4, i + 1, dtype, f"step {i}: ")
+    for tok, tgt in batches:
+        got = sess.train_step_manual(rec, tok, tgt, spill=False, collect=False)
+    sess.flush()
+    assert_same_state(host_state(sess, rec), final, "resident: ")
+    assert got["loss"] == loss
     sess.close()
 
 
@@ -430,8 +523,8 @@ def test_graph_replay_of_shard_visits(rt, dtype, max_slots, lanes, nm):
     """HYDRA_FLAG_GRAPHS: the kernel sequence of a block-shard visit is captured on its second run with a given
     shard buffer and replayed afterwards.  Five minibatches of two models, so every combination is run plainly,
     captured and replayed several times with the uncaptured work (loads, Adam, write-backs, head, embedding) and
-    stream synchronisations in between; weights and loss against the oracle after the last one, and the result
-    must be bit-identical to the same run without graphs.  With few buffers the shards move between buffers, which
+    stream synchronisations in between; the result must be bit-identical to each model run alone without graphs
+    (which is checked against the oracle step by step).  With few buffers the shards move between buffers, which
     gives one graph per (shard, buffer) pair."""
     H, R = rt
     base = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=2, dtype=dtype, n_models=2, lrs=[1e-4, 3e-4])
@@ -440,42 +533,17 @@ def test_graph_replay_of_shard_visits(rt, dtype, max_slots, lanes, nm):
     n, steps = 2, 5
     Ws = [SI.make_weights(base, 80 + m) for m in range(n)]
     batches = [[SI.make_batch(big, 500 + 10 * m + i) for i in range(steps)] for m in range(n)]
-    fc, bc = SI.task_costs(base)
-    results = []
-    for flags in (H.FLAG_GRAPHS, 0):
-        sess = R.Session(R.arena_bytes_for([cfg] * n, 12, lanes=lanes), max_slots=max_slots, lanes=lanes, flags=flags)
-        recs = [sess.add_model(cfg, Ws[m], base["lrs"][m]) for m in range(n)]
-        sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [steps] * n, [list(fc) + list(bc)] * n)
-        toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
-        tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
-        H.hydra_sched_run(sch, toks, tgts, sess.ctx)
-        sess.flush()
-        st = H.hydra_get_stats(sess.ctx)
-        if flags:
-            assert st["n_graph_launches"] > 0
-        else:
-            assert st["n_graph_launches"] == 0
-        results.append(([sess.unpack(recs[m], recs[m]["master"].copy()) for m in range(n)],
-                        [H.hydra_get_loss(sess.ctx, recs[m]["id"]) for m in range(n)]))
-        H.hydra_sched_destroy(sch)
-        sess.close()
-    (wg, lg), (we, le) = results
-    assert lg == le
-    for m in range(n):
-        for name in wg[m]:
-            assert (wg[m][name] == we[m][name]).all(), name       # graphs change nothing
-        refs, P, _, _ = oracle_steps(big, Ws[m], base["lrs"][m], batches[m])
-        ill = {}
-        for r in refs:
-            update_ill(ill, r["grads"], dtype)
-        assert abs(lg[m] - refs[-1]["loss"]) <= TOL[dtype] * refs[-1]["loss"]
-        check_weights(wg[m], P, refs[0]["before"], ill, base["lrs"][m], steps, dtype, f"model {m} ")
+    trace, states, losses, st = scheduled_run(rt, [cfg] * n, Ws, base["lrs"], batches, [steps] * n, [costs_of(base)] * n,
+                                              max_slots=max_slots, lanes=lanes, flags=H.FLAG_GRAPHS)
+    assert st["n_graph_launches"] > 0
+    check_against_models_alone(rt, [cfg] * n, [big] * n, Ws, base["lrs"], batches, states, losses, dtype)
 
 
 def test_overlap_trace_of_a_spilled_run(rt):
     """HYDRA_FLAG_OVERLAP: the event pairs around promotes, write-backs and shard tasks of a spilled two-model run
     give interval unions that are consistent with each other and with the byte counters; without the flag the call
-    reports a state error.  The traced run's weights equal those of an untraced run bit for bit."""
+    reports a state error.  With HYDRA_FLAG_TIMING as well the kernel-level figures are filled in and cannot exceed
+    the task-level ones.  The traced runs' weights equal those of an untraced run bit for bit."""
     H, R = rt
     cfg = SI.small_cfg(L=4, d=64, H=4, F=256, V=211, T=64, B=2, k=1, dtype="bf16", n_models=2, lrs=[1e-4, 3e-4])
     n, steps = 2, 3
@@ -483,7 +551,7 @@ def test_overlap_trace_of_a_spilled_run(rt):
     batches = [[SI.make_batch(cfg, 900 + 10 * m + i) for i in range(steps)] for m in range(n)]
     fc, bc = SI.task_costs(cfg)
     finals = []
-    for flags in (H.FLAG_OVERLAP, 0):
+    for flags in (H.FLAG_OVERLAP, H.FLAG_OVERLAP | H.FLAG_TIMING, 0):
         sess = R.Session(R.arena_bytes_for([cfg] * n, 3, lanes=2), max_slots=3, lanes=2, flags=flags)
         recs = [sess.add_model(cfg, Ws[m], cfg["lrs"][m]) for m in range(n)]
         sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [steps] * n, [list(fc) + list(bc)] * n)
@@ -502,6 +570,12 @@ def test_overlap_trace_of_a_spilled_run(rt):
             assert max(o["h2d_ms"], o["d2h_ms"]) <= o["transfer_ms"] + eps <= o["h2d_ms"] + o["d2h_ms"] + 2 * eps
             assert 0 <= o["hidden_ms"] <= min(o["transfer_ms"], o["compute_ms"]) + eps
             assert o["transfer_ms"] <= o["wall_ms"] + eps
+            if flags & H.FLAG_TIMING:
+                # kernels execute inside their task's bracket, so their union is the smaller one
+                assert 0 < o["kernel_ms"] <= o["compute_ms"] + 0.05
+                assert 0 <= o["hidden_kernel_ms"] <= min(o["hidden_ms"] + 0.05, o["kernel_ms"] + eps)
+            else:
+                assert o["kernel_ms"] == 0 and o["hidden_kernel_ms"] == 0
             H.hydra_overlap_reset(sess.ctx)
             assert H.hydra_overlap_stats(sess.ctx)["n_intervals"] == 0
         else:
@@ -512,5 +586,6 @@ def test_overlap_trace_of_a_spilled_run(rt):
         finals.append([recs[m]["master"].copy() for m in range(n)])
         H.hydra_sched_destroy(sch)
         sess.close()
-    for a, b in zip(*finals):
-        assert np.isfinite(a).all() and (a == b).all()
+    for other in finals[1:]:
+        for a, b in zip(finals[0], other):
+            assert np.isfinite(a).all() and (a == b).all()

@@ -142,7 +142,7 @@ def test_dry_run_error_codes_and_state_machine():
     assert st["bytes_d2h"] == 12 * rng[3]
     assert st["n_slots"] == 2 and st["n_writebacks"] == 1
     assert code(H.hydra_register_model, ctx, s.models[0]["desc"], s.models[0]["master"], s.models[0]["m"],
-                s.models[0]["v"]) == H.E_STATE
+                s.models[0]["v"], None, s.models[0]["stage"]) == H.E_STATE
     s.close()
 
 
@@ -217,3 +217,116 @@ def test_tied_layout_drops_the_head_matrix():
     names = [H.hydra_model_tensor(desc, i)[0] for i in range(lay.n_tensors)]
     assert names[-2:] == ["lnf_g", "lnf_b"] and "w_lm" not in names
     assert H.hydra_shard_footprint(desc, 0) >= 18 * (2 * d + d * V)
+
+
+# ---- the five workloads as stated: buffer caps, exact task order and link traffic (no GPU) -----------------------
+
+def _slot_bytes(cfg):
+    desc = H.model_desc(cfg, 1e-4)
+    lay = H.hydra_model_layout(desc)
+    largest = max(H.hydra_shard_range(desc, s)[1] for s in range(lay.n_shards))
+    return ((largest + 63) // 64 * 64 * 20 + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("name,cap_bytes,max_slots,want_slots", [
+    ("gpt2xl", 24 * 10 ** 9, 0, 6),        # BASELINE config 4: shard buffers capped at 24 GB (6 buffers of 3.7 GB)
+    ("gpt6b", 0, 2, 2),                    # BASELINE config 5: two shard buffers of 2 layers
+    ("gpt6b", 17 * 10 ** 9, 0, 2),         # the same cap stated in bytes (a buffer is 8.06 GB)
+    ("gpt2m", 0, 3, 3),
+])
+def test_buffer_caps_of_the_stated_workloads(name, cap_bytes, max_slots, want_slots):
+    cfg = SI.CONFIGS[name]
+    s = Session(1 << 42, shard_buffer_cap_bytes=cap_bytes, max_slots=max_slots, dry_run=True, lanes=2)
+    for m in range(cfg["n_models"]):
+        s.add_model(cfg, None, cfg["lrs"][m])
+    H.hydra_shard_load_async(s.ctx, 0, 0, H.LOAD_PARAMS)        # forces the arena to be planned
+    st = H.hydra_get_stats(s.ctx)
+    assert st["slot_bytes"] == _slot_bytes(cfg)
+    assert st["n_slots"] == want_slots
+    if cap_bytes:
+        assert st["n_slots"] * st["slot_bytes"] <= cap_bytes < (st["n_slots"] + 1) * st["slot_bytes"]
+    s.close()
+
+
+def test_a_cap_below_one_buffer_is_an_error():
+    cfg = SI.CONFIGS["gpt2s"]
+    s = Session(1 << 40, shard_buffer_cap_bytes=_slot_bytes(cfg) - 1, dry_run=True)
+    s.add_model(cfg, None, 1e-4)
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_shard_load_async(s.ctx, 0, 0, H.LOAD_PARAMS)
+    assert e.value.code == H.E_NOMEM
+    s.close()
+
+
+@pytest.mark.parametrize("name,cap_bytes,max_slots,lanes", [
+    ("gpt2s", 0, 6, 2), ("gpt2m", 0, 3, 2), ("gpt2xl", 24 * 10 ** 9, 0, 2), ("gpt6b", 0, 2, 1), ("gpt6b", 0, 2, 2)])
+def test_stated_workloads_dry_run_order_and_traffic(name, cap_bytes, max_slots, lanes):
+    """Every BASELINE workload with its model count, depth, shard size and buffer cap through hydra_sched_run in
+    dry-run mode, two minibatches per model: the executed order equals the oracle's Sharded-LRTF, every shard's
+    updated state goes back to the host once per minibatch (12 bytes per parameter), and promotes bring 12 to 16
+    bytes per parameter (4 on the forward visit, 12 on the backward visit, less what is still resident)."""
+    cfg = SI.CONFIGS[name]
+    n, nmb = cfg["n_models"], 2
+    s = Session(1 << 42, shard_buffer_cap_bytes=cap_bytes, max_slots=max_slots, dry_run=True, lanes=lanes)
+    for m in range(n):
+        s.add_model(cfg, None, cfg["lrs"][m])
+    S = cfg["L"] // cfg["k"]
+    tab = [_costs(cfg)] * n
+    sch = H.hydra_sched_create(s.ctx, list(range(n)), [nmb] * n, tab)
+    small = dict(cfg)
+    toks = [np.stack([SI.make_batch(small, 10 * m + i)[0] for i in range(nmb)]) for m in range(n)]
+    tgts = [np.stack([SI.make_batch(small, 10 * m + i)[1] for i in range(nmb)]) for m in range(n)]
+    trace, done = H.hydra_sched_run(sch, toks, tgts, s.ctx, trace_cap=4096)
+    chains = [SP.model_task_chain(cfg, nmb) for _ in range(n)]
+    costs = [[tab[m][sh] if ph == SP.FWD else tab[m][S + 2 + sh] for sh, ph in ch] for m, ch in enumerate(chains)]
+    order = SP.sharded_lrtf(chains, costs)
+    per = 2 * (S + 2)
+    assert done == len(order) == n * nmb * per
+    assert trace == [(m, chains[m][i][0], chains[m][i][1], i // per) for m, i in order]
+    # equal models, equal costs: Sharded-LRTF alternates the models shard by shard (round-robin)
+    assert [t[0] for t in trace[: 2 * n]] == list(range(n)) * 2
+    st = H.hydra_get_stats(s.ctx)
+    n_par = SI.n_params(cfg)
+    assert st["bytes_d2h"] == n * nmb * n_par * 12
+    assert n * nmb * n_par * 12 <= st["bytes_h2d"] <= n * nmb * n_par * 16
+    assert st["n_tasks"] == done
+    H.hydra_sched_destroy(sch)
+    s.close()
+
+
+def test_prefetch_depth_one_is_plain_double_buffering():
+    """prefetch_depth = 1: exactly one task ahead (the paper's double buffering); the default goes as far as
+    buffers can be freed.  Neither changes the executed order or the bytes written back."""
+    cfg = SI.small_cfg(L=4, k=1)
+    out = []
+    for depth in (1, 0):
+        s = Session(1 << 34, max_slots=4, dry_run=True, prefetch_depth=depth)
+        for m in range(2):
+            s.add_model(cfg, None, 1e-3)
+        sch = H.hydra_sched_create(s.ctx, [0, 1], [2, 2], [_costs(cfg)] * 2)
+        toks = [np.stack([SI.make_batch(cfg, 10 * m + i)[0] for i in range(2)]) for m in range(2)]
+        tgts = [np.stack([SI.make_batch(cfg, 10 * m + i)[1] for i in range(2)]) for m in range(2)]
+        trace, done = H.hydra_sched_run(sch, toks, tgts, s.ctx, trace_cap=1000)
+        st = H.hydra_get_stats(s.ctx)
+        out.append((trace, st["bytes_d2h"], st["bytes_h2d"]))
+        H.hydra_sched_destroy(sch)
+        s.close()
+    assert out[0][0] == out[1][0] and out[0][1] == out[1][1]
+
+
+def test_init_rejects_bad_lane_and_copy_arguments():
+    for kw in (dict(compute_lanes=9), dict(copy_blocks=-1), dict(copy_blocks=5000), dict(prefetch_depth=-2)):
+        with pytest.raises(H.HydraError) as e:
+            H.hydra_init(256, 1 << 30, flags=H.FLAG_DRY_RUN, **kw)
+        assert e.value.code == H.E_INVAL, kw
+
+
+def test_register_model_needs_a_batch_staging_array():
+    s, cfg = _dry_session(1)
+    r = s.models[0]
+    ctx = H.hydra_init(256, 1 << 34, flags=H.FLAG_DRY_RUN)
+    with pytest.raises(H.HydraError) as e:
+        H.hydra_register_model(ctx, r["desc"], r["master"], r["m"], r["v"], None, None)
+    assert e.value.code == H.E_INVAL
+    H.hydra_destroy(ctx)
+    s.close()
