@@ -42,10 +42,11 @@ def rt():
 #       homogeneous of degree 0 in the gradient history and its logarithmic derivatives sum to at most about 1 in
 #       magnitude per step, so a relative perturbation rel of the gradients moves each step by at most
 #       about 2 * lr * rel.  The share of well-conditioned elements per tensor is reported and must
-#       stay above MIN_WELL (the key third of b_qkv is left out of that share: softmax is invariant to a shift
+#       stay above MIN_WELL per step taken (the key third of b_qkv is left out of that share: softmax is invariant to a shift
 #       along the key axis, its exact gradient is zero).
 WELL = 0.2
-MIN_WELL = {"f32": 0.99, "bf16": 0.85}     # measured: at most 0.10 excused (small bias vectors), 0.06 on the large workloads
+MIN_WELL = {"f32": 0.99, "bf16": 0.90}     # per step (an element stays excused once any step excused it); measured:
+                                           # 0.03-0.08 excused per step, 0.06 after one step of the large workloads
 EXCLUDED_SHARE = {}          # test id -> tensor -> share of elements not well-conditioned (printed with -s)
 
 
@@ -99,7 +100,7 @@ class UpdateCheck:
             bad = well & (np.abs(dgot - dref) > allowed)
             assert not bad.any(), f"{tag}: delta differs on {bad.sum()} well-conditioned elements"
             # (a share over a few dozen elements is too coarse to bound)
-            assert keep.sum() < 256 or 1.0 - self.share[name] >= MIN_WELL[self.dtype], \
+            assert keep.sum() < 256 or 1.0 - self.share[name] >= MIN_WELL[self.dtype] ** t, \
                 f"{tag}: only {1 - self.share[name]:.3f} of the elements are well-conditioned"
 
     def report(self, test_id):
