@@ -372,6 +372,19 @@ hydra_status hydra_op_layernorm_bwd(const float *dy, const float *x, const float
                                     const float *gamma, const float *dres, float *dx, void *dx_bf16,
                                     float *dgamma, float *dbeta, float *dx_colsum, float *scratch, int32_t M,
                                     int32_t d, void *stream);
+/* hydra_op_layernorm_bwd for callers that cannot allocate device memory and cannot hand over a workspace either:
+ * code under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments
+ * minus 'scratch', same kernels, same results bit for bit; the partial column sums live in a fixed array of 2 Mi
+ * floats (8 MiB) that every GPU the library runs on holds until the process ends.  3 * d * ceil(M / 8) must not
+ * exceed 2 Mi (HYDRA_E_INVAL otherwise; d = 1024 allows M up to 5456 rows).  The call allocates nothing and frees
+ * nothing (the array's address on a GPU is looked up by hydra_init, or by the first call on that GPU).  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU race - order them on one stream or with
+ * events.  Nothing in the array needs clearing between calls (every partial sum read is written first by the same
+ * call). */
+hydra_status hydra_op_layernorm_bwd_static(const float *dy, const float *x, const float *mean, const float *rstd,
+                                           const float *gamma, const float *dres, float *dx, void *dx_bf16,
+                                           float *dgamma, float *dbeta, float *dx_colsum, int32_t M, int32_t d,
+                                           void *stream);
 /* Causal softmax over rows of S fp32 [n_mat, T, T] -> P (dtype); entries j>i are 0. */
 hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T,
                                      void *stream);

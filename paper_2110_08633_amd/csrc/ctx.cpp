@@ -180,6 +180,14 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
       return fail(nullptr, HYDRA_E_HIP, "no HIP device available");
     }
   }
+  if (!ctx->dry) {  // set-up of the entry point that may not allocate later on: resolve this GPU's scratch array now
+    float *unused = nullptr;
+    const hydra_status ss = static_scratch(&unused);
+    if (ss) {
+      delete ctx;
+      return ss;
+    }
+  }
   for (int i = 1; i < n_lanes && !ctx->dry; ++i) {
     hipStream_t ls = (hipStream_t)desc->lane_streams[i - 1];
     bool distinct = ls != nullptr && ls != ctx->lanes[0].stream && ls != ctx->s_h2d && ls != ctx->s_d2h;

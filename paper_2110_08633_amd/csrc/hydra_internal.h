@@ -166,6 +166,8 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
 hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
 hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
 uint64_t workspace_need(const ModelShape &s, int dtype);
+// device address of the current GPU's static scratch array (hydra_op_layernorm_bwd_static)
+hydra_status static_scratch(float **out);
 
 }  // namespace hydra
 

@@ -29,6 +29,12 @@ struct ProfScope {
   long idx_;
 };
 
+// While one of these lives on a thread, ProfScope records nothing on that thread.
+struct ProfSuppress {
+  ProfSuppress();
+  ~ProfSuppress();
+};
+
 struct GemmDesc {
   int dtype = DT_BF16;
   int ta = 0, tb = 0;  // ta: A stored [K,M]; tb: B stored [K,N] (else [N,K])

@@ -1,8 +1,47 @@
 // Single-kernel entry points of the C ABI, used by parity tests and by the
 // roofline measurements.  All pointers are device pointers.
+#include <mutex>
+
 #include "hydra_internal.h"
 
 using namespace hydra;
+
+// ---------------------------------------------------------------------------
+// Scratch memory of hydra_op_layernorm_bwd_static, the one entry point that
+// must not allocate: a fixed array in every GPU's copy of the code object
+// instead of a caller-supplied workspace.  In host code `scratch` is only a
+// handle for the symbol; the array's device address - a different one on every
+// GPU - comes from hipGetSymbolAddress with that GPU current and is what the
+// kernels are given.
+// ---------------------------------------------------------------------------
+constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)2 << 20;  // 8 MiB on every GPU the library runs on
+static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
+
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static float *g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];  // per GPU: device address of its copy of `scratch`
+static std::mutex g_scratch_mu;
+
+namespace hydra {
+
+// Device address of the current GPU's scratch array; resolved once per GPU (hydra_init does it for the GPU its
+// context is created on, the entry point itself on its first call on any other).
+hydra_status static_scratch(float **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hipfail(nullptr, e, "hipGetDevice");
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return fail(nullptr, HYDRA_E_INVAL, "device index out of range");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hipfail(nullptr, e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = (float *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return HYDRA_OK;
+}
+
+}  // namespace hydra
 
 static hydra_status ret(hipError_t e, const char *what) {
   if (e == hipSuccess) return HYDRA_OK;
@@ -55,6 +94,31 @@ hydra_status hydra_op_layernorm_bwd(const float *dy, const float *x, const float
   fin.add(scratch + d, 3 * (int64_t)d, nb, d, dbeta);
   if (dx_colsum) fin.add(scratch + 2 * d, 3 * (int64_t)d, nb, d, dx_colsum);
   return ret(launch_colsum_finish(fin, st), "layernorm_bwd (column sums)");
+}
+
+hydra_status hydra_op_layernorm_bwd_static(const float *dy, const float *x, const float *mean, const float *rstd,
+                                           const float *gamma, const float *dres, float *dx, void *dx_bf16,
+                                           float *dgamma, float *dbeta, float *dx_colsum, int32_t M, int32_t d,
+                                           void *stream) {
+  if (!dy || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || M < 0 || d <= 0 ||
+      !layernorm_bwd_fused_supported(d))
+    return fail(nullptr, HYDRA_E_INVAL, "bad LayerNorm backward argument (d % 4 == 0, d <= 2048)");
+  const int nb = layernorm_bwd_fused_blocks(M);
+  if ((size_t)3 * (size_t)d * (size_t)nb > STATIC_SCRATCH_FLOATS)
+    return fail(nullptr, HYDRA_E_INVAL, "3 * d * ceil(M / 8) exceeds the 2 Mi floats of the static scratch array");
+  if (M == 0) return HYDRA_OK;
+  float *part = nullptr;  // this GPU's array: every partial sum read below is written first by this same call
+  hydra_status st = static_scratch(&part);
+  if (st) return st;
+  hipStream_t hs = (hipStream_t)stream;
+  ProfSuppress quiet;  // event brackets of a timing context would create events: nothing here may allocate
+  hipError_t e = launch_layernorm_bwd_fused(dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, M, d, hs);
+  if (e != hipSuccess) return ret(e, "layernorm_bwd");
+  ColsumFinish fin;
+  fin.add(part, 3 * (int64_t)d, nb, d, dgamma);
+  fin.add(part + d, 3 * (int64_t)d, nb, d, dbeta);
+  if (dx_colsum) fin.add(part + 2 * d, 3 * (int64_t)d, nb, d, dx_colsum);
+  return ret(launch_colsum_finish(fin, hs), "layernorm_bwd (column sums)");
 }
 
 hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T, void *stream) {

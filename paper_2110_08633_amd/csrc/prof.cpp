@@ -32,6 +32,10 @@ struct Profiler {
 };
 
 static Profiler *g_prof = nullptr;
+static thread_local int g_prof_quiet = 0;
+
+ProfSuppress::ProfSuppress() { ++g_prof_quiet; }
+ProfSuppress::~ProfSuppress() { --g_prof_quiet; }
 
 Profiler *prof_create() { return new Profiler(); }
 void prof_destroy(Profiler *p) {
@@ -59,7 +63,7 @@ static hipEvent_t get_event(Profiler *p) {
 
 ProfScope::ProfScope(const char *name, hipStream_t s, double flops, double bytes) : stream_(s), idx_(-1) {
   Profiler *p = g_prof;
-  if (!p) return;
+  if (!p || g_prof_quiet) return;
   ProfRec r{name, get_event(p), get_event(p), flops, bytes};
   if (!r.e0 || !r.e1) return;
   (void)hipEventRecord(r.e0, s);
