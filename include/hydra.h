@@ -122,7 +122,14 @@ typedef struct {
                                    /* distinct non-null handles (ignored with HYDRA_FLAG_DRY_RUN)                   */
   int32_t prefetch_depth;          /* how many tasks ahead hydra_sched_run promotes shards for; 0 = as far as free   */
                                    /* shard buffers allow (at least one: the paper's double buffering, Section 2.3)  */
-  int32_t reserved;
+  int32_t stage_threads;           /* host threads per direction that copy between ordinary memory and the staging   */
+                                   /* area; 0 = 3                                                                     */
+  void *stage;                     /* page-locked host memory (256-byte aligned, >= 16 MiB), or NULL.  With it, a     */
+  uint64_t stage_bytes;            /* model's master / adam_m / adam_v may be ORDINARY (pageable) host memory: their  */
+                                   /* promotes and write-backs then travel through this area chunk by chunk (host     */
+                                   /* threads of the library copy between the arrays and the area, the copy streams   */
+                                   /* between the area and the shard buffers) - for state larger than the driver lets */
+                                   /* a process page-lock.  The area belongs to the library until hydra_destroy.     */
 } hydra_init_desc;
 
 typedef struct {
@@ -141,7 +148,8 @@ typedef struct {
 } hydra_model_desc;
 
 typedef struct {
-  /* caller-owned, page-locked host memory; must outlive the model */
+  /* caller-owned host memory; must outlive the model.  Page-locked - except that master, adam_m and adam_v may be
+   * ordinary memory when hydra_init was given a staging area (all three are then treated as ordinary memory) */
   float *master;  /* [n_params] fp32, canonical flat layout */
   float *adam_m;  /* [n_params]                               */
   float *adam_v;  /* [n_params]                               */

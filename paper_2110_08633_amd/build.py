@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhydra.so")
-SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "layout.cpp", "ctx.cpp", "exec.cpp", "sched.cpp", "ops_api.cpp", "prof.cpp", "partition.cpp"]
+SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "layout.cpp", "ctx.cpp", "exec.cpp", "sched.cpp", "ops_api.cpp", "prof.cpp", "partition.cpp", "pager.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # Per-source additions.  The attention kernels do vector arithmetic on every MFMA result (mask, exponential,
@@ -38,7 +38,7 @@ def build(verbose=False):
             sys.stderr.write(f"--- {src} ---\n{out}\n")
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB] + objs
     subprocess.check_call(cmd)
     return LIB
 

@@ -47,13 +47,106 @@ hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, con
   return HYDRA_OK;
 }
 
-// host -> device copy on the h2d stream.  SDMA (hipMemcpyAsync): the copy kernel reading page-locked memory through
-// its device-side mapping reaches the same link rate but slows the compute kernels it shares CUs with and the
-// write-backs (measured: 147 against 123 ms per step of the two-model GPT-2-small workload).
-hydra_status copy_h2d(hydra_ctx *ctx, void *dst, const void *host_src, size_t bytes) {
-  if (ctx->dry) return HYDRA_OK;
-  HYDRA_HIP(ctx, hipMemcpyAsync(dst, host_src, bytes, hipMemcpyHostToDevice, ctx->s_h2d));
+// What one promote or one write-back puts on its copy stream: waits for events other streams recorded, copies, and
+// events to record behind them.  Without a staging tier the calling thread issues it at once; with one it is a job
+// of that direction's coordinator thread (pager.cpp), which is why nothing in here may touch the context's
+// bookkeeping or its error text.
+struct CopyPlan {
+  struct Seg {
+    void *dst;
+    const void *src;
+    void *dst_mapped;  // write-backs into page-locked memory: the destination as the device sees it
+    size_t bytes;
+    int kind;          // SEG_*
+  };
+  enum { SEG_PINNED = 0, SEG_PAGEABLE = 1, SEG_DEVICE = 2 };
+  std::vector<hipEvent_t> waits;
+  std::vector<uint64_t> d2h_tickets;  // staging tier: write-back jobs that must have finished first
+  std::vector<Seg> segs;
+  std::vector<hipEvent_t> records;
+  int trace_tag = 0;
+  uint64_t trace_bytes = 0;
+  int64_t tokens_per_visit = 0;
+  bool poison = false;                // write-backs: fill the whole buffer with NaN patterns afterwards
+  void *poison_base = nullptr;
+  int64_t poison_words = 0;
+};
+
+#define PLAN_HIP(call)                            \
+  do {                                            \
+    if ((call) != hipSuccess) return HYDRA_E_HIP; \
+  } while (0)
+
+static hydra_status run_h2d_plan(hydra_ctx *ctx, const CopyPlan &p) {
+  hipStream_t s = ctx->s_h2d;
+  for (uint64_t t : p.d2h_tickets) pager_wait(ctx->pager, PQ_D2H, t);
+  for (hipEvent_t e : p.waits) PLAN_HIP(hipStreamWaitEvent(s, e, 0));
+  const int tr = p.trace_bytes ? trace_begin(ctx, TRACE_H2D, s, p.trace_tag) : -1;
+  for (const CopyPlan::Seg &g : p.segs) {
+    if (g.kind == CopyPlan::SEG_PAGEABLE) {
+      const hydra_status st = pager_h2d(ctx->pager, g.dst, g.src, g.bytes);
+      if (st) return st;
+    } else {
+      // SDMA (hipMemcpyAsync): the copy kernel reading page-locked memory through its device-side mapping reaches the
+      // same link rate but slows the compute kernels it shares CUs with and the write-backs (measured: 147 against
+      // 123 ms per step of the two-model GPT-2-small workload)
+      PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes,
+                              g.kind == CopyPlan::SEG_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
+    }
+  }
+  trace_end(ctx, tr, s, p.trace_bytes);
+  for (hipEvent_t e : p.records) PLAN_HIP(hipEventRecord(e, s));
   return HYDRA_OK;
+}
+
+static hydra_status run_d2h_plan(hydra_ctx *ctx, const CopyPlan &p) {
+  hipStream_t s = ctx->s_d2h;
+  for (hipEvent_t e : p.waits) PLAN_HIP(hipStreamWaitEvent(s, e, 0));
+  const int tr = p.trace_bytes ? trace_begin(ctx, TRACE_D2H, s, p.trace_tag) : -1;
+  for (const CopyPlan::Seg &g : p.segs) {
+    if (g.kind == CopyPlan::SEG_PAGEABLE) {
+      const hydra_status st = pager_d2h(ctx->pager, g.dst, g.src, g.bytes, p.tokens_per_visit);
+      if (st) return st;
+    } else if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY) {
+      PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes, hipMemcpyDeviceToHost, s));
+    } else {
+      PLAN_HIP(launch_copy_to_host(g.dst_mapped, g.src, g.bytes, p.tokens_per_visit, ctx->init.copy_blocks, s));
+    }
+  }
+  trace_end(ctx, tr, s, p.trace_bytes);
+  if (p.poison) PLAN_HIP(launch_fill_u32((uint32_t *)p.poison_base, 0x7fc07fc0u, p.poison_words, s));
+  for (hipEvent_t e : p.records) PLAN_HIP(hipEventRecord(e, s));
+  return HYDRA_OK;
+}
+
+// Issues a plan: at once, or as a job of the staging tier's coordinator for that direction (ticket returned).
+static hydra_status issue_plan(hydra_ctx *ctx, int which, const CopyPlan &p, uint64_t *ticket) {
+  *ticket = 0;
+  if (ctx->dry) return HYDRA_OK;
+  if (!ctx->pager) {
+    const hydra_status st = which == PQ_H2D ? run_h2d_plan(ctx, p) : run_d2h_plan(ctx, p);
+    if (st) return fail(ctx, st, which == PQ_H2D ? "a HIP call of a promote failed" : "a HIP call of a write-back failed");
+    return HYDRA_OK;
+  }
+  *ticket = pager_submit(ctx->pager, which,
+                         [ctx, which, p]() { return which == PQ_H2D ? run_h2d_plan(ctx, p) : run_d2h_plan(ctx, p); });
+  return HYDRA_OK;
+}
+
+// an error of the staging tier's threads surfaces at the next call that touches the swap engine
+static hydra_status pager_check(hydra_ctx *ctx) {
+  if (!ctx->pager) return HYDRA_OK;
+  std::string text;
+  const hydra_status st = pager_error(ctx->pager, &text);
+  return st ? fail(ctx, st, text) : HYDRA_OK;
+}
+
+// waits until the staging tier's coordinators have nothing left to issue (no-op without one)
+hydra_status drain_copies(hydra_ctx *ctx) {
+  if (!ctx->pager) return HYDRA_OK;
+  std::string text;
+  const hydra_status st = pager_drain(ctx->pager, &text);
+  return st ? fail(ctx, st, text) : HYDRA_OK;
 }
 
 // device-side address of caller memory that must be page-locked and mapped
@@ -70,6 +163,13 @@ static hydra_status mapped_pointer(hydra_ctx *ctx, const void *host, const char 
   if (((uintptr_t)at.devicePointer) & 15) return fail(ctx, HYDRA_E_INVAL, std::string(what) + " must be 16-byte aligned");
   *out = (float *)at.devicePointer;
   return HYDRA_OK;
+}
+
+static bool page_locked(const void *host) {
+  hipPointerAttribute_t at;
+  const bool yes = hipPointerGetAttributes(&at, host) == hipSuccess && at.type == hipMemoryTypeHost;
+  if (!yes) (void)hipGetLastError();
+  return yes;
 }
 
 static hydra_status make_event(hydra_ctx *ctx, hipEvent_t *ev) {
@@ -207,6 +307,18 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
     prof_activate(ctx->prof);
   }
   if (!ctx->dry && (desc->flags & HYDRA_FLAG_OVERLAP)) ctx->tracer = trace_create();
+  if (!ctx->dry && desc->stage) {
+    if (desc->stage_threads < 0 || desc->stage_threads > 16) {
+      hydra_destroy(ctx);
+      return fail(nullptr, HYDRA_E_INVAL, "stage_threads must be 0..16");
+    }
+    std::string perr;
+    ctx->pager = pager_create(ctx, desc->stage, desc->stage_bytes, desc->stage_threads > 0 ? desc->stage_threads - 1 : 2, &perr);
+    if (!ctx->pager) {
+      hydra_destroy(ctx);
+      return fail(nullptr, HYDRA_E_INVAL, perr);
+    }
+  }
   *out = ctx;
   return HYDRA_OK;
 }
@@ -214,6 +326,11 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
 hydra_status hydra_destroy(hydra_ctx *ctx) {
   if (!ctx) return HYDRA_OK;
   if (!ctx->dry) {
+    if (ctx->pager) {
+      (void)pager_drain(ctx->pager, nullptr);
+      pager_destroy(ctx->pager);
+      ctx->pager = nullptr;
+    }
     for (hydra_ctx::Lane &ln : ctx->lanes) (void)hipStreamSynchronize(ln.stream);
     (void)hipStreamSynchronize(ctx->s_h2d);
     (void)hipStreamSynchronize(ctx->s_d2h);
@@ -238,6 +355,8 @@ hydra_status hydra_destroy(hydra_ctx *ctx) {
 hydra_status hydra_sync(hydra_ctx *ctx) {
   if (!ctx) return fail(nullptr, HYDRA_E_INVAL, "null context");
   if (ctx->dry) return HYDRA_OK;
+  hydra_status st = drain_copies(ctx);
+  if (st) return st;
   HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
   for (hydra_ctx::Lane &ln : ctx->lanes) HYDRA_HIP(ctx, hipStreamSynchronize(ln.stream));
   HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
@@ -270,7 +389,19 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   }
   m->desc = *desc;
   m->host = *host;
-  if ((st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master)) ||
+  m->pageable = !ctx->dry && (!page_locked(host->master) || !page_locked(host->adam_m) || !page_locked(host->adam_v));
+  if (m->pageable && !ctx->pager) {
+    delete m;
+    return fail(ctx, HYDRA_E_INVAL, "master / adam_m / adam_v are not page-locked and hydra_init was given no staging area");
+  }
+  if (m->pageable) {
+    m->host_dev = *host;  // never used: state in ordinary memory travels through the staging ring
+    st = mapped_pointer(ctx, host->ckpt, "ckpt", &m->host_dev.ckpt);
+    if (st) {
+      delete m;
+      return st;
+    }
+  } else if ((st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master)) ||
       (st = mapped_pointer(ctx, host->adam_m, "adam_m", &m->host_dev.adam_m)) ||
       (st = mapped_pointer(ctx, host->adam_v, "adam_v", &m->host_dev.adam_v)) ||
       (st = mapped_pointer(ctx, host->ckpt, "ckpt", &m->host_dev.ckpt))) {
@@ -306,6 +437,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   }
   m->slot_of.assign(s.S + 2, -1);
   m->wb_pending.assign(s.S + 2, 0);
+  m->wb_ticket.assign(s.S + 2, 0);
   m->lane = (int)(ctx->models.size() % ctx->lanes.size());
   m->stage = host->batch_stage;
   if (!ctx->dry) {
@@ -375,15 +507,12 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   if ((st = ensure_planned(ctx))) return st;
   Model *m = ctx->models[model];
   const int64_t off = m->sh.shard_off[shard], cnt = m->sh.shard_off[shard + 1] - off;
+  if ((st = pager_check(ctx))) return st;
   ctx->stats.n_loads++;
   Slot *sl = slot_for(ctx, model, shard);
-  bool copied = false;
-  // overlap trace: the interval opens when the copy stream reaches the first copy of this call
-  int tr = -1;
-  const uint64_t h2d_before = ctx->stats.bytes_h2d;
-  auto trace_open = [&]() {
-    if (tr < 0 && !ctx->dry) tr = trace_begin(ctx, TRACE_H2D, ctx->s_h2d, model << 16 | shard);
-  };
+  CopyPlan plan;
+  plan.trace_tag = model << 16 | shard;
+  const int host_kind = m->pageable ? CopyPlan::SEG_PAGEABLE : CopyPlan::SEG_PINNED;
   if (!sl) {
     int free_i = -1;
     for (size_t i = 0; i < ctx->slots.size(); ++i)
@@ -398,9 +527,10 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     sl->wb_seq = 0;
     m->slot_of[shard] = free_i;
     // the buffer's previous occupant must be done with it
-    if (!ctx->dry) {
-      if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, sl->ev_compute, 0));
-      if (sl->spill_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, sl->ev_spilled, 0));
+    if (sl->compute_pending) plan.waits.push_back(sl->ev_compute);
+    if (sl->spill_pending) {
+      plan.waits.push_back(sl->ev_spilled);
+      if (sl->spill_ticket) plan.d2h_tickets.push_back(sl->spill_ticket);
     }
     sl->compute_pending = sl->spill_pending = false;
   } else if (sl->has_params && (sl->has_opt || !(what & HYDRA_LOAD_OPT))) {
@@ -409,15 +539,14 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   // the host arrays of a shard are read only after its last write-back has landed (the buffer it was written
   // back from may be a different one)
   if ((!sl->has_params || ((what & HYDRA_LOAD_OPT) && !sl->has_opt)) && m->wb_pending[shard]) {
-    if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_wb[shard], 0));
+    if (!ctx->dry) plan.waits.push_back(m->ev_wb[shard]);
+    if (m->wb_ticket[shard]) plan.d2h_tickets.push_back(m->wb_ticket[shard]);
     m->wb_pending[shard] = 0;
   }
   if (!sl->has_params) {
-    trace_open();
-    if ((st = copy_h2d(ctx, sl->w, m->host.master + off, cnt * 4))) return st;
-    ctx->stats.bytes_h2d += cnt * 4;
+    plan.segs.push_back({sl->w, m->host.master + off, nullptr, (size_t)cnt * 4, host_kind});
+    plan.trace_bytes += (uint64_t)cnt * 4;
     sl->has_params = true;
-    copied = true;
   }
   if (m->sh.tie && shard == m->sh.S + 1 && !sl->tied_valid) {
     // tied LM head: the buffer keeps a copy of wte behind the final LayerNorm's parameters.  Taken from the EMBED
@@ -425,38 +554,35 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     const uint64_t bytes = (uint64_t)m->sh.V * m->sh.d * 4;
     Slot *e = slot_for(ctx, model, 0);
     if (e && e->has_params) {
-      if (!ctx->dry) {
-        if (e->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, e->ev_compute, 0));
-        HYDRA_HIP(ctx, hipMemcpyAsync(sl->w + 2 * m->sh.d, e->w, bytes, hipMemcpyDeviceToDevice, ctx->s_h2d));
-      }
+      if (e->compute_pending) plan.waits.push_back(e->ev_compute);
+      plan.segs.push_back({sl->w + 2 * m->sh.d, e->w, nullptr, (size_t)bytes, CopyPlan::SEG_DEVICE});
     } else {
       if (m->wb_pending[0]) {
-        if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_h2d, m->ev_wb[0], 0));
+        if (!ctx->dry) plan.waits.push_back(m->ev_wb[0]);
+        if (m->wb_ticket[0]) plan.d2h_tickets.push_back(m->wb_ticket[0]);
         m->wb_pending[0] = 0;
       }
-      trace_open();
-      if (!ctx->dry)
-        HYDRA_HIP(ctx, hipMemcpyAsync(sl->w + 2 * m->sh.d, m->host.master, bytes, hipMemcpyHostToDevice, ctx->s_h2d));
-      ctx->stats.bytes_h2d += bytes;
+      plan.segs.push_back({sl->w + 2 * m->sh.d, m->host.master, nullptr, (size_t)bytes, host_kind});
+      plan.trace_bytes += bytes;
     }
     sl->tied_valid = true;
     sl->wb_valid = false;
-    copied = true;
   }
   if ((what & HYDRA_LOAD_OPT) && !sl->has_opt) {
-    trace_open();
-    if ((st = copy_h2d(ctx, sl->m, m->host.adam_m + off, cnt * 4)) ||
-        (st = copy_h2d(ctx, sl->v, m->host.adam_v + off, cnt * 4)))
-      return st;
-    ctx->stats.bytes_h2d += cnt * 8;
+    plan.segs.push_back({sl->m, m->host.adam_m + off, nullptr, (size_t)cnt * 4, host_kind});
+    plan.segs.push_back({sl->v, m->host.adam_v + off, nullptr, (size_t)cnt * 4, host_kind});
+    plan.trace_bytes += (uint64_t)cnt * 8;
     sl->has_opt = true;
-    copied = true;
   }
-  if (copied) {
-    if (!ctx->dry) HYDRA_HIP(ctx, hipEventRecord(sl->ev_loaded, ctx->s_h2d));
+  ctx->stats.bytes_h2d += plan.trace_bytes;
+  if (!plan.segs.empty()) {
+    plan.records.push_back(sl->ev_loaded);
     sl->need_wait_load = true;
   }
-  trace_end(ctx, tr, ctx->s_h2d, ctx->stats.bytes_h2d - h2d_before);
+  if (ctx->dry || (plan.segs.empty() && plan.waits.empty())) return HYDRA_OK;
+  uint64_t ticket = 0;
+  if ((st = issue_plan(ctx, PQ_H2D, plan, &ticket))) return st;
+  if (!plan.segs.empty()) sl->load_ticket = ticket;
   return HYDRA_OK;
 }
 
@@ -471,34 +597,43 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
   if ((what & HYDRA_SPILL_EVICT) && sl->dirty && !(what & HYDRA_SPILL_WRITEBACK))
     return fail(ctx, HYDRA_E_STATE, "evicting a shard whose updated state was not written back");
   const int64_t off = m->sh.shard_off[shard], cnt = m->sh.shard_off[shard + 1] - off;
-  if ((what & HYDRA_SPILL_WRITEBACK) && sl->dirty) {
-    if (!ctx->dry) {
-      if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
-      hydra_status cs;
-      const int tr = trace_begin(ctx, TRACE_D2H, ctx->s_d2h, model << 16 | shard);
-      if ((cs = copy_d2h(ctx, m->host.master + off, m->host_dev.master + off, sl->w, cnt * 4, m->sh.Mt)) ||
-          (cs = copy_d2h(ctx, m->host.adam_m + off, m->host_dev.adam_m + off, sl->m, cnt * 4, m->sh.Mt)) ||
-          (cs = copy_d2h(ctx, m->host.adam_v + off, m->host_dev.adam_v + off, sl->v, cnt * 4, m->sh.Mt)))
-        return cs;
-      trace_end(ctx, tr, ctx->s_d2h, (uint64_t)cnt * 12);
-      HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
-      HYDRA_HIP(ctx, hipEventRecord(m->ev_wb[shard], ctx->s_d2h));
+  if ((st = pager_check(ctx))) return st;
+  const bool writeback = (what & HYDRA_SPILL_WRITEBACK) && sl->dirty;
+  const bool poison = (what & HYDRA_SPILL_EVICT) && (ctx->init.flags & HYDRA_FLAG_POISON);
+  if (writeback || poison) {
+    CopyPlan plan;
+    plan.trace_tag = model << 16 | shard;
+    plan.tokens_per_visit = m->sh.Mt;
+    // after the last task that used the buffer
+    if (sl->compute_pending) plan.waits.push_back(sl->ev_compute);
+    if (writeback) {
+      const int kind = m->pageable ? CopyPlan::SEG_PAGEABLE : CopyPlan::SEG_PINNED;
+      plan.segs.push_back({m->host.master + off, sl->w, m->host_dev.master + off, (size_t)cnt * 4, kind});
+      plan.segs.push_back({m->host.adam_m + off, sl->m, m->host_dev.adam_m + off, (size_t)cnt * 4, kind});
+      plan.segs.push_back({m->host.adam_v + off, sl->v, m->host_dev.adam_v + off, (size_t)cnt * 4, kind});
+      plan.trace_bytes = (uint64_t)cnt * 12;
+      if (!ctx->dry) plan.records.push_back(m->ev_wb[shard]);
     }
-    m->wb_pending[shard] = 1;
+    if (poison) {  // on the d2h stream: behind the write-back
+      plan.poison = true;
+      plan.poison_base = sl->base;
+      plan.poison_words = (int64_t)(ctx->slot_bytes / 4);
+    }
+    if (!ctx->dry) plan.records.push_back(sl->ev_spilled);
+    uint64_t ticket = 0;
+    if ((st = issue_plan(ctx, PQ_D2H, plan, &ticket))) return st;
     sl->spill_pending = true;
-    sl->wb_seq = ++ctx->wb_counter;
-    sl->dirty = false;
-    ctx->stats.bytes_d2h += cnt * 12;
-    ctx->stats.n_writebacks++;
+    sl->spill_ticket = ticket;
+    if (writeback) {
+      m->wb_pending[shard] = 1;
+      m->wb_ticket[shard] = ticket;
+      sl->wb_seq = ++ctx->wb_counter;
+      sl->dirty = false;
+      ctx->stats.bytes_d2h += cnt * 12;
+      ctx->stats.n_writebacks++;
+    }
   }
   if (what & HYDRA_SPILL_EVICT) {
-    if ((ctx->init.flags & HYDRA_FLAG_POISON) && !ctx->dry) {
-      // on the d2h stream: after the write-back (same stream) and after the last task that used the buffer
-      if (sl->compute_pending) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->s_d2h, sl->ev_compute, 0));
-      HYDRA_HIP(ctx, launch_fill_u32((uint32_t *)sl->base, 0x7fc07fc0u, (int64_t)(ctx->slot_bytes / 4), ctx->s_d2h));
-      HYDRA_HIP(ctx, hipEventRecord(sl->ev_spilled, ctx->s_d2h));
-      sl->spill_pending = true;
-    }
     m->slot_of[shard] = -1;
     sl->model = sl->shard = -1;
     sl->has_params = sl->has_opt = sl->wb_valid = sl->wbt_valid = sl->grads_valid = sl->tied_valid = false;
@@ -539,7 +674,12 @@ static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out)
   if (ctx->models[model]->sh.tie && shard == ctx->models[model]->sh.S + 1 && !sl->tied_valid)
     return fail(ctx, HYDRA_E_STATE, "tied LM head: load the shard again after the embedding shard's update");
   if (sl->need_wait_load) {
-    if (!ctx->dry) HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[ctx->models[model]->lane].stream, sl->ev_loaded, 0));
+    if (!ctx->dry) {
+      // with a staging tier the promote is issued by another thread: the event can be waited for once it is recorded
+      if (ctx->pager && sl->load_ticket) pager_wait(ctx->pager, PQ_H2D, sl->load_ticket);
+      if ((st = pager_check(ctx))) return st;
+      HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[ctx->models[model]->lane].stream, sl->ev_loaded, 0));
+    }
     sl->need_wait_load = false;
   }
   *out = sl;
@@ -669,11 +809,7 @@ hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int
   Model *m = ctx->models[model];
   const ModelShape &s = m->sh;
   const uint64_t act = (uint64_t)s.Mt * s.d * 4;
-  if (!ctx->dry) {
-    HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
-    for (hydra_ctx::Lane &ln : ctx->lanes) HYDRA_HIP(ctx, hipStreamSynchronize(ln.stream));
-    HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
-  }
+  if (!ctx->dry && (st = hydra_sync(ctx))) return st;
   const void *src = nullptr;
   uint64_t need = 0;
   switch (which) {

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <functional>
 #include <map>
 #include <string>
 #include <vector>
@@ -24,6 +25,10 @@ struct Tracer;
 enum { TRACE_COMPUTE = 0, TRACE_H2D = 1, TRACE_D2H = 2 };
 Tracer *trace_create();
 void trace_destroy(Tracer *t);
+
+// staging tier for host state that is not page-locked (pager.cpp)
+struct Pager;
+enum { PQ_H2D = 0, PQ_D2H = 1 };
 
 struct TensorInfo {
   std::string name;
@@ -66,6 +71,7 @@ struct Slot {
   bool compute_pending = false, spill_pending = false;
   bool tied_valid = false;  // HEAD shard of a tied model: the buffer's copy of wte is current
   uint64_t last_use = 0;  // value of the context's task counter when a task last ran on this buffer
+  uint64_t load_ticket = 0, spill_ticket = 0;  // staging tier: the jobs that issue the buffer's last promote / write-back
   uint64_t wb_seq = 0;    // position of the buffer's last write-back in the order write-backs were enqueued (0: none
                           // since it was filled); the d2h stream works in that order, so a smaller value is free earlier
 };
@@ -105,6 +111,8 @@ struct Model {
   float *tied_g = nullptr;   // tied LM head: its part of the wte gradient [V,d], from HEAD backward to EMBED backward
   std::vector<hipEvent_t> ev_wb;   // per shard: last write-back to the host arrays
   std::vector<char> wb_pending;
+  std::vector<uint64_t> wb_ticket;  // staging tier: job of the shard's last write-back
+  bool pageable = false;            // master / m / v are ordinary host memory: copies go through the staging ring
 };
 
 }  // namespace hydra
@@ -134,6 +142,7 @@ struct hydra_ctx {
   uint64_t wb_counter = 0;  // write-backs enqueued so far
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
   hydra::Tracer *tracer = nullptr;  // promote / write-back / task intervals (HYDRA_FLAG_OVERLAP)
+  hydra::Pager *pager = nullptr;    // staging ring and its threads (hydra_init_desc.stage)
   // captured block-shard visits (HYDRA_FLAG_GRAPHS); key: model, shard, phase, shard buffer, boundary-gradient parity
   struct GraphEntry {
     int seen = 0;  // visits run so far without a graph
@@ -166,6 +175,16 @@ hydra_status exec_forward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
 hydra_status exec_backward(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
 hydra_status exec_adam(hydra_ctx *ctx, Model *mm, Slot *sl, int shard);
 uint64_t workspace_need(const ModelShape &s, int dtype);
+// staging tier
+Pager *pager_create(hydra_ctx *ctx, void *stage, uint64_t stage_bytes, int helpers, std::string *err);
+void pager_destroy(Pager *p);
+uint64_t pager_submit(Pager *p, int which, std::function<hydra_status()> job);  // returns the job's ticket
+void pager_wait(Pager *p, int which, uint64_t ticket);                          // until that job has run
+hydra_status pager_error(Pager *p, std::string *text);
+hydra_status pager_drain(Pager *p, std::string *text);
+hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t bytes);
+hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit);
+hydra_status drain_copies(hydra_ctx *ctx);
 // device address of the current GPU's static scratch array (hydra_op_layernorm_bwd_static)
 hydra_status static_scratch(float **out);
 

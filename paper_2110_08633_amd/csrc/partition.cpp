@@ -143,6 +143,7 @@ hydra_status hydra_pilot_costs(hydra_ctx *ctx, int32_t model, const int32_t *tok
     }
     for (int s = 0; s < n && !st; ++s) {
       if ((st = hydra_shard_load_async(ctx, model, s, HYDRA_LOAD_PARAMS))) break;
+      if ((st = drain_copies(ctx))) break;  // (a staging tier issues the promote from its own thread)
       if (hipStreamSynchronize(ctx->s_h2d) != hipSuccess) { st = fail(ctx, HYDRA_E_HIP, "sync"); break; }
       (void)hipEventRecord(ev[2 * s], cs);
       if ((st = hydra_shard_forward(ctx, model, s))) break;
@@ -151,6 +152,7 @@ hydra_status hydra_pilot_costs(hydra_ctx *ctx, int32_t model, const int32_t *tok
     }
     for (int s = n - 1; s >= 0 && !st; --s) {
       if ((st = hydra_shard_load_async(ctx, model, s, HYDRA_LOAD_PARAMS | HYDRA_LOAD_OPT))) break;
+      if ((st = drain_copies(ctx))) break;  // (a staging tier issues the promote from its own thread)
       if (hipStreamSynchronize(ctx->s_h2d) != hipSuccess) { st = fail(ctx, HYDRA_E_HIP, "sync"); break; }
       (void)hipEventRecord(ev[2 * n + 2 * s], cs);
       if ((st = hydra_shard_backward(ctx, model, s))) break;

@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
 
 #include "hydra_internal.h"
 
@@ -24,6 +25,7 @@ struct ProfAgg {
 };
 
 struct Profiler {
+  std::mutex mu;  // launches come from the calling thread and, with a staging tier, from its coordinator threads
   std::vector<ProfRec> recs;
   std::vector<std::pair<double, double>> ivals;  // launch intervals (ms after the overlap trace's base event)
   std::vector<hipEvent_t> pool;
@@ -64,6 +66,7 @@ static hipEvent_t get_event(Profiler *p) {
 ProfScope::ProfScope(const char *name, hipStream_t s, double flops, double bytes) : stream_(s), idx_(-1) {
   Profiler *p = g_prof;
   if (!p || g_prof_quiet) return;
+  std::lock_guard<std::mutex> lock(p->mu);
   ProfRec r{name, get_event(p), get_event(p), flops, bytes};
   if (!r.e0 || !r.e1) return;
   (void)hipEventRecord(r.e0, s);
@@ -74,12 +77,14 @@ ProfScope::ProfScope(const char *name, hipStream_t s, double flops, double bytes
 ProfScope::~ProfScope() {
   Profiler *p = g_prof;
   if (!p || idx_ < 0) return;
+  std::lock_guard<std::mutex> lock(p->mu);
   (void)hipEventRecord(p->recs[idx_].e1, stream_);
 }
 
 // caller has synchronised the streams.  base (may be null): an event recorded before all of these launches; the
 // launches' intervals relative to it are kept for the overlap trace.
 void prof_collect(Profiler *p, hipEvent_t base) {
+  std::lock_guard<std::mutex> lock(p->mu);
   for (ProfRec &r : p->recs) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
@@ -134,6 +139,7 @@ struct TraceRec {
 };
 
 struct Tracer {
+  std::mutex mu;  // intervals are opened by the calling thread and by the staging tier's coordinator threads
   std::vector<TraceRec> recs;
   std::vector<hipEvent_t> pool;
   hipEvent_t base = nullptr;
@@ -167,6 +173,7 @@ static hipEvent_t trace_event(Tracer *t) {
 int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s, int tag) {
   Tracer *t = ctx->tracer;
   if (!t) return -1;
+  std::lock_guard<std::mutex> lock(t->mu);
   if (!t->base_recorded) {
     if (!t->base && hipEventCreate(&t->base) != hipSuccess) return -1;
     if (hipEventRecord(t->base, s) != hipSuccess) return -1;
@@ -185,7 +192,9 @@ int trace_begin(hydra_ctx *ctx, int kind, hipStream_t s, int tag) {
 
 void trace_end(hydra_ctx *ctx, int idx, hipStream_t s, uint64_t bytes) {
   Tracer *t = ctx->tracer;
-  if (!t || idx < 0 || idx >= (int)t->recs.size()) return;
+  if (!t || idx < 0) return;
+  std::lock_guard<std::mutex> lock(t->mu);
+  if (idx >= (int)t->recs.size()) return;
   (void)hipEventRecord(t->recs[idx].e1, s);
   t->recs[idx].bytes = bytes;
   t->recs[idx].closed = true;

@@ -33,7 +33,8 @@ class InitDesc(C.Structure):
                 ("shard_buffer_cap_bytes", C.c_uint64), ("max_slots", C.c_int32), ("flags", C.c_int32),
                 ("compute_stream", C.c_void_p), ("h2d_stream", C.c_void_p), ("d2h_stream", C.c_void_p),
                 ("compute_lanes", C.c_int32), ("copy_blocks", C.c_int32),
-                ("lane_streams", C.c_void_p * (MAX_LANES - 1)), ("prefetch_depth", C.c_int32), ("reserved", C.c_int32)]
+                ("lane_streams", C.c_void_p * (MAX_LANES - 1)), ("prefetch_depth", C.c_int32), ("stage_threads", C.c_int32),
+                ("stage", C.c_void_p), ("stage_bytes", C.c_uint64)]
 
 
 class ModelDesc(C.Structure):
@@ -163,11 +164,12 @@ def model_desc(cfg, lr, dtype=None, beta1=0.9, beta2=0.999, eps=1e-8):
 
 def hydra_init(arena, arena_bytes, compute_stream=None, h2d_stream=None, d2h_stream=None, flags=0,
                shard_buffer_cap_bytes=0, max_slots=0, compute_lanes=1, lane_streams=(), copy_blocks=0,
-               prefetch_depth=0):
+               prefetch_depth=0, stage=None, stage_bytes=0, stage_threads=0):
     lanes = (C.c_void_p * (MAX_LANES - 1))(*[_stream(x) for x in lane_streams])
     d = InitDesc(arena if isinstance(arena, int) else _ptr(arena), arena_bytes, shard_buffer_cap_bytes, max_slots,
                  flags, _stream(compute_stream), _stream(h2d_stream), _stream(d2h_stream), compute_lanes, copy_blocks,
-                 lanes, prefetch_depth, 0)
+                 lanes, prefetch_depth, stage_threads, stage if isinstance(stage, int) or stage is None else _ptr(stage),
+                 stage_bytes)
     out = _vp()
     _check(lib.hydra_init(C.byref(d), C.byref(out)))
     return out

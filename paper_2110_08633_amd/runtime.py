@@ -61,7 +61,9 @@ class Session:
     """One hydra context with its arena, three streams and registered models."""
 
     def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False, lanes=1,
-                 copy_blocks=0, prefetch_depth=0):
+                 copy_blocks=0, prefetch_depth=0, stage_bytes=0, stage_threads=0):
+        """stage_bytes > 0: a page-locked staging area of that size is handed to the library, and models may be added
+        with pageable=True (master / m / v in ordinary memory, for state beyond what can be page-locked)."""
         self.dry = dry_run
         self.models = []      # dicts: desc, cfg, master, m, v, ckpt, id, names
         self._pinned = []
@@ -78,24 +80,31 @@ class Session:
             arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
             self.streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
             self.lane_streams = [torch.cuda.Stream() for _ in range(lanes - 1)]     # default priority
-        self.ctx = H.hydra_init(arena_ptr, arena_bytes, *self.streams, flags=flags,
+        self.stage = None
+        if stage_bytes and not dry_run:
+            self.stage = PinnedArray(stage_bytes + 256, np.uint8, zero=False)
+            self._pinned.append(self.stage)
+        stage_ptr = (self.stage.ptr + 255) // 256 * 256 if self.stage else None
+        self.ctx = H.hydra_init(arena_ptr, arena_bytes, *self.streams, flags=flags, stage=stage_ptr,
+                                stage_bytes=stage_bytes if self.stage else 0, stage_threads=stage_threads,
                                 shard_buffer_cap_bytes=shard_buffer_cap_bytes, max_slots=max_slots,
                                 compute_lanes=lanes, lane_streams=self.lane_streams, copy_blocks=copy_blocks,
                                 prefetch_depth=prefetch_depth)
         self.flags = flags
 
-    def _host(self, n, dtype=np.float32):
-        if self.dry:
+    def _host(self, n, dtype=np.float32, pageable=False):
+        if self.dry or pageable:
             return np.zeros(n, dtype)
         buf = PinnedArray(n, dtype)
         self._pinned.append(buf)
         return buf.array
 
-    def add_model(self, cfg, weights, lr, dtype=None):
-        """weights: dict name -> float32 array (names as given by hydra_model_tensor)."""
+    def add_model(self, cfg, weights, lr, dtype=None, pageable=False):
+        """weights: dict name -> float32 array (names as given by hydra_model_tensor).  pageable: the model's
+        state arrays are ordinary host memory (needs a session with a staging area)."""
         desc = H.model_desc(cfg, lr, dtype)
         lay = H.hydra_model_layout(desc)
-        master, m, v = self._host(lay.n_params), self._host(lay.n_params), self._host(lay.n_params)
+        master, m, v = (self._host(lay.n_params, pageable=pageable) for _ in range(3))
         tensors = {}
         for i in range(lay.n_tensors):
             name, off, rows, cols, shard = H.hydra_model_tensor(desc, i)

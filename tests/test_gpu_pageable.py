@@ -1,0 +1,92 @@
+"""Model state in ordinary (pageable) host memory: promotes and write-backs travel through the page-locked staging
+ring (hydra_init_desc.stage) on the library's own threads.  The staging tier moves bytes and nothing else, so every
+result must equal the page-locked path bit for bit - with rings of 1 MiB chunks, so that a shard takes many chunks
+and the ring wraps several times per copy."""
+import numpy as np
+import pytest
+
+import synth_inputs as SI
+from tests.test_gpu_parity import (assert_same_state, check_against_models_alone, costs_of, oracle_order, run_manual,
+                                   scheduled_run)
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+STAGE = dict(stage_bytes=16 << 20)        # two rings of eight 1 MiB chunks
+
+
+@pytest.fixture(scope="module")
+def rt():
+    from paper_2110_08633_amd import hydra, runtime
+    return hydra, runtime
+
+
+def _cfg(dtype, **kw):
+    # embedding / head shards of 5 MB per state array, block shards of 3 MB: several ring chunks each
+    c = SI.small_cfg(L=4, d=128, H=2, F=512, V=10007, T=64, B=2, k=2, dtype=dtype, lrs=[1e-4])
+    c.update(kw)
+    return c
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pageable_state_step_by_step_against_the_oracle(rt, dtype):
+    """Every shard promoted from and written back to ordinary memory, two steps, everything against the oracle, and
+    the final state equal to the page-locked path's bit for bit."""
+    H, R = rt
+    cfg = _cfg(dtype)
+    _, staged, loss_s, _ = run_manual(rt, cfg, 2, max_slots=2, flags=H.FLAG_POISON, session_kw=STAGE, pageable=True,
+                                      test_id=f"pageable {dtype}")
+    _, pinned, loss_p, _ = run_manual(rt, cfg, 2, max_slots=2, flags=H.FLAG_POISON, oracle=False)
+    assert_same_state(staged, pinned, "pageable vs page-locked: ")
+    assert loss_s == loss_p
+
+
+@pytest.mark.parametrize("max_slots,lanes,threads", [(2, 1, 1), (3, 2, 3), (0, 2, 2)])
+def test_scheduled_run_with_pageable_and_page_locked_models(rt, max_slots, lanes, threads):
+    """Three models through the scheduler, the first and the last in ordinary memory and the middle one
+    page-locked, with deep prefetch, write-backs right after Adam and buffers reused across models: exact task
+    order, and every model equals its run alone (page-locked, compared with the oracle step by step)."""
+    H, R = rt
+    cfg = _cfg("bf16", n_models=3, lrs=[1e-4, 3e-4, 1e-5])
+    n, nmb = 3, [2, 2, 1]
+    Ws = [SI.make_weights(cfg, 10 + m) for m in range(n)]
+    batches = [[SI.make_batch(cfg, 100 + 10 * m + i) for i in range(nmb[m])] for m in range(n)]
+    tables = [costs_of(cfg)] * n
+    want, _, _ = oracle_order([cfg] * n, nmb, tables)
+    trace, states, losses, st = scheduled_run(rt, [cfg] * n, Ws, cfg["lrs"], batches, nmb, tables, max_slots=max_slots,
+                                              lanes=lanes, flags=H.FLAG_POISON,
+                                              session_kw=dict(STAGE, stage_threads=threads), pageable=[True, False, True])
+    assert trace == want
+    if max_slots:
+        assert st["bytes_d2h"] == sum(nmb) * 12 * SI.n_params(cfg)
+    check_against_models_alone(rt, [cfg] * n, [cfg] * n, Ws, cfg["lrs"], batches, states, losses, "bf16")
+
+
+def test_tied_head_and_micro_batches_with_pageable_state(rt):
+    """The tied LM head takes its copy of wte from the host arrays or from the embedding shard's buffer; with the
+    state in ordinary memory the first goes through the staging ring."""
+    H, R = rt
+    base = _cfg("bf16", tie=True, L=2, k=1)
+    cfg = dict(base, n_micro=2)
+    big = dict(base, B=base["B"] * 2)
+    W = SI.make_weights(base, 31)
+    batches = [SI.make_batch(big, 400 + i) for i in range(3)]
+    _, pinned, loss_p, _ = run_manual(rt, cfg, 3, max_slots=2, W=W, lr=1e-4, batches=batches, oracle_cfg=big,
+                                      test_id="tied, page-locked")
+    trace, states, losses, st = scheduled_run(rt, [cfg], [W], [1e-4], [batches], [3], [costs_of(base)], max_slots=3,
+                                              session_kw=STAGE, pageable=[True], slots_for_arena=3)
+    assert_same_state(states[0], pinned, "tied, pageable, scheduled: ")
+    assert losses[0] == loss_p
+
+
+def test_pageable_state_needs_a_staging_area(rt):
+    H, R = rt
+    cfg = _cfg("bf16")
+    sess = R.Session(R.arena_bytes_for([cfg], 2), max_slots=2)
+    with pytest.raises(H.HydraError) as e:
+        sess.add_model(cfg, None, 1e-4, pageable=True)
+    assert e.value.code == H.E_INVAL
+    sess.close()
+    with pytest.raises(H.HydraError) as e:      # an area too small for two rings
+        R.Session(R.arena_bytes_for([cfg], 2), max_slots=2, stage_bytes=1 << 20)
+    assert e.value.code == H.E_INVAL

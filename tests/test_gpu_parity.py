@@ -123,7 +123,7 @@ def host_state(sess, rec):
 
 
 def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False, W=None, lr=None, batches=None, oracle_cfg=None,
-               test_id=None, cap=0, oracle=True):
+               test_id=None, cap=0, oracle=True, session_kw=None, pageable=False):
     """n_steps minibatches of one model through the shard calls one by one (every shard spilled between visits),
     everything compared with the oracle after every step: logits, loss, every gradient tensor, updated weights,
     weight deltas, Adam state.  Returns the per-step oracle losses, the final host state (w, m, v), the last loss
@@ -135,8 +135,8 @@ def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False, W=None, lr=No
     if batches is None:
         batches = [SI.make_batch(ocfg, SI.batch_seed(cfg, 0, i), zipf=zipf) for i in range(n_steps)]
     sess = R.Session(R.arena_bytes_for([cfg], max_slots or 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags,
-                     max_slots=max_slots or 4, shard_buffer_cap_bytes=cap)
-    rec = sess.add_model(cfg, W, lr)
+                     max_slots=max_slots or 4, shard_buffer_cap_bytes=cap, **(session_kw or {}))
+    rec = sess.add_model(cfg, W, lr, pageable=pageable)
     if oracle:
         P = D.cast_params(W, np.float64)
         Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
@@ -225,13 +225,14 @@ def test_embedding_forward_is_bit_exact_and_absent_rows_untouched(rt):
     sess.close()
 
 
-def scheduled_run(rt, cfgs, Ws, lrs, batches, nmb, tables, max_slots=0, lanes=1, flags=0, cap=0, slots_for_arena=12):
+def scheduled_run(rt, cfgs, Ws, lrs, batches, nmb, tables, max_slots=0, lanes=1, flags=0, cap=0, slots_for_arena=12,
+                  session_kw=None, pageable=None):
     """All models through hydra_sched_run; returns (trace, per-model host state, per-model last loss, stats)."""
     H, R = rt
     n = len(cfgs)
     sess = R.Session(R.arena_bytes_for(cfgs, slots_for_arena, bool(flags & H.FLAG_CKPT_SPILL), lanes=lanes),
-                     max_slots=max_slots, lanes=lanes, flags=flags, shard_buffer_cap_bytes=cap)
-    recs = [sess.add_model(cfgs[m], Ws[m], lrs[m]) for m in range(n)]
+                     max_slots=max_slots, lanes=lanes, flags=flags, shard_buffer_cap_bytes=cap, **(session_kw or {}))
+    recs = [sess.add_model(cfgs[m], Ws[m], lrs[m], pageable=bool(pageable and pageable[m])) for m in range(n)]
     sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, tables)
     toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
     tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
