@@ -1,22 +1,23 @@
 #!/usr/bin/env python3
 """Throughput of spilled, shard-alternated training on one MI355X.
 
-Workload (BASELINE config 2): two GPT-2-small-shaped models (12 layers, d 768,
-12 heads, MLP 3072, vocab 50257, seq 512, batch 4; bf16 compute with fp32
-master weights; lr 1e-4 / 3e-5) whose 2-layer shards are alternated by the
-Sharded-LRTF scheduler.  One step = one minibatch of every model through the
-whole path: promote shard, forward visit, checkpoint, backward visit with
-recomputation, Adam, demote.
+Headline workload (BASELINE config 5, the largest that one GPU serves): two ~6 B-parameter GPT-style decoders (28
+layers, d 4096, 32 heads, MLP 16384, vocab 50400, seq 1024, batch 1; bf16 compute with fp32 master weights and
+Adam state) whose 2-layer shards are alternated by the Sharded-LRTF scheduler on TWO shard buffers; all state
+(145 GB) lives in host DRAM.  One step = one minibatch of every model through the whole path: promote shard,
+forward visit, checkpoint, backward visit with recomputation, Adam, demote.  If the host cannot hold that state the
+run falls back to config 4 (four GPT-2-XL-shaped models, 24 GB of shard buffers) and says so in config.workload.
 
-Default mode "spill": six shard buffers (per compute lane one computing, one filling, one draining), so every shard's state streams in
-from pinned host DRAM before each visit and the updated state streams back.
-Mode "resident": as many buffers as shards (state crosses the link once).
+Host state that exceeds what the driver lets a process page-lock (64 GiB on the machines this was developed on) is
+kept in ordinary memory and travels through the library's page-locked staging ring.
 
-Prints ONE JSON line.  `value` is tokens/s over all models with all inputs
-(weights in pinned host memory, token batches) prepared before the timed
-region.  `roofline` describes the kernel with the largest share of GPU time,
-timed with HIP events on its own stream in a second pass over the same work.
-`cpu_baseline` times the CPU oracle on a bounded sample of the same workload.
+Prints ONE JSON line.  `value` is tokens/s over all models with all inputs (weights in host memory, token batches)
+prepared before the timed region.  `roofline` describes the kernel with the largest share of GPU time in a second
+pass over the same work in the SAME mode (spilled, two lanes) with every launch bracketed by HIP events on its own
+stream - where every byte of state crosses the host link twice per step that is the write-back copy kernel, bound
+by the link; `roofline_mfma` is the matrix kernel with the largest share of the same pass.  The other BASELINE
+workloads (configs 2-4) follow as objects of their own, and `cpu_baseline` times the CPU oracle on a bounded
+sample of the headline workload.
 """
 import argparse
 import json
@@ -33,32 +34,100 @@ import synth_inputs as SI  # noqa: E402
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBPS = 8000.0
+PCIE_GEN5_X16_GBPS = 64.0       # per direction, theoretical
+LINK_CAP_GBPS = 87.7            # both directions together, measured on this hardware (1 GB copies, SDMA in + copy kernel out)
+STAGE_BYTES = 1 << 30           # page-locked staging ring for state in ordinary memory: 2 x 8 chunks of 64 MiB
+
+# per workload: shard buffers / byte cap as BASELINE states them (config 3 names none: three buffers per lane)
+WORKLOADS = {
+    "gpt6b": dict(max_slots=2, cap=0, what="2 shard buffers of 2 layers (BASELINE config 5)"),
+    "gpt2xl": dict(max_slots=0, cap=24 * 10 ** 9, what="shard buffers capped at 24 GB (BASELINE config 4)"),
+    "gpt2m": dict(max_slots=6, cap=0, what="6 shard buffers, every shard spilled between uses (BASELINE config 3)"),
+    "gpt2s": dict(max_slots=6, cap=0, what="6 shard buffers (BASELINE config 2)"),
+}
 
 
-SPILL_SLOTS = 4
-TRACE_OVERLAP = True
-EXTRA_FLAGS = 0
-LINK_CAP_GBPS = 87.7
-LANES = 2
+T_START = time.perf_counter()
 
 
-def make_session(cfg, n_models, mode, timing, R, H):
+def log(msg):
+    """Progress on stderr (stdout carries the one JSON line): a run of several minutes must not look hung."""
+    print(f"[bench {time.perf_counter() - T_START:6.1f}s] {msg}", file=sys.stderr, flush=True)
+
+
+def mem_available_gb():
+    for line in open("/proc/meminfo"):
+        if line.startswith("MemAvailable:"):
+            return int(line.split()[1]) * 1024 / 1e9
+    return 0.0
+
+
+class HostState:
+    """master / m / v of every model of a workload: page-locked if the driver allows that much, else ordinary memory
+    (the library then stages every copy).  Weights: one seeded N(0, 0.02) block tiled over the master array,
+    LayerNorm gains 1, biases 0 - cheap to produce at 6 B parameters and irrelevant to kernel time."""
+
+    def __init__(self, cfg, n_models, R, H):
+        self.cfg, self.n = cfg, n_models
+        desc = H.model_desc(cfg, 1e-4)
+        lay = H.hydra_model_layout(desc)
+        self.n_params = lay.n_params
+        self.pinned_bufs, self.arrays, self.pageable = [], [], False
+        try:
+            for _ in range(n_models):
+                bufs = [R.PinnedArray(lay.n_params, np.float32, zero=False) for _ in range(3)]
+                self.pinned_bufs += bufs
+                self.arrays.append(tuple(b.array for b in bufs))
+        except MemoryError:
+            self.free()
+            self.pageable = True
+            self.arrays = [tuple(np.zeros(lay.n_params, np.float32) for _ in range(3)) for _ in range(n_models)]
+        tensors = [H.hydra_model_tensor(desc, i) for i in range(lay.n_tensors)]
+        for m in range(n_models):
+            master, am, av = self.arrays[m]
+            rng = np.random.default_rng(SI.model_seed(cfg, m))
+            block = (rng.standard_normal(1 << 24, dtype=np.float32) * np.float32(SI.INIT_STD))
+            full = master.size // block.size
+            if full:
+                master[: full * block.size].reshape(full, block.size)[:] = block
+            master[full * block.size:] = block[: master.size - full * block.size]
+            for name, off, rows, cols, _ in tensors:
+                leaf = name.split(".")[-1]
+                if leaf in ("ln1_g", "ln2_g", "lnf_g"):
+                    master[off:off + rows * cols] = 1.0
+                elif leaf.startswith("b_") or leaf in ("ln1_b", "ln2_b", "lnf_b"):
+                    master[off:off + rows * cols] = 0.0
+            if not self.pageable:
+                am[:] = 0.0
+                av[:] = 0.0
+
+    def free(self):
+        self.arrays = []
+        for b in self.pinned_bufs:
+            b.free()
+        self.pinned_bufs = []
+
+
+SESSION_KW = {}     # prefetch depth / staging threads / copy workgroups from the command line (experiments)
+
+
+def make_session(cfg, n_models, host, wl, flags, lanes, R, H, mode="spill"):
     n_shards = n_models * (cfg["L"] // cfg["k"] + 2)
-    slots = SPILL_SLOTS if mode == "spill" else n_shards
-    # event pairs around promotes, write-backs and tasks (a few hundred per step) give the overlap figures
-    flags = (H.FLAG_TIMING if timing else (H.FLAG_OVERLAP if TRACE_OVERLAP and mode == "spill" else 0)) | EXTRA_FLAGS
-    lanes = 1 if timing else LANES      # per-kernel timing wants kernels one at a time
-    sess = R.Session(R.arena_bytes_for([cfg] * n_models, slots, lanes=lanes), flags=flags, max_slots=slots, lanes=lanes)
-    recs = []
-    for m in range(n_models):
-        W = SI.make_weights(cfg, SI.model_seed(cfg, m))
-        recs.append(sess.add_model(cfg, W, cfg["lrs"][m]))
-        del W
+    if mode == "resident":
+        slots, cap = n_shards, 0
+    else:
+        slots, cap = wl["max_slots"], wl["cap"]
+    arena_slots = slots if slots else max(1, cap // (20 * max_shard_elems(cfg, H))) + 1
+    sess = R.Session(R.arena_bytes_for([cfg] * n_models, arena_slots, lanes=lanes), flags=flags, max_slots=slots,
+                     shard_buffer_cap_bytes=cap, lanes=lanes, stage_bytes=STAGE_BYTES if host.pageable else 0, **SESSION_KW)
+    recs = [sess.add_model(cfg, None, cfg["lrs"][m], host=host.arrays[m], pageable=host.pageable) for m in range(n_models)]
     return sess, recs
 
 
-def flags_have_overlap(sess, H):
-    return bool(sess.flags & H.FLAG_OVERLAP)
+def max_shard_elems(cfg, H):
+    desc = H.model_desc(cfg, 1e-4)
+    lay = H.hydra_model_layout(desc)
+    return max(H.hydra_shard_range(desc, s)[1] for s in range(lay.n_shards))
 
 
 def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
@@ -68,63 +137,131 @@ def run_steps(sess, recs, cfg, n_mb, first_step, H, torch):
     toks = [np.stack([SI.make_batch(big, SI.batch_seed(cfg, m, first_step + i))[0] for i in range(n_mb)]) for m in range(n)]
     tgts = [np.stack([SI.make_batch(big, SI.batch_seed(cfg, m, first_step + i))[1] for i in range(n_mb)]) for m in range(n)]
     sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [n_mb] * n, [list(fc) + list(bc)] * n)
+    H.hydra_sync(sess.ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     H.hydra_sched_run(sch, toks, tgts, sess.ctx)
-    run_steps.enqueue_s = time.perf_counter() - t0
+    enq = time.perf_counter() - t0
     H.hydra_sync(sess.ctx)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     H.hydra_sched_destroy(sch)
-    return dt
+    return dt, enq
 
 
-def measure(cfg, n_models, mode, steps, warmup, timing, R, H, torch, pilot=False):
-    sess, recs = make_session(cfg, n_models, mode, timing, R, H)
+def measure(cfg, n_models, host, wl, steps, warmup, R, H, torch, mode="spill", timing=False, lanes=2, extra_flags=0,
+            pilot=False):
+    flags = extra_flags | (H.FLAG_OVERLAP if mode == "spill" else 0) | (H.FLAG_TIMING if timing else 0)
+    log(f"  {mode} pass, {steps} steps after {warmup} warm-up, {lanes} lane(s)" + (", kernels bracketed" if timing else "")
+        + (f", {cfg['n_micro']} micro-batches per visit" if cfg.get("n_micro", 1) > 1 else ""))
+    sess, recs = make_session(cfg, n_models, host, wl, flags, lanes, R, H, mode)
     pilot_ns = None
     if pilot:   # the partitioner's pilot pass: measured cost of every shard task of model 0 (updates discarded)
         big = dict(cfg, B=cfg["B"] * cfg.get("n_micro", 1))
         tok, tgt = SI.make_batch(big, SI.batch_seed(cfg, 0, 0))
         pilot_ns = H.hydra_pilot_costs(sess.ctx, recs[0]["id"], tok, tgt, cfg["L"] // cfg["k"] + 2)
     if warmup:
-        run_steps(sess, recs, cfg, warmup, 0, H, torch)
+        dtw, _ = run_steps(sess, recs, cfg, warmup, 0, H, torch)
+        log(f"    warm-up done ({dtw:.1f} s)")
     if timing:
         H.hydra_kernel_stats_reset(sess.ctx)
-    elif flags_have_overlap(sess, H):
+    if flags & H.FLAG_OVERLAP:
         H.hydra_overlap_reset(sess.ctx)
     st0 = H.hydra_get_stats(sess.ctx)
-    dt = run_steps(sess, recs, cfg, steps, warmup, H, torch)
+    dt, enq = run_steps(sess, recs, cfg, steps, warmup, H, torch)
     st1 = H.hydra_get_stats(sess.ctx)
+    log(f"    {steps} steps in {dt:.2f} s")
     kst = H.hydra_kernel_stats(sess.ctx) if timing else None
-    ov = H.hydra_overlap_stats(sess.ctx) if flags_have_overlap(sess, H) else None
+    ov = H.hydra_overlap_stats(sess.ctx) if flags & H.FLAG_OVERLAP else None
     losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
     sess.close()
     del sess
     torch.cuda.empty_cache()
-    return dict(seconds=dt, enqueue_seconds=run_steps.enqueue_s, h2d=st1["bytes_h2d"] - st0["bytes_h2d"], d2h=st1["bytes_d2h"] - st0["bytes_d2h"],
-                n_slots=st1["n_slots"], kernels=kst, losses=losses, pilot_ns=pilot_ns, overlap=ov,
-                host_promote_ms=st1["host_promote_ms"] - st0["host_promote_ms"],
-                host_writeback_ms=st1["host_writeback_ms"] - st0["host_writeback_ms"],
-                host_task_ms=st1["host_task_ms"] - st0["host_task_ms"],
-                host_batch_ms=st1["host_batch_ms"] - st0["host_batch_ms"])
+    d = {k: st1[k] - st0[k] for k in ("bytes_h2d", "bytes_d2h", "host_promote_ms", "host_writeback_ms", "host_task_ms",
+                                      "host_batch_ms")}
+    return dict(seconds=dt, enqueue_seconds=enq, steps=steps, h2d=d["bytes_h2d"], d2h=d["bytes_d2h"], n_slots=st1["n_slots"],
+                kernels=kst, losses=losses, pilot_ns=pilot_ns, overlap=ov, host=d)
 
 
-def overlap_report(run, steps):
-    """Swap / compute overlap of a run from the library's event trace: busy times are lengths of interval unions
-    (a shard task running on any lane; a promote or a write-back in flight), per step."""
+def link_report(run):
+    s = run["seconds"]
+    both = (run["h2d"] + run["d2h"]) / s / 1e9
+    return {"h2d_GB_per_step": round(run["h2d"] / run["steps"] / 1e9, 3),
+            "d2h_GB_per_step": round(run["d2h"] / run["steps"] / 1e9, 3),
+            "h2d_GBps_over_wall": round(run["h2d"] / s / 1e9, 2), "d2h_GBps_over_wall": round(run["d2h"] / s / 1e9, 2),
+            # what bounds a spilled step: both directions of the host link together carried 87.7 GB/s on this hardware
+            # (each alone 57.6 / 54.7 GB/s); PCIe Gen5 x16 is 64 GB/s per direction on paper
+            "both_directions_GBps_over_wall": round(both, 2), "both_directions_GBps_measured_cap": LINK_CAP_GBPS,
+            "frac_of_link_cap": round(both / LINK_CAP_GBPS, 3), "frac_of_pcie_gen5_x16_both_directions": round(both / (2 * PCIE_GEN5_X16_GBPS), 3)}
+
+
+def overlap_report(run):
+    """Swap / compute overlap of a run from the library's event trace.  Busy times are lengths of interval unions per
+    step: a promote or write-back in flight; a shard task in flight on any lane (from its first kernel's start to its
+    last kernel's end, launch gaps included: `tasks_in_flight`); and, in a pass that also brackets every kernel
+    launch, a kernel executing (`kernel_busy`).  transfer_hidden_frac - the share of swap time with compute under it,
+    the figure the 80 % target is judged on - is taken at kernel level where available."""
     o = run["overlap"]
     if not o or not o["n_intervals"] or o["transfer_ms"] <= 0:
         return None
-    r = lambda x: round(x / steps, 3)
-    return {"compute_busy_ms_per_step": r(o["compute_ms"]), "h2d_busy_ms_per_step": r(o["h2d_ms"]),
-            "d2h_busy_ms_per_step": r(o["d2h_ms"]), "transfer_busy_ms_per_step": r(o["transfer_ms"]),
-            "transfer_hidden_frac": round(o["hidden_ms"] / o["transfer_ms"], 4),
-            "hidden_frac_upper_bound": round(min(1.0, o["compute_ms"] / o["transfer_ms"]), 4),
-            "compute_with_transfer_in_flight_frac": round(o["hidden_ms"] / max(o["compute_ms"], 1e-9), 4),
-            "h2d_GBps_while_busy": round(o["bytes_h2d"] / max(o["h2d_ms"], 1e-9) / 1e6, 2),
-            "d2h_GBps_while_busy": round(o["bytes_d2h"] / max(o["d2h_ms"], 1e-9) / 1e6, 2),
-            "host_promote_ms_per_step": r(run["host_promote_ms"]), "host_writeback_ms_per_step": r(run["host_writeback_ms"]),
-            "host_task_enqueue_ms_per_step": r(run["host_task_ms"]), "host_set_batch_ms_per_step": r(run["host_batch_ms"])}
+    n = run["steps"]
+    r = lambda x: round(x / n, 3)
+    out = {"h2d_busy_ms_per_step": r(o["h2d_ms"]), "d2h_busy_ms_per_step": r(o["d2h_ms"]),
+           "transfer_busy_ms_per_step": r(o["transfer_ms"]),
+           "tasks_in_flight_ms_per_step": r(o["compute_ms"]),
+           "tasks_in_flight_frac_of_transfer": round(o["hidden_ms"] / o["transfer_ms"], 4),
+           "transfer_in_flight_frac_of_tasks": round(o["hidden_ms"] / max(o["compute_ms"], 1e-9), 4),
+           "h2d_GBps_while_busy": round(o["bytes_h2d"] / max(o["h2d_ms"], 1e-9) / 1e6, 2),
+           "d2h_GBps_while_busy": round(o["bytes_d2h"] / max(o["d2h_ms"], 1e-9) / 1e6, 2),
+           "host_promote_ms_per_step": r(run["host"]["host_promote_ms"]),
+           "host_writeback_ms_per_step": r(run["host"]["host_writeback_ms"]),
+           "host_task_enqueue_ms_per_step": r(run["host"]["host_task_ms"]),
+           "host_set_batch_ms_per_step": r(run["host"]["host_batch_ms"])}
+    if o["kernel_ms"] > 0:
+        out["kernel_busy_ms_per_step"] = r(o["kernel_ms"])
+        out["transfer_hidden_frac"] = round(o["hidden_kernel_ms"] / o["transfer_ms"], 4)
+        out["hidden_frac_upper_bound"] = round(min(1.0, o["kernel_ms"] / o["transfer_ms"]), 4)
+    return out
+
+
+def kernel_report(t):
+    """Per-kernel figures of a pass with every launch bracketed by HIP events on its stream."""
+    ks = sorted(t["kernels"], key=lambda k: -k["ms"])
+    total_ms = sum(k["ms"] for k in ks)
+    steps = t["steps"]
+
+    def roof(k):
+        avg = 1e3 * k["ms"] / k["launches"]
+        if k["name"] == "copy_to_host":
+            ach = k["bytes"] / (k["ms"] * 1e-3) / 1e9
+            return {"bound": "link", "achieved": round(ach, 2), "peak": PCIE_GEN5_X16_GBPS, "unit": "GB/s",
+                    "frac": round(ach / PCIE_GEN5_X16_GBPS, 4), "traffic": None, "kernel": k["name"],
+                    "launches": k["launches"], "avg_us": round(avg, 2),
+                    "peak_note": "PCIe Gen5 x16, one direction, theoretical; with promotes in flight the two directions "
+                                 f"shared {LINK_CAP_GBPS} GB/s on this hardware"}
+        if k["flops"] > 0:
+            ach = k["flops"] / (k["ms"] * 1e-3) / 1e12
+            return {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "kernel": k["name"],
+                    "launches": k["launches"], "avg_us": round(avg, 2)}
+        ach = k["bytes"] / (k["ms"] * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "kernel": k["name"], "launches": k["launches"],
+                "avg_us": round(avg, 2)}
+
+    gemm = [k for k in ks if k["flops"] > 0]
+    out = {"roofline": roof(ks[0]),
+           "kernels": [{"name": k["name"], "launches": k["launches"], "ms_per_step": round(k["ms"] / steps, 4),
+                        "share": round(k["ms"] / total_ms, 4),
+                        **({"TFLOPs": round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 1)} if k["flops"] > 0 else
+                           {"GBps": round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1)})} for k in ks]}
+    if gemm:
+        tf = sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12
+        out["roofline_mfma"] = roof(gemm[0])
+        out["gemm_aggregate"] = {"TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                                 "gemm_ms_per_step": round(sum(k["ms"] for k in gemm) / steps, 3),
+                                 "kernel_ms_per_step": round(total_ms / steps, 3)}
+    return out
 
 
 def measured_traffic(config, kernel):
@@ -141,32 +278,102 @@ def measured_traffic(config, kernel):
     return None
 
 
+def workload_text(name, cfg, n_models, wl, host):
+    return (f"{name}: {n_models} GPT-2-style decoders ({cfg['L']}L d{cfg['d']} H{cfg['H']} F{cfg['F']} V{cfg['V']}, "
+            f"{host.n_params / 1e9:.3f} B parameters each), B{cfg['B']} T{cfg['T']}, {cfg['k']}-layer shards alternated by "
+            f"Sharded-LRTF, {wl['what']}, bf16 MFMA + fp32 master/Adam, "
+            f"{n_models * host.n_params * 12 / 1e9:.1f} GB of state in "
+            + ("ordinary host memory (more than the driver page-locks: copies staged through a page-locked ring)"
+               if host.pageable else "page-locked host memory")
+            + "; weights: a seeded N(0,0.02) block tiled, LayerNorm gains 1, biases 0; uniform tokens")
+
+
+def bench_workload(name, steps, warmup, timing_steps, R, H, torch, n_models=0, layers=0, lanes=2, extra_flags=0,
+                   micro=1):
+    """One BASELINE workload as stated: spilled run (value), then the same mode with every kernel bracketed."""
+    cfg = dict(SI.CONFIGS[name])
+    if layers:
+        cfg["L"] = layers
+    if n_models:
+        cfg["n_models"] = n_models
+        cfg["lrs"] = (cfg["lrs"] * n_models)[:n_models]
+    if micro > 1:
+        cfg["n_micro"] = micro
+    n = cfg["n_models"]
+    wl = WORKLOADS[name]
+    log(f"{name}: preparing the host state of {n} model(s)")
+    host = HostState(cfg, n, R, H)
+    log(f"  {n * host.n_params * 12 / 1e9:.1f} GB of state, " + ("ordinary memory (staged)" if host.pageable else "page-locked"))
+    tokens = n * micro * cfg["B"] * cfg["T"]
+    run = measure(cfg, n, host, wl, steps, warmup, R, H, torch, lanes=lanes, extra_flags=extra_flags)
+    out = {"workload": workload_text(name, cfg, n, wl, host) + (" [depth / model count changed on the command line]" if layers or n_models else ""),
+           "value": round(tokens * steps / run["seconds"], 1), "unit": "tokens/s", "steps": steps, "warmup": warmup,
+           "ms_per_step": round(1e3 * run["seconds"] / steps, 3), "tokens_per_step": tokens,
+           "host_enqueue_ms_per_step": round(1e3 * run["enqueue_seconds"] / steps, 3),
+           "shard_buffers": run["n_slots"], "compute_lanes": lanes, "state_page_locked": not host.pageable,
+           "link": link_report(run), "overlap": overlap_report(run), "final_losses": [round(x, 4) for x in run["losses"]]}
+    if timing_steps:
+        t = measure(cfg, n, host, wl, timing_steps, 1, R, H, torch, timing=True, lanes=lanes, extra_flags=extra_flags)
+        out["kernel_pass"] = {"steps": timing_steps, "ms_per_step": round(1e3 * t["seconds"] / timing_steps, 3),
+                              "overlap": overlap_report(t), **kernel_report(t)}
+        # the kernels by themselves: one model, every shard resident, one lane - no second lane and no write-back
+        # sharing the chip with the kernel between its two events
+        q = measure(cfg, 1, host, wl, timing_steps, 1, R, H, torch, mode="resident", timing=True, lanes=1,
+                    extra_flags=extra_flags)
+        kq = kernel_report(q)
+        out["kernels_alone"] = {"what": "one model, all shards resident, one lane: each kernel alone on the device",
+                                "ms_per_step": round(1e3 * q["seconds"] / timing_steps, 3),
+                                "gemm_aggregate": kq.get("gemm_aggregate"), "roofline": kq["roofline"],
+                                "kernels": kq["kernels"][:12]}
+    return out, cfg, host
+
+
 def cpu_baseline(cfg):
-    """The CPU oracle (float32 instance) on one model-minibatch of the same workload."""
+    """The CPU oracle (float32 instance) on a bounded sample of the workload: whole minibatches of one model where
+    that takes seconds; for the large models, steps of two depth-reduced copies (one and two block shards, same
+    widths), whose difference gives the cost of a block and from it the cost of the full depth."""
     from oracle import decoder as D
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count()
-    W = SI.make_weights(cfg, SI.model_seed(cfg, 0))
-    P = D.cast_params(W, np.float32)
-    Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
-    n_steps = 5
-    batches = [SI.make_batch(cfg, SI.batch_seed(cfg, 0, i)) for i in range(n_steps)]
-    t0 = time.perf_counter()
-    for i, (tok, tgt) in enumerate(batches):
-        out = D.train_step(P, Mo, Vo, tok, tgt, cfg, cfg["lrs"][0], i + 1)
-    dt = time.perf_counter() - t0
-    return dict(value=n_steps * cfg["B"] * cfg["T"] / dt, unit="tokens/s", cores=int(threads), kind="oracle",
-                sample=f"1 model x {n_steps} minibatches ({n_steps * cfg['B'] * cfg['T']} tokens) of the same workload, "
-                       f"float32 numpy oracle, unsharded steps, {dt:.1f} s; loss {out['loss']:.4f}")
+
+    def step_seconds(c, n_steps):
+        W = SI.make_weights(c, SI.model_seed(c, 0))
+        P = D.cast_params(W, np.float32)
+        del W
+        Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
+        batches = [SI.make_batch(c, SI.batch_seed(c, 0, i)) for i in range(n_steps)]
+        t0 = time.perf_counter()
+        for i, (tok, tgt) in enumerate(batches):
+            out = D.train_step(P, Mo, Vo, tok, tgt, c, c["lrs"][0], i + 1)
+        return (time.perf_counter() - t0) / n_steps, out["loss"]
+
+    tokens = cfg["B"] * cfg["T"]
+    if SI.n_params(cfg) <= 5e8:
+        n_steps = 5 if SI.n_params(cfg) <= 2e8 else 2
+        log("cpu baseline: oracle on whole minibatches")
+        dt, loss = step_seconds(cfg, n_steps)
+        return dict(value=tokens / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                    sample=f"1 model x {n_steps} minibatches ({n_steps * tokens} tokens) of the same workload, float32 "
+                           f"numpy oracle, unsharded steps, {dt * n_steps:.1f} s; loss {loss:.4f}")
+    k = cfg["k"]
+    log("cpu baseline: oracle on depth-reduced copies")
+    t1, _ = step_seconds(dict(cfg, L=k), 1)
+    log(f"  depth {k}: {t1:.1f} s")
+    t2, loss = step_seconds(dict(cfg, L=2 * k), 1)
+    per_layer = max(t2 - t1, 1e-9) / k
+    full = t1 + (cfg["L"] - k) * per_layer
+    return dict(value=tokens / full, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"float32 numpy oracle, one minibatch ({tokens} tokens) of one model at depth {k} ({t1:.1f} s) and "
+                       f"{2 * k} ({t2:.1f} s), same widths, vocabulary and sequence; cost per layer {per_layer:.2f} s "
+                       f"extrapolated to {cfg['L']} layers = {full:.1f} s per minibatch; loss {loss:.4f}")
 
 
 def block_gemm_large_shapes(H, torch, iters=20):
-    """Context beside the workload's own figures: the library's GEMM entry point on the block products of the
-    largest configuration (28 layers, d 4096, F 16384, 1024 tokens per visit), where a product fills the chip:
-    HIP events over back-to-back launches, bf16 operands, bf16 result, flops = 2 M N K."""
+    """The library's GEMM entry point on the block products of the largest configuration alone (HIP events over
+    back-to-back launches, bf16 operands and result, flops = 2 M N K): context for the in-pipeline figures."""
     res = {}
     for name, (M, N, K) in {"qkv": (1024, 12288, 4096), "mlp_up": (1024, 16384, 4096), "mlp_down": (1024, 4096, 16384)}.items():
         A = torch.randn((M, K), device="cuda").to(torch.bfloat16)
@@ -189,39 +396,62 @@ def block_gemm_large_shapes(H, torch, iters=20):
     return res
 
 
+def gpt2s_extras(cfg, host, R, H, torch, steps):
+    """Config 2 beyond the stated run: everything resident (the compute-bound figure), pilot-pass costs, the
+    partitioner's footprints, and several micro-batches per shard visit (same state traffic, more tokens)."""
+    wl = WORKLOADS["gpt2s"]
+    n = cfg["n_models"]
+    tokens = n * cfg["B"] * cfg["T"]
+    out = {}
+    o = measure(cfg, n, host, wl, steps, 2, R, H, torch, mode="resident", pilot=True)
+    n_sh = cfg["L"] // cfg["k"] + 2
+    out["pilot_costs_us"] = {"forward": [round(x / 1e3, 1) for x in o["pilot_ns"][:n_sh]],
+                             "backward_with_adam": [round(x / 1e3, 1) for x in o["pilot_ns"][n_sh:]],
+                             "shards": "EMBED, block shards 1..S, HEAD; model 0, each task alone on the device"}
+    fp = [H.hydra_shard_footprint(H.model_desc(cfg, 1e-4), k) for k in range(0, cfg["L"] + 1)]
+    out["partitioner"] = {"footprint_MB_by_layers_in_shard": [round(x / 1e6, 1) for x in fp[1:]],
+                          "embed_head_MB": round(fp[0] / 1e6, 1),
+                          "cuts_at_bound_of_2_layer_shard": H.hydra_partition(H.model_desc(cfg, 1e-4), max(fp[2], fp[0]))[0]}
+    out["resident"] = {"value": round(tokens * steps / o["seconds"], 1), "unit": "tokens/s",
+                       "ms_per_step": round(1e3 * o["seconds"] / steps, 3),
+                       "host_enqueue_ms_per_step": round(1e3 * o["enqueue_seconds"] / steps, 3), "shard_buffers": o["n_slots"]}
+    steps_m = max(2, steps // 2)
+    for nm in (4, 8):
+        # with many tokens per visit the host spends most of a step blocked in kernel launches: graphs on
+        mc = dict(cfg, n_micro=nm)
+        o = measure(mc, n, host, wl, steps_m, 1, R, H, torch, extra_flags=H.FLAG_GRAPHS)
+        tt = measure(mc, n, host, wl, 2, 1, R, H, torch, timing=True)      # (graphs are off in a timing pass)
+        out[f"spill_micro{nm}"] = {"value": round(tokens * nm * steps_m / o["seconds"], 1), "unit": "tokens/s",
+                                   "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens * nm,
+                                   "hip_graphs": True, "link": link_report(o), "overlap": overlap_report(o),
+                                   "kernel_pass_overlap": overlap_report(tt)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=16)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--mode", choices=["spill", "resident"], default="spill")
-    ap.add_argument("--config", default="gpt2s")
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="auto", help="headline workload: gpt6b (default when the host holds its 145 GB "
+                    "of state), gpt2xl, gpt2m or gpt2s")
+    ap.add_argument("--only", action="store_true", help="measure the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extra", action="store_true", help="skip the second mode and the timing pass")
+    ap.add_argument("--no-kernel-pass", action="store_true", help="skip the pass that brackets every kernel launch")
     ap.add_argument("--large-gemm-only", action="store_true",
                     help="only time the block products of the largest configuration (for counter runs) and print them")
-    ap.add_argument("--slots", type=int, default=6, help="shard buffers in spill mode (three per compute lane)")
-    ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
     ap.add_argument("--lanes", type=int, default=2, help="compute lanes (streams); models are spread over them")
-    ap.add_argument("--graphs", action="store_true",
-                    help="replay block-shard visits as HIP graphs (halves the host's enqueue time; the device is the "
-                         "bottleneck at this workload, so the throughput does not move)")
-    ap.add_argument("--ckpt-spill", action="store_true",
-                    help="boundary activations travel through host DRAM between visits (HYDRA_FLAG_CKPT_SPILL)")
-    ap.add_argument("--layers", type=int, default=0, help="cut the model depth (other configs than the default: a "
-                    "depth-reduced copy with full widths; reported in config)")
-    ap.add_argument("--models", type=int, default=0, help="number of models (default: the config's)")
-    ap.add_argument("--no-overlap-trace", action="store_true",
-                    help="spill mode: do not record the event pairs behind the 'overlap' figures")
-    ap.add_argument("--micro", type=int, default=1,
-                    help="micro-batches of B samples per shard visit (1 = the workload as BASELINE states it)")
-    ap.add_argument("--extra-micro", type=int, default=4,
-                    help="also report spill-mode throughput with this many micro-batches per visit (0 = skip)")
+    ap.add_argument("--layers", type=int, default=0, help="cut the model depth of the headline workload (reported)")
+    ap.add_argument("--models", type=int, default=0, help="number of models of the headline workload (reported)")
+    ap.add_argument("--micro", type=int, default=1, help="micro-batches of B samples per shard visit (1 = as stated)")
+    ap.add_argument("--graphs", action="store_true", help="replay block-shard visits as HIP graphs")
+    ap.add_argument("--ckpt-spill", action="store_true", help="boundary activations travel through host DRAM too")
+    ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
+    ap.add_argument("--prefetch-depth", type=int, default=0, help="tasks ahead that shards are promoted for (0 = as far as buffers allow)")
+    ap.add_argument("--stage-threads", type=int, default=0, help="host threads per direction of the staging tier (0 = 3)")
+    ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups of the write-back copy kernel (0 = by tokens per visit)")
+    ap.add_argument("--slots", type=int, default=0, help="shard buffers of the headline workload (0 = as BASELINE states)")
     args = ap.parse_args()
-    global SPILL_SLOTS, EXTRA_FLAGS, LANES, TRACE_OVERLAP
-    TRACE_OVERLAP = not args.no_overlap_trace
-    SPILL_SLOTS = args.slots
-    LANES = args.lanes
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the method shards over host DRAM, not over GPUs); "
               "use --gpus 1", file=sys.stderr)
@@ -232,116 +462,63 @@ def main():
     if args.large_gemm_only:
         print(json.dumps({"block_gemm_large_shapes": block_gemm_large_shapes(H, torch)}))
         return
-    if args.d2h_memcpy:
-        EXTRA_FLAGS |= H.FLAG_D2H_MEMCPY
-    if args.graphs:
-        EXTRA_FLAGS |= H.FLAG_GRAPHS
-    if args.ckpt_spill:
-        EXTRA_FLAGS |= H.FLAG_CKPT_SPILL
-    cfg = dict(SI.CONFIGS[args.config])
-    if args.micro > 1:
-        cfg["n_micro"] = args.micro
-    if args.layers:
-        cfg["L"] = args.layers
-    if args.models:
-        cfg["n_models"] = args.models
-        cfg["lrs"] = (cfg["lrs"] * args.models)[:args.models]
-    n_models = cfg["n_models"]
-    tokens_per_step = n_models * args.micro * cfg["B"] * cfg["T"]
-
-    main_run = measure(cfg, n_models, args.mode, args.steps, args.warmup, False, R, H, torch)
-    value = tokens_per_step * args.steps / main_run["seconds"]
-    out = {
-        "metric": "training tokens/sec (all models, 1 MI355X)", "value": round(value, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(1e3 * main_run["seconds"] / args.steps, 3),
-        "host_enqueue_ms_per_step": round(1e3 * main_run["enqueue_seconds"] / args.steps, 3), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: {n_models} GPT-2-shaped models ({cfg['L']}L d{cfg['d']} H{cfg['H']} "
-                               f"F{cfg['F']} V{cfg['V']}), B{cfg['B']} T{cfg['T']}, {cfg['k']}-layer shards alternated by "
-                               "Sharded-LRTF, bf16 MFMA + fp32 master/Adam, seeded N(0,0.02) weights, uniform tokens"
-                               + (" [depth / model count reduced on the command line]" if args.layers or args.models else ""),
-                   "mode": args.mode, "shard_buffers": main_run["n_slots"], "compute_lanes": args.lanes, "hip_graphs": args.graphs, "checkpoints_through_host": args.ckpt_spill,
-                   "micro_batches_per_visit": args.micro, "tokens_per_step": tokens_per_step},
-        "link": {"h2d_GB_per_step": round(main_run["h2d"] / args.steps / 1e9, 3),
-                 "d2h_GB_per_step": round(main_run["d2h"] / args.steps / 1e9, 3),
-                 "h2d_GBps_over_wall": round(main_run["h2d"] / main_run["seconds"] / 1e9, 2),
-                 "d2h_GBps_over_wall": round(main_run["d2h"] / main_run["seconds"] / 1e9, 2),
-                 # what bounds `value` in spill mode: both directions of the host link together took 87.7 GB/s on this
-                 # hardware (1 GB copies, SDMA in next to the copy kernel out; each direction alone 57.6 / 54.7 GB/s)
-                 "both_directions_GBps_over_wall": round((main_run["h2d"] + main_run["d2h"]) / main_run["seconds"] / 1e9, 2),
-                 "both_directions_GBps_measured_cap": LINK_CAP_GBPS,
-                 "frac_of_link_cap": round((main_run["h2d"] + main_run["d2h"]) / main_run["seconds"] / 1e9 / LINK_CAP_GBPS, 3)},
-        "final_losses": [round(x, 4) for x in main_run["losses"]],
-    }
-    if main_run["overlap"]:
-        out["overlap"] = overlap_report(main_run, args.steps)
-    if not args.no_extra:
-        other = "resident" if args.mode == "spill" else "spill"
-        o = measure(cfg, n_models, other, args.steps, args.warmup, False, R, H, torch, pilot=True)
-        n_sh = cfg["L"] // cfg["k"] + 2
-        out["pilot_costs_us"] = {"forward": [round(x / 1e3, 1) for x in o["pilot_ns"][:n_sh]],
-                                 "backward_with_adam": [round(x / 1e3, 1) for x in o["pilot_ns"][n_sh:]],
-                                 "shards": "EMBED, block shards 1..S, HEAD; model 0, each task alone on the device"}
-        fp = [H.hydra_shard_footprint(H.model_desc(cfg, 1e-4), n) for n in range(0, cfg["L"] + 1)]
-        out["partitioner"] = {"footprint_MB_by_layers_in_shard": [round(x / 1e6, 1) for x in fp[1:]],
-                              "embed_head_MB": round(fp[0] / 1e6, 1),
-                              "cuts_at_bound_of_2_layer_shard": H.hydra_partition(H.model_desc(cfg, 1e-4), max(fp[2], fp[0]))[0]}
-        out[other] = {"value": round(tokens_per_step * args.steps / o["seconds"], 1), "unit": "tokens/s",
-                      "ms_per_step": round(1e3 * o["seconds"] / args.steps, 3),
-                      "host_enqueue_ms_per_step": round(1e3 * o["enqueue_seconds"] / args.steps, 3),
-                      "shard_buffers": o["n_slots"]}
-        if args.extra_micro > 1 and args.micro == 1:
-            # same models, shards and buffers, but every shard visit runs several micro-batches while the shard is
-            # resident: the state traffic per step is unchanged and serves that many times the tokens
-            steps_m = max(2, args.steps // 2)
-            for nm in (args.extra_micro, 2 * args.extra_micro):
-                mc = dict(cfg, n_micro=nm)
-                o = measure(mc, n_models, "spill", steps_m, 1, False, R, H, torch)
-                out[f"spill_micro{nm}"] = {
-                    "value": round(tokens_per_step * nm * steps_m / o["seconds"], 1), "unit": "tokens/s",
-                    "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * nm,
-                    "h2d_GB_per_step": round(o["h2d"] / steps_m / 1e9, 3), "shard_buffers": o["n_slots"],
-                    "overlap": overlap_report(o, steps_m)}
-            # the same 4x tokens per shard visit as ONE micro-batch of 4x the samples: activation memory grows
-            # fourfold (no issue on a 288 GB part), the GEMMs become four times larger and fill the chip
-            bc = dict(cfg, B=cfg["B"] * args.extra_micro)
-            o = measure(bc, n_models, "spill", steps_m, 1, False, R, H, torch)
-            out[f"spill_batch_x{args.extra_micro}"] = {
-                "value": round(tokens_per_step * args.extra_micro * steps_m / o["seconds"], 1), "unit": "tokens/s",
-                "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens_per_step * args.extra_micro,
-                "batch": bc["B"], "shard_buffers": o["n_slots"], "overlap": overlap_report(o, steps_m)}
-        # per-kernel HIP-event timing over the same steps (resident buffers so that copies do not perturb kernels)
-        t = measure(cfg, n_models, "resident", args.steps, args.warmup, True, R, H, torch)
-        ks = sorted(t["kernels"], key=lambda k: -k["ms"])
-        total_ms = sum(k["ms"] for k in ks)
-        dom = ks[0]
-        if dom["flops"] > 0:
-            ach = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-            out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                               "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4),
-                               "traffic": measured_traffic(args.config, dom["name"]),
-                               "kernel": dom["name"], "launches": dom["launches"],
-                               "avg_us": round(1e3 * dom["ms"] / dom["launches"], 2)}
-        else:
-            ach = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
-            out["roofline"] = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                               "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(args.config, dom["name"]),
-                               "kernel": dom["name"],
-                               "launches": dom["launches"], "avg_us": round(1e3 * dom["ms"] / dom["launches"], 2)}
-        out["kernels"] = [
-            {"name": k["name"], "launches": k["launches"], "ms_per_step": round(k["ms"] / args.steps, 4),
-             "share": round(k["ms"] / total_ms, 4),
-             **({"TFLOPs": round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 1)} if k["flops"] > 0 else
-                {"GBps": round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1)})}
-            for k in ks]
-        gemm = [k for k in ks if k["flops"] > 0]
-        out["gemm_aggregate"] = {"TFLOPs": round(sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12, 1),
-                                 "frac_of_mfma_peak": round(sum(k["flops"] for k in gemm) / (sum(k["ms"] for k in gemm) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                                 "kernel_ms_per_step": round(total_ms / args.steps, 3)}
+    flags = (H.FLAG_GRAPHS if args.graphs else 0) | (H.FLAG_CKPT_SPILL if args.ckpt_spill else 0) | \
+            (H.FLAG_D2H_MEMCPY if args.d2h_memcpy else 0)
+    SESSION_KW.update(prefetch_depth=args.prefetch_depth, stage_threads=args.stage_threads, copy_blocks=args.copy_blocks)
+    avail = mem_available_gb()
+    name = args.config
+    fallback = None
+    if name == "auto":
+        # config 5 keeps 145 GB of state in host DRAM (plus what the process itself needs)
+        name = "gpt6b" if avail >= 175 else "gpt2xl"
+        if name != "gpt6b":
+            fallback = f"host has {avail:.0f} GB available: config 5's 145 GB of state does not fit, config 4 measured instead"
+    if args.slots:
+        WORKLOADS[name] = dict(WORKLOADS[name], max_slots=args.slots, cap=0, what=f"{args.slots} shard buffers [command line]")
+    main_out, cfg, host = bench_workload(name, args.steps, args.warmup, 0 if args.no_kernel_pass else 2, R, H, torch,
+                                         n_models=args.models, layers=args.layers, lanes=args.lanes, extra_flags=flags,
+                                         micro=args.micro)
+    out = {"metric": "training tokens/sec (all models, 1 MI355X)", "value": main_out["value"], "unit": "tokens/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_out["ms_per_step"],
+           "host_enqueue_ms_per_step": main_out["host_enqueue_ms_per_step"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": main_out["workload"], "mode": "spill", "shard_buffers": main_out["shard_buffers"],
+                      "compute_lanes": args.lanes, "hip_graphs": args.graphs, "checkpoints_through_host": args.ckpt_spill,
+                      "micro_batches_per_visit": args.micro, "tokens_per_step": main_out["tokens_per_step"],
+                      "host_memory_available_GB": round(avail, 1), "state_page_locked": main_out["state_page_locked"]},
+           "link": main_out["link"], "overlap": main_out["overlap"], "final_losses": main_out["final_losses"]}
+    if fallback:
+        out["config"]["fallback"] = fallback
+    if "kernel_pass" in main_out:
+        kp = main_out["kernel_pass"]
+        out["roofline"] = kp["roofline"]
+        out["roofline"]["traffic"] = measured_traffic(name, kp["roofline"]["kernel"])
+        if "roofline_mfma" in kp:
+            out["roofline_mfma"] = kp["roofline_mfma"]
+            out["roofline_mfma"]["traffic"] = measured_traffic(name, kp["roofline_mfma"]["kernel"])
+            out["gemm_aggregate"] = kp["gemm_aggregate"]
+        out["kernels_alone"] = main_out["kernels_alone"]
+        out["kernel_pass"] = {"what": "the same steps in the same mode with every kernel launch bracketed by HIP events",
+                              "steps": kp["steps"], "ms_per_step": kp["ms_per_step"], "overlap": kp["overlap"]}
+        out["kernels"] = kp["kernels"]
+    cpu_cfg = cfg
+    host.free()
+    del host
+    if not args.only:
+        for other, (st, wu) in {"gpt2xl": (3, 1), "gpt2m": (5, 1), "gpt2s": (16, 2)}.items():
+            if other == name:
+                continue
+            o, ocfg, ohost = bench_workload(other, st, wu, 0 if args.no_kernel_pass else 2, R, H, torch, lanes=args.lanes)
+            if "kernel_pass" in o:
+                o["kernel_pass"]["kernels"] = o["kernel_pass"]["kernels"][:8]
+            if other == "gpt2s":
+                o.update(gpt2s_extras(ocfg, ohost, R, H, torch, st))
+            ohost.free()
+            del ohost
+            out[other] = o
         out["block_gemm_large_shapes"] = block_gemm_large_shapes(H, torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg)
+        out["cpu_baseline"] = cpu_baseline(cpu_cfg)
     print(json.dumps(out))
 
 

@@ -117,11 +117,12 @@ typedef struct {
   int32_t compute_lanes;           /* 0 or 1: every task on compute_stream.  n > 1: model i runs on lane i % n, so  */
                                    /* that tasks of different models overlap on the device; lane 0 is compute_stream */
   int32_t copy_blocks;             /* workgroups of the write-back copy kernel; 0 = chosen from the tokens a shard  */
-                                   /* visit works on (48 down to 8: fewer the more compute there is to disturb)     */
+                                   /* visit works on and the shard's size (48 down to 8: fewer the more compute     */
+                                   /* there is to disturb and the longer promote and write-back run side by side)   */
   void *lane_streams[HYDRA_MAX_LANES - 1]; /* caller's streams (default priority) of lanes 1 .. compute_lanes - 1;  */
                                    /* distinct non-null handles (ignored with HYDRA_FLAG_DRY_RUN)                   */
-  int32_t prefetch_depth;          /* how many tasks ahead hydra_sched_run promotes shards for; 0 = as far as free   */
-                                   /* shard buffers allow (at least one: the paper's double buffering, Section 2.3)  */
+  int32_t prefetch_depth;          /* how many tasks ahead hydra_sched_run promotes shards for; 0 = one (the paper's  */
+                                   /* double buffering, Section 2.3); more only helps while buffers can be freed     */
   int32_t stage_threads;           /* host threads per direction that copy between ordinary memory and the staging   */
                                    /* area; 0 = 3                                                                     */
   void *stage;                     /* page-locked host memory (256-byte aligned, >= 16 MiB), or NULL.  With it, a     */
@@ -299,8 +300,8 @@ hydra_status hydra_sched_destroy(hydra_sched *s);
 /* Next decision; returns 1 (not an error) when all tasks have been handed out. */
 hydra_status hydra_sched_next(hydra_sched *s, hydra_task *out);
 /* Runs every remaining task: the shards of the following tasks are promoted
- * before task n is enqueued - as many tasks ahead as buffers can be freed without
- * touching a shard an earlier task needs, at most hydra_init_desc.prefetch_depth -
+ * before task n is enqueued - hydra_init_desc.prefetch_depth tasks ahead (default one),
+ * as long as buffers can be freed without touching a shard an earlier task needs -
  * and a shard's updated state is written back right after its Adam step.
  * tokens[m] / targets[m]: host int32 [n_minibatches[m], n_micro*B, T].  trace (may be
  * NULL) receives the executed order. Returns after everything is enqueued

@@ -43,7 +43,7 @@ hydra_status copy_d2h(hydra_ctx *ctx, void *host_dst, void *host_dst_mapped, con
   if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)
     HYDRA_HIP(ctx, hipMemcpyAsync(host_dst, src, bytes, hipMemcpyDeviceToHost, ctx->s_d2h));
   else
-    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, tokens_per_visit, ctx->init.copy_blocks, ctx->s_d2h));
+    HYDRA_HIP(ctx, launch_copy_to_host(host_dst_mapped, src, bytes, tokens_per_visit, ctx->init.copy_blocks, bytes, ctx->s_d2h));
   return HYDRA_OK;
 }
 
@@ -110,7 +110,7 @@ static hydra_status run_d2h_plan(hydra_ctx *ctx, const CopyPlan &p) {
     } else if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY) {
       PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes, hipMemcpyDeviceToHost, s));
     } else {
-      PLAN_HIP(launch_copy_to_host(g.dst_mapped, g.src, g.bytes, p.tokens_per_visit, ctx->init.copy_blocks, s));
+      PLAN_HIP(launch_copy_to_host(g.dst_mapped, g.src, g.bytes, p.tokens_per_visit, ctx->init.copy_blocks, g.bytes, s));
     }
   }
   trace_end(ctx, tr, s, p.trace_bytes);

@@ -166,10 +166,11 @@ hipError_t launch_cast_act(int dtype, const float *in, int64_t ld_in, void *out,
 hipError_t launch_stream_marker(hipStream_t s);  // empty kernel
 hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t n, hipStream_t s);
 // device -> page-locked host memory through its device-side mapping (both 16-byte aligned); blocks workgroups, or
-// (blocks <= 0) as many as copy_to_host_blocks gives for the tokens a shard visit works on
+// (blocks <= 0) as many as copy_to_host_blocks gives for the tokens a shard visit works on and the size of the state
+// array the copy is (a piece of)
 hipError_t launch_copy_to_host(void *dst_mapped, const void *src, size_t bytes, int64_t tokens_per_visit, int blocks,
-                               hipStream_t s);
-int copy_to_host_blocks(int64_t tokens_per_visit);
+                               size_t array_bytes, hipStream_t s);
+int copy_to_host_blocks(int64_t tokens_per_visit, size_t array_bytes);
 // the same kernel in either direction (one side is the device-side mapping of page-locked host memory), grid capped
 hipError_t launch_copy_link(void *dst, const void *src, size_t bytes, int max_blocks, hipStream_t s);
 

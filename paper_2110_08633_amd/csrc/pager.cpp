@@ -293,7 +293,7 @@ hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t byt
         e = hipMemcpyAsync(r.host + (size_t)k * r.chunk, (const char *)src_dev + off, n, hipMemcpyDeviceToHost, s);
       else
         e = launch_copy_to_host(r.mapped + (size_t)k * r.chunk, (const char *)src_dev + off, n, tokens_per_visit,
-                                ctx->init.copy_blocks, s);
+                                ctx->init.copy_blocks, bytes, s);
       if (e != hipSuccess) return HYDRA_E_HIP;
       if (hipEventRecord(r.ev[k], s) != hipSuccess) return HYDRA_E_HIP;
       ++issued;

@@ -89,7 +89,9 @@ void prof_collect(Profiler *p, hipEvent_t base) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
       float a = 0.f;
-      if (base && hipEventElapsedTime(&a, base, r.e0) == hipSuccess && a >= 0.f) p->ivals.push_back({a, a + ms});
+      // (the write-back's copy kernel is a transfer, not compute)
+      if (base && strcmp(r.name, "copy_to_host") != 0 && hipEventElapsedTime(&a, base, r.e0) == hipSuccess && a >= 0.f)
+        p->ivals.push_back({a, a + ms});
       auto it = p->agg.find(r.name);
       if (it == p->agg.end()) {
         p->order.push_back(r.name);

@@ -189,9 +189,11 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
   for (Model *m : ctx->models) total_shards += m->sh.S + 2;
   const bool all_fit = ctx->slots.size() >= total_shards;
   int64_t done = 0;
-  // how many tasks ahead shards are promoted for: as far as buffers can be found (each prefetched shard holds one),
-  // or the caller's limit
-  const size_t depth = ctx->init.prefetch_depth > 0 ? (size_t)ctx->init.prefetch_depth : ctx->slots.size();
+  // How many tasks ahead shards are promoted for: one (the paper's double buffering) unless the caller asks for
+  // more.  Deeper prefetch measured slower with six buffers on the two-model GPT-2-small workload (100.7 ms per
+  // step one task ahead, 114 / 112 / 119 ms two / three / six ahead): promotes queue in order on one copy stream, and
+  // one that waits for its buffer's write-back holds back the promotes behind it whose buffers are free.
+  const size_t depth = ctx->init.prefetch_depth > 0 ? (size_t)ctx->init.prefetch_depth : 1;
   if (s->promoted < s->cursor) s->promoted = s->cursor;
   while (s->cursor < s->order.size()) {
     const size_t i = s->cursor;

@@ -44,6 +44,7 @@ class PinnedArray:
         p = C.c_void_p()
         e = _hip_runtime().hipHostMalloc(C.byref(p), self.nbytes, 0)
         if e != 0 or not p.value:
+            _hip_runtime().hipGetLastError()      # the failed call's error must not surface at the next HIP call
             raise MemoryError(f"hipHostMalloc of {self.nbytes} bytes failed (HIP error {e})")
         self.ptr = p.value
         if zero:
@@ -99,12 +100,13 @@ class Session:
         self._pinned.append(buf)
         return buf.array
 
-    def add_model(self, cfg, weights, lr, dtype=None, pageable=False):
-        """weights: dict name -> float32 array (names as given by hydra_model_tensor).  pageable: the model's
-        state arrays are ordinary host memory (needs a session with a staging area)."""
+    def add_model(self, cfg, weights, lr, dtype=None, pageable=False, host=None):
+        """weights: dict name -> float32 array (names as given by hydra_model_tensor), or None to leave the master
+        array as it is.  pageable: the model's state arrays are ordinary host memory (needs a session with a staging
+        area).  host: (master, m, v) arrays to use instead of allocating (they stay the caller's)."""
         desc = H.model_desc(cfg, lr, dtype)
         lay = H.hydra_model_layout(desc)
-        master, m, v = (self._host(lay.n_params, pageable=pageable) for _ in range(3))
+        master, m, v = host if host is not None else (self._host(lay.n_params, pageable=pageable) for _ in range(3))
         tensors = {}
         for i in range(lay.n_tensors):
             name, off, rows, cols, shard = H.hydra_model_tensor(desc, i)

@@ -295,11 +295,11 @@ def test_stated_workloads_dry_run_order_and_traffic(name, cap_bytes, max_slots, 
 
 
 def test_prefetch_depth_one_is_plain_double_buffering():
-    """prefetch_depth = 1: exactly one task ahead (the paper's double buffering); the default goes as far as
+    """prefetch_depth 0 / 1: one task ahead (the paper's double buffering); 3: as far as three tasks ahead while
     buffers can be freed.  Neither changes the executed order or the bytes written back."""
     cfg = SI.small_cfg(L=4, k=1)
     out = []
-    for depth in (1, 0):
+    for depth in (1, 0, 3):
         s = Session(1 << 34, max_slots=4, dry_run=True, prefetch_depth=depth)
         for m in range(2):
             s.add_model(cfg, None, 1e-3)
@@ -311,7 +311,8 @@ def test_prefetch_depth_one_is_plain_double_buffering():
         out.append((trace, st["bytes_d2h"], st["bytes_h2d"]))
         H.hydra_sched_destroy(sch)
         s.close()
-    assert out[0][0] == out[1][0] and out[0][1] == out[1][1]
+    assert out[0][0] == out[1][0] == out[2][0] and out[0][1] == out[1][1] == out[2][1]
+    assert out[0][2] == out[1][2]
 
 
 def test_init_rejects_bad_lane_and_copy_arguments():
