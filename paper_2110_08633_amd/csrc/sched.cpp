@@ -89,6 +89,7 @@ hydra_status promote(hydra_sched *s, size_t j, size_t i) {
       int victim = -1, oldest = -1;
       size_t far = 0;
       uint64_t oldest_use = ~0ull, oldest_wb = ~0ull;
+      bool oldest_recent = true;
       const size_t soon = 2 * ctx->slots.size();
       for (size_t q = 0; q < ctx->slots.size(); ++q) {
         const Slot &sl = ctx->slots[q];
@@ -99,10 +100,18 @@ hydra_status promote(hydra_sched *s, size_t j, size_t i) {
         if (nu <= j) continue;  // a task that runs before the prefetched one (or that one itself) works on it
         if (victim < 0 || nu > far) { victim = (int)q; far = nu; }
         const uint64_t wb = sl.dirty ? ~0ull - 1 : sl.wb_seq;  // a write-back not even enqueued yet comes last
-        if ((nu == (size_t)-1 || nu - i > soon) && (wb < oldest_wb || (wb == oldest_wb && sl.last_use < oldest_use))) {
-          oldest = (int)q;
-          oldest_use = sl.last_use;
-          oldest_wb = wb;
+        // a buffer that one of the last tasks (one per lane) ran on is free only when that task has finished: its
+        // old write-back says nothing (taking it made the promote wait 4 ms per step for a forward visit just enqueued)
+        const bool recent = ctx->use_counter - sl.last_use < ctx->lanes.size() && sl.last_use > 0;
+        if (nu == (size_t)-1 || nu - i > soon) {
+          const bool better = oldest < 0 || (oldest_recent && !recent) ||
+                              (oldest_recent == recent && (wb < oldest_wb || (wb == oldest_wb && sl.last_use < oldest_use)));
+          if (better) {
+            oldest = (int)q;
+            oldest_use = sl.last_use;
+            oldest_wb = wb;
+            oldest_recent = recent;
+          }
         }
       }
       if (oldest >= 0) victim = oldest;
