@@ -1097,7 +1097,16 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
                                                            int64_t n16, uint8_t *dst_tail, const uint8_t *src_tail,
                                                            int tail) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  // non-temporal stores: the data is never read back on the device, and keeping it out of the L2's way measured
+  // 1-3 % more throughput of the whole spilled step than plain stores (two-model GPT-2-small workload with 1, 4 and
+  // 8 micro-batches per visit, alternating runs on one machine)
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+    const uint4 v = src[i];
+    __builtin_nontemporal_store(v.x, &dst[i].x);
+    __builtin_nontemporal_store(v.y, &dst[i].y);
+    __builtin_nontemporal_store(v.z, &dst[i].z);
+    __builtin_nontemporal_store(v.w, &dst[i].w);
+  }
   if (blockIdx.x == 0 && threadIdx.x < tail) dst_tail[threadIdx.x] = src_tail[threadIdx.x];
 }
 

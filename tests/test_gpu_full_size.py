@@ -121,3 +121,72 @@ def test_gpt6b_models_on_two_shard_buffers(rt, lanes):
         assert_same_state(states[m], final, f"gpt6b model {m}: ")
         assert losses[m] == loss
         assert abs(loss - np.log(cfg["V"])) < 1.0
+
+
+def test_gpt6b_as_stated_full_depth_properties(rt):
+    """BASELINE config 5 exactly as stated and as bench.py times it: two 6.06 B-parameter models, 28 layers in
+    fourteen 2-layer shards, two shard buffers, two lanes, all 145 GB of state in host memory (ordinary memory
+    through the staging ring where the driver will not page-lock that much).  One minibatch of each.  The oracle
+    cannot run this size inside a test, so what is checked is what holds at any size: the executed order equals the
+    oracle's Sharded-LRTF; every shard's state crosses the link as often as the method says; the losses are those
+    of a random model (ln V); the embedding forward is exact on sampled rows; and on windows at the start, middle
+    and end of every shard of both models the written-back state is a first Adam step of ONE gradient g per element:
+    m = (1-b1) g, v = (1-b2) g^2 (so v = 0.1 m^2) and w - w0 = -lr g / (|g| + eps), to fp32 rounding."""
+    import bench as B
+    H, R = rt
+    cfg = dict(SI.CONFIGS["gpt6b"])
+    n = cfg["n_models"]
+    if B.mem_available_gb() < 175:
+        pytest.skip("needs 145 GB of host memory for the models' state")
+    host = B.HostState(cfg, n, R, H)
+    desc = H.model_desc(cfg, 1e-4)
+    lay = H.hydra_model_layout(desc)
+    shard_rng = [H.hydra_shard_range(desc, s) for s in range(lay.n_shards)]
+    win = 1 << 18
+    windows = []
+    for off, cnt in shard_rng:
+        for a in (off, off + cnt // 2, off + cnt - win):
+            windows.append((max(off, min(a, off + cnt - win)), win))
+    w0 = [[host.arrays[m][0][a:a + k].copy() for a, k in windows] for m in range(n)]
+    sess, recs = B.make_session(cfg, n, host, B.WORKLOADS["gpt6b"], 0, 2, R, H)
+    tables = [costs_of(cfg)] * n
+    want, _, _ = oracle_order([cfg] * n, [1] * n, tables)
+    batches = [SI.make_batch(cfg, SI.batch_seed(cfg, m, 0)) for m in range(n)]
+    sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], [1] * n, tables)
+    trace, done = H.hydra_sched_run(sch, [b[0][None] for b in batches], [b[1][None] for b in batches], sess.ctx,
+                                    trace_cap=4096)
+    sess.flush()
+    st = H.hydra_get_stats(sess.ctx)
+    assert trace == want and done == n * 2 * lay.n_shards
+    assert st["n_slots"] == 2
+    assert st["bytes_d2h"] == n * 12 * lay.n_params
+    # 4 B per parameter for the forward visit, 12 for the backward visit; only the head (last forward, first
+    # backward shard) and the embedding can still be resident when their next visit comes
+    assert n * lay.n_params * 16 - n * 4 * (shard_rng[0][1] + shard_rng[-1][1]) <= st["bytes_h2d"] <= n * lay.n_params * 16
+    for m in range(n):
+        loss = H.hydra_get_loss(sess.ctx, recs[m]["id"])
+        assert abs(loss - np.log(cfg["V"])) < 1.5, loss
+        lr = cfg["lrs"][m]
+        master, am, av = host.arrays[m]
+        for (a, k), before in zip(windows, w0[m]):
+            mm = am[a:a + k].astype(np.float64)
+            vv = av[a:a + k].astype(np.float64)
+            ww = master[a:a + k].astype(np.float64)
+            assert np.isfinite(mm).all() and np.isfinite(vv).all() and np.isfinite(ww).all()
+            g = mm / 0.1
+            assert (np.abs(vv - 0.001 * g * g) <= 1e-5 * (0.001 * g * g) + 1e-37).all(), (m, a)
+            step = -lr * g / (np.abs(g) + 1e-8)
+            assert (np.abs((ww - before.astype(np.float64)) - step) <= 1e-3 * lr + 1.5e-7 * np.abs(ww)).all(), (m, a)
+        # token ids 0..63 (the rows of wte inside the first window): a row moves if and only if its id is in the batch
+        d = cfg["d"]
+        in_batch = set(np.unique(batches[m][0]).tolist())
+        rows0 = w0[m][0][: 64 * d].reshape(64, d)
+        rows1 = master[: 64 * d].reshape(64, d)
+        for r in range(64):
+            if r in in_batch:
+                assert (rows1[r] != rows0[r]).any(), (m, r)
+            else:
+                assert (rows1[r] == rows0[r]).all() and (am[r * d:(r + 1) * d] == 0).all(), (m, r)
+    H.hydra_sched_destroy(sch)
+    sess.close()
+    host.free()
