@@ -34,8 +34,12 @@ struct GemmArgs {
 // XCDs, each with its own L2) is a block of grp tile rows by a few tile columns: every XCD then fetches grp row
 // panels of A and those few column panels of B once.  grp minimises the operand rows + columns such a block
 // spans; a fixed 8 made the XCDs of an N = 768 product fetch 60 MB for 17 MB of operands, 4 rows give 44 MB.
-static int xcd_group_rows(int tiles_m, int tiles_n, int bm, int bn) {
-  const long per = ((long)tiles_m * tiles_n + 7) / 8;  // tiles per XCD
+// What shares an L2 in time is the set of tiles in flight on the XCD (32 CUs x blocks per CU), not its whole run:
+// a launch of several rounds is sized for that set, walked column by column so that the row panels stay (the
+// 4096 x 16384 x 1024 weight gradient: 16 rows per group 588, 8 rows 605 TFLOP/s; 16384 x 4096: 527 -> 604).
+static int xcd_group_rows(int tiles_m, int tiles_n, int bm, int bn, int inflight_per_xcd = 64) {
+  long per = ((long)tiles_m * tiles_n + 7) / 8;  // tiles per XCD
+  if (per > inflight_per_xcd) per = inflight_per_xcd;
   int best = 1;
   long best_cost = -1;
   for (int g = 1; g <= 16 && g <= tiles_m; ++g) {
@@ -945,7 +949,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   do {                                                                                          \
     a.tiles_m = (d.M + BM_ - 1) / BM_;                                                          \
     a.tiles_n = (d.N + BN_ - 1) / BN_;                                                          \
-    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_);                                     \
+    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_, 32 * OCC_);                          \
     static const char *names[4] = {NAME_ "_nt", NAME_ "_nn", NAME_ "_tt", NAME_ "_tn"};         \
     ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
     return launch_bf16_big<BM_, BN_, BK_, S_, OCC_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s);   \
@@ -954,7 +958,7 @@ hipError_t launch_gemm(const GemmDesc &d, hipStream_t s) {
   do {                                                                                          \
     a.tiles_m = (d.M + BM_ - 1) / BM_;                                                          \
     a.tiles_n = (d.N + BN_ - 1) / BN_;                                                          \
-    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_);                                     \
+    a.grp = xcd_group_rows(a.tiles_m, a.tiles_n, BM_, BN_, 32 * OCC_);                          \
     static const char *names[4] = {NAME_ "_nt", NAME_ "_nn", NAME_ "_tt", NAME_ "_tn"};         \
     ProfScope ps(names[d.ta * 2 + d.tb], s, gemm_flops(d), 0);                                  \
     return launch_bf16_big<BM_, BN_, BK_, S_, OCC_, KW_, WGN_>(a, d.ta, d.tb, a.tiles_m * a.tiles_n, s); \
