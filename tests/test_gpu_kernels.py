@@ -230,9 +230,9 @@ LARGE_NT = [(1024, 12288, 1024), (1000, 12200, 512), (2048, 4096, 1024), (2000, 
 
 
 @pytest.mark.parametrize("M,N,K", LARGE_NT)
-def test_gemm_large_tiles_on_sampled_rows(H, M, N, K):
-    """Full-size products against the oracle on sampled rows of C (all columns): the rows at tile boundaries and
-    a random set; the fp32 and the bf16 output, bias and residual included."""
+def test_gemm_large_tiles_every_element(H, M, N, K):
+    """Full-size products against the oracle's float64 product, every element of C: the fp32 and the bf16 output,
+    scale, bias and residual included."""
     rng = np.random.default_rng(M + 3 * N + 7 * K)
     A = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
     Bt = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
@@ -243,18 +243,46 @@ def test_gemm_large_tiles_on_sampled_rows(H, M, N, K):
     H.hydra_op_gemm(1, 0, 0, M, N, K, 0.25, dev(A, torch.bfloat16), K, dev(Bt, torch.bfloat16), K, dev(bias),
                     dev(resid), out, out_act, N)
     torch.cuda.synchronize()
-    rows = {0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 257, M // 2, M - 129, M - 33, M - 2, M - 1}
-    rows |= set(int(r) for r in rng.integers(0, M, 48))
-    rows = np.array(sorted(r for r in rows if 0 <= r < M))
-    ref = 0.25 * D.linear_fwd(A[rows].astype(np.float64), Bt.T.astype(np.float64)) + bias + resid[rows]
-    assert_close(out[rows].cpu().numpy(), ref, 1e-5, "large gemm f32 out")
-    assert_close(out_act[rows].float().cpu().numpy(), ref, 8e-3, "large gemm bf16 out")
-    # every element was written exactly once with a finite value: compare the checksum of all rows in fp64
-    full = out.double().sum(dim=1).cpu().numpy()
-    ref_sum = 0.25 * (A.astype(np.float64) @ Bt.astype(np.float64).sum(axis=0)) + bias.astype(np.float64).sum() \
-        + resid.astype(np.float64).sum(axis=1)
-    scale = np.sqrt(N) * np.abs(ref).max()
-    assert np.abs(full - ref_sum).max() <= 1e-4 * scale, "row checksums"
+    ref = 0.25 * D.linear_fwd(A.astype(np.float64), Bt.T.astype(np.float64)) + bias + resid
+    got = out.cpu().numpy().astype(np.float64)
+    # element by element: fp32 accumulation of K products of magnitude ~1 and one rounding of the result
+    tol = 4e-6 * np.sqrt(K) + 2e-7 * np.abs(ref)
+    bad = np.abs(got - ref) > tol
+    assert not bad.any(), f"{bad.sum()} elements of the fp32 result differ (worst {np.abs(got - ref).max():.3e})"
+    got16 = out_act.float().cpu().numpy().astype(np.float64)
+    bad = np.abs(got16 - ref) > tol + 2.0 ** -8 * np.abs(ref)          # one rounding to bf16 on top
+    assert not bad.any(), f"{bad.sum()} elements of the bf16 result differ"
+
+
+# weight-gradient shaped products (both operands stored with the contraction index strided, fp32 result, with and
+# without accumulation into the result): several rounds of tiles, so that the tile groups an XCD walks wrap; ragged
+# edges; the vocabulary-sized one of the LM head
+LARGE_TN = [(4096, 8192, 1024), (1600, 6400, 1024), (1000, 3000, 520), (768, 50257, 2048), (16384, 1024, 256)]
+
+
+@pytest.mark.parametrize("M,N,K", LARGE_TN)
+def test_weight_gradient_products_every_element(H, M, N, K):
+    rng = np.random.default_rng(5 * M + N + 11 * K)
+    Kp, Np = (K + 7) // 8 * 8, (N + 7) // 8 * 8        # leading dimensions must be multiples of 8 elements
+    A = bf16_round(rng.standard_normal((K, M)).astype(np.float32))      # x^T is wanted: A is stored [K, M]
+    B = np.zeros((K, Np), np.float32)
+    B[:, :N] = bf16_round(rng.standard_normal((K, N)).astype(np.float32))
+    prev = rng.standard_normal((M, N)).astype(np.float32)
+    ref = A.astype(np.float64).T @ B[:, :N].astype(np.float64)
+    # Each fp32 addition into a running sum s_k of k unit-variance products rounds by up to 2^-24 |s_k| with |s_k| ~
+    # sqrt(k), so the error of one element is a sum of K such terms: rms near 1e-8 K, with a heavy tail (plain
+    # in-order fp32 summation on the CPU reaches 16 rms within 1e6 elements).  Tens of millions of elements are
+    # compared here, hence 2.5e-7 K; a dropped or doubled product (magnitude ~1) is still 1000 times outside it.
+    tol = 2.5e-7 * K
+    for acc in (False, True):
+        out = torch.from_numpy(prev.copy()).cuda()
+        H.hydra_op_gemm(1, 1, 1, M, N, K, 1.0, dev(A, torch.bfloat16), M, dev(B, torch.bfloat16), Np, None,
+                        out if acc else None, out, None, N)
+        torch.cuda.synchronize()
+        want = ref + prev if acc else ref
+        got = out.cpu().numpy().astype(np.float64)
+        bad = np.abs(got - want) > tol + 2e-7 * np.abs(want)
+        assert not bad.any(), f"acc={acc}: {bad.sum()} elements differ (worst {np.abs(got - want).max():.3e})"
 
 
 @pytest.mark.parametrize("M,N,K", [(2048, 4096, 1024), (1024, 4096, 4096), (2048, 2304, 768)])
