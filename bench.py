@@ -82,6 +82,12 @@ class HostState:
             self.free()
             self.pageable = True
             self.arrays = [tuple(np.zeros(lay.n_params, np.float32) for _ in range(3)) for _ in range(n_models)]
+        # The library's bf16 rounding of the master, which forward promotes of block shards then carry: given with
+        # state in ordinary memory, where the staging tier's host threads produce it for free (+7 % and +9 % on the
+        # two large workloads); page-locked state would send it over the link with every write-back, which measured
+        # neutral (-0.7 % / +1.8 % on the two small workloads).
+        self.work_copy = WORK_COPY and self.pageable and cfg["dtype"] == "bf16"
+        self.work = [np.zeros(lay.n_params, np.uint16) if self.work_copy else False for _ in range(n_models)]
         tensors = [H.hydra_model_tensor(desc, i) for i in range(lay.n_tensors)]
         for m in range(n_models):
             master, am, av = self.arrays[m]
@@ -102,12 +108,13 @@ class HostState:
                 av[:] = 0.0
 
     def free(self):
-        self.arrays = []
+        self.arrays, self.work = [], []
         for b in self.pinned_bufs:
             b.free()
         self.pinned_bufs = []
 
 
+WORK_COPY = True    # --no-work-copy: forward promotes carry the fp32 master
 SESSION_KW = {}     # prefetch depth / staging threads / copy workgroups from the command line (experiments)
 
 
@@ -120,7 +127,8 @@ def make_session(cfg, n_models, host, wl, flags, lanes, R, H, mode="spill"):
     arena_slots = slots if slots else max(1, cap // (20 * max_shard_elems(cfg, H))) + 1
     sess = R.Session(R.arena_bytes_for([cfg] * n_models, arena_slots, lanes=lanes), flags=flags, max_slots=slots,
                      shard_buffer_cap_bytes=cap, lanes=lanes, stage_bytes=STAGE_BYTES if host.pageable else 0, **SESSION_KW)
-    recs = [sess.add_model(cfg, None, cfg["lrs"][m], host=host.arrays[m], pageable=host.pageable) for m in range(n_models)]
+    recs = [sess.add_model(cfg, None, cfg["lrs"][m], host=host.arrays[m], pageable=host.pageable, work_copy=host.work[m])
+            for m in range(n_models)]
     return sess, recs
 
 
@@ -310,7 +318,7 @@ def bench_workload(name, steps, warmup, timing_steps, R, H, torch, n_models=0, l
            "value": round(tokens * steps / run["seconds"], 1), "unit": "tokens/s", "steps": steps, "warmup": warmup,
            "ms_per_step": round(1e3 * run["seconds"] / steps, 3), "tokens_per_step": tokens,
            "host_enqueue_ms_per_step": round(1e3 * run["enqueue_seconds"] / steps, 3),
-           "shard_buffers": run["n_slots"], "compute_lanes": lanes, "state_page_locked": not host.pageable,
+           "shard_buffers": run["n_slots"], "compute_lanes": lanes, "state_page_locked": not host.pageable, "work_copy": host.work_copy,
            "link": link_report(run), "overlap": overlap_report(run), "final_losses": [round(x, 4) for x in run["losses"]]}
     if timing_steps:
         t = measure(cfg, n, host, wl, timing_steps, 1, R, H, torch, timing=True, lanes=lanes, extra_flags=extra_flags)
@@ -429,6 +437,7 @@ def gpt2s_extras(cfg, host, R, H, torch, steps):
 
 
 def main():
+    global WORK_COPY
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
@@ -447,8 +456,10 @@ def main():
     ap.add_argument("--graphs", action="store_true", help="replay block-shard visits as HIP graphs")
     ap.add_argument("--ckpt-spill", action="store_true", help="boundary activations travel through host DRAM too")
     ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
+    ap.add_argument("--no-work-copy", action="store_true",
+                    help="no bf16 copy of the master on the host: forward promotes carry the fp32 master")
     ap.add_argument("--prefetch-depth", type=int, default=0, help="tasks ahead that shards are promoted for (0 = as far as buffers allow)")
-    ap.add_argument("--stage-threads", type=int, default=0, help="host threads per direction of the staging tier (0 = 3)")
+    ap.add_argument("--stage-threads", type=int, default=0, help="host threads per direction of the staging tier (0 = 5)")
     ap.add_argument("--copy-blocks", type=int, default=0, help="workgroups of the write-back copy kernel (0 = by tokens per visit)")
     ap.add_argument("--slots", type=int, default=0, help="shard buffers of the headline workload (0 = as BASELINE states)")
     args = ap.parse_args()
@@ -464,6 +475,7 @@ def main():
         return
     flags = (H.FLAG_GRAPHS if args.graphs else 0) | (H.FLAG_CKPT_SPILL if args.ckpt_spill else 0) | \
             (H.FLAG_D2H_MEMCPY if args.d2h_memcpy else 0)
+    WORK_COPY = not args.no_work_copy
     SESSION_KW.update(prefetch_depth=args.prefetch_depth, stage_threads=args.stage_threads, copy_blocks=args.copy_blocks)
     avail = mem_available_gb()
     name = args.config
@@ -485,7 +497,8 @@ def main():
            "config": {"workload": main_out["workload"], "mode": "spill", "shard_buffers": main_out["shard_buffers"],
                       "compute_lanes": args.lanes, "hip_graphs": args.graphs, "checkpoints_through_host": args.ckpt_spill,
                       "micro_batches_per_visit": args.micro, "tokens_per_step": main_out["tokens_per_step"],
-                      "host_memory_available_GB": round(avail, 1), "state_page_locked": main_out["state_page_locked"]},
+                      "host_memory_available_GB": round(avail, 1), "state_page_locked": main_out["state_page_locked"],
+                      "bf16_host_copy_for_forward_promotes": main_out["work_copy"]},
            "link": main_out["link"], "overlap": main_out["overlap"], "final_losses": main_out["final_losses"]}
     if fallback:
         out["config"]["fallback"] = fallback

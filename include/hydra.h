@@ -124,7 +124,7 @@ typedef struct {
   int32_t prefetch_depth;          /* how many tasks ahead hydra_sched_run promotes shards for; 0 = one (the paper's  */
                                    /* double buffering, Section 2.3); more only helps while buffers can be freed     */
   int32_t stage_threads;           /* host threads per direction that copy between ordinary memory and the staging   */
-                                   /* area; 0 = 3                                                                     */
+                                   /* area; 0 = 5                                                                     */
   void *stage;                     /* page-locked host memory (256-byte aligned, >= 16 MiB), or NULL.  With it, a     */
   uint64_t stage_bytes;            /* model's master / adam_m / adam_v may be ORDINARY (pageable) host memory: their  */
                                    /* promotes and write-backs then travel through this area chunk by chunk (host     */
@@ -157,6 +157,17 @@ typedef struct {
   float *ckpt;    /* [(S+1) * n_micro*B*T * d] fp32; only read/written with HYDRA_FLAG_CKPT_SPILL, else may be NULL */
   int32_t *batch_stage; /* [4 * n_micro*B*T] int32: staging of two minibatches' token ids and targets on their   */
                         /* way to the device; contents belong to the library while the model is registered        */
+  uint16_t *work_bf16;  /* optional (NULL: not used; ignored for dtype 0): [n_params] bf16, the master rounded to   */
+                        /* nearest-even, same layout.  Written by the library only: from master at registration   */
+                        /* and with every write-back of a block shard.  A forward visit multiplies by this         */
+                        /* rounding of the weights in any case, so with the array present the promote for a        */
+                        /* FORWARD visit of a block shard (Section 2.3) carries it (2 bytes per parameter) plus    */
+                        /* the shard's fp32 vectors instead of the whole fp32 master (4 bytes per parameter);      */
+                        /* results do not change by a bit.  Page-locked if master is (the write-back then sends    */
+                        /* the device's bf16 copy after the master); ordinary memory if master is (the staging     */
+                        /* tier's host threads then round the master as they move it out of the staging area, and  */
+                        /* nothing extra crosses the link).  The caller must not change master while the model is  */
+                        /* registered, or this copy goes stale.                                                    */
 } hydra_host_state;
 
 typedef struct {

@@ -58,6 +58,7 @@ struct CopyPlan {
     void *dst_mapped;  // write-backs into page-locked memory: the destination as the device sees it
     size_t bytes;
     int kind;          // SEG_*
+    uint16_t *rounded = nullptr;  // staged write-backs of the master: where the host threads leave its bf16 rounding
   };
   enum { SEG_PINNED = 0, SEG_PAGEABLE = 1, SEG_DEVICE = 2 };
   std::vector<hipEvent_t> waits;
@@ -105,7 +106,7 @@ static hydra_status run_d2h_plan(hydra_ctx *ctx, const CopyPlan &p) {
   const int tr = p.trace_bytes ? trace_begin(ctx, TRACE_D2H, s, p.trace_tag) : -1;
   for (const CopyPlan::Seg &g : p.segs) {
     if (g.kind == CopyPlan::SEG_PAGEABLE) {
-      const hydra_status st = pager_d2h(ctx->pager, g.dst, g.src, g.bytes, p.tokens_per_visit);
+      const hydra_status st = pager_d2h(ctx->pager, g.dst, g.src, g.bytes, p.tokens_per_visit, g.rounded);
       if (st) return st;
     } else if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY) {
       PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes, hipMemcpyDeviceToHost, s));
@@ -313,7 +314,7 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
       return fail(nullptr, HYDRA_E_INVAL, "stage_threads must be 0..16");
     }
     std::string perr;
-    ctx->pager = pager_create(ctx, desc->stage, desc->stage_bytes, desc->stage_threads > 0 ? desc->stage_threads - 1 : 2, &perr);
+    ctx->pager = pager_create(ctx, desc->stage, desc->stage_bytes, desc->stage_threads > 0 ? desc->stage_threads - 1 : 4, &perr);
     if (!ctx->pager) {
       hydra_destroy(ctx);
       return fail(nullptr, HYDRA_E_INVAL, perr);
@@ -409,6 +410,18 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
     return st;
   }
   m->dtype = desc->dtype;
+  m->fwd_bf16 = host->work_bf16 != nullptr && desc->dtype == DT_BF16;
+  if (m->fwd_bf16 && !ctx->dry) {
+    if (!m->pageable) {
+      float *dev = nullptr;
+      if ((st = mapped_pointer(ctx, host->work_bf16, "work_bf16", &dev))) {
+        delete m;
+        return st;
+      }
+      m->work_dev = (uint16_t *)dev;
+    }
+    host_round_bf16_threads(host->work_bf16, host->master, (size_t)m->sh.n_params, 8);
+  }
   const ModelShape &s = m->sh;
   const uint64_t act = (uint64_t)s.Mt * s.d * 4;  // boundary tensors hold all micro-batches
   const bool spill = (ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) != 0;
@@ -524,6 +537,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     sl = &ctx->slots[free_i];
     sl->model = model; sl->shard = shard;
     sl->has_params = sl->has_opt = sl->wb_valid = sl->wbt_valid = sl->grads_valid = sl->dirty = sl->tied_valid = false;
+    sl->has_fwd = false;
     sl->wb_seq = 0;
     m->slot_of[shard] = free_i;
     // the buffer's previous occupant must be done with it
@@ -533,20 +547,44 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
       if (sl->spill_ticket) plan.d2h_tickets.push_back(sl->spill_ticket);
     }
     sl->compute_pending = sl->spill_pending = false;
-  } else if (sl->has_params && (sl->has_opt || !(what & HYDRA_LOAD_OPT))) {
+  } else if ((sl->has_params && (sl->has_opt || !(what & HYDRA_LOAD_OPT))) || (sl->has_fwd && !(what & HYDRA_LOAD_OPT))) {
     ctx->stats.n_load_hits++;
   }
+  // a promote for a forward visit of a block shard of a model with a bf16 host copy carries that copy and the fp32
+  // vectors; every other promote the fp32 master
+  const bool fwd_only = m->fwd_bf16 && shard >= 1 && shard <= m->sh.S && !(what & HYDRA_LOAD_OPT);
+  const bool need_master = !sl->has_params && !fwd_only, need_fwd = fwd_only && !sl->has_params && !sl->has_fwd;
   // the host arrays of a shard are read only after its last write-back has landed (the buffer it was written
   // back from may be a different one)
-  if ((!sl->has_params || ((what & HYDRA_LOAD_OPT) && !sl->has_opt)) && m->wb_pending[shard]) {
+  if ((need_master || need_fwd || ((what & HYDRA_LOAD_OPT) && !sl->has_opt)) && m->wb_pending[shard]) {
     if (!ctx->dry) plan.waits.push_back(m->ev_wb[shard]);
     if (m->wb_ticket[shard]) plan.d2h_tickets.push_back(m->wb_ticket[shard]);
     m->wb_pending[shard] = 0;
   }
-  if (!sl->has_params) {
+  if (need_master) {
     plan.segs.push_back({sl->w, m->host.master + off, nullptr, (size_t)cnt * 4, host_kind});
     plan.trace_bytes += (uint64_t)cnt * 4;
-    sl->has_params = true;
+    sl->has_params = sl->has_fwd = true;
+  }
+  if (need_fwd) {
+    plan.segs.push_back({sl->wb, m->host.work_bf16 + off, nullptr, (size_t)cnt * 2, host_kind});
+    plan.trace_bytes += (uint64_t)cnt * 2;
+    // the vectors of a block lie in four runs between its matrices (the last one runs on into the next block's first)
+    const BlockOffsets &o = m->sh.bo;
+    const int64_t d = m->sh.d, F = m->sh.F;
+    auto run = [&](int64_t at, int64_t n) {
+      plan.segs.push_back({sl->w + at, m->host.master + off + at, nullptr, (size_t)n * 4, host_kind});
+      plan.trace_bytes += (uint64_t)n * 4;
+    };
+    for (int j = 0; j < m->sh.k; ++j) {
+      const int64_t base = (int64_t)j * o.size;
+      if (j == 0) run(base + o.ln1_g, 2 * d);
+      run(base + o.b_qkv, 3 * d);
+      run(base + o.b_o, 3 * d);
+      run(base + o.b_fc, F);
+      run(base + o.b_proj, j + 1 < m->sh.k ? 3 * d : d);
+    }
+    sl->has_fwd = sl->wb_valid = true;
   }
   if (m->sh.tie && shard == m->sh.S + 1 && !sl->tied_valid) {
     // tied LM head: the buffer keeps a copy of wte behind the final LayerNorm's parameters.  Taken from the EMBED
@@ -612,6 +650,17 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
       plan.segs.push_back({m->host.adam_m + off, sl->m, m->host_dev.adam_m + off, (size_t)cnt * 4, kind});
       plan.segs.push_back({m->host.adam_v + off, sl->v, m->host_dev.adam_v + off, (size_t)cnt * 4, kind});
       plan.trace_bytes = (uint64_t)cnt * 12;
+      if (m->fwd_bf16 && shard >= 1 && shard <= m->sh.S) {
+        // the host's bf16 copy follows the master: rounded by the staging tier's threads on the way out of the ring,
+        // or (page-locked state) the copy the optimizer step left in the buffer is sent after the master
+        if (m->pageable) {
+          plan.segs[plan.segs.size() - 3].rounded = m->host.work_bf16 + off;
+        } else {
+          if (!ctx->dry && !sl->wb_valid) return fail(ctx, HYDRA_E_STATE, "the buffer's bf16 copy is not current");
+          plan.segs.push_back({m->host.work_bf16 + off, sl->wb, m->work_dev + off, (size_t)cnt * 2, kind});
+          plan.trace_bytes += (uint64_t)cnt * 2;
+        }
+      }
       if (!ctx->dry) plan.records.push_back(m->ev_wb[shard]);
     }
     if (poison) {  // on the d2h stream: behind the write-back
@@ -629,7 +678,7 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
       m->wb_ticket[shard] = ticket;
       sl->wb_seq = ++ctx->wb_counter;
       sl->dirty = false;
-      ctx->stats.bytes_d2h += cnt * 12;
+      ctx->stats.bytes_d2h += plan.trace_bytes;
       ctx->stats.n_writebacks++;
     }
   }
@@ -637,6 +686,7 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     m->slot_of[shard] = -1;
     sl->model = sl->shard = -1;
     sl->has_params = sl->has_opt = sl->wb_valid = sl->wbt_valid = sl->grads_valid = sl->tied_valid = false;
+    sl->has_fwd = false;
     ctx->stats.n_evictions++;
   }
   return HYDRA_OK;
@@ -665,12 +715,12 @@ static hydra_status promote_checkpoint(hydra_ctx *ctx, Model *m, int b) {
 }
 
 // common entry of the three compute calls: the shard must have been promoted
-static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out) {
+static hydra_status begin_task(hydra_ctx *ctx, int model, int shard, Slot **out, bool forward = false) {
   hydra_status st = check_model(ctx, model, shard);
   if (st) return st;
   if ((st = ensure_planned(ctx))) return st;
   Slot *sl = slot_for(ctx, model, shard);
-  if (!sl || !sl->has_params) return fail(ctx, HYDRA_E_STATE, "shard was not loaded");
+  if (!sl || !(forward ? sl->has_fwd : sl->has_params)) return fail(ctx, HYDRA_E_STATE, "shard was not loaded");
   if (ctx->models[model]->sh.tie && shard == ctx->models[model]->sh.S + 1 && !sl->tied_valid)
     return fail(ctx, HYDRA_E_STATE, "tied LM head: load the shard again after the embedding shard's update");
   if (sl->need_wait_load) {
@@ -701,7 +751,7 @@ static hydra_status end_task(hydra_ctx *ctx, Model *m, Slot *sl, int tr) {
 
 hydra_status hydra_shard_forward(hydra_ctx *ctx, int32_t model, int32_t shard) {
   Slot *sl = nullptr;
-  hydra_status st = begin_task(ctx, model, shard, &sl);
+  hydra_status st = begin_task(ctx, model, shard, &sl, true);
   if (st) return st;
   Model *m = ctx->models[model];
   if (m->t == 0) return fail(ctx, HYDRA_E_STATE, "no minibatch set");
@@ -832,6 +882,7 @@ hydra_status hydra_read_device(hydra_ctx *ctx, int32_t model, int32_t shard, int
       if (which == HYDRA_RD_GRADS && !sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients held");
       if ((which == HYDRA_RD_ADAM_M || which == HYDRA_RD_ADAM_V) && !sl->has_opt)
         return fail(ctx, HYDRA_E_STATE, "Adam state not resident");
+      if (which == HYDRA_RD_PARAMS && !sl->has_params) return fail(ctx, HYDRA_E_STATE, "fp32 master not resident");
       src = which == HYDRA_RD_GRADS ? sl->g : which == HYDRA_RD_PARAMS ? sl->w : which == HYDRA_RD_ADAM_M ? sl->m : sl->v;
       need = (uint64_t)(s.shard_off[shard + 1] - s.shard_off[shard]) * 4;
       break;

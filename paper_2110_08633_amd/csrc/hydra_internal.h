@@ -66,6 +66,8 @@ struct Slot {
                           // that forward products have both operands contraction-contiguous
   int model = -1, shard = -1;
   bool has_params = false, has_opt = false, wb_valid = false, wbt_valid = false, grads_valid = false, dirty = false;
+  bool has_fwd = false;  // what a forward visit reads is resident (bf16 copy wb and the fp32 vectors in w), be the fp32
+                         // master resident or not
   bool need_wait_load = false;  // a copy into this slot was enqueued since the compute stream last waited
   hipEvent_t ev_loaded = nullptr, ev_compute = nullptr, ev_spilled = nullptr;
   bool compute_pending = false, spill_pending = false;
@@ -113,6 +115,9 @@ struct Model {
   std::vector<char> wb_pending;
   std::vector<uint64_t> wb_ticket;  // staging tier: job of the shard's last write-back
   bool pageable = false;            // master / m / v are ordinary host memory: copies go through the staging ring
+  bool fwd_bf16 = false;            // the host keeps a bf16 rounding of the master (hydra_host_state.work_bf16):
+                                    // promotes for forward visits of block shards carry that instead of the master
+  uint16_t *work_dev = nullptr;     // page-locked work_bf16 as the device sees it
 };
 
 }  // namespace hydra
@@ -183,7 +188,11 @@ void pager_wait(Pager *p, int which, uint64_t ticket);                          
 hydra_status pager_error(Pager *p, std::string *text);
 hydra_status pager_drain(Pager *p, std::string *text);
 hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t bytes);
-hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit);
+hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit,
+                       uint16_t *rounded);
+// fp32 -> bf16 on the host with the device casts' rounding
+void host_round_bf16(uint16_t *dst, const float *src, size_t n);
+void host_round_bf16_threads(uint16_t *dst, const float *src, size_t n, int threads);
 hydra_status drain_copies(hydra_ctx *ctx);
 // device address of the current GPU's static scratch array (hydra_op_layernorm_bwd_static)
 hydra_status static_scratch(float **out);

@@ -20,6 +20,8 @@
 // calling thread never copies: it submits a job and gets a ticket; whoever
 // depends on the job having been ISSUED to the stream (an event recorded by it)
 // waits for the ticket first.
+#include <immintrin.h>
+
 #include <atomic>
 #include <condition_variable>
 #include <cstring>
@@ -32,9 +34,75 @@
 
 namespace hydra {
 
+// fp32 -> bf16, round to nearest even (NaN stays NaN): bit for bit what the device's casts produce
+static void round_bf16_plain(uint16_t *dst, const float *src, size_t n) {
+  for (size_t i = 0; i < n; ++i) {
+    uint32_t u;
+    memcpy(&u, src + i, 4);
+    const uint32_t r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    dst[i] = (uint16_t)((u & 0x7fffffffu) > 0x7f800000u ? ((u >> 16) | 0x40u) : r);
+  }
+}
+
+// the same, 16 values per step (the write-back path of the staging tier rounds a third of all bytes it moves: the
+// plain loop halved what a helper thread moves per second)
+__attribute__((target("avx2"))) static inline __m256i round8_avx2(const float *p) {
+  const __m256i u = _mm256_loadu_si256((const __m256i *)p);
+  const __m256i hi = _mm256_srli_epi32(u, 16);
+  const __m256i r = _mm256_srli_epi32(
+      _mm256_add_epi32(_mm256_add_epi32(u, _mm256_set1_epi32(0x7fff)), _mm256_and_si256(hi, _mm256_set1_epi32(1))), 16);
+  // both sides of the comparison are below 2^31: the signed one does
+  const __m256i nan = _mm256_cmpgt_epi32(_mm256_and_si256(u, _mm256_set1_epi32(0x7fffffff)), _mm256_set1_epi32(0x7f800000));
+  return _mm256_blendv_epi8(r, _mm256_or_si256(hi, _mm256_set1_epi32(0x40)), nan);
+}
+
+__attribute__((target("avx2"))) static void round_bf16_avx2(uint16_t *dst, const float *src, size_t n) {
+  size_t i = 0;
+  for (; i + 16 <= n; i += 16) {
+    // the pack works per 128-bit half (a0-3 b0-3 | a4-7 b4-7): the permutation restores the order
+    const __m256i p = _mm256_packus_epi32(round8_avx2(src + i), round8_avx2(src + i + 8));
+    _mm256_storeu_si256((__m256i *)(dst + i), _mm256_permute4x64_epi64(p, 0xD8));
+  }
+  round_bf16_plain(dst + i, src + i, n - i);
+}
+
+void host_round_bf16(uint16_t *dst, const float *src, size_t n) {
+  static const bool avx2 = __builtin_cpu_supports("avx2");
+  if (avx2) round_bf16_avx2(dst, src, n);
+  else round_bf16_plain(dst, src, n);
+}
+
+void host_round_bf16_threads(uint16_t *dst, const float *src, size_t n, int threads) {
+  if (threads < 1) threads = 1;
+  if (n < ((size_t)1 << 22)) threads = 1;
+  const size_t per = (n + threads - 1) / threads;
+  std::vector<std::thread> th;
+  for (int t = 1; t < threads; ++t) {
+    const size_t lo = per * t, hi = lo + per < n ? lo + per : n;
+    if (lo < hi) th.emplace_back([=] { host_round_bf16(dst + lo, src + lo, hi - lo); });
+  }
+  host_round_bf16(dst, src, per < n ? per : n);
+  for (std::thread &t : th) t.join();
+}
+
 namespace {
 
-// n bytes copied by the calling thread and a few helpers, each a contiguous part
+// one part of a chunk: copied, and (rounded != null) its floats also rounded to bf16 while they are in the cache
+inline void copy_part(char *dst, const char *src, size_t n, uint16_t *rounded) {
+  if (!rounded) {
+    memcpy(dst, src, n);
+    return;
+  }
+  const size_t blk = 1u << 16;  // bytes
+  for (size_t o = 0; o < n; o += blk) {
+    const size_t c = n - o < blk ? n - o : blk;
+    memcpy(dst + o, src + o, c);
+    host_round_bf16(rounded + o / 4, (const float *)(src + o), c / 4);
+  }
+}
+
+// n bytes copied by the calling thread and a few helpers, each a contiguous part; with 'rounded' the bytes are floats
+// whose bf16 roundings go to rounded[0 .. n/4)
 class CopyPool {
  public:
   explicit CopyPool(int helpers) {
@@ -48,21 +116,21 @@ class CopyPool {
     cv_.notify_all();
     for (std::thread &t : th_) t.join();
   }
-  void copy(void *dst, const void *src, size_t n) {
+  void copy(void *dst, const void *src, size_t n, uint16_t *rounded = nullptr) {
     const size_t parts = th_.size() + 1;
     if (n < (1u << 20) || parts == 1) {
-      memcpy(dst, src, n);
+      copy_part((char *)dst, (const char *)src, n, rounded);
       return;
     }
     const size_t per = (n / parts + 4095) & ~(size_t)4095;
     {
       std::lock_guard<std::mutex> l(mu_);
-      dst_ = (char *)dst; src_ = (const char *)src; n_ = n; per_ = per;
+      dst_ = (char *)dst; src_ = (const char *)src; n_ = n; per_ = per; rounded_ = rounded;
       pending_ = (int)th_.size();
       ++gen_;
     }
     cv_.notify_all();
-    memcpy(dst, src, per < n ? per : n);  // part 0
+    copy_part((char *)dst, (const char *)src, per < n ? per : n, rounded);  // part 0
     std::unique_lock<std::mutex> l(mu_);
     done_.wait(l, [this] { return pending_ == 0; });
   }
@@ -79,8 +147,9 @@ class CopyPool {
       const size_t hi = lo + per_ < n_ ? lo + per_ : n_;
       char *d = dst_;
       const char *s = src_;
+      uint16_t *r = rounded_;
       l.unlock();
-      if (lo < hi) memcpy(d + lo, s + lo, hi - lo);
+      if (lo < hi) copy_part(d + lo, s + lo, hi - lo, r ? r + lo / 4 : nullptr);
       l.lock();
       if (--pending_ == 0) done_.notify_one();
     }
@@ -92,6 +161,7 @@ class CopyPool {
   uint64_t gen_ = 0;
   char *dst_ = nullptr;
   const char *src_ = nullptr;
+  uint16_t *rounded_ = nullptr;
   size_t n_ = 0, per_ = 0;
   int pending_ = 0;
 };
@@ -104,6 +174,8 @@ struct Ring {
   std::vector<hipEvent_t> ev;  // per chunk: last operation of the copy stream that touched it
   std::vector<char> used;
   uint64_t next = 0;
+  int small_k = -1;      // promotes: the chunk that collects copies of less than 1 MiB (-1: none), and how much of
+  size_t small_off = 0;  // it they have taken
 };
 
 struct Queue {
@@ -262,9 +334,25 @@ hydra_status pager_drain(Pager *p, std::string *text) {
 hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t bytes) {
   Ring &r = p->ring[PQ_H2D];
   hipStream_t s = p->ctx->s_h2d;
+  if (bytes < (1u << 20)) {
+    // small copies (a shard's vectors) share one chunk instead of taking a ring position each
+    if (r.small_k < 0 || r.small_off + bytes > r.chunk) {
+      r.small_k = (int)(r.next++ % r.n);
+      r.small_off = 0;
+      if (r.used[r.small_k] && hipEventSynchronize(r.ev[r.small_k]) != hipSuccess) return HYDRA_E_HIP;
+    }
+    char *at = r.host + (size_t)r.small_k * r.chunk + r.small_off;
+    memcpy(at, src_host, bytes);
+    if (hipMemcpyAsync(dst_dev, at, bytes, hipMemcpyHostToDevice, s) != hipSuccess) return HYDRA_E_HIP;
+    if (hipEventRecord(r.ev[r.small_k], s) != hipSuccess) return HYDRA_E_HIP;
+    r.used[r.small_k] = 1;
+    r.small_off += (bytes + 255) & ~(size_t)255;
+    return HYDRA_OK;
+  }
   for (size_t off = 0; off < bytes; off += r.chunk) {
     const size_t n = bytes - off < r.chunk ? bytes - off : r.chunk;
     const int k = (int)(r.next++ % r.n);
+    if (k == r.small_k) r.small_k = -1;  // the ring has come round to the chunk of the small copies
     if (r.used[k] && hipEventSynchronize(r.ev[k]) != hipSuccess) return HYDRA_E_HIP;
     p->pool[PQ_H2D]->copy(r.host + (size_t)k * r.chunk, (const char *)src_host + off, n);
     if (hipMemcpyAsync((char *)dst_dev + off, r.host + (size_t)k * r.chunk, n, hipMemcpyHostToDevice, s) != hipSuccess)
@@ -277,7 +365,9 @@ hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t byt
 
 // Runs on the d2h coordinator.  Keeps up to ring-size chunks in flight from the device into the ring and moves each
 // into the pageable destination as it lands.  Returns when the data is in dst_host.
-hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit) {
+// With 'rounded' the bytes are floats and their bf16 roundings are written to rounded[0 .. bytes/4) as well.
+hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit,
+                       uint16_t *rounded) {
   Ring &r = p->ring[PQ_D2H];
   hydra_ctx *ctx = p->ctx;
   hipStream_t s = ctx->s_d2h;
@@ -302,7 +392,7 @@ hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t byt
     const size_t n = bytes - off < r.chunk ? bytes - off : r.chunk;
     const int k = (int)(drained % r.n);
     if (hipEventSynchronize(r.ev[k]) != hipSuccess) return HYDRA_E_HIP;
-    p->pool[PQ_D2H]->copy((char *)dst_host + off, r.host + (size_t)k * r.chunk, n);
+    p->pool[PQ_D2H]->copy((char *)dst_host + off, r.host + (size_t)k * r.chunk, n, rounded ? rounded + off / 4 : nullptr);
     ++drained;
   }
   return HYDRA_OK;

@@ -47,7 +47,7 @@ class ModelDesc(C.Structure):
 
 class HostState(C.Structure):
     _fields_ = [("master", C.c_void_p), ("adam_m", C.c_void_p), ("adam_v", C.c_void_p), ("ckpt", C.c_void_p),
-                ("batch_stage", C.c_void_p)]
+                ("batch_stage", C.c_void_p), ("work_bf16", C.c_void_p)]
 
 
 class Layout(C.Structure):
@@ -245,8 +245,8 @@ def hydra_shard_range(desc, shard):
     return off.value, cnt.value
 
 
-def hydra_register_model(ctx, desc, master, adam_m, adam_v, ckpt, batch_stage):
-    hs = HostState(_ptr(master), _ptr(adam_m), _ptr(adam_v), _ptr(ckpt), _ptr(batch_stage))
+def hydra_register_model(ctx, desc, master, adam_m, adam_v, ckpt, batch_stage, work_bf16=None):
+    hs = HostState(_ptr(master), _ptr(adam_m), _ptr(adam_v), _ptr(ckpt), _ptr(batch_stage), _ptr(work_bf16))
     mid = _i32()
     _check(lib.hydra_register_model(ctx, C.byref(desc), C.byref(hs), C.byref(mid)), ctx)
     return mid.value

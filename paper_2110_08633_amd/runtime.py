@@ -100,10 +100,12 @@ class Session:
         self._pinned.append(buf)
         return buf.array
 
-    def add_model(self, cfg, weights, lr, dtype=None, pageable=False, host=None):
+    def add_model(self, cfg, weights, lr, dtype=None, pageable=False, host=None, work_copy=False):
         """weights: dict name -> float32 array (names as given by hydra_model_tensor), or None to leave the master
         array as it is.  pageable: the model's state arrays are ordinary host memory (needs a session with a staging
-        area).  host: (master, m, v) arrays to use instead of allocating (they stay the caller's)."""
+        area).  host: (master, m, v) arrays to use instead of allocating (they stay the caller's).  work_copy: also
+        give the library a bf16 array of the model's size, page-locked or not as the state is (forward promotes of
+        block shards then carry 2 instead of 4 bytes per parameter); True allocates it, an array is used as it is."""
         desc = H.model_desc(cfg, lr, dtype)
         lay = H.hydra_model_layout(desc)
         master, m, v = host if host is not None else (self._host(lay.n_params, pageable=pageable) for _ in range(3))
@@ -117,9 +119,13 @@ class Session:
         if self.flags & H.FLAG_CKPT_SPILL:
             ckpt = self._host((lay.n_block_shards + 1) * cfg.get("n_micro", 1) * cfg["B"] * cfg["T"] * cfg["d"])
         stage = self._host(4 * cfg.get("n_micro", 1) * cfg["B"] * cfg["T"], np.int32)
-        mid = H.hydra_register_model(self.ctx, desc, master, m, v, ckpt, stage)
+        if isinstance(work_copy, np.ndarray):
+            work = work_copy                      # the caller's array
+        else:
+            work = self._host(lay.n_params, np.uint16, pageable=pageable) if work_copy else None
+        mid = H.hydra_register_model(self.ctx, desc, master, m, v, ckpt, stage, work)
         rec = dict(id=mid, desc=desc, cfg=cfg, layout=lay, master=master, m=m, v=v, ckpt=ckpt, stage=stage, tensors=tensors,
-                   S=lay.n_block_shards)
+                   S=lay.n_block_shards, work=work)
         self.models.append(rec)
         return rec
 
@@ -192,7 +198,7 @@ class Session:
             H.hydra_destroy(self.ctx)
             self.ctx = None
         for rec in self.models:
-            for k in ("master", "m", "v", "ckpt", "stage"):
+            for k in ("master", "m", "v", "ckpt", "stage", "work"):
                 rec[k] = None
         for buf in self._pinned:
             buf.free()

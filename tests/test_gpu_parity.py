@@ -123,11 +123,12 @@ def host_state(sess, rec):
 
 
 def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False, W=None, lr=None, batches=None, oracle_cfg=None,
-               test_id=None, cap=0, oracle=True, session_kw=None, pageable=False):
+               test_id=None, cap=0, oracle=True, session_kw=None, pageable=False, work_copy=False, extras=None):
     """n_steps minibatches of one model through the shard calls one by one (every shard spilled between visits),
     everything compared with the oracle after every step: logits, loss, every gradient tensor, updated weights,
     weight deltas, Adam state.  Returns the per-step oracle losses, the final host state (w, m, v), the last loss
-    and the oracle's final (P, m, v).  oracle=False only runs the GPU side (for bit-for-bit comparisons)."""
+    and the oracle's final (P, m, v).  oracle=False only runs the GPU side (for bit-for-bit comparisons).  work_copy:
+    the model gets a bf16 host copy; extras (a dict) receives that copy and the context's counters at the end."""
     H, R = rt
     W = SI.make_weights(cfg, SI.model_seed(cfg, 0)) if W is None else W
     lr = cfg["lrs"][0] if lr is None else lr
@@ -136,7 +137,7 @@ def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False, W=None, lr=No
         batches = [SI.make_batch(ocfg, SI.batch_seed(cfg, 0, i), zipf=zipf) for i in range(n_steps)]
     sess = R.Session(R.arena_bytes_for([cfg], max_slots or 4, bool(flags & H.FLAG_CKPT_SPILL)), flags=flags,
                      max_slots=max_slots or 4, shard_buffer_cap_bytes=cap, **(session_kw or {}))
-    rec = sess.add_model(cfg, W, lr, pageable=pageable)
+    rec = sess.add_model(cfg, W, lr, pageable=pageable, work_copy=work_copy)
     if oracle:
         P = D.cast_params(W, np.float64)
         Mo, Vo = D.zeros_like_params(P), D.zeros_like_params(P)
@@ -162,6 +163,9 @@ def run_manual(rt, cfg, n_steps, flags=0, max_slots=0, zipf=False, W=None, lr=No
     if oracle:
         chk.report(test_id or f"manual {cfg['dtype']} L{cfg['L']} d{cfg['d']} T{cfg['T']}")
     final = host_state(sess, rec)
+    if extras is not None:
+        extras["stats"] = H.hydra_get_stats(sess.ctx)
+        extras["work"] = None if rec["work"] is None else rec["work"].copy()
     sess.close()
     return refs, final, loss, ((P, Mo, Vo) if oracle else None)
 
@@ -226,13 +230,15 @@ def test_embedding_forward_is_bit_exact_and_absent_rows_untouched(rt):
 
 
 def scheduled_run(rt, cfgs, Ws, lrs, batches, nmb, tables, max_slots=0, lanes=1, flags=0, cap=0, slots_for_arena=12,
-                  session_kw=None, pageable=None):
-    """All models through hydra_sched_run; returns (trace, per-model host state, per-model last loss, stats)."""
+                  session_kw=None, pageable=None, work_copy=None, extras=None):
+    """All models through hydra_sched_run; returns (trace, per-model host state, per-model last loss, stats).
+    work_copy: per model, whether it gets a bf16 host copy; extras (a dict) receives those copies."""
     H, R = rt
     n = len(cfgs)
     sess = R.Session(R.arena_bytes_for(cfgs, slots_for_arena, bool(flags & H.FLAG_CKPT_SPILL), lanes=lanes),
                      max_slots=max_slots, lanes=lanes, flags=flags, shard_buffer_cap_bytes=cap, **(session_kw or {}))
-    recs = [sess.add_model(cfgs[m], Ws[m], lrs[m], pageable=bool(pageable and pageable[m])) for m in range(n)]
+    recs = [sess.add_model(cfgs[m], Ws[m], lrs[m], pageable=bool(pageable and pageable[m]),
+                           work_copy=bool(work_copy and work_copy[m])) for m in range(n)]
     sch = H.hydra_sched_create(sess.ctx, [r["id"] for r in recs], nmb, tables)
     toks = [np.stack([b[0] for b in batches[m]]) for m in range(n)]
     tgts = [np.stack([b[1] for b in batches[m]]) for m in range(n)]
@@ -241,6 +247,8 @@ def scheduled_run(rt, cfgs, Ws, lrs, batches, nmb, tables, max_slots=0, lanes=1,
     st = H.hydra_get_stats(sess.ctx)
     states = [host_state(sess, r) for r in recs]
     losses = [H.hydra_get_loss(sess.ctx, r["id"]) for r in recs]
+    if extras is not None:
+        extras["work"] = [None if r["work"] is None else r["work"].copy() for r in recs]
     assert done == len(trace) == st["n_tasks"]
     H.hydra_sched_destroy(sch)
     sess.close()

@@ -294,6 +294,28 @@ def test_stated_workloads_dry_run_order_and_traffic(name, cap_bytes, max_slots, 
     s.close()
 
 
+def test_dry_run_traffic_with_a_bf16_host_copy():
+    """With hydra_host_state.work_bf16 the promote for a forward visit of a block shard brings 2 bytes per parameter
+    plus the shard's fp32 vectors instead of 4 per parameter, and (page-locked state) the write-back of a block
+    shard sends the bf16 copy after the master: 14 instead of 12 bytes per parameter."""
+    cfg = SI.small_cfg(L=4, k=2, dtype="bf16")
+    out = {}
+    for copy in (False, True):
+        s = Session(1 << 34, max_slots=2, dry_run=True)
+        rec = s.add_model(cfg, None, 1e-3, work_copy=copy)
+        tok, tgt = SI.make_batch(cfg, 5)
+        for _ in range(2):
+            s.train_step_manual(rec, tok, tgt, collect=False)
+        out[copy] = H.hydra_get_stats(s.ctx)
+        c = [H.hydra_shard_range(rec["desc"], sh)[1] for sh in range(rec["S"] + 2)]
+        s.close()
+    blocks, vec = sum(c[1:-1]), (cfg["L"] // cfg["k"]) * cfg["k"] * (9 * cfg["d"] + cfg["F"])
+    plain = 2 * (4 * sum(c) + 12 * sum(c[:-1]) + 8 * c[-1])      # the HEAD shard stays resident for its backward visit
+    assert out[False]["bytes_h2d"] == plain and out[False]["bytes_d2h"] == 2 * 12 * sum(c)
+    assert out[True]["bytes_h2d"] == plain - 2 * (2 * blocks - 4 * vec)
+    assert out[True]["bytes_d2h"] == 2 * (12 * sum(c) + 2 * blocks)
+
+
 def test_prefetch_depth_one_is_plain_double_buffering():
     """prefetch_depth 0 / 1: one task ahead (the paper's double buffering); 3: as far as three tasks ahead while
     buffers can be freed.  Neither changes the executed order or the bytes written back."""
