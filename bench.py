@@ -481,10 +481,10 @@ def main():
     name = args.config
     fallback = None
     if name == "auto":
-        # config 5 keeps 145 GB of state in host DRAM (plus what the process itself needs)
-        name = "gpt6b" if avail >= 175 else "gpt2xl"
+        # config 5 keeps 145 GB of state and 24 GB of bf16 copies in host DRAM (plus what the process itself needs)
+        name = "gpt6b" if avail >= 200 else "gpt2xl"
         if name != "gpt6b":
-            fallback = f"host has {avail:.0f} GB available: config 5's 145 GB of state does not fit, config 4 measured instead"
+            fallback = f"host has {avail:.0f} GB available: config 5's 170 GB of state do not fit, config 4 measured instead"
     if args.slots:
         WORKLOADS[name] = dict(WORKLOADS[name], max_slots=args.slots, cap=0, what=f"{args.slots} shard buffers [command line]")
     main_out, cfg, host = bench_workload(name, args.steps, args.warmup, 0 if args.no_kernel_pass else 2, R, H, torch,
