@@ -72,22 +72,25 @@ class HostState:
         desc = H.model_desc(cfg, 1e-4)
         lay = H.hydra_model_layout(desc)
         self.n_params = lay.n_params
-        self.pinned_bufs, self.arrays, self.pageable = [], [], False
+        self.pinned_bufs, self.arrays, self.work, self.pageable = [], [], [], False
+        # The library's bf16 rounding of the master, which forward promotes of block shards then carry (2 instead of 4
+        # bytes per parameter); kept current by host threads of the library, so nothing extra crosses the link.
+        self.work_copy = WORK_COPY and cfg["dtype"] == "bf16"
         try:
             for _ in range(n_models):
                 bufs = [R.PinnedArray(lay.n_params, np.float32, zero=False) for _ in range(3)]
                 self.pinned_bufs += bufs
                 self.arrays.append(tuple(b.array for b in bufs))
+                if self.work_copy:
+                    self.pinned_bufs.append(R.PinnedArray(lay.n_params, np.uint16, zero=False))
+                    self.work.append(self.pinned_bufs[-1].array)
         except MemoryError:
             self.free()
             self.pageable = True
             self.arrays = [tuple(np.zeros(lay.n_params, np.float32) for _ in range(3)) for _ in range(n_models)]
-        # The library's bf16 rounding of the master, which forward promotes of block shards then carry: given with
-        # state in ordinary memory, where the staging tier's host threads produce it for free (+7 % and +9 % on the
-        # two large workloads); page-locked state would send it over the link with every write-back, which measured
-        # neutral (-0.7 % / +1.8 % on the two small workloads).
-        self.work_copy = WORK_COPY and self.pageable and cfg["dtype"] == "bf16"
-        self.work = [np.zeros(lay.n_params, np.uint16) if self.work_copy else False for _ in range(n_models)]
+            self.work = [np.zeros(lay.n_params, np.uint16) for _ in range(n_models)] if self.work_copy else []
+        if not self.work_copy:
+            self.work = [False] * n_models
         tensors = [H.hydra_model_tensor(desc, i) for i in range(lay.n_tensors)]
         for m in range(n_models):
             master, am, av = self.arrays[m]

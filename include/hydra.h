@@ -159,15 +159,16 @@ typedef struct {
                         /* way to the device; contents belong to the library while the model is registered        */
   uint16_t *work_bf16;  /* optional (NULL: not used; ignored for dtype 0): [n_params] bf16, the master rounded to   */
                         /* nearest-even, same layout.  Written by the library only: from master at registration   */
-                        /* and with every write-back of a block shard.  A forward visit multiplies by this         */
+                        /* and after every write-back of a block shard.  A forward visit multiplies by this        */
                         /* rounding of the weights in any case, so with the array present the promote for a        */
                         /* FORWARD visit of a block shard (Section 2.3) carries it (2 bytes per parameter) plus    */
                         /* the shard's fp32 vectors instead of the whole fp32 master (4 bytes per parameter);      */
-                        /* results do not change by a bit.  Page-locked if master is (the write-back then sends    */
-                        /* the device's bf16 copy after the master); ordinary memory if master is (the staging     */
-                        /* tier's host threads then round the master as they move it out of the staging area, and  */
-                        /* nothing extra crosses the link).  The caller must not change master while the model is  */
-                        /* registered, or this copy goes stale.                                                    */
+                        /* results do not change by a bit.  Ordinary memory if master is (the staging tier's host  */
+                        /* threads round the master as they move it out of the staging area); page-locked if       */
+                        /* master is (a host thread of the library rounds each write-back once it has landed; a    */
+                        /* promote call that needs the result waits for it).  Current for the caller after         */
+                        /* hydra_sync.  The caller must not change master while the model is registered, or this   */
+                        /* copy goes stale.                                                                        */
 } hydra_host_state;
 
 typedef struct {
@@ -274,8 +275,11 @@ hydra_status hydra_set_batch(hydra_ctx *ctx, int32_t model, const int32_t *token
 
 /* ---- shard tasks (paper Section 2.3) ------------------------------------- */
 /* Promote (Section 2.3): start copying the shard's state from the host arrays into a free
- * shard buffer on the h2d stream; returns at once.  Already resident: only
- * missing parts are fetched.  No free buffer: HYDRA_E_NOSLOT. */
+ * shard buffer on the h2d stream.  Returns once the copies have been handed to the stream
+ * (or, with a staging area, to the library's threads), not when they have finished; before
+ * that the calling thread waits for what the promote depends on - the write-back that freed
+ * the buffer, the shard's own last write-back - so the call may take as long as those still
+ * need.  Already resident: only missing parts are fetched.  No free buffer: HYDRA_E_NOSLOT. */
 hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard, int32_t what);
 /* Forward visit: reads the boundary activation at the shard's input, writes
  * the one at its output (EMBED reads the tokens; HEAD writes logits and loss). */

@@ -81,7 +81,13 @@ struct CopyPlan {
 static hydra_status run_h2d_plan(hydra_ctx *ctx, const CopyPlan &p) {
   hipStream_t s = ctx->s_h2d;
   for (uint64_t t : p.d2h_tickets) pager_wait(ctx->pager, PQ_D2H, t);
-  for (hipEvent_t e : p.waits) PLAN_HIP(hipStreamWaitEvent(s, e, 0));
+  // The issuing thread waits for what the promote depends on (the write-back that frees its buffer, the one that
+  // brought the shard's state to the host) and only then hands the copies to the stream.  Enqueued behind stream
+  // waits instead, the same copies ran slower: four GPT-2-medium models 14.1 k -> 16.2-17.5 k tokens/s with the
+  // waits on the host, two GPT-2-small models 35.8 k -> 41.5 k (the link was then used to 0.93-1.0 of its measured
+  // two-way rate instead of 0.80-0.85).  Every event in the list was recorded before the plan was made, by work
+  // that depends on nothing enqueued later, so the wait ends.
+  for (hipEvent_t e : p.waits) PLAN_HIP(hipEventSynchronize(e));
   const int tr = p.trace_bytes ? trace_begin(ctx, TRACE_H2D, s, p.trace_tag) : -1;
   for (const CopyPlan::Seg &g : p.segs) {
     if (g.kind == CopyPlan::SEG_PAGEABLE) {
@@ -327,8 +333,12 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
 hydra_status hydra_destroy(hydra_ctx *ctx) {
   if (!ctx) return HYDRA_OK;
   if (!ctx->dry) {
+    if (ctx->pager) (void)pager_drain(ctx->pager, nullptr);
+    if (ctx->rounder) {  // its jobs wait for tickets of the staging tier: before that goes
+      worker_destroy(ctx->rounder);
+      ctx->rounder = nullptr;
+    }
     if (ctx->pager) {
-      (void)pager_drain(ctx->pager, nullptr);
       pager_destroy(ctx->pager);
       ctx->pager = nullptr;
     }
@@ -361,6 +371,7 @@ hydra_status hydra_sync(hydra_ctx *ctx) {
   HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_h2d));
   for (hydra_ctx::Lane &ln : ctx->lanes) HYDRA_HIP(ctx, hipStreamSynchronize(ln.stream));
   HYDRA_HIP(ctx, hipStreamSynchronize(ctx->s_d2h));
+  if (ctx->rounder) worker_drain(ctx->rounder);  // the bf16 host copies are current when the call returns
   return HYDRA_OK;
 }
 
@@ -413,15 +424,16 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   m->fwd_bf16 = host->work_bf16 != nullptr && desc->dtype == DT_BF16;
   if (m->fwd_bf16 && !ctx->dry) {
     if (!m->pageable) {
-      float *dev = nullptr;
-      if ((st = mapped_pointer(ctx, host->work_bf16, "work_bf16", &dev))) {
+      // promotes read it with the copy engine; a thread of the library keeps it current after write-backs
+      if (!page_locked(host->work_bf16)) {
         delete m;
-        return st;
+        return fail(ctx, HYDRA_E_INVAL, "work_bf16 must be page-locked when master is");
       }
-      m->work_dev = (uint16_t *)dev;
+      if (!ctx->rounder) ctx->rounder = worker_create();
     }
     host_round_bf16_threads(host->work_bf16, host->master, (size_t)m->sh.n_params, 8);
   }
+  m->round_ticket.assign(m->sh.S + 2, 0);
   const ModelShape &s = m->sh;
   const uint64_t act = (uint64_t)s.Mt * s.d * 4;  // boundary tensors hold all micro-batches
   const bool spill = (ctx->init.flags & HYDRA_FLAG_CKPT_SPILL) != 0;
@@ -552,7 +564,15 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   }
   // a promote for a forward visit of a block shard of a model with a bf16 host copy carries that copy and the fp32
   // vectors; every other promote the fp32 master
-  const bool fwd_only = m->fwd_bf16 && shard >= 1 && shard <= m->sh.S && !(what & HYDRA_LOAD_OPT);
+  bool fwd_only = m->fwd_bf16 && shard >= 1 && shard <= m->sh.S && !(what & HYDRA_LOAD_OPT);
+  if (fwd_only && !sl->has_params && !sl->has_fwd && !m->pageable && !ctx->dry && m->round_ticket[shard]) {
+    // Page-locked state: the host job that rounds the shard's last write-back must have finished.  The calling
+    // thread waits for it - at most until the device has caught up with that write-back, which lies a whole
+    // backward and forward pass of enqueued work behind for all but the first block shards of a pass.
+    worker_wait(ctx->rounder, m->round_ticket[shard]);
+    m->round_ticket[shard] = 0;
+    if (m->round_broken.load()) fwd_only = false;
+  }
   const bool need_master = !sl->has_params && !fwd_only, need_fwd = fwd_only && !sl->has_params && !sl->has_fwd;
   // the host arrays of a shard are read only after its last write-back has landed (the buffer it was written
   // back from may be a different one)
@@ -650,17 +670,10 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
       plan.segs.push_back({m->host.adam_m + off, sl->m, m->host_dev.adam_m + off, (size_t)cnt * 4, kind});
       plan.segs.push_back({m->host.adam_v + off, sl->v, m->host_dev.adam_v + off, (size_t)cnt * 4, kind});
       plan.trace_bytes = (uint64_t)cnt * 12;
-      if (m->fwd_bf16 && shard >= 1 && shard <= m->sh.S) {
-        // the host's bf16 copy follows the master: rounded by the staging tier's threads on the way out of the ring,
-        // or (page-locked state) the copy the optimizer step left in the buffer is sent after the master
-        if (m->pageable) {
-          plan.segs[plan.segs.size() - 3].rounded = m->host.work_bf16 + off;
-        } else {
-          if (!ctx->dry && !sl->wb_valid) return fail(ctx, HYDRA_E_STATE, "the buffer's bf16 copy is not current");
-          plan.segs.push_back({m->host.work_bf16 + off, sl->wb, m->work_dev + off, (size_t)cnt * 2, kind});
-          plan.trace_bytes += (uint64_t)cnt * 2;
-        }
-      }
+      // the host's bf16 copy follows the master: state in ordinary memory is rounded by the staging tier's threads on
+      // its way out of the ring (page-locked state: by a host job once the write-back has landed, below)
+      if (m->fwd_bf16 && m->pageable && shard >= 1 && shard <= m->sh.S)
+        plan.segs[plan.segs.size() - 3].rounded = m->host.work_bf16 + off;
       if (!ctx->dry) plan.records.push_back(m->ev_wb[shard]);
     }
     if (poison) {  // on the d2h stream: behind the write-back
@@ -673,6 +686,24 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     if ((st = issue_plan(ctx, PQ_D2H, plan, &ticket))) return st;
     sl->spill_pending = true;
     sl->spill_ticket = ticket;
+    if (writeback && m->fwd_bf16 && !m->pageable && !ctx->dry && shard >= 1 && shard <= m->sh.S) {
+      // The write-back's event may be recorded by the staging tier's thread (a context with a staging area issues
+      // every plan there): wait for that, then for the event, then round.  The shard's next write-back is a whole
+      // minibatch away, so the event is not recorded again before this job has waited for it.
+      Pager *pg = ctx->pager;
+      hipEvent_t ev = m->ev_wb[shard];
+      uint16_t *dst = m->host.work_bf16 + off;
+      const float *src = m->host.master + off;
+      m->round_ticket[shard] = worker_submit(ctx->rounder, [pg, ticket, ev, dst, src, cnt, m] {
+        if (pg && ticket) pager_wait(pg, PQ_D2H, ticket);
+        if (hipEventSynchronize(ev) != hipSuccess) {
+          (void)hipGetLastError();
+          m->round_broken.store(true);
+          return;
+        }
+        host_round_bf16_threads(dst, src, (size_t)cnt, 4);
+      });
+    }
     if (writeback) {
       m->wb_pending[shard] = 1;
       m->wb_ticket[shard] = ticket;

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <functional>
 #include <map>
 #include <string>
@@ -28,6 +29,7 @@ void trace_destroy(Tracer *t);
 
 // staging tier for host state that is not page-locked (pager.cpp)
 struct Pager;
+struct HostWorker;
 enum { PQ_H2D = 0, PQ_D2H = 1 };
 
 struct TensorInfo {
@@ -117,7 +119,9 @@ struct Model {
   bool pageable = false;            // master / m / v are ordinary host memory: copies go through the staging ring
   bool fwd_bf16 = false;            // the host keeps a bf16 rounding of the master (hydra_host_state.work_bf16):
                                     // promotes for forward visits of block shards carry that instead of the master
-  uint16_t *work_dev = nullptr;     // page-locked work_bf16 as the device sees it
+  std::vector<uint64_t> round_ticket;  // page-locked state: per shard, the host job that rounds its last write-back
+                                       // into work_bf16 (0: none pending)
+  std::atomic<bool> round_broken{false};  // such a job could not wait for its write-back: the copy is no longer used
 };
 
 }  // namespace hydra
@@ -148,6 +152,7 @@ struct hydra_ctx {
   hydra::Profiler *prof = nullptr;  // per-kernel event timing (HYDRA_FLAG_TIMING)
   hydra::Tracer *tracer = nullptr;  // promote / write-back / task intervals (HYDRA_FLAG_OVERLAP)
   hydra::Pager *pager = nullptr;    // staging ring and its threads (hydra_init_desc.stage)
+  hydra::HostWorker *rounder = nullptr;  // rounds written-back page-locked masters into their bf16 host copies
   // captured block-shard visits (HYDRA_FLAG_GRAPHS); key: model, shard, phase, shard buffer, boundary-gradient parity
   struct GraphEntry {
     int seen = 0;  // visits run so far without a graph
@@ -190,6 +195,12 @@ hydra_status pager_drain(Pager *p, std::string *text);
 hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t bytes);
 hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit,
                        uint16_t *rounded);
+// a thread that runs host-side jobs in submission order; tickets count from 1 (0: nothing to wait for)
+HostWorker *worker_create();
+void worker_destroy(HostWorker *w);  // after running what is still queued
+uint64_t worker_submit(HostWorker *w, std::function<void()> job);
+void worker_wait(HostWorker *w, uint64_t ticket);
+void worker_drain(HostWorker *w);
 // fp32 -> bf16 on the host with the device casts' rounding
 void host_round_bf16(uint16_t *dst, const float *src, size_t n);
 void host_round_bf16_threads(uint16_t *dst, const float *src, size_t n, int threads);

@@ -85,6 +85,72 @@ void host_round_bf16_threads(uint16_t *dst, const float *src, size_t n, int thre
   for (std::thread &t : th) t.join();
 }
 
+// A thread of the library's own that runs host-side jobs in submission order (the rounding of a written-back
+// page-locked master into the host's bf16 copy).
+struct HostWorker {
+  std::thread th;
+  std::mutex mu;
+  std::condition_variable cv, progress;
+  std::deque<std::function<void()>> q;
+  uint64_t submitted = 0, executed = 0;
+  bool stop = false;
+};
+
+HostWorker *worker_create() {
+  HostWorker *w = new HostWorker();
+  w->th = std::thread([w] {
+    for (;;) {
+      std::function<void()> job;
+      {
+        std::unique_lock<std::mutex> l(w->mu);
+        w->cv.wait(l, [&] { return w->stop || !w->q.empty(); });
+        if (w->q.empty()) return;
+        job = std::move(w->q.front());
+        w->q.pop_front();
+      }
+      job();
+      {
+        std::lock_guard<std::mutex> l(w->mu);
+        ++w->executed;
+      }
+      w->progress.notify_all();
+    }
+  });
+  return w;
+}
+
+void worker_destroy(HostWorker *w) {
+  if (!w) return;
+  {
+    std::lock_guard<std::mutex> l(w->mu);
+    w->stop = true;
+  }
+  w->cv.notify_all();
+  if (w->th.joinable()) w->th.join();  // runs what is still queued first
+  delete w;
+}
+
+uint64_t worker_submit(HostWorker *w, std::function<void()> job) {
+  uint64_t ticket;
+  {
+    std::lock_guard<std::mutex> l(w->mu);
+    w->q.push_back(std::move(job));
+    ticket = ++w->submitted;
+  }
+  w->cv.notify_one();
+  return ticket;
+}
+
+void worker_wait(HostWorker *w, uint64_t ticket) {
+  std::unique_lock<std::mutex> l(w->mu);
+  w->progress.wait(l, [&] { return w->executed >= ticket; });
+}
+
+void worker_drain(HostWorker *w) {
+  std::unique_lock<std::mutex> l(w->mu);
+  w->progress.wait(l, [&] { return w->executed >= w->submitted; });
+}
+
 namespace {
 
 // one part of a chunk: copied, and (rounded != null) its floats also rounded to bf16 while they are in the cache

@@ -209,17 +209,15 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
     const hydra_task t = s->order[i];
     const int mid = s->model_id[t.model];
     Model *mm = ctx->models[mid];
-    // promote this task's shard if that has not happened yet, and prefetch the shards of the tasks after it while
-    // this one runs (double buffering, paper Section 2.3; deeper where more buffers are free)
+    // promote this task's shard if that has not happened yet (the previous task's prefetch usually did)
     {
       HostTimer ht(&ctx->stats.host_promote_ms);
-      while (s->promoted < s->order.size() && s->promoted <= i + depth) {
+      while (s->promoted <= i) {
         st = promote(s, s->promoted, i);
-        if (st == 1) break;  // every buffer holds a shard that a task before that one needs
+        if (st == 1) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the next task");
         if (st) return st;
         s->promoted++;
       }
-      if (s->promoted <= i) return fail(ctx, HYDRA_E_NOSLOT, "no shard buffer can be freed for the next task");
     }
     if (t.phase == 0 && t.shard == 0) {
       HostTimer ht(&ctx->stats.host_batch_ms);
@@ -249,6 +247,18 @@ hydra_status hydra_sched_run(hydra_sched *s, const int32_t *const *tokens, const
     }
     ++done;
     s->cursor++;
+    // Prefetch the shards of the tasks after this one while it runs (double buffering, paper Section 2.3; deeper
+    // where the caller asks for it).  After the task has been enqueued, not before: a promote call returns only
+    // when what the promote depends on has finished, and the device should be computing meanwhile.
+    {
+      HostTimer ht(&ctx->stats.host_promote_ms);
+      while (s->promoted < s->order.size() && s->promoted <= i + depth) {
+        st = promote(s, s->promoted, i + 1);
+        if (st == 1) break;  // every buffer holds a shard that a task before that one needs
+        if (st) return st;
+        s->promoted++;
+      }
+    }
   }
   if (n_executed) *n_executed = done;
   return HYDRA_OK;

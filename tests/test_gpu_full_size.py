@@ -136,8 +136,8 @@ def test_gpt6b_as_stated_full_depth_properties(rt):
     H, R = rt
     cfg = dict(SI.CONFIGS["gpt6b"])
     n = cfg["n_models"]
-    if B.mem_available_gb() < 175:
-        pytest.skip("needs 145 GB of host memory for the models' state")
+    if B.mem_available_gb() < 200:
+        pytest.skip("needs 170 GB of host memory for the models' state and its bf16 copies")
     host = B.HostState(cfg, n, R, H)
     desc = H.model_desc(cfg, 1e-4)
     lay = H.hydra_model_layout(desc)
@@ -161,8 +161,13 @@ def test_gpt6b_as_stated_full_depth_properties(rt):
     assert st["n_slots"] == 2
     assert st["bytes_d2h"] == n * 12 * lay.n_params
     # 4 B per parameter for the forward visit, 12 for the backward visit; only the head (last forward, first
-    # backward shard) and the embedding can still be resident when their next visit comes
-    assert n * lay.n_params * 16 - n * 4 * (shard_rng[0][1] + shard_rng[-1][1]) <= st["bytes_h2d"] <= n * lay.n_params * 16
+    # backward shard) and the embedding can still be resident when their next visit comes.  With the state in
+    # ordinary memory bench.py gives the library a bf16 host copy: the forward visit of a block shard then brings 2 B
+    # per parameter and the shard's fp32 vectors.
+    most = lay.n_params * 16
+    if host.work_copy:
+        most -= 2 * sum(c for _, c in shard_rng[1:-1]) - 4 * cfg["L"] * (9 * cfg["d"] + cfg["F"])
+    assert n * most - n * 4 * (shard_rng[0][1] + shard_rng[-1][1]) <= st["bytes_h2d"] <= n * most
     for m in range(n):
         loss = H.hydra_get_loss(sess.ctx, recs[m]["id"])
         assert abs(loss - np.log(cfg["V"])) < 1.5, loss
@@ -177,6 +182,10 @@ def test_gpt6b_as_stated_full_depth_properties(rt):
             assert (np.abs(vv - 0.001 * g * g) <= 1e-5 * (0.001 * g * g) + 1e-37).all(), (m, a)
             step = -lr * g / (np.abs(g) + 1e-8)
             assert (np.abs((ww - before.astype(np.float64)) - step) <= 1e-3 * lr + 1.5e-7 * np.abs(ww)).all(), (m, a)
+            if host.work_copy and shard_rng[1][0] <= a < shard_rng[-1][0]:
+                # the host's bf16 copy of a block shard follows the master (rounded by the staging tier's threads)
+                u = master[a:a + k].view(np.uint32).astype(np.uint64)
+                assert np.array_equal(host.work[m][a:a + k], ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)), (m, a)
         # token ids 0..63 (the rows of wte inside the first window): a row moves if and only if its id is in the batch
         d = cfg["d"]
         in_batch = set(np.unique(batches[m][0]).tolist())
