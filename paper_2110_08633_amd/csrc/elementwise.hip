@@ -1115,19 +1115,20 @@ __global__ __launch_bounds__(256) void copy_to_host_kernel(uint4 *__restrict__ d
 // of everybody else's requests, until the link has taken them; the same write-back through SDMA slows nothing, but
 // reaches only 15-30 GB/s next to the promotes), and the more of the link the write-back takes from the promote
 // that runs beside it (48 workgroups: 50 GB/s out, 38 in; 12: 46 out, 45 in - together more than before).
-//  - Few tokens per visit, small shards (up to 192 MB per state array): a step is bound by the link and by the
-//    chain promote -> task -> write-back -> promote into the same buffer, the buffer has to be free again as early as
-//    possible, and 48 workgroups are best (two-model GPT-2-small workload: 101 / 110 / 117 ms per step with 48 / 24 /
-//    12).
-//  - Few tokens per visit, large shards: the promote of the next shard and the write-back of the last one run side
-//    by side for their whole length and carry the same bytes, so they should take equally long: 12 workgroups (four
-//    GPT-2-medium models 625 against 660 ms per step with 48, four GPT-2-XL models 2266 against 2390, two 6 B models
-//    4317 against 4599; 8 and 4 workgroups starve the write-back: 4690, 5198 ms).
+//  - Few tokens per visit, large shards (more than 192 MB per state array): the promote of the next shard and the
+//    write-back of the last one run side by side for their whole length and carry the same bytes, so they should
+//    take equally long: 12 workgroups (four GPT-2-medium models 625 against 660 ms per step with 48, four GPT-2-XL
+//    models 2266 against 2390, two 6 B models 4317 against 4599; 8 and 4 workgroups starve the write-back: 4690,
+//    5198 ms).
+//  - Few tokens per visit, small shards: 16 (two-model GPT-2-small workload, 8 / 12 / 16 / 24 / 48 / 96 workgroups:
+//    112 / 97.3 / 96.3 / 97.2 / 99.3 / 101.8 ms per step.  While promotes were still enqueued behind stream waits,
+//    48 was best here - the chain promote -> task -> write-back -> promote into the same buffer wanted the buffer
+//    free early; with the waits on the host that no longer pays.)
 //  - The more tokens a visit works on, the more the compute kernels matter and the fewer workgroups a write-back gets
 //    (GPT-2-small workload, tokens per visit 2048 x 4 / 6 / 8 / 12: best at 16 / 12 / 8 / 8 workgroups, up to a fifth
 //    faster than with 32 throughout).
 int copy_to_host_blocks(int64_t tokens_per_visit, size_t array_bytes) {
-  if (tokens_per_visit < 6144) return array_bytes > ((size_t)192 << 20) ? 12 : 48;
+  if (tokens_per_visit < 6144) return array_bytes > ((size_t)192 << 20) ? 12 : 16;
   if (tokens_per_visit < 12288) return 16;
   if (tokens_per_visit < 16384) return 12;
   return 8;
