@@ -58,13 +58,66 @@ class PinnedArray:
             self.ptr = None
 
 
+_STREAMS = {}
+
+
+def independent_streams(n):
+    """n streams (default priority) of which as many as possible do not hold each other up.
+
+    HIP multiplexes a process's streams onto a few hardware queues (four by default), work of streams that share one
+    runs in order, and which streams share is not round-robin: of torch's pooled streams 2 and 3 shared a queue on
+    the machines this was developed on.  The swap engine needs its promote stream, its write-back stream and the
+    compute lanes to really run side by side (with two of them on one queue the two-model GPT-2-small workload took
+    108-112 instead of 96 ms per step), so candidates are tried pair by pair: a spin kernel of about a millisecond on
+    one, a tiny kernel on the other; streams whose tiny kernel had to wait for the spin share a queue.  Chosen once
+    per process and count."""
+    if n in _STREAMS:
+        return _STREAMS[n]
+    import torch
+    x = torch.zeros(64, device="cuda:0")
+
+    def held_up(a, b):
+        torch.cuda.synchronize()
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(a):
+            torch.cuda._sleep(2_500_000)
+            ea.record(a)
+        with torch.cuda.stream(b):
+            x.add_(1.0)
+            eb.record(b)
+        torch.cuda.synchronize()
+        return eb.elapsed_time(ea) < 0.25      # b's kernel ended less than 0.25 ms before a's spin (or after it)
+
+    chosen, rest = [], []
+    try:
+        warm = torch.cuda.Stream()
+        held_up(warm, warm)                    # first use of the spin kernel and of the events
+        rest.append(warm)
+        for _ in range(24):
+            if len(chosen) >= n:
+                break
+            c = torch.cuda.Stream()
+            if all(not held_up(k, c) for k in chosen):
+                chosen.append(c)
+            else:
+                rest.append(c)
+    except Exception:                          # no spin kernel in this torch build: take streams as they come
+        pass
+    while len(chosen) < n:                     # more streams than hardware queues (or no test): the others share
+        chosen.append(rest.pop() if rest else torch.cuda.Stream())
+    _STREAMS[n] = chosen
+    return chosen
+
+
 class Session:
     """One hydra context with its arena, three streams and registered models."""
 
     def __init__(self, arena_bytes, flags=0, shard_buffer_cap_bytes=0, max_slots=0, dry_run=False, lanes=1,
-                 copy_blocks=0, prefetch_depth=0, stage_bytes=0, stage_threads=0):
+                 copy_blocks=0, prefetch_depth=0, stage_bytes=0, stage_threads=0, arena=None):
         """stage_bytes > 0: a page-locked staging area of that size is handed to the library, and models may be added
-        with pageable=True (master / m / v in ordinary memory, for state beyond what can be page-locked)."""
+        with pageable=True (master / m / v in ordinary memory, for state beyond what can be page-locked).
+        arena: a uint8 device tensor of at least arena_bytes + 256 to use instead of allocating one (a process that
+        opens one context after another can keep its device memory that way)."""
         self.dry = dry_run
         self.models = []      # dicts: desc, cfg, master, m, v, ckpt, id, names
         self._pinned = []
@@ -77,10 +130,14 @@ class Session:
         else:
             import torch
             self.torch = torch
-            self.arena = torch.empty(arena_bytes + 256, dtype=torch.uint8, device="cuda:0")
+            if arena is not None and arena.numel() < arena_bytes + 256:
+                raise ValueError("arena tensor too small")
+            self.arena = arena if arena is not None else torch.empty(arena_bytes + 256, dtype=torch.uint8, device="cuda:0")
             arena_ptr = (self.arena.data_ptr() + 255) // 256 * 256
-            self.streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
-            self.lane_streams = [torch.cuda.Stream() for _ in range(lanes - 1)]     # default priority
+            # promote, write-back and the first lanes on hardware queues of their own (compute, h2d, d2h, lanes 1..)
+            pool = independent_streams(2 + lanes)
+            self.streams = (pool[2], pool[0], pool[1])
+            self.lane_streams = pool[3:]
         self.stage = None
         if stage_bytes and not dry_run:
             self.stage = PinnedArray(stage_bytes + 256, np.uint8, zero=False)

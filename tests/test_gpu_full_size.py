@@ -148,7 +148,7 @@ def test_gpt6b_as_stated_full_depth_properties(rt):
         for a in (off, off + cnt // 2, off + cnt - win):
             windows.append((max(off, min(a, off + cnt - win)), win))
     w0 = [[host.arrays[m][0][a:a + k].copy() for a, k in windows] for m in range(n)]
-    sess, recs = B.make_session(cfg, n, host, B.WORKLOADS["gpt6b"], 0, 2, R, H)
+    sess, recs = B.make_session(cfg, n, host, B.WORKLOADS["gpt6b"], 0, 2, R, H, torch)
     tables = [costs_of(cfg)] * n
     want, _, _ = oracle_order([cfg] * n, [1] * n, tables)
     batches = [SI.make_batch(cfg, SI.batch_seed(cfg, m, 0)) for m in range(n)]
