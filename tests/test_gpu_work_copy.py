@@ -162,3 +162,37 @@ def test_fp32_models_ignore_the_copy_and_page_locked_state_needs_a_page_locked_c
         H.hydra_register_model(sess.ctx, desc, master, m, v, None, stage, np.zeros(n, np.uint16))
     assert e.value.code == H.E_INVAL
     sess.close()
+
+
+def test_runtime_streams_and_caller_arena(rt):
+    """The runtime's stream set is chosen once per count, holds distinct streams, and two of its first four do not
+    hold each other up; a context can run in a caller's device buffer, and one that is too small is refused."""
+    H, R = rt
+    four = R.independent_streams(4)
+    assert len(four) == 4 and len({s.cuda_stream for s in four}) == 4
+    assert R.independent_streams(4) is four
+    x = torch.zeros(64, device="cuda")
+    for a, b in ((four[0], four[1]), (four[2], four[3]), (four[0], four[3])):
+        torch.cuda.synchronize()
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(a):
+            torch.cuda._sleep(2_500_000)
+            ea.record(a)
+        with torch.cuda.stream(b):
+            x.add_(1.0)
+            eb.record(b)
+        torch.cuda.synchronize()
+        assert eb.elapsed_time(ea) > 0.25, "a small kernel on one stream waited for the spin kernel on another"
+    cfg = _cfg()
+    need = R.arena_bytes_for([cfg], 2)
+    buf = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ValueError):
+        R.Session(need, max_slots=2, arena=buf[: need // 2])
+    results = []
+    for arena in (buf, None):
+        sess = R.Session(need, max_slots=2, arena=arena)
+        rec = sess.add_model(cfg, SI.make_weights(cfg, 5), 1e-4)
+        tok, tgt = SI.make_batch(cfg, 6)
+        results.append(sess.train_step_manual(rec, tok, tgt, collect=False)["loss"])
+        sess.close()
+    assert results[0] == results[1]
