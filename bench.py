@@ -444,18 +444,16 @@ def gpt2s_extras(cfg, host, R, H, torch, steps):
                        "host_enqueue_ms_per_step": round(1e3 * o["enqueue_seconds"] / steps, 3), "shard_buffers": o["n_slots"]}
     steps_m = max(2, steps // 2)
     for nm in (4, 8):
-        # with many tokens per visit the host spends most of a step blocked in kernel launches: graphs on
+        # plain launches: replaying visits as graphs saved host time while the host was the bottleneck of these runs;
+        # it no longer is, and the gate that keeps the library's threads out of the runtime during a capture costs more
+        # (172 k against 163 k tokens/s with four micro-batches, 334 k against 313 k with eight)
         mc = dict(cfg, n_micro=nm)
-        o = measure(mc, n, host, wl, steps_m, 2, R, H, torch, extra_flags=H.FLAG_GRAPHS)   # visits are captured in step 2
-        tt = measure(mc, n, host, wl, 2, 1, R, H, torch, timing=True)      # (graphs are off in a timing pass)
+        o = measure(mc, n, host, wl, steps_m, 2, R, H, torch)
+        tt = measure(mc, n, host, wl, 2, 1, R, H, torch, timing=True)
         out[f"spill_micro{nm}"] = {"value": round(tokens * nm * steps_m / o["seconds"], 1), "unit": "tokens/s",
                                    "ms_per_step": round(1e3 * o["seconds"] / steps_m, 3), "tokens_per_step": tokens * nm,
-                                   "hip_graphs": True, "link": link_report(o), "overlap": overlap_report(o),
-                                   "kernel_pass_overlap": overlap_report(tt),
-                                   "kernel_pass_note": "every launch bracketed by events and no graphs: with this many "
-                                   "launches per visit the host is the bottleneck of that pass and kernels come in bursts, "
-                                   "so its transfer_hidden_frac is a lower estimate; tasks_in_flight_frac_of_transfer of "
-                                   "'overlap' (the timed run, visits replayed as graphs) is the upper one"}
+                                   "hip_graphs": False, "link": link_report(o), "overlap": overlap_report(o),
+                                   "kernel_pass_overlap": overlap_report(tt)}
     return out
 
 
@@ -478,7 +476,8 @@ def main():
     ap.add_argument("--micro", type=int, default=1, help="micro-batches of B samples per shard visit (1 = as stated)")
     ap.add_argument("--graphs", action="store_true", help="replay block-shard visits as HIP graphs")
     ap.add_argument("--ckpt-spill", action="store_true", help="boundary activations travel through host DRAM too")
-    ap.add_argument("--d2h-memcpy", action="store_true", help="demote with hipMemcpyAsync instead of the copy kernel")
+    ap.add_argument("--d2h-memcpy", action="store_true", help="every write-back through the copy engine (default: page-locked state only)")
+    ap.add_argument("--d2h-kernel", action="store_true", help="every write-back through the library's copy kernel (default: staged state only)")
     ap.add_argument("--no-work-copy", action="store_true",
                     help="no bf16 copy of the master on the host: forward promotes carry the fp32 master")
     ap.add_argument("--prefetch-depth", type=int, default=0, help="tasks ahead that shards are promoted for (0 = as far as buffers allow)")
@@ -497,7 +496,7 @@ def main():
         print(json.dumps({"block_gemm_large_shapes": block_gemm_large_shapes(H, torch)}))
         return
     flags = (H.FLAG_GRAPHS if args.graphs else 0) | (H.FLAG_CKPT_SPILL if args.ckpt_spill else 0) | \
-            (H.FLAG_D2H_MEMCPY if args.d2h_memcpy else 0)
+            (H.FLAG_D2H_MEMCPY if args.d2h_memcpy else 0) | (H.FLAG_D2H_KERNEL if args.d2h_kernel else 0)
     WORK_COPY = not args.no_work_copy
     SESSION_KW.update(prefetch_depth=args.prefetch_depth, stage_threads=args.stage_threads, copy_blocks=args.copy_blocks)
     avail = mem_available_gb()

@@ -78,17 +78,23 @@ struct CopyPlan {
     if ((call) != hipSuccess) return HYDRA_E_HIP; \
   } while (0)
 
+// Both functions run on the coordinator thread of their direction.  Calls into the HIP runtime are made inside a
+// HipGate scope and events are waited for with wait_event (see hydra_ctx::hip_gate).
 static hydra_status run_h2d_plan(hydra_ctx *ctx, const CopyPlan &p) {
   hipStream_t s = ctx->s_h2d;
   for (uint64_t t : p.d2h_tickets) pager_wait(ctx->pager, PQ_D2H, t);
-  // The issuing thread waits for what the promote depends on (the write-back that frees its buffer, the one that
-  // brought the shard's state to the host) and only then hands the copies to the stream.  Enqueued behind stream
-  // waits instead, the same copies ran slower: four GPT-2-medium models 14.1 k -> 16.2-17.5 k tokens/s with the
-  // waits on the host, two GPT-2-small models 35.8 k -> 41.5 k (the link was then used to 0.93-1.0 of its measured
-  // two-way rate instead of 0.80-0.85).  Every event in the list was recorded before the plan was made, by work
-  // that depends on nothing enqueued later, so the wait ends.
-  for (hipEvent_t e : p.waits) PLAN_HIP(hipEventSynchronize(e));
-  const int tr = p.trace_bytes ? trace_begin(ctx, TRACE_H2D, s, p.trace_tag) : -1;
+  // The thread waits for what the promote depends on (the write-back that frees its buffer, the one that brought
+  // the shard's state to the host) and only then hands the copies to the stream.  Enqueued behind stream waits
+  // instead, the same copies ran slower: four GPT-2-medium models 14.1 k -> 16.2-17.5 k tokens/s with the waits on
+  // the host, two GPT-2-small models 35.8 k -> 41.5 k (the link was then used to 0.93-1.0 of its measured two-way
+  // rate instead of 0.80-0.85).  Every event in the list was recorded before the plan was made, by work that
+  // depends on nothing enqueued later, so the wait ends.
+  for (hipEvent_t e : p.waits) PLAN_HIP(wait_event(ctx, e));
+  int tr = -1;
+  if (p.trace_bytes) {
+    HipGate gate(ctx);
+    tr = trace_begin(ctx, TRACE_H2D, s, p.trace_tag);
+  }
   for (const CopyPlan::Seg &g : p.segs) {
     if (g.kind == CopyPlan::SEG_PAGEABLE) {
       const hydra_status st = pager_h2d(ctx->pager, g.dst, g.src, g.bytes);
@@ -97,10 +103,12 @@ static hydra_status run_h2d_plan(hydra_ctx *ctx, const CopyPlan &p) {
       // SDMA (hipMemcpyAsync): the copy kernel reading page-locked memory through its device-side mapping reaches the
       // same link rate but slows the compute kernels it shares CUs with and the write-backs (measured: 147 against
       // 123 ms per step of the two-model GPT-2-small workload)
+      HipGate gate(ctx);
       PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes,
                               g.kind == CopyPlan::SEG_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s));
     }
   }
+  HipGate gate(ctx);
   trace_end(ctx, tr, s, p.trace_bytes);
   for (hipEvent_t e : p.records) PLAN_HIP(hipEventRecord(e, s));
   return HYDRA_OK;
@@ -108,18 +116,33 @@ static hydra_status run_h2d_plan(hydra_ctx *ctx, const CopyPlan &p) {
 
 static hydra_status run_d2h_plan(hydra_ctx *ctx, const CopyPlan &p) {
   hipStream_t s = ctx->s_d2h;
-  for (hipEvent_t e : p.waits) PLAN_HIP(hipStreamWaitEvent(s, e, 0));
-  const int tr = p.trace_bytes ? trace_begin(ctx, TRACE_D2H, s, p.trace_tag) : -1;
+  // as for promotes: the thread waits for the task that last used the buffer, then issues the copies
+  for (hipEvent_t e : p.waits) PLAN_HIP(wait_event(ctx, e));
+  int tr = -1;
+  if (p.trace_bytes) {
+    HipGate gate(ctx);
+    tr = trace_begin(ctx, TRACE_D2H, s, p.trace_tag);
+  }
   for (const CopyPlan::Seg &g : p.segs) {
     if (g.kind == CopyPlan::SEG_PAGEABLE) {
       const hydra_status st = pager_d2h(ctx->pager, g.dst, g.src, g.bytes, p.tokens_per_visit, g.rounded);
       if (st) return st;
-    } else if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY) {
+    } else if (!(ctx->init.flags & HYDRA_FLAG_D2H_KERNEL)) {
+      // Page-locked state: the copy engine.  Issued like this - by a thread that has waited for the task, so that
+      // the copy can start at once - it carries 49-50 GB/s next to the promotes and leaves the compute kernels
+      // alone, where the copy kernel carries 41-47 and slows every kernel on the device (two GPT-2-small models
+      // 42.7 k -> 43.8 k tokens/s, four GPT-2-medium models 17.4 k -> 18.6 k, eight micro-batches per visit 287 k ->
+      // 333 k).  Enqueued behind a stream wait the same copies reached 25-35 GB/s.  State behind the staging area
+      // stays with the copy kernel: through the ring's 64 MiB chunks the copy engine was faster on some runs and
+      // slower on others (two 6 B models: 507 / 534 / 470 tokens/s against 526-528).
+      HipGate gate(ctx);
       PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes, hipMemcpyDeviceToHost, s));
     } else {
+      HipGate gate(ctx);
       PLAN_HIP(launch_copy_to_host(g.dst_mapped, g.src, g.bytes, p.tokens_per_visit, ctx->init.copy_blocks, g.bytes, s));
     }
   }
+  HipGate gate(ctx);
   trace_end(ctx, tr, s, p.trace_bytes);
   if (p.poison) PLAN_HIP(launch_fill_u32((uint32_t *)p.poison_base, 0x7fc07fc0u, p.poison_words, s));
   for (hipEvent_t e : p.records) PLAN_HIP(hipEventRecord(e, s));
@@ -305,6 +328,10 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
     }
     ctx->lanes[i].stream = ls;
   }
+  if ((desc->flags & HYDRA_FLAG_D2H_MEMCPY) && (desc->flags & HYDRA_FLAG_D2H_KERNEL)) {
+    delete ctx;
+    return fail(nullptr, HYDRA_E_INVAL, "HYDRA_FLAG_D2H_MEMCPY and HYDRA_FLAG_D2H_KERNEL exclude each other");
+  }
   if (desc->copy_blocks < 0 || desc->copy_blocks > 1024 || desc->prefetch_depth < 0) {
     delete ctx;
     return fail(nullptr, HYDRA_E_INVAL, "copy_blocks must be 0..1024 and prefetch_depth >= 0");
@@ -314,7 +341,9 @@ hydra_status hydra_init(const hydra_init_desc *desc, hydra_ctx **out) {
     prof_activate(ctx->prof);
   }
   if (!ctx->dry && (desc->flags & HYDRA_FLAG_OVERLAP)) ctx->tracer = trace_create();
-  if (!ctx->dry && desc->stage) {
+  ctx->gate_on = !ctx->dry && (desc->flags & HYDRA_FLAG_GRAPHS) != 0;
+  if (!ctx->dry) {
+    // one coordinator thread per copy direction issues every promote and write-back (with or without a staging area)
     if (desc->stage_threads < 0 || desc->stage_threads > 16) {
       hydra_destroy(ctx);
       return fail(nullptr, HYDRA_E_INVAL, "stage_threads must be 0..16");
@@ -402,7 +431,7 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   m->desc = *desc;
   m->host = *host;
   m->pageable = !ctx->dry && (!page_locked(host->master) || !page_locked(host->adam_m) || !page_locked(host->adam_v));
-  if (m->pageable && !ctx->pager) {
+  if (m->pageable && !ctx->init.stage) {
     delete m;
     return fail(ctx, HYDRA_E_INVAL, "master / adam_m / adam_v are not page-locked and hydra_init was given no staging area");
   }
@@ -694,9 +723,9 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
       hipEvent_t ev = m->ev_wb[shard];
       uint16_t *dst = m->host.work_bf16 + off;
       const float *src = m->host.master + off;
-      m->round_ticket[shard] = worker_submit(ctx->rounder, [pg, ticket, ev, dst, src, cnt, m] {
+      m->round_ticket[shard] = worker_submit(ctx->rounder, [ctx, pg, ticket, ev, dst, src, cnt, m] {
         if (pg && ticket) pager_wait(pg, PQ_D2H, ticket);
-        if (hipEventSynchronize(ev) != hipSuccess) {
+        if (wait_event(ctx, ev) != hipSuccess) {
           (void)hipGetLastError();
           m->round_broken.store(true);
           return;
@@ -851,7 +880,10 @@ hydra_status hydra_shard_adam_step(hydra_ctx *ctx, int32_t model, int32_t shard)
   if (!sl->grads_valid) return fail(ctx, HYDRA_E_STATE, "no gradients: run the backward visit first");
   if (!sl->has_opt) return fail(ctx, HYDRA_E_STATE, "Adam state not resident: load with HYDRA_LOAD_OPT");
   if (sl->spill_pending && !ctx->dry) {
-    // a write-back of this buffer (the shard stayed resident after it) may still be reading w, m and v
+    // a write-back of this buffer (the shard stayed resident after it) may still be reading w, m and v; its event
+    // can be waited for once the coordinator thread has recorded it
+    if (ctx->pager && sl->spill_ticket) pager_wait(ctx->pager, PQ_D2H, sl->spill_ticket);
+    if ((st = pager_check(ctx))) return st;
     HYDRA_HIP(ctx, hipStreamWaitEvent(ctx->lanes[m->lane].stream, sl->ev_spilled, 0));
   }
   const int tr = ctx->dry ? -1 : trace_begin(ctx, TRACE_COMPUTE, ctx->lanes[m->lane].stream, model << 16 | shard);

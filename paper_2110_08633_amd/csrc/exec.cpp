@@ -437,6 +437,9 @@ hydra_status run_visit(hydra_ctx *ctx, Model *mm, Slot *sl, int shard, int phase
     return HYDRA_OK;
   }
   hipGraph_t graph = nullptr;
+  // no other thread of the library calls into the HIP runtime while the visit is being captured (hydra_ctx::hip_gate)
+  std::unique_lock<std::mutex> gate(ctx->hip_gate, std::defer_lock);
+  if (ctx->gate_on) gate.lock();
   hipError_t err = hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed);
   if (err == hipSuccess) {
     const hipError_t launch_err = enqueue();
@@ -444,6 +447,7 @@ hydra_status run_visit(hydra_ctx *ctx, Model *mm, Slot *sl, int shard, int phase
     if (err == hipSuccess) err = launch_err;
   }
   if (err == hipSuccess) err = hipGraphInstantiate(&e.exec, graph, nullptr, nullptr, 0);
+  if (gate.owns_lock()) gate.unlock();
   if (graph) (void)hipGraphDestroy(graph);
   if (err != hipSuccess) {  // capture is an optimisation: fall back to plain launches for this combination
     (void)hipGetLastError();

@@ -6,6 +6,7 @@
 #include <atomic>
 #include <functional>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -153,6 +154,11 @@ struct hydra_ctx {
   hydra::Tracer *tracer = nullptr;  // promote / write-back / task intervals (HYDRA_FLAG_OVERLAP)
   hydra::Pager *pager = nullptr;    // staging ring and its threads (hydra_init_desc.stage)
   hydra::HostWorker *rounder = nullptr;  // rounds written-back page-locked masters into their bf16 host copies
+  // With HYDRA_FLAG_GRAPHS: the calling thread holds this while it captures a shard visit, and the library's threads
+  // take it around every HIP call they make (and poll events instead of blocking in the runtime).  A capture was
+  // invalidated whenever one of them called into the runtime meanwhile, whatever capture mode either side declared.
+  std::mutex hip_gate;
+  bool gate_on = false;
   // captured block-shard visits (HYDRA_FLAG_GRAPHS); key: model, shard, phase, shard buffer, boundary-gradient parity
   struct GraphEntry {
     int seen = 0;  // visits run so far without a graph
@@ -201,6 +207,16 @@ void worker_destroy(HostWorker *w);  // after running what is still queued
 uint64_t worker_submit(HostWorker *w, std::function<void()> job);
 void worker_wait(HostWorker *w, uint64_t ticket);
 void worker_drain(HostWorker *w);
+// scope in which a library thread may call the HIP runtime (no-op unless the context replays graphs)
+struct HipGate {
+  hydra_ctx *c;
+  explicit HipGate(hydra_ctx *ctx) : c(ctx) { if (c->gate_on) c->hip_gate.lock(); }
+  ~HipGate() { if (c->gate_on) c->hip_gate.unlock(); }
+  HipGate(const HipGate &) = delete;
+  HipGate &operator=(const HipGate &) = delete;
+};
+// a library thread's wait for an event: hipEventSynchronize, or polling under the gate
+hipError_t wait_event(hydra_ctx *ctx, hipEvent_t e);
 // fp32 -> bf16 on the host with the device casts' rounding
 void host_round_bf16(uint16_t *dst, const float *src, size_t n);
 void host_round_bf16_threads(uint16_t *dst, const float *src, size_t n, int threads);

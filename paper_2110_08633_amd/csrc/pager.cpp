@@ -23,6 +23,7 @@
 #include <immintrin.h>
 
 #include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <cstring>
 #include <deque>
@@ -95,6 +96,19 @@ struct HostWorker {
   uint64_t submitted = 0, executed = 0;
   bool stop = false;
 };
+
+hipError_t wait_event(hydra_ctx *ctx, hipEvent_t e) {
+  if (!ctx->gate_on) return hipEventSynchronize(e);
+  for (;;) {
+    hipError_t r;
+    {
+      HipGate g(ctx);
+      r = hipEventQuery(e);
+    }
+    if (r != hipErrorNotReady) return r;
+    std::this_thread::sleep_for(std::chrono::microseconds(20));
+  }
+}
 
 HostWorker *worker_create() {
   HostWorker *w = new HostWorker();
@@ -302,6 +316,12 @@ static void queue_loop(Pager *p, int which) {
 }
 
 Pager *pager_create(hydra_ctx *ctx, void *stage, uint64_t stage_bytes, int helpers, std::string *err) {
+  if (!stage) {  // no staging area: the two coordinator threads only issue what goes straight to page-locked memory
+    Pager *p = new Pager();
+    p->ctx = ctx;
+    for (int w = 0; w < 2; ++w) p->queue[w].th = std::thread(queue_loop, p, w);
+    return p;
+  }
   hipPointerAttribute_t at;
   if (hipPointerGetAttributes(&at, stage) != hipSuccess || at.type != hipMemoryTypeHost || !at.devicePointer) {
     (void)hipGetLastError();
@@ -399,16 +419,18 @@ hydra_status pager_drain(Pager *p, std::string *text) {
 // from the pageable source, hand it to the copy engine.  Returns once every chunk has been ISSUED.
 hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t bytes) {
   Ring &r = p->ring[PQ_H2D];
+  if (r.n == 0) return HYDRA_E_STATE;  // no staging area
   hipStream_t s = p->ctx->s_h2d;
   if (bytes < (1u << 20)) {
     // small copies (a shard's vectors) share one chunk instead of taking a ring position each
     if (r.small_k < 0 || r.small_off + bytes > r.chunk) {
       r.small_k = (int)(r.next++ % r.n);
       r.small_off = 0;
-      if (r.used[r.small_k] && hipEventSynchronize(r.ev[r.small_k]) != hipSuccess) return HYDRA_E_HIP;
+      if (r.used[r.small_k] && wait_event(p->ctx, r.ev[r.small_k]) != hipSuccess) return HYDRA_E_HIP;
     }
     char *at = r.host + (size_t)r.small_k * r.chunk + r.small_off;
     memcpy(at, src_host, bytes);
+    HipGate gate(p->ctx);
     if (hipMemcpyAsync(dst_dev, at, bytes, hipMemcpyHostToDevice, s) != hipSuccess) return HYDRA_E_HIP;
     if (hipEventRecord(r.ev[r.small_k], s) != hipSuccess) return HYDRA_E_HIP;
     r.used[r.small_k] = 1;
@@ -419,8 +441,9 @@ hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t byt
     const size_t n = bytes - off < r.chunk ? bytes - off : r.chunk;
     const int k = (int)(r.next++ % r.n);
     if (k == r.small_k) r.small_k = -1;  // the ring has come round to the chunk of the small copies
-    if (r.used[k] && hipEventSynchronize(r.ev[k]) != hipSuccess) return HYDRA_E_HIP;
+    if (r.used[k] && wait_event(p->ctx, r.ev[k]) != hipSuccess) return HYDRA_E_HIP;
     p->pool[PQ_H2D]->copy(r.host + (size_t)k * r.chunk, (const char *)src_host + off, n);
+    HipGate gate(p->ctx);
     if (hipMemcpyAsync((char *)dst_dev + off, r.host + (size_t)k * r.chunk, n, hipMemcpyHostToDevice, s) != hipSuccess)
       return HYDRA_E_HIP;
     if (hipEventRecord(r.ev[k], s) != hipSuccess) return HYDRA_E_HIP;
@@ -435,6 +458,7 @@ hydra_status pager_h2d(Pager *p, void *dst_dev, const void *src_host, size_t byt
 hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t bytes, int64_t tokens_per_visit,
                        uint16_t *rounded) {
   Ring &r = p->ring[PQ_D2H];
+  if (r.n == 0) return HYDRA_E_STATE;  // no staging area
   hydra_ctx *ctx = p->ctx;
   hipStream_t s = ctx->s_d2h;
   const size_t nchunks = (bytes + r.chunk - 1) / r.chunk;
@@ -445,6 +469,7 @@ hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t byt
       const size_t n = bytes - off < r.chunk ? bytes - off : r.chunk;
       const int k = (int)(issued % r.n);  // every chunk of the ring is free when a call starts
       hipError_t e;
+      HipGate gate(ctx);
       if (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)
         e = hipMemcpyAsync(r.host + (size_t)k * r.chunk, (const char *)src_dev + off, n, hipMemcpyDeviceToHost, s);
       else
@@ -457,7 +482,7 @@ hydra_status pager_d2h(Pager *p, void *dst_host, const void *src_dev, size_t byt
     const size_t off = drained * r.chunk;
     const size_t n = bytes - off < r.chunk ? bytes - off : r.chunk;
     const int k = (int)(drained % r.n);
-    if (hipEventSynchronize(r.ev[k]) != hipSuccess) return HYDRA_E_HIP;
+    if (wait_event(ctx, r.ev[k]) != hipSuccess) return HYDRA_E_HIP;
     p->pool[PQ_D2H]->copy((char *)dst_host + off, r.host + (size_t)k * r.chunk, n, rounded ? rounded + off / 4 : nullptr);
     ++drained;
   }

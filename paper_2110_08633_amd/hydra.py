@@ -22,6 +22,7 @@ lib = C.CDLL(LIB_PATH)
 
 OK, E_INVAL, E_NOSLOT, E_STATE, E_HIP, E_NOMEM = 0, -1, -2, -3, -4, -5
 FLAG_DRY_RUN, FLAG_CKPT_SPILL, FLAG_POISON, FLAG_TIMING, FLAG_D2H_MEMCPY, FLAG_GRAPHS, FLAG_OVERLAP = 1, 2, 4, 8, 16, 32, 64
+FLAG_D2H_KERNEL = 128
 LOAD_PARAMS, LOAD_OPT = 1, 2
 SPILL_WRITEBACK, SPILL_EVICT = 1, 2
 MAX_LANES = 8

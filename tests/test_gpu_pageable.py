@@ -90,3 +90,22 @@ def test_pageable_state_needs_a_staging_area(rt):
     with pytest.raises(H.HydraError) as e:      # an area too small for two rings
         R.Session(R.arena_bytes_for([cfg], 2), max_slots=2, stage_bytes=1 << 20)
     assert e.value.code == H.E_INVAL
+
+
+def test_write_back_mechanisms_agree(rt):
+    """Write-backs travel through the copy engine or through the library's copy kernel: by default the first for
+    page-locked state and the second behind the staging area; either can be forced for both.  They move bytes:
+    every combination must leave the same state."""
+    H, R = rt
+    cfg = _cfg("bf16")
+    _, want, loss_w, _ = run_manual(rt, cfg, 2, max_slots=2, flags=H.FLAG_POISON, oracle=False)
+    for flag in (H.FLAG_D2H_KERNEL, H.FLAG_D2H_MEMCPY):
+        for pageable in (False, True):
+            kw = dict(session_kw=STAGE, pageable=True) if pageable else {}
+            _, got, loss, _ = run_manual(rt, cfg, 2, max_slots=2, flags=H.FLAG_POISON | flag | (H.FLAG_CKPT_SPILL if pageable else 0),
+                                         oracle=False, **kw)
+            assert_same_state(got, want, f"write-back flag {flag}, pageable={pageable}: ")
+            assert loss == loss_w
+    with pytest.raises(H.HydraError) as e:
+        R.Session(R.arena_bytes_for([cfg], 2), max_slots=2, flags=H.FLAG_D2H_KERNEL | H.FLAG_D2H_MEMCPY)
+    assert e.value.code == H.E_INVAL
