@@ -74,10 +74,10 @@ enum {
                              /* "intermediate data" is demoted too); the device keeps a ping-pong pair       */
   HYDRA_FLAG_POISON = 4,     /* fill a shard buffer with NaN patterns when it is freed                       */
   HYDRA_FLAG_TIMING = 8,     /* bracket every kernel launch with HIP events; read with hydra_kernel_stats    */
-  HYDRA_FLAG_D2H_MEMCPY = 16, /* every write-back through the copy engine (hipMemcpyAsync).  Without this flag and */
-                              /* without HYDRA_FLAG_D2H_KERNEL: page-locked state goes back through the copy      */
-                              /* engine, state in ordinary memory (staging area) and spilled checkpoints through   */
-                              /* the library's own copy kernel - what measured best for each                       */
+  HYDRA_FLAG_D2H_MEMCPY = 16, /* every write-back through hipMemcpyAsync.  Without this flag and without           */
+                              /* HYDRA_FLAG_D2H_KERNEL: page-locked state goes back through hipMemcpyAsync, state   */
+                              /* in ordinary memory (staging area) and spilled checkpoints through the library's   */
+                              /* own copy kernel - what measured best for each                                     */
   HYDRA_FLAG_GRAPHS = 32,    /* block-shard visits are captured as HIP graphs on their second run with a given  */
                              /* shard buffer and replayed from then on (one graph launch instead of dozens of   */
                              /* kernel launches: the host is the bottleneck otherwise); ignored with TIMING     */

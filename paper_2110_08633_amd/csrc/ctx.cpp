@@ -128,12 +128,13 @@ static hydra_status run_d2h_plan(hydra_ctx *ctx, const CopyPlan &p) {
       const hydra_status st = pager_d2h(ctx->pager, g.dst, g.src, g.bytes, p.tokens_per_visit, g.rounded);
       if (st) return st;
     } else if (!(ctx->init.flags & HYDRA_FLAG_D2H_KERNEL)) {
-      // Page-locked state: the copy engine.  Issued like this - by a thread that has waited for the task, so that
-      // the copy can start at once - it carries 49-50 GB/s next to the promotes and leaves the compute kernels
-      // alone, where the copy kernel carries 41-47 and slows every kernel on the device (two GPT-2-small models
+      // Page-locked state: hipMemcpyAsync (which this runtime executes as a copy kernel of its own, not on a copy
+      // engine).  Issued like this - by a thread that has waited for the task, so that the copy can start at once -
+      // it carries 49-50 GB/s next to the promotes and hardly touches the compute kernels, where the library's
+      // copy kernel carries 41-47 and slows every kernel on the device (two GPT-2-small models
       // 42.7 k -> 43.8 k tokens/s, four GPT-2-medium models 17.4 k -> 18.6 k, eight micro-batches per visit 287 k ->
       // 333 k).  Enqueued behind a stream wait the same copies reached 25-35 GB/s.  State behind the staging area
-      // stays with the copy kernel: through the ring's 64 MiB chunks the copy engine was faster on some runs and
+      // stays with the copy kernel: through the ring's 64 MiB chunks the runtime's copy was faster on some runs and
       // slower on others (two 6 B models: 507 / 534 / 470 tokens/s against 526-528).
       HipGate gate(ctx);
       PLAN_HIP(hipMemcpyAsync(g.dst, g.src, g.bytes, hipMemcpyDeviceToHost, s));

@@ -93,7 +93,7 @@ def test_pageable_state_needs_a_staging_area(rt):
 
 
 def test_write_back_mechanisms_agree(rt):
-    """Write-backs travel through the copy engine or through the library's copy kernel: by default the first for
+    """Write-backs travel through hipMemcpyAsync or through the library's copy kernel: by default the first for
     page-locked state and the second behind the staging area; either can be forced for both.  They move bytes:
     every combination must leave the same state."""
     H, R = rt
