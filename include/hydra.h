@@ -413,6 +413,10 @@ hydra_status hydra_op_layernorm_bwd_static(const float *dy, const float *x, cons
                                            const float *gamma, const float *dres, float *dx, void *dx_bf16,
                                            float *dgamma, float *dbeta, float *dx_colsum, int32_t M, int32_t d,
                                            void *stream);
+/* Plumbing, host only (no HIP call): n floats at src -> their bf16 roundings at dst (round to nearest even, NaN stays
+ * NaN), the rounding every cast of the device path uses and the one hydra_host_state.work_bf16 is kept with.  HOST
+ * pointers; src and dst must not overlap. */
+hydra_status hydra_host_round_bf16(uint16_t *dst, const float *src, int64_t n);
 /* Causal softmax over rows of S fp32 [n_mat, T, T] -> P (dtype); entries j>i are 0. */
 hydra_status hydra_op_softmax_causal(int32_t dtype, const float *S, void *P, int32_t n_mat, int32_t T,
                                      void *stream);

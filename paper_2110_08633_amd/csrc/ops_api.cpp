@@ -134,6 +134,12 @@ hydra_status hydra_op_cross_entropy(int32_t dtype, const float *logits, const in
              "cross_entropy");
 }
 
+hydra_status hydra_host_round_bf16(uint16_t *dst, const float *src, int64_t n) {
+  if (!dst || !src || n < 0) return fail(nullptr, HYDRA_E_INVAL, "bad argument");
+  host_round_bf16(dst, src, (size_t)n);
+  return HYDRA_OK;
+}
+
 hydra_status hydra_op_attention_fwd(const void *qkv, void *o, float *lse, int32_t B, int32_t H, int32_t T, int32_t dh,
                                     void *stream) {
   if (!qkv || !o || !lse || B <= 0 || H <= 0 || T <= 0 || (T & 7) || !attention_fused_supported(DT_BF16, dh))

@@ -118,6 +118,7 @@ SIGNATURES = {
     "hydra_op_layernorm_fwd": (_i32, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_layernorm_bwd": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_layernorm_bwd_static": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
+    "hydra_host_round_bf16": (_i32, [_vp, _vp, _i64]),
     "hydra_op_softmax_causal": (_i32, [_i32, _vp, _vp, _i32, _i32, _vp]),
     "hydra_op_cross_entropy": (_i32, [_i32, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _f32, _vp]),
 }
@@ -366,6 +367,10 @@ def hydra_op_layernorm_bwd(dy, x, mean, rstd, gamma, dres, dx, dx_bf16, dgamma, 
     return _check(lib.hydra_op_layernorm_bwd(_ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(dres),
                                              _ptr(dx), _ptr(dx_bf16), _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum),
                                              _ptr(scratch), M, d, _stream(stream)))
+
+
+def hydra_host_round_bf16(dst, src, n):
+    return _check(lib.hydra_host_round_bf16(_ptr(dst), _ptr(src), n))
 
 
 def hydra_op_layernorm_bwd_static(dy, x, mean, rstd, gamma, dres, dx, dx_bf16, dgamma, dbeta, dx_colsum, M, d, stream=None):

@@ -353,3 +353,27 @@ def test_register_model_needs_a_batch_staging_array():
     assert e.value.code == H.E_INVAL
     H.hydra_destroy(ctx)
     s.close()
+
+
+def test_host_rounding_to_bf16_is_round_to_nearest_even():
+    """The rounding the staging tier's threads apply to written-back masters (AVX2 or plain loop, chosen at run time)
+    against the definition written out on the bit patterns: ties to even, signed zeros, infinities, NaNs stay NaNs,
+    denormals, the largest finite values (which round up to infinity), random bit patterns; lengths that leave a
+    tail for the scalar loop."""
+    rng = np.random.default_rng(3)
+    special = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.0, 1.00390625, 1.01171875, 1.0078125, 3.3895314e38,
+                        -3.3895314e38, 3.4028235e38, 1e-40, 2.0 ** -126, 2.0 ** -133], np.float32)
+    bits = rng.integers(0, 2 ** 32, 100003, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    x = np.concatenate([special, bits, rng.standard_normal(4099).astype(np.float32)])
+    u = x.view(np.uint32).astype(np.uint64)
+    want = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    nan = (u & 0x7FFFFFFF) > 0x7F800000
+    want[nan] = ((u[nan] >> 16) | 0x40).astype(np.uint16)
+    assert want[5] == 0x3F80 and want[6] == 0x3F80 and want[7] == 0x3F82 and want[8] == 0x3F81    # ties go to even
+    assert want[11] == 0x7F80                                                                     # rounds up to inf
+    for n in (x.size, 17, 16, 15, 1, 0):
+        got = np.full(max(n, 1), 0xABCD, np.uint16)
+        H.hydra_host_round_bf16(got, x, n)
+        assert np.array_equal(got[:n], want[:n]) and (n > 0 or got[0] == 0xABCD)
+    with pytest.raises(H.HydraError):
+        H.hydra_host_round_bf16(None, x, 4)
