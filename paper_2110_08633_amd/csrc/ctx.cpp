@@ -181,10 +181,13 @@ hydra_status drain_copies(hydra_ctx *ctx) {
 }
 
 // device-side address of caller memory that must be page-locked and mapped
-static hydra_status mapped_pointer(hydra_ctx *ctx, const void *host, const char *what, float **out) {
+// (state: one of master / adam_m / adam_v, which the library's copy kernel writes only with HYDRA_FLAG_D2H_KERNEL;
+// checkpoints go through it unless HYDRA_FLAG_D2H_MEMCPY is set)
+static hydra_status mapped_pointer(hydra_ctx *ctx, const void *host, const char *what, float **out, bool state = false) {
   *out = (float *)host;
   // the device-side mapping is what the library's copy kernel stores through; hipMemcpyAsync takes the host address
-  if (ctx->dry || !host || (ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY)) return HYDRA_OK;
+  const bool kernel_writes_it = state ? (ctx->init.flags & HYDRA_FLAG_D2H_KERNEL) != 0 : !(ctx->init.flags & HYDRA_FLAG_D2H_MEMCPY);
+  if (ctx->dry || !host || !kernel_writes_it) return HYDRA_OK;
   hipPointerAttribute_t at;
   hipError_t e = hipPointerGetAttributes(&at, host);
   if (e != hipSuccess || at.type != hipMemoryTypeHost || !at.devicePointer) {
@@ -443,9 +446,9 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
       delete m;
       return st;
     }
-  } else if ((st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master)) ||
-      (st = mapped_pointer(ctx, host->adam_m, "adam_m", &m->host_dev.adam_m)) ||
-      (st = mapped_pointer(ctx, host->adam_v, "adam_v", &m->host_dev.adam_v)) ||
+  } else if ((st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master, true)) ||
+      (st = mapped_pointer(ctx, host->adam_m, "adam_m", &m->host_dev.adam_m, true)) ||
+      (st = mapped_pointer(ctx, host->adam_v, "adam_v", &m->host_dev.adam_v, true)) ||
       (st = mapped_pointer(ctx, host->ckpt, "ckpt", &m->host_dev.ckpt))) {
     delete m;
     return st;
