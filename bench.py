@@ -66,34 +66,55 @@ def mem_available_gb():
 
 
 class HostState:
-    """master / m / v of every model of a workload: page-locked if the driver allows that much, else ordinary memory
-    (the library then stages every copy).  Weights: one seeded N(0, 0.02) block tiled over the master array,
-    LayerNorm gains 1, biases 0 - cheap to produce at 6 B parameters and irrelevant to kernel time."""
+    """master / m / v (and the bf16 copy) of every model of a workload.  As many of the arrays as the driver allows
+    are page-locked - the second moments of all models first, then the first moments, the masters, the bf16 copies -
+    and the rest is ordinary memory that the library moves through its staging area.  Weights: one seeded N(0, 0.02)
+    block tiled over the master array, LayerNorm gains 1, biases 0 - cheap to produce at 6 B parameters and
+    irrelevant to kernel time."""
+
+    HEADROOM = 3 << 30      # left for the staging area, token staging and whatever else the process page-locks
 
     def __init__(self, cfg, n_models, R, H):
         self.cfg, self.n = cfg, n_models
         desc = H.model_desc(cfg, 1e-4)
         lay = H.hydra_model_layout(desc)
         self.n_params = lay.n_params
-        self.pinned_bufs, self.arrays, self.work, self.pageable = [], [], [], False
+        self.pinned_bufs = []
         # The library's bf16 rounding of the master, which forward promotes of block shards then carry (2 instead of 4
         # bytes per parameter); kept current by host threads of the library, so nothing extra crosses the link.
         self.work_copy = WORK_COPY and cfg["dtype"] == "bf16"
-        try:
-            for _ in range(n_models):
-                for _ in range(3):      # one by one: an array that was page-locked before the failure must be freed
-                    self.pinned_bufs.append(R.PinnedArray(lay.n_params, np.float32, zero=False))
-                self.arrays.append(tuple(b.array for b in self.pinned_bufs[-3:]))
-                if self.work_copy:
-                    self.pinned_bufs.append(R.PinnedArray(lay.n_params, np.uint16, zero=False))
-                    self.work.append(self.pinned_bufs[-1].array)
-        except MemoryError:
-            self.free()
-            self.pageable = True
-            self.arrays = [tuple(np.zeros(lay.n_params, np.float32) for _ in range(3)) for _ in range(n_models)]
-            self.work = [np.zeros(lay.n_params, np.uint16) for _ in range(n_models)] if self.work_copy else []
-        if not self.work_copy:
-            self.work = [False] * n_models
+        kinds = [2, 1, 0] + ([3] if self.work_copy else [])          # v, m, master, bf16 copy
+        slots = {(m, k): None for k in kinds for m in range(n_models)}
+        full = not PAGE_LOCK
+        for k in kinds:
+            for m in range(n_models):
+                if full:
+                    break
+                try:
+                    self.pinned_bufs.append(R.PinnedArray(lay.n_params, np.uint16 if k == 3 else np.float32, zero=False))
+                    slots[(m, k)] = self.pinned_bufs[-1].array
+                except MemoryError:
+                    full = True
+        if full:      # make sure the staging area will still fit
+            while self.pinned_bufs:
+                try:
+                    R.PinnedArray(self.HEADROOM, np.uint8, zero=False).free()
+                    break
+                except MemoryError:
+                    last = self.pinned_bufs.pop()
+                    for key, a in slots.items():
+                        if a is last.array:
+                            slots[key] = None
+                    last.free()
+        self.locked = {key: a is not None for key, a in slots.items()}
+        for (m, k), a in slots.items():
+            if a is None:
+                slots[(m, k)] = np.zeros(lay.n_params, np.uint16 if k == 3 else np.float32)
+        self.arrays = [tuple(slots[(m, k)] for k in range(3)) for m in range(n_models)]
+        self.work = [slots[(m, 3)] if self.work_copy else False for m in range(n_models)]
+        self.pageable = not all(self.locked.values())
+        lock_b = sum((2 if k == 3 else 4) for (m, k), v in self.locked.items() if v)
+        self.locked_fraction = lock_b / sum((2 if k == 3 else 4) for (m, k) in self.locked)
         tensors = [H.hydra_model_tensor(desc, i) for i in range(lay.n_tensors)]
         for m in range(n_models):
             master, am, av = self.arrays[m]
@@ -109,9 +130,9 @@ class HostState:
                     master[off:off + rows * cols] = 1.0
                 elif leaf.startswith("b_") or leaf in ("ln1_b", "ln2_b", "lnf_b"):
                     master[off:off + rows * cols] = 0.0
-            if not self.pageable:
-                am[:] = 0.0
-                av[:] = 0.0
+            for k, arr in ((1, am), (2, av)):
+                if self.locked[(m, k)]:        # fresh ordinary memory is zero already
+                    arr[:] = 0.0
 
     def free(self):
         self.arrays, self.work = [], []
@@ -120,6 +141,7 @@ class HostState:
         self.pinned_bufs = []
 
 
+PAGE_LOCK = True    # --no-page-lock: all state in ordinary memory (for comparison)
 WORK_COPY = True    # --no-work-copy: forward promotes carry the fp32 master
 SESSION_KW = {}     # prefetch depth / staging threads / copy workgroups from the command line (experiments)
 
@@ -316,7 +338,8 @@ def workload_text(name, cfg, n_models, wl, host):
             f"{host.n_params / 1e9:.3f} B parameters each), B{cfg['B']} T{cfg['T']}, {cfg['k']}-layer shards alternated by "
             f"Sharded-LRTF, {wl['what']}, bf16 MFMA + fp32 master/Adam, "
             f"{n_models * host.n_params * 12 / 1e9:.1f} GB of state in "
-            + ("ordinary host memory (more than the driver page-locks: copies staged through a page-locked ring)"
+            + (f"host memory, {100 * host.locked_fraction:.0f} % of it page-locked (as much as the driver allows) and the rest "
+               "ordinary memory whose copies are staged through a page-locked ring"
                if host.pageable else "page-locked host memory")
             + "; weights: a seeded N(0,0.02) block tiled, LayerNorm gains 1, biases 0; uniform tokens")
 
@@ -336,14 +359,15 @@ def bench_workload(name, steps, warmup, timing_steps, R, H, torch, n_models=0, l
     wl = WORKLOADS[name]
     log(f"{name}: preparing the host state of {n} model(s)")
     host = HostState(cfg, n, R, H)
-    log(f"  {n * host.n_params * 12 / 1e9:.1f} GB of state, " + ("ordinary memory (staged)" if host.pageable else "page-locked"))
+    log(f"  {n * host.n_params * 12 / 1e9:.1f} GB of state, {100 * host.locked_fraction:.0f} % of the host arrays' bytes page-locked")
     tokens = n * micro * cfg["B"] * cfg["T"]
     run = measure(cfg, n, host, wl, steps, warmup, R, H, torch, lanes=lanes, extra_flags=extra_flags)
     out = {"workload": workload_text(name, cfg, n, wl, host) + (" [depth / model count changed on the command line]" if layers or n_models else ""),
            "value": round(tokens * steps / run["seconds"], 1), "unit": "tokens/s", "steps": steps, "warmup": warmup,
            "ms_per_step": round(1e3 * run["seconds"] / steps, 3), "tokens_per_step": tokens,
            "host_enqueue_ms_per_step": round(1e3 * run["enqueue_seconds"] / steps, 3),
-           "shard_buffers": run["n_slots"], "compute_lanes": lanes, "state_page_locked": not host.pageable, "work_copy": host.work_copy,
+           "shard_buffers": run["n_slots"], "compute_lanes": lanes, "state_page_locked": not host.pageable, "host_bytes_page_locked_frac": round(host.locked_fraction, 3),
+           "work_copy": host.work_copy,
            "link": link_report(run, host.pageable), "overlap": overlap_report(run),
            "final_losses": [round(x, 4) for x in run["losses"]]}
     if timing_steps:
@@ -465,7 +489,7 @@ def gpt2s_extras(cfg, host, R, H, torch, steps):
 
 
 def main():
-    global WORK_COPY
+    global WORK_COPY, PAGE_LOCK
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
@@ -485,6 +509,7 @@ def main():
     ap.add_argument("--ckpt-spill", action="store_true", help="boundary activations travel through host DRAM too")
     ap.add_argument("--d2h-memcpy", action="store_true", help="every write-back through hipMemcpyAsync (default: page-locked state only)")
     ap.add_argument("--d2h-kernel", action="store_true", help="every write-back through the library's copy kernel (default: staged state only)")
+    ap.add_argument("--no-page-lock", action="store_true", help="keep all model state in ordinary host memory")
     ap.add_argument("--no-work-copy", action="store_true",
                     help="no bf16 copy of the master on the host: forward promotes carry the fp32 master")
     ap.add_argument("--prefetch-depth", type=int, default=0, help="tasks ahead that shards are promoted for (0 = as far as buffers allow)")
@@ -505,6 +530,7 @@ def main():
     flags = (H.FLAG_GRAPHS if args.graphs else 0) | (H.FLAG_CKPT_SPILL if args.ckpt_spill else 0) | \
             (H.FLAG_D2H_MEMCPY if args.d2h_memcpy else 0) | (H.FLAG_D2H_KERNEL if args.d2h_kernel else 0)
     WORK_COPY = not args.no_work_copy
+    PAGE_LOCK = not args.no_page_lock
     SESSION_KW.update(prefetch_depth=args.prefetch_depth, stage_threads=args.stage_threads, copy_blocks=args.copy_blocks)
     avail = mem_available_gb()
     name = args.config
@@ -527,6 +553,7 @@ def main():
                       "compute_lanes": args.lanes, "hip_graphs": args.graphs, "checkpoints_through_host": args.ckpt_spill,
                       "micro_batches_per_visit": args.micro, "tokens_per_step": main_out["tokens_per_step"],
                       "host_memory_available_GB": round(avail, 1), "state_page_locked": main_out["state_page_locked"],
+                      "host_bytes_page_locked_frac": main_out["host_bytes_page_locked_frac"],
                       "bf16_host_copy_for_forward_promotes": main_out["work_copy"]},
            "link": main_out["link"], "overlap": main_out["overlap"], "final_losses": main_out["final_losses"]}
     if fallback:

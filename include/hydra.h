@@ -153,8 +153,10 @@ typedef struct {
 } hydra_model_desc;
 
 typedef struct {
-  /* caller-owned host memory; must outlive the model.  Page-locked - except that master, adam_m and adam_v may be
-   * ordinary memory when hydra_init was given a staging area (all three are then treated as ordinary memory) */
+  /* caller-owned host memory; must outlive the model.  Page-locked - except that master, adam_m, adam_v and
+   * work_bf16 may each be ordinary memory when hydra_init was given a staging area: an array in ordinary memory
+   * travels through that area, a page-locked one directly (so a caller can page-lock as many of a model's arrays
+   * as the driver allows and leave the rest) */
   float *master;  /* [n_params] fp32, canonical flat layout */
   float *adam_m;  /* [n_params]                               */
   float *adam_v;  /* [n_params]                               */
@@ -167,10 +169,10 @@ typedef struct {
                         /* rounding of the weights in any case, so with the array present the promote for a        */
                         /* FORWARD visit of a block shard (Section 2.3) carries it (2 bytes per parameter) plus    */
                         /* the shard's fp32 vectors instead of the whole fp32 master (4 bytes per parameter);      */
-                        /* results do not change by a bit.  Ordinary memory if master is (the staging tier's host  */
-                        /* threads round the master as they move it out of the staging area); page-locked if       */
-                        /* master is (a host thread of the library rounds each write-back once it has landed; a    */
-                        /* promote call that needs the result waits for it).  Current for the caller after         */
+                        /* results do not change by a bit.  Kept current by host threads of the library: those of  */
+                        /* the staging area round a master in ordinary memory as they move it out of the area; a   */
+                        /* page-locked master is rounded by a thread of its own once a write-back has landed, and  */
+                        /* a promote call that needs the result waits for it.  Current for the caller after        */
                         /* hydra_sync.  The caller must not change master while the model is registered, or this   */
                         /* copy goes stale.                                                                        */
 } hydra_host_state;

@@ -434,36 +434,31 @@ hydra_status hydra_register_model(hydra_ctx *ctx, const hydra_model_desc *desc, 
   }
   m->desc = *desc;
   m->host = *host;
-  m->pageable = !ctx->dry && (!page_locked(host->master) || !page_locked(host->adam_m) || !page_locked(host->adam_v));
-  if (m->pageable && !ctx->init.stage) {
+  // each state array on its own: page-locked memory is copied directly, ordinary memory through the staging area
+  // (what the driver lets a process page-lock may cover some of a model's arrays and not the others)
+  auto kind_of = [&](const void *p) { return ctx->dry || page_locked(p) ? CopyPlan::SEG_PINNED : CopyPlan::SEG_PAGEABLE; };
+  m->kind_w = kind_of(host->master);
+  m->kind_m = kind_of(host->adam_m);
+  m->kind_v = kind_of(host->adam_v);
+  m->pageable = m->kind_w == CopyPlan::SEG_PAGEABLE;
+  m->dtype = desc->dtype;
+  m->fwd_bf16 = host->work_bf16 != nullptr && desc->dtype == DT_BF16;
+  m->kind_work = m->fwd_bf16 ? kind_of(host->work_bf16) : CopyPlan::SEG_PINNED;
+  if ((m->kind_w || m->kind_m || m->kind_v || m->kind_work) && !ctx->init.stage) {
     delete m;
-    return fail(ctx, HYDRA_E_INVAL, "master / adam_m / adam_v are not page-locked and hydra_init was given no staging area");
+    return fail(ctx, HYDRA_E_INVAL, "a state array is not page-locked and hydra_init was given no staging area");
   }
-  if (m->pageable) {
-    m->host_dev = *host;  // never used: state in ordinary memory travels through the staging ring
-    st = mapped_pointer(ctx, host->ckpt, "ckpt", &m->host_dev.ckpt);
-    if (st) {
-      delete m;
-      return st;
-    }
-  } else if ((st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master, true)) ||
-      (st = mapped_pointer(ctx, host->adam_m, "adam_m", &m->host_dev.adam_m, true)) ||
-      (st = mapped_pointer(ctx, host->adam_v, "adam_v", &m->host_dev.adam_v, true)) ||
+  m->host_dev = *host;  // entries of arrays in ordinary memory are never used
+  if ((!m->kind_w && (st = mapped_pointer(ctx, host->master, "master", &m->host_dev.master, true))) ||
+      (!m->kind_m && (st = mapped_pointer(ctx, host->adam_m, "adam_m", &m->host_dev.adam_m, true))) ||
+      (!m->kind_v && (st = mapped_pointer(ctx, host->adam_v, "adam_v", &m->host_dev.adam_v, true))) ||
       (st = mapped_pointer(ctx, host->ckpt, "ckpt", &m->host_dev.ckpt))) {
     delete m;
     return st;
   }
-  m->dtype = desc->dtype;
-  m->fwd_bf16 = host->work_bf16 != nullptr && desc->dtype == DT_BF16;
   if (m->fwd_bf16 && !ctx->dry) {
-    if (!m->pageable) {
-      // promotes read it with the copy engine; a thread of the library keeps it current after write-backs
-      if (!page_locked(host->work_bf16)) {
-        delete m;
-        return fail(ctx, HYDRA_E_INVAL, "work_bf16 must be page-locked when master is");
-      }
-      if (!ctx->rounder) ctx->rounder = worker_create();
-    }
+    // a page-locked master is rounded into the copy by a thread of the library after each write-back
+    if (!m->pageable && !ctx->rounder) ctx->rounder = worker_create();
     host_round_bf16_threads(host->work_bf16, host->master, (size_t)m->sh.n_params, 8);
   }
   m->round_ticket.assign(m->sh.S + 2, 0);
@@ -570,7 +565,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
   Slot *sl = slot_for(ctx, model, shard);
   CopyPlan plan;
   plan.trace_tag = model << 16 | shard;
-  const int host_kind = m->pageable ? CopyPlan::SEG_PAGEABLE : CopyPlan::SEG_PINNED;
+  const int host_kind = m->kind_w;
   if (!sl) {
     int free_i = -1;
     for (size_t i = 0; i < ctx->slots.size(); ++i)
@@ -620,7 +615,7 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     sl->has_params = sl->has_fwd = true;
   }
   if (need_fwd) {
-    plan.segs.push_back({sl->wb, m->host.work_bf16 + off, nullptr, (size_t)cnt * 2, host_kind});
+    plan.segs.push_back({sl->wb, m->host.work_bf16 + off, nullptr, (size_t)cnt * 2, m->kind_work});
     plan.trace_bytes += (uint64_t)cnt * 2;
     // the vectors of a block lie in four runs between its matrices (the last one runs on into the next block's first)
     const BlockOffsets &o = m->sh.bo;
@@ -660,8 +655,8 @@ hydra_status hydra_shard_load_async(hydra_ctx *ctx, int32_t model, int32_t shard
     sl->wb_valid = false;
   }
   if ((what & HYDRA_LOAD_OPT) && !sl->has_opt) {
-    plan.segs.push_back({sl->m, m->host.adam_m + off, nullptr, (size_t)cnt * 4, host_kind});
-    plan.segs.push_back({sl->v, m->host.adam_v + off, nullptr, (size_t)cnt * 4, host_kind});
+    plan.segs.push_back({sl->m, m->host.adam_m + off, nullptr, (size_t)cnt * 4, m->kind_m});
+    plan.segs.push_back({sl->v, m->host.adam_v + off, nullptr, (size_t)cnt * 4, m->kind_v});
     plan.trace_bytes += (uint64_t)cnt * 8;
     sl->has_opt = true;
   }
@@ -698,10 +693,9 @@ hydra_status hydra_shard_spill(hydra_ctx *ctx, int32_t model, int32_t shard, int
     // after the last task that used the buffer
     if (sl->compute_pending) plan.waits.push_back(sl->ev_compute);
     if (writeback) {
-      const int kind = m->pageable ? CopyPlan::SEG_PAGEABLE : CopyPlan::SEG_PINNED;
-      plan.segs.push_back({m->host.master + off, sl->w, m->host_dev.master + off, (size_t)cnt * 4, kind});
-      plan.segs.push_back({m->host.adam_m + off, sl->m, m->host_dev.adam_m + off, (size_t)cnt * 4, kind});
-      plan.segs.push_back({m->host.adam_v + off, sl->v, m->host_dev.adam_v + off, (size_t)cnt * 4, kind});
+      plan.segs.push_back({m->host.master + off, sl->w, m->host_dev.master + off, (size_t)cnt * 4, m->kind_w});
+      plan.segs.push_back({m->host.adam_m + off, sl->m, m->host_dev.adam_m + off, (size_t)cnt * 4, m->kind_m});
+      plan.segs.push_back({m->host.adam_v + off, sl->v, m->host_dev.adam_v + off, (size_t)cnt * 4, m->kind_v});
       plan.trace_bytes = (uint64_t)cnt * 12;
       // the host's bf16 copy follows the master: state in ordinary memory is rounded by the staging tier's threads on
       // its way out of the ring (page-locked state: by a host job once the write-back has landed, below)

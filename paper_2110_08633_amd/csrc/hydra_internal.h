@@ -117,7 +117,9 @@ struct Model {
   std::vector<hipEvent_t> ev_wb;   // per shard: last write-back to the host arrays
   std::vector<char> wb_pending;
   std::vector<uint64_t> wb_ticket;  // staging tier: job of the shard's last write-back
-  bool pageable = false;            // master / m / v are ordinary host memory: copies go through the staging ring
+  bool pageable = false;            // the master is ordinary host memory: its copies go through the staging ring, and
+                                    // the ring's threads keep the bf16 host copy
+  int kind_w = 0, kind_m = 0, kind_v = 0, kind_work = 0;  // CopyPlan::SEG_PINNED / SEG_PAGEABLE of each host array
   bool fwd_bf16 = false;            // the host keeps a bf16 rounding of the master (hydra_host_state.work_bf16):
                                     // promotes for forward visits of block shards carry that instead of the master
   std::vector<uint64_t> round_ticket;  // page-locked state: per shard, the host job that rounds its last write-back

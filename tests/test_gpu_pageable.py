@@ -109,3 +109,32 @@ def test_write_back_mechanisms_agree(rt):
     with pytest.raises(H.HydraError) as e:
         R.Session(R.arena_bytes_for([cfg], 2), max_slots=2, flags=H.FLAG_D2H_KERNEL | H.FLAG_D2H_MEMCPY)
     assert e.value.code == H.E_INVAL
+
+
+@pytest.mark.parametrize("locked", [(True, False, True, False), (False, True, True, True), (True, True, False, None)])
+def test_some_arrays_page_locked_and_some_not(rt, locked):
+    """What the driver lets a process page-lock may cover some of a model's arrays only: master, m, v and the bf16
+    copy are each taken as they come (locked[i]: page-locked or ordinary memory; None: no bf16 copy)."""
+    H, R = rt
+    cfg = _cfg("bf16")
+    W = SI.make_weights(cfg, SI.model_seed(cfg, 0))
+    batches = [SI.make_batch(cfg, SI.batch_seed(cfg, 0, i)) for i in range(2)]
+    _, want, loss_w, _ = run_manual(rt, cfg, 2, max_slots=2, flags=H.FLAG_POISON, oracle=False)
+    sess = R.Session(R.arena_bytes_for([cfg], 2), max_slots=2, flags=H.FLAG_POISON, **STAGE)
+    n = H.hydra_model_layout(H.model_desc(cfg, 1e-4)).n_params
+    arrays = [sess._host(n, np.uint16 if i == 3 else np.float32, pageable=not locked[i]) if locked[i] is not None else False
+              for i in range(4)]
+    rec = sess.add_model(cfg, W, cfg["lrs"][0], host=tuple(arrays[:3]), work_copy=arrays[3])
+    for tok, tgt in batches:
+        loss = sess.train_step_manual(rec, tok, tgt, collect=False)["loss"]
+    H.hydra_sync(sess.ctx)
+    from tests.test_gpu_parity import host_state
+    got = host_state(sess, rec)
+    if locked[3] is not None:
+        u = rec["master"].view(np.uint32).astype(np.uint64)
+        lo = H.hydra_shard_range(rec["desc"], 1)[0]
+        hi = sum(H.hydra_shard_range(rec["desc"], rec["S"]))
+        assert np.array_equal(rec["work"][lo:hi], ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)[lo:hi])
+    sess.close()
+    assert_same_state(got, want, f"arrays page-locked {locked}: ")
+    assert loss == loss_w
