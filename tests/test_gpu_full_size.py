@@ -199,3 +199,5 @@ def test_gpt6b_as_stated_full_depth_properties(rt):
     H.hydra_sched_destroy(sch)
     sess.close()
     host.free()
+    B._ARENA[0] = None          # bench.py keeps its device arena for the next context: not wanted here
+    torch.cuda.empty_cache()

@@ -30,9 +30,11 @@ def _case(H, M, d, seed, with_res, static):
     dg, db, dc = (torch.full((d,), float("nan"), device="cuda") for _ in range(3))
     if static:
         torch.cuda.synchronize()
-        before = torch.cuda.memory_allocated()
+        # torch's count of allocations made so far (it only grows; bytes in use may fall when the collector frees
+        # garbage of earlier tests at this very moment)
+        before = torch.cuda.memory_stats()["allocation.all.allocated"]
         H.hydra_op_layernorm_bwd_static(dyd, xd, mean, rstd, gd, rd, dx, dxh, dg, db, dc, M, d)
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     else:
         scratch = torch.empty(3 * d * ((M + 7) // 8), device="cuda")
         H.hydra_op_layernorm_bwd(dyd, xd, mean, rstd, gd, rd, dx, dxh, dg, db, dc, scratch, M, d)
