@@ -45,7 +45,7 @@ STAGE_BYTES = 1 << 30           # page-locked staging ring for state in ordinary
 WORKLOADS = {
     "gpt6b": dict(max_slots=2, cap=0, what="2 shard buffers of 2 layers (BASELINE config 5)"),
     "gpt2xl": dict(max_slots=0, cap=24 * 10 ** 9, what="shard buffers capped at 24 GB (BASELINE config 4)"),
-    "gpt2m": dict(max_slots=6, cap=0, what="6 shard buffers, every shard spilled between uses (BASELINE config 3)"),
+    "gpt2m": dict(max_slots=8, cap=0, what="8 shard buffers (two per model), every shard spilled between uses (BASELINE config 3)"),
     "gpt2s": dict(max_slots=6, cap=0, what="6 shard buffers (BASELINE config 2)"),
 }
 

@@ -259,7 +259,7 @@ def test_a_cap_below_one_buffer_is_an_error():
 
 
 @pytest.mark.parametrize("name,cap_bytes,max_slots,lanes", [
-    ("gpt2s", 0, 6, 2), ("gpt2m", 0, 3, 2), ("gpt2xl", 24 * 10 ** 9, 0, 2), ("gpt6b", 0, 2, 1), ("gpt6b", 0, 2, 2)])
+    ("gpt2s", 0, 6, 2), ("gpt2m", 0, 3, 2), ("gpt2m", 0, 8, 2), ("gpt2xl", 24 * 10 ** 9, 0, 2), ("gpt6b", 0, 2, 1), ("gpt6b", 0, 2, 2)])
 def test_stated_workloads_dry_run_order_and_traffic(name, cap_bytes, max_slots, lanes):
     """Every BASELINE workload with its model count, depth, shard size and buffer cap through hydra_sched_run in
     dry-run mode, two minibatches per model: the executed order equals the oracle's Sharded-LRTF, every shard's
